@@ -1,0 +1,262 @@
+"""Pins for the oracle's data-movement and ordering semantics (CPU only).
+
+Each check compares the C oracle with something it does not contain: a
+byte-level Python model kept by the test, numpy strided assignment, the ring
+exchange of Listing 2, or an invariant that must hold for every delivery
+order.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workgen
+
+HB = 1 << 16
+
+
+def fill(w, seed):
+    for p in range(w.npes):
+        w.heap(p)[:] = workgen.random_words(seed + p, w.heap_bytes // 8).view(np.uint8)
+
+
+def model_apply(model, d):
+    """Byte-level model of one descriptor applied at once (eager)."""
+    k, me, pe = int(d["kind"]), int(d["pe_self"]), int(d["pe"])
+    lo, so, n = int(d["local_off"]), int(d["sym_off"]), int(d["count"])
+    if k == workgen.OP_PUT:
+        model[pe][so:so + n] = model[me][lo:lo + n].copy()
+    elif k == workgen.OP_GET:
+        model[me][lo:lo + n] = model[pe][so:so + n].copy()
+    else:
+        raise AssertionError(k)
+
+
+@pytest.mark.parametrize("mode", [oracle.AT_QUIET, oracle.SHUFFLED])
+def test_put_is_deferred_and_snapshots_source(mode):
+    w = oracle.World(2, HB, mode, 3)
+    fill(w, 11)
+    src = w.heap(0)[256:256 + 100].copy()
+    before = w.heap(1).copy()
+    assert w.put(0, 4096, 256, 100, 1) == 0
+    assert w.pending(0) == 1
+    assert np.array_equal(w.heap(1), before)          # not yet delivered
+    w.heap(0)[256:356] = 0                            # source reusable after return
+    w.quiet(1)                                        # somebody else's quiet: no effect
+    assert np.array_equal(w.heap(1), before)
+    w.quiet(0)
+    assert w.pending(0) == 0
+    after = w.heap(1)
+    assert np.array_equal(after[4096:4196], src)      # target == source as of the put
+    assert np.array_equal(after[:4096], before[:4096])
+    assert np.array_equal(after[4196:], before[4196:])
+
+
+def test_eager_mode_delivers_at_once_and_get_is_blocking():
+    w = oracle.World(3, HB, oracle.EAGER, 0)
+    fill(w, 5)
+    src = w.heap(2)[8:72].copy()
+    w.put(2, 1024, 8, 64, 0)
+    assert np.array_equal(w.heap(0)[1024:1088], src)
+    w2 = oracle.World(3, HB, oracle.SHUFFLED, 0)
+    fill(w2, 5)
+    remote = w2.heap(1)[512:520].copy()
+    w2.get(0, 0, 512, 8, 1)
+    assert np.array_equal(w2.heap(0)[0:8], remote)    # no quiet needed
+
+
+def test_zero_byte_put_and_self_put_and_errors():
+    w = oracle.World(2, HB, oracle.SHUFFLED, 1)
+    fill(w, 2)
+    snap = w.heaps().copy()
+    assert w.put(0, 0, 0, 0, 1) == 0 and w.pending(0) == 0
+    w.barrier_all()
+    assert np.array_equal(w.heaps(), snap)
+    w.put(1, 4096, 0, 128, 1)                          # initiator == target PE is legal
+    w.barrier_all()
+    assert np.array_equal(w.heap(1)[4096:4224], snap[1][0:128])
+    assert w.put(0, HB - 8, 0, 16, 1) == -5            # overruns the target segment
+    assert w.put(0, 0, HB - 8, 16, 1) == -5            # overruns the source segment
+    assert w.put(0, 0, 0, 8, 2) == -4 and w.put(-1, 0, 0, 8, 0) == -4
+    assert w.get(0, HB, 0, 1, 1) == -5
+    assert w.iput(0, 0, 0, 0, 1, 4, 4, 1) == -3        # stride < 1
+    assert w.iput(0, 2, 0, 1, 1, 4, 4, 1) == -6        # misaligned for the element
+    assert w.iput(0, 0, 0, 1, 1, 4, 3, 1) == -3        # element size
+    assert w.iput(0, 0, 0, HB // 4, 1, 2, 4, 1) == -5  # second element out of range
+
+
+def test_fence_orders_puts_to_the_same_pe():
+    outcomes_nofence = set()
+    for seed in range(40):
+        for fenced in (False, True):
+            w = oracle.World(2, HB, oracle.SHUFFLED, seed)
+            w.heap(0)[0:8] = 0xAA
+            w.heap(0)[8:16] = 0xBB
+            w.put(0, 1024, 0, 8, 1)
+            if fenced:
+                w.fence(0)
+            w.put(0, 1024, 8, 8, 1)
+            w.quiet(0)
+            got = int(w.heap(1)[1024])
+            if fenced:
+                assert got == 0xBB                     # the later put lands last
+            else:
+                outcomes_nofence.add(got)
+    assert outcomes_nofence == {0xAA, 0xBB}            # unordered without a fence
+
+
+def test_signal_completes_after_earlier_puts_to_that_peer():
+    # Sec. III-A ordering rule: batch puts, signal once; a reader that sees the
+    # signal sees all payloads.  Puts to a different peer may still be pending.
+    w = oracle.World(3, HB, oracle.SHUFFLED, 9)
+    fill(w, 77)
+    want = [w.heap(0)[64 * i:64 * i + 64].copy() for i in range(5)]
+    for i in range(5):
+        w.put(0, 8192 + 64 * i, 64 * i, 64, 1)
+    w.put(0, 8192, 0, 64, 2)
+    assert w.atomic_fetch_add(1, 0, 0, 1) is not None
+    w.heap(1)[0:8] = 0
+    w.signal_add(0, 0, 1, 1)
+    assert int(w.heap(1)[0:8].view(np.uint64)[0]) == 1
+    for i in range(5):
+        assert np.array_equal(w.heap(1)[8192 + 64 * i:8192 + 64 * i + 64], want[i])
+    assert w.pending(0) == 1                           # the put to PE 2 is still in flight
+
+
+def test_ring_exchange_worked_example(golden_dir):
+    cases = [tuple(map(int, l.split())) for l in open(f"{golden_dir}/ring_exchange.txt")
+             if l.strip() and not l.startswith("#")]
+    assert cases
+    for n, ds in cases:
+        hb = max(4096, ((2 * n * ds + 256 + 255) // 256) * 256)
+        w = oracle.World(n, hb, oracle.SHUFFLED, n + ds)
+        send, recv, sig = 0, n * ds, 2 * n * ds
+        sig = (sig + 7) // 8 * 8
+        rng = np.random.default_rng(ds)
+        sent = [rng.integers(0, 256, n * ds, dtype=np.uint8) for _ in range(n)]
+        for r in range(n):
+            w.heap(r)[send:send + n * ds] = sent[r]
+            w.heap(r)[recv:recv + n * ds] = 0x5A       # sentinel
+            w.heap(r)[sig:sig + 8] = 0
+        for r in range(n):                             # rank r's kernel body
+            peer = (r + 1) % n
+            w.put(r, recv + r * ds, send + peer * ds, ds, peer)
+            w.signal_add(r, sig, 1, peer)
+        for p in range(n):
+            q = (p - 1 + n) % n
+            assert int(w.heap(p)[sig:sig + 8].view(np.uint64)[0]) == 1
+            got = w.heap(p)[recv:recv + n * ds]
+            exp = np.full(n * ds, 0x5A, dtype=np.uint8)
+            exp[q * ds:(q + 1) * ds] = sent[q][p * ds:(p + 1) * ds]
+            assert np.array_equal(got, exp), (n, ds, p)
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_iput_iget_closed_form(eb):
+    rng = np.random.default_rng(eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    for trial in range(30):
+        n = int(rng.integers(0, 200))
+        sst, dst = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        w = oracle.World(2, HB, oracle.SHUFFLED, trial)
+        fill(w, 100 + trial)
+        so = int(rng.integers(0, 64)) * eb
+        do = int(rng.integers(0, 64)) * eb
+        src = w.heap(0).view(dt).copy()
+        exp = w.heap(1).view(dt).copy()
+        exp[do // eb: do // eb + n * dst: dst][:n] = src[so // eb: so // eb + n * sst: sst][:n]
+        assert w.iput(0, do, so, dst, sst, n, eb, 1) == 0
+        w.quiet(0)
+        assert np.array_equal(w.heap(1).view(dt), exp)  # gaps untouched too
+        # iget with swapped strides brings the elements back to where they came from
+        w.heap(0)[:] = 0
+        assert w.iget(0, so, do, sst, dst, n, eb, 1) == 0
+        back = w.heap(0).view(dt)
+        chk = np.zeros_like(back)
+        chk[so // eb: so // eb + n * sst: sst][:n] = src[so // eb: so // eb + n * sst: sst][:n]
+        assert np.array_equal(back, chk)
+
+
+def test_iput_stride_one_is_put():
+    a = oracle.World(2, HB, oracle.SHUFFLED, 1)
+    b = oracle.World(2, HB, oracle.SHUFFLED, 2)
+    fill(a, 9); fill(b, 9)
+    a.iput(0, 512, 64, 1, 1, 300, 4, 1); a.quiet(0)
+    b.put(0, 512, 64, 1200, 1); b.quiet(0)
+    assert np.array_equal(a.heaps(), b.heaps())
+
+
+def test_put_value_inline():
+    w = oracle.World(2, HB, oracle.AT_QUIET, 0)
+    w.heap(1)[:] = 0xEE
+    w.put_value(0, 16, 0x1122334455667788, 4, 1)
+    assert int(w.heap(1)[16]) == 0xEE
+    w.quiet(0)
+    assert list(w.heap(1)[16:20]) == [0x88, 0x77, 0x66, 0x55]
+    assert int(w.heap(1)[20]) == 0xEE and int(w.heap(1)[15]) == 0xEE
+    assert w.put_value(0, 16, 1, 3, 1) == -3
+
+
+def batch_is_conflict_free(ops):
+    reads, writes = {}, {}
+    for d in ops:
+        k, me, pe = int(d["kind"]), int(d["pe_self"]), int(d["pe"])
+        lo, so, n = int(d["local_off"]), int(d["sym_off"]), int(d["count"])
+        r, wr = ((me, lo), (pe, so)) if k == workgen.OP_PUT else ((pe, so), (me, lo))
+        reads.setdefault(r[0], []).append((r[1], r[1] + n))
+        writes.setdefault(wr[0], []).append((wr[1], wr[1] + n))
+    for pe, ws in writes.items():
+        ws = sorted(ws)
+        for (a, b), (c, d_) in zip(ws, ws[1:]):
+            if c < b:
+                return False
+        for (a, b) in ws:
+            for (c, d_) in reads.get(pe, []):
+                if c < b and a < d_:
+                    return False
+    return True
+
+
+@pytest.mark.parametrize("nops,npes,hb", [(1500, 4, 1 << 16), (10000, 4, 1 << 20)])
+def test_config1_table_every_delivery_order_and_byte_model(nops, npes, hb):
+    ops = workgen.cfg1_op_table(npes=npes, heap_bytes=hb, nops=nops)
+    assert len(ops) == nops and set(np.unique(ops["kind"])) == {0, 1}
+    assert int(ops["count"].min()) >= 8 and int(ops["count"].max()) <= 4096
+    assert (ops["local_off"] % 8 == 0).all() and (ops["sym_off"] % 8 == 0).all()
+    for b in range(0, nops, 100):
+        assert batch_is_conflict_free(ops[b:b + 100]), b
+    init = [workgen.random_words(workgen.BASE_SEED + 100 + p, hb // 8).view(np.uint8) for p in range(npes)]
+    model = [x.copy() for x in init]
+    for d in ops:
+        model_apply(model, d)
+    results = []
+    for mode, seed in [(oracle.EAGER, 0), (oracle.AT_QUIET, 0), (oracle.SHUFFLED, 1), (oracle.SHUFFLED, 2)]:
+        w = oracle.World(npes, hb, mode, seed)
+        for p in range(npes):
+            w.heap(p)[:] = init[p]
+        assert w.op_batch(ops, 100) == 0
+        results.append(w.heaps().copy())
+        w.close()
+    for r in results:
+        assert np.array_equal(r, np.stack(model))
+    assert not np.array_equal(results[0], np.stack(init))
+
+
+def test_racy_table_is_detected_by_shuffle():
+    # two puts to one target range inside one quiet window: the result depends
+    # on the delivery seed, which is how a racy generator would be caught
+    ops = np.zeros(2, dtype=workgen.OP_DESC)
+    ops["kind"] = workgen.OP_PUT
+    ops["pe_self"] = [0, 1]; ops["pe"] = 2
+    ops["local_off"] = 0; ops["sym_off"] = 64; ops["count"] = 8
+    seen = set()
+    for seed in range(32):
+        w = oracle.World(3, HB, oracle.SHUFFLED, seed)
+        w.heap(0)[0:8] = 1; w.heap(1)[0:8] = 2
+        # one initiator per put: order across initiators follows the PE loop,
+        # so race two puts of the same initiator instead
+        w.put(0, 64, 0, 8, 2)
+        w.heap(0)[0:8] = 3
+        w.put(0, 64, 0, 8, 2)
+        w.quiet(0)
+        seen.add(int(w.heap(2)[64]))
+    assert seen == {1, 3}
