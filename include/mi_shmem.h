@@ -1,0 +1,228 @@
+/*
+ * mi_shmem -- one-sided (PGAS / OpenSHMEM-style) communication primitives on a
+ * single MI355X, with processing elements (PEs) emulated as workgroup teams
+ * that share one symmetric heap in HBM.
+ *
+ * C ABI.  Every pointer argument says whether it is a HOST or a DEVICE pointer.
+ * Nothing here allocates device memory: the caller owns the heap, the scratch
+ * words, every dev_* array and the HIP stream, and keeps them alive until
+ * shmem_finalize().  The library owns only host-side allocator metadata.
+ *
+ * Model
+ *   - shmem_init() is given one device buffer of npes * heap_bytes_per_pe
+ *     bytes.  PE p's segment is [p * heap_bytes_per_pe, (p+1) * heap_bytes_per_pe).
+ *     Buffers are registered from an existing allocation; allocation and
+ *     registration are decoupled and every segment has the same size
+ *     (Sec. III-A, "Windows-based symmetric memory").
+ *   - A SYMMETRIC ADDRESS is a device address inside PE 0's segment (what
+ *     shmem_malloc returns).  Together with a PE number it names that PE's copy:
+ *     shmem_ptr(sym, pe) = sym + pe * heap_bytes_per_pe.
+ *   - A LOCAL address is an ordinary device pointer (for the initiator's own
+ *     copy of a symmetric object pass shmem_ptr(sym, pe_self)).
+ *   - Every call that moves data is STREAM-ORDERED on the stream given to
+ *     shmem_init and executed entirely by device kernels; pe_self names the
+ *     emulated initiator, whose workgroup team performs the operation.
+ *
+ * Status: 0 = OK, < 0 = error.  Errors that the host can see (not initialised,
+ * bad PE, address outside a segment, range overrun, stride < 1, misalignment,
+ * heap exhausted) are returned at once and enqueue nothing.  Errors only the
+ * device can see (a bad descriptor inside a device-resident table) set a
+ * device error word, skip that op and surface at shmem_stream_sync().
+ * No exceptions, no abort(), nothing printed.
+ */
+#ifndef MI_SHMEM_H
+#define MI_SHMEM_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SHMEM_OK = 0,
+    SHMEM_ERR_NOT_INIT = -1,
+    SHMEM_ERR_ALREADY_INIT = -2,
+    SHMEM_ERR_INVALID_ARG = -3,
+    SHMEM_ERR_INVALID_PE = -4,
+    SHMEM_ERR_OUT_OF_RANGE = -5,
+    SHMEM_ERR_ALIGN = -6,
+    SHMEM_ERR_NOMEM = -7,
+    SHMEM_ERR_BAD_FREE = -8,
+    SHMEM_ERR_DEVICE = -9,       /* a HIP runtime call failed            */
+    SHMEM_ERR_DEVICE_FAULT = -10 /* an op was rejected on the device     */
+};
+/* HOST: static string for a status code. */
+const char *shmem_strerror(int status);
+
+/* ---- set-up (Sec. III-B "Usage workflow": create, register, use) ---------- */
+
+/* Bytes of zero-initialisable device scratch the library needs for npes PEs
+ * (barrier words, device error word, work counters).  0 if npes < 1. */
+size_t shmem_scratch_bytes(int npes);
+
+/* dev_heap: DEVICE, npes * heap_bytes_per_pe bytes, 256-byte aligned;
+ * heap_bytes_per_pe a multiple of 256.  dev_scratch: DEVICE,
+ * shmem_scratch_bytes(npes) bytes, 256-byte aligned; the library zeroes it.
+ * hip_stream: a hipStream_t (NULL = the default stream).
+ * Errors: ALREADY_INIT, INVALID_ARG, ALIGN, DEVICE. */
+int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scratch, void *hip_stream);
+/* Waits for the stream, forgets everything.  Live allocations are dropped. */
+int shmem_finalize(void);
+int shmem_n_pes(void);                 /* 0 when not initialised */
+
+/* Symmetric allocator (same offset on every PE).  Address-ordered first fit,
+ * 256-byte granularity and minimum alignment, neighbours coalesced on free.
+ * Return a symmetric address (DEVICE, inside PE 0's segment) or NULL on
+ * failure / nbytes == 0 / alignment not a power of two.  Host-side only. */
+void *shmem_malloc(size_t nbytes);
+void *shmem_align(size_t alignment, size_t nbytes);
+int shmem_free(void *sym);             /* BAD_FREE unless sym came from malloc/align */
+/* Address of PE pe's copy; NULL if sym is not inside PE 0's segment or pe is
+ * out of range. */
+void *shmem_ptr(const void *sym, int pe);
+
+/* ---- one-sided data movement (Sec. III-A; Table II put / get) ------------- */
+
+/* put: copy nbytes from src_local (DEVICE) to PE pe's copy of dst_sym.  The
+ * source is reusable once the call is stream-complete; delivery is guaranteed
+ * after shmem_quiet / shmem_barrier_all (here: by stream order).  nbytes == 0
+ * and pe == pe_self are legal.  Source and destination must not overlap. */
+int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, int pe);
+/* get: copy nbytes from PE pe's copy of src_sym to dst_local (DEVICE); blocking
+ * in stream order. */
+int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, int pe);
+/* iput: dest[i * dst_stride] = src[i * src_stride] for i < nelems; strides in
+ * elements, >= 1; elem_bytes in {1,2,4,8}; both addresses aligned to it.
+ * Bytes between destination elements are not written. */
+int shmem_iput(int pe_self, void *dst_sym, const void *src_local, ptrdiff_t dst_stride,
+               ptrdiff_t src_stride, size_t nelems, size_t elem_bytes, int pe);
+/* iget: the mirror of iput (strided read from PE pe, strided local write). */
+int shmem_iget(int pe_self, void *dst_local, const void *src_sym, ptrdiff_t dst_stride,
+               ptrdiff_t src_stride, size_t nelems, size_t elem_bytes, int pe);
+
+/* ---- atomic memory operations on a 64-bit word (Table II memory atomics) -- */
+/* Each is indivisible with respect to every other AMO on the same word and
+ * writes the previous value to *dev_result (DEVICE, may be NULL). */
+int shmem_atomic_fetch_add(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result);
+int shmem_atomic_compare_swap(int pe_self, uint64_t *dst_sym, uint64_t cond, uint64_t value, int pe,
+                              uint64_t *dev_result);
+int shmem_atomic_fetch_or(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result);
+
+/* ---- ordering (Sec. III-A "Ordering semantics"; Table II quiet / barrier) - */
+/* fence: earlier puts of pe_self to a PE are delivered before its later puts
+ * to that PE.  quiet: earlier puts and AMOs of pe_self (-1: of every PE) are
+ * complete and visible to all PEs -- the stronger reading, unlike the paper's
+ * flush, which only promises that sources are reusable.  barrier_all: quiet
+ * on every PE, then all PEs synchronise.  At this host level each earlier call
+ * is a finished kernel in stream order, so these enqueue no work; their
+ * in-kernel forms are what the batched entry points below execute. */
+int shmem_fence(int pe_self);
+int shmem_quiet(int pe_self);
+int shmem_barrier_all(void);
+/* HOST waits for the stream.  DEVICE_FAULT if the device error word is set
+ * (the word is then cleared); *first_bad_index (HOST, may be NULL) receives
+ * the index of the first rejected op. */
+int shmem_stream_sync(uint64_t *first_bad_index);
+
+/* ---- batched entry points: inputs device-resident, one launch each -------- */
+
+/* 64-byte operation descriptor (the record shape of the Proxy backend's
+ * queue entries, Sec. III-C: window offsets, sizes, an inline value). */
+typedef struct {
+    uint32_t kind;        /* SHMEM_OP_*                                        */
+    uint32_t pe_self;     /* initiator                                         */
+    uint32_t pe;          /* remote PE                                         */
+    uint32_t elem_bytes;  /* IPUT/IGET: 1,2,4,8; PUT/GET: ignored              */
+    uint64_t local_off;   /* byte offset in the initiator's segment            */
+    uint64_t sym_off;     /* byte offset in PE pe's segment                    */
+    uint64_t count;       /* PUT/GET: bytes; IPUT/IGET: elements               */
+    int64_t local_stride; /* in elements (IPUT/IGET)                           */
+    int64_t sym_stride;   /* in elements (IPUT/IGET)                           */
+    uint64_t value;       /* reserved for inline-value ops                     */
+} shmem_op_desc;
+enum { SHMEM_OP_PUT = 0, SHMEM_OP_GET = 1, SHMEM_OP_IPUT = 2, SHMEM_OP_IGET = 3 };
+
+/* Executes n descriptors (DEVICE table) in ONE persistent launch of
+ * npes * wgs_per_pe workgroups.  PE team p executes the descriptors whose
+ * pe_self is p.  After every quiet_every descriptors (by table index; 0 = only
+ * at the end) and at the end every wave performs quiet and all teams meet in
+ * an in-kernel world barrier.  Ops between two barriers run concurrently and
+ * unordered (GIN operations are unordered by default): a table in which an op
+ * writes bytes that another op of the same window reads or writes has no
+ * defined result.  A descriptor with a bad kind / PE / range / stride /
+ * alignment is skipped and recorded in the device error word.
+ * Errors: NOT_INIT, INVALID_ARG (wgs_per_pe < 1 or more workgroups than can be
+ * co-resident), DEVICE. */
+int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_per_pe);
+
+/* Bandwidth sweep cell.  Every PE p, as initiator, issues ops_per_pe operations
+ * of `kind` towards PE (p+1) mod npes, back to back in one launch of
+ * npes * wgs_per_pe workgroups.  Op k works on slot k mod nslots: the local
+ * buffer at local_sym + slot * local_slot_bytes in p's own segment and the
+ * remote buffer at remote_sym + slot * remote_slot_bytes in the peer's segment.
+ * PUT/GET move `count` bytes; IPUT/IGET move `count` elements of elem_bytes
+ * with the given strides (local_stride applies to the local side).  Completion
+ * is the kernel boundary.  Errors as for the single ops, checked for the last
+ * slot too. */
+int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
+                     ptrdiff_t remote_stride, ptrdiff_t local_stride, size_t remote_slot_bytes,
+                     size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe);
+
+/* n AMOs on the symmetric counter array ctr_sym (uint64[T] on every PE).
+ * Op i targets word dev_idx[i] of PE dev_pe[i] and is issued by PE
+ * i / ceil(n / npes).  kind FETCH_ADD: add dev_a[i]; COMPARE_SWAP: cond dev_a[i],
+ * value dev_b[i]; FETCH_OR: or dev_a[i]; MIN_CAS_LOOP: store dev_a[i] if the
+ * word is 0 or larger, through a compare-swap retry loop.  dev_old[i]
+ * (DEVICE, may be NULL) receives the fetched value.  All arrays DEVICE.
+ * `aggregate` != 0 lets a workgroup combine its ops on the same word before
+ * they reach memory (FETCH_ADD, FETCH_OR, MIN_CAS_LOOP); results are
+ * indistinguishable from some serial order either way. */
+enum { SHMEM_AMO_FETCH_ADD = 0, SHMEM_AMO_COMPARE_SWAP = 1, SHMEM_AMO_FETCH_OR = 2, SHMEM_AMO_MIN_CAS_LOOP = 3 };
+int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe, const uint32_t *dev_idx,
+                    const uint64_t *dev_a, const uint64_t *dev_b, uint64_t *dev_old, size_t n,
+                    int wgs_per_pe, int aggregate);
+
+/* Distributed open-addressing hash table: table_sym is uint64[slots_per_pe]
+ * on every PE, 0 = empty, keys != 0.  h = mix64(key) (the SplitMix64
+ * finaliser); owner = h mod npes; home = (h / npes) mod slots_per_pe; linear
+ * probing inside the owner's table.  insert: compare_swap(slot, 0, key) per
+ * probe; dev_status[i] (DEVICE, may be NULL) = INSERTED / DUPLICATE / FULL.
+ * lookup: 8-byte gets until the key (dev_found[i] = 1) or an empty slot (0).
+ * Key i is held by PE i / ceil(n / npes). */
+enum { SHMEM_HASH_INSERTED = 0, SHMEM_HASH_DUPLICATE = 1, SHMEM_HASH_FULL = 2 };
+int shmem_hash_insert(uint64_t *table_sym, size_t slots_per_pe, const uint64_t *dev_keys, size_t n,
+                      uint8_t *dev_status, int wgs_per_pe);
+int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint64_t *dev_keys, size_t n,
+                      uint8_t *dev_found, int wgs_per_pe);
+
+/* Level-synchronous BFS, 1D block vertex partition: owner(v) = v / vpp with
+ * vpp = ceil(nverts / npes).  A vertex is claimed with fetch_or on its owner's
+ * visited bitmap; the claimer reserves a slot in the owner's next-frontier
+ * queue with fetch_add and puts the vertex, its parent and its level there;
+ * levels are separated by quiet + barrier_all.
+ * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
+ * neighbours uint32[nnz]; PE p reads only its own rows) and allocates the
+ * per-PE state from the symmetric heap (bitmap, level, parent, two queues,
+ * tails: about 17 bytes per owned vertex).  Errors: NOMEM, INVALID_ARG. */
+typedef struct {
+    uint32_t nlevels;           /* number of non-empty frontiers               */
+    uint64_t reached;           /* vertices with level >= 0                    */
+    uint64_t edges_traversed;   /* (sum of degrees of reached vertices) / 2    */
+    uint64_t frontier_size[64]; /* vertices per level                          */
+} shmem_bfs_stats;
+#define SHMEM_BFS_NONE 0xFFFFFFFFu
+int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_t *dev_nbr,
+                     int wgs_per_pe, void **graph_out /* HOST */);
+int shmem_bfs_destroy(void *graph);
+/* Runs one search; blocks the host (one stream sync per level).  dev_level
+ * (int32[nverts], -1 = unreached) and dev_parent (uint32[nverts],
+ * SHMEM_BFS_NONE = unreached; parent[root] = root) are DEVICE and may be NULL;
+ * stats is HOST and may be NULL.  Errors: INVALID_ARG (root >= nverts, more
+ * than 64 levels), DEVICE. */
+int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,231 @@
+"""Thin ctypes binding over ``libmi_shmem.so`` (the C ABI of ``include/mi_shmem.h``).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  Device memory is passed as integer addresses (``tensor.data_ptr()``)
+or as torch tensors, from which the address is taken.  There is no CPU
+fallback: if the library is missing, importing this package raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmi_shmem.so")
+
+OK = 0
+ERR_NOT_INIT, ERR_ALREADY_INIT, ERR_INVALID_ARG, ERR_INVALID_PE = -1, -2, -3, -4
+ERR_OUT_OF_RANGE, ERR_ALIGN, ERR_NOMEM, ERR_BAD_FREE, ERR_DEVICE, ERR_DEVICE_FAULT = -5, -6, -7, -8, -9, -10
+OP_PUT, OP_GET, OP_IPUT, OP_IGET = 0, 1, 2, 3
+AMO_FETCH_ADD, AMO_COMPARE_SWAP, AMO_FETCH_OR, AMO_MIN_CAS_LOOP = 0, 1, 2, 3
+HASH_INSERTED, HASH_DUPLICATE, HASH_FULL = 0, 1, 2
+BFS_NONE = 0xFFFFFFFF
+
+
+class ShmemError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+class BfsStats(C.Structure):
+    _fields_ = [("nlevels", C.c_uint32), ("reached", C.c_uint64),
+                ("edges_traversed", C.c_uint64), ("frontier_size", C.c_uint64 * 64)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+        "This package has no CPU fallback.")
+
+_L = C.CDLL(LIB_PATH)
+_vp, _i, _u64, _sz, _pd = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t, C.c_ssize_t
+_SIG = {
+    "shmem_strerror": (C.c_char_p, [_i]),
+    "shmem_scratch_bytes": (_sz, [_i]),
+    "shmem_init": (_i, [_i, _sz, _vp, _vp, _vp]),
+    "shmem_finalize": (_i, []),
+    "shmem_n_pes": (_i, []),
+    "shmem_malloc": (_vp, [_sz]),
+    "shmem_align": (_vp, [_sz, _sz]),
+    "shmem_free": (_i, [_vp]),
+    "shmem_ptr": (_vp, [_vp, _i]),
+    "shmem_put": (_i, [_i, _vp, _vp, _sz, _i]),
+    "shmem_get": (_i, [_i, _vp, _vp, _sz, _i]),
+    "shmem_iput": (_i, [_i, _vp, _vp, _pd, _pd, _sz, _sz, _i]),
+    "shmem_iget": (_i, [_i, _vp, _vp, _pd, _pd, _sz, _sz, _i]),
+    "shmem_atomic_fetch_add": (_i, [_i, _vp, _u64, _i, _vp]),
+    "shmem_atomic_compare_swap": (_i, [_i, _vp, _u64, _u64, _i, _vp]),
+    "shmem_atomic_fetch_or": (_i, [_i, _vp, _u64, _i, _vp]),
+    "shmem_fence": (_i, [_i]),
+    "shmem_quiet": (_i, [_i]),
+    "shmem_barrier_all": (_i, []),
+    "shmem_stream_sync": (_i, [C.POINTER(C.c_uint64)]),
+    "shmem_op_batch": (_i, [_vp, _sz, _sz, _i]),
+    "shmem_copy_sweep": (_i, [_i, _vp, _vp, _sz, _sz, _pd, _pd, _sz, _sz, _sz, _i, _i]),
+    "shmem_amo_batch": (_i, [_i, _vp, _sz, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i]),
+    "shmem_hash_insert": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
+    "shmem_hash_lookup": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
+    "shmem_bfs_create": (_i, [C.c_uint32, _vp, _vp, _i, C.POINTER(_vp)]),
+    "shmem_bfs_destroy": (_i, [_vp]),
+    "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
+}
+for _name, (_res, _args) in _SIG.items():
+    _fn = getattr(_L, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+EXPORTS = tuple(_SIG)
+
+
+def _addr(x):
+    """Integer device address of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _check(status: int, where: str) -> int:
+    if status != OK:
+        raise ShmemError(status, where)
+    return status
+
+
+def strerror(status: int) -> str:
+    return _L.shmem_strerror(status).decode()
+
+
+def scratch_bytes(npes: int) -> int:
+    return _L.shmem_scratch_bytes(npes)
+
+
+def init(npes, heap_bytes_per_pe, dev_heap, dev_scratch, hip_stream=0):
+    return _check(_L.shmem_init(npes, heap_bytes_per_pe, _addr(dev_heap), _addr(dev_scratch),
+                                _addr(hip_stream) or None), "shmem_init")
+
+
+def finalize():
+    return _check(_L.shmem_finalize(), "shmem_finalize")
+
+
+def n_pes() -> int:
+    return _L.shmem_n_pes()
+
+
+def malloc(nbytes: int):
+    """Symmetric address (int) or None."""
+    return _L.shmem_malloc(nbytes)
+
+
+def align(alignment: int, nbytes: int):
+    return _L.shmem_align(alignment, nbytes)
+
+
+def free(sym):
+    return _check(_L.shmem_free(sym), "shmem_free")
+
+
+def ptr(sym, pe: int):
+    return _L.shmem_ptr(sym, pe)
+
+
+def put(pe_self, dst_sym, src_local, nbytes, pe):
+    return _check(_L.shmem_put(pe_self, _addr(dst_sym), _addr(src_local), nbytes, pe), "shmem_put")
+
+
+def get(pe_self, dst_local, src_sym, nbytes, pe):
+    return _check(_L.shmem_get(pe_self, _addr(dst_local), _addr(src_sym), nbytes, pe), "shmem_get")
+
+
+def iput(pe_self, dst_sym, src_local, dst_stride, src_stride, nelems, elem_bytes, pe):
+    return _check(_L.shmem_iput(pe_self, _addr(dst_sym), _addr(src_local), dst_stride, src_stride,
+                                nelems, elem_bytes, pe), "shmem_iput")
+
+
+def iget(pe_self, dst_local, src_sym, dst_stride, src_stride, nelems, elem_bytes, pe):
+    return _check(_L.shmem_iget(pe_self, _addr(dst_local), _addr(src_sym), dst_stride, src_stride,
+                                nelems, elem_bytes, pe), "shmem_iget")
+
+
+def atomic_fetch_add(pe_self, dst_sym, value, pe, dev_result=None):
+    return _check(_L.shmem_atomic_fetch_add(pe_self, _addr(dst_sym), value, pe, _addr(dev_result)),
+                  "shmem_atomic_fetch_add")
+
+
+def atomic_compare_swap(pe_self, dst_sym, cond, value, pe, dev_result=None):
+    return _check(_L.shmem_atomic_compare_swap(pe_self, _addr(dst_sym), cond, value, pe, _addr(dev_result)),
+                  "shmem_atomic_compare_swap")
+
+
+def atomic_fetch_or(pe_self, dst_sym, value, pe, dev_result=None):
+    return _check(_L.shmem_atomic_fetch_or(pe_self, _addr(dst_sym), value, pe, _addr(dev_result)),
+                  "shmem_atomic_fetch_or")
+
+
+def fence(pe_self):
+    return _check(_L.shmem_fence(pe_self), "shmem_fence")
+
+
+def quiet(pe_self=-1):
+    return _check(_L.shmem_quiet(pe_self), "shmem_quiet")
+
+
+def barrier_all():
+    return _check(_L.shmem_barrier_all(), "shmem_barrier_all")
+
+
+def stream_sync():
+    """Waits for the stream; raises ShmemError(ERR_DEVICE_FAULT) with the first bad op index."""
+    bad = C.c_uint64(0)
+    rc = _L.shmem_stream_sync(C.byref(bad))
+    if rc == ERR_DEVICE_FAULT:
+        e = ShmemError(rc, f"shmem_stream_sync (first rejected op {bad.value})")
+        e.first_bad_index = bad.value
+        raise e
+    return _check(rc, "shmem_stream_sync")
+
+
+def op_batch(dev_ops, n, quiet_every, wgs_per_pe):
+    return _check(_L.shmem_op_batch(_addr(dev_ops), n, quiet_every, wgs_per_pe), "shmem_op_batch")
+
+
+def copy_sweep(kind, remote_sym, local_sym, count, elem_bytes=1, remote_stride=1, local_stride=1,
+               remote_slot_bytes=0, local_slot_bytes=0, nslots=1, ops_per_pe=1, wgs_per_pe=1):
+    return _check(_L.shmem_copy_sweep(kind, _addr(remote_sym), _addr(local_sym), count, elem_bytes,
+                                      remote_stride, local_stride, remote_slot_bytes, local_slot_bytes,
+                                      nslots, ops_per_pe, wgs_per_pe), "shmem_copy_sweep")
+
+
+def amo_batch(kind, ctr_sym, T, dev_pe, dev_idx, dev_a, dev_b, dev_old, n, wgs_per_pe, aggregate=0):
+    return _check(_L.shmem_amo_batch(kind, _addr(ctr_sym), T, _addr(dev_pe), _addr(dev_idx), _addr(dev_a),
+                                     _addr(dev_b), _addr(dev_old), n, wgs_per_pe, aggregate),
+                  "shmem_amo_batch")
+
+
+def hash_insert(table_sym, slots_per_pe, dev_keys, n, dev_status, wgs_per_pe):
+    return _check(_L.shmem_hash_insert(_addr(table_sym), slots_per_pe, _addr(dev_keys), n,
+                                       _addr(dev_status), wgs_per_pe), "shmem_hash_insert")
+
+
+def hash_lookup(table_sym, slots_per_pe, dev_keys, n, dev_found, wgs_per_pe):
+    return _check(_L.shmem_hash_lookup(_addr(table_sym), slots_per_pe, _addr(dev_keys), n,
+                                       _addr(dev_found), wgs_per_pe), "shmem_hash_lookup")
+
+
+def bfs_create(nverts, dev_row_off, dev_nbr, wgs_per_pe):
+    g = _vp(0)
+    _check(_L.shmem_bfs_create(nverts, _addr(dev_row_off), _addr(dev_nbr), wgs_per_pe, C.byref(g)),
+           "shmem_bfs_create")
+    return g
+
+
+def bfs_destroy(graph):
+    return _check(_L.shmem_bfs_destroy(graph), "shmem_bfs_destroy")
+
+
+def bfs(graph, root, dev_level=None, dev_parent=None):
+    st = BfsStats()
+    _check(_L.shmem_bfs(graph, int(root), _addr(dev_level), _addr(dev_parent), C.byref(st)), "shmem_bfs")
+    return {"nlevels": st.nlevels, "reached": st.reached, "edges_traversed": st.edges_traversed,
+            "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}

@@ -1,0 +1,153 @@
+// put / get / iput / iget kernels: stand-alone ops, the descriptor-table
+// executor and the bandwidth-sweep cell.
+#pragma once
+#include "../../include/mi_shmem.h"
+#include "shmemx.hpp"
+
+namespace shmemx {
+
+// One contiguous put or get: the whole grid is the initiator's team.
+__global__ __launch_bounds__(256) void k_copy(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n)
+{
+    copy(dst, src, n, (size_t)blockIdx.x * blockDim.x + threadIdx.x, (size_t)gridDim.x * blockDim.x);
+}
+
+// One strided iput or iget.
+__global__ __launch_bounds__(256) void k_strided(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src,
+                                                 int64_t ds, int64_t ss, size_t nelems, uint32_t eb)
+{
+    strided(dst, src, ds, ss, nelems, eb, (size_t)blockIdx.x * blockDim.x + threadIdx.x,
+            (size_t)gridDim.x * blockDim.x);
+}
+
+// ---------------------------------------------------------------------------
+// Descriptor-table executor (one persistent launch).  PE team p = workgroups
+// [p * wgs_per_pe, (p+1) * wgs_per_pe).  Every wave of a team walks the
+// window's descriptors (uniform loads) and picks its share of the team's ops:
+// small ops go round-robin to single waves (wave-cooperative put / get), ops
+// above BIG_OP bytes are done by all waves of the team together.  At a window
+// end every wave performs quiet and the teams meet in the world barrier.
+constexpr uint64_t BIG_OP = 64 * 1024;
+
+__device__ __forceinline__ bool desc_valid(const Ctx &c, const shmem_op_desc &d)
+{
+    if (d.pe >= (uint32_t)c.npes) return false;
+    if (d.kind == SHMEM_OP_PUT || d.kind == SHMEM_OP_GET)
+        return d.local_off <= c.seg && d.count <= c.seg - d.local_off && d.sym_off <= c.seg &&
+               d.count <= c.seg - d.sym_off;
+    if (d.kind == SHMEM_OP_IPUT || d.kind == SHMEM_OP_IGET) {
+        const uint32_t eb = d.elem_bytes;
+        if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return false;
+        if (d.local_stride < 1 || d.sym_stride < 1) return false;
+        if (d.local_off % eb || d.sym_off % eb) return false;
+        if (d.count == 0) return d.local_off <= c.seg && d.sym_off <= c.seg;
+        // spans, with overflow guarded by bounding each factor by the segment size
+        if (d.count > c.seg || (uint64_t)d.local_stride > c.seg || (uint64_t)d.sym_stride > c.seg) return false;
+        const unsigned __int128 ls = (unsigned __int128)(d.count - 1) * (uint64_t)d.local_stride * eb + eb;
+        const unsigned __int128 ss = (unsigned __int128)(d.count - 1) * (uint64_t)d.sym_stride * eb + eb;
+        return d.local_off <= c.seg && ls <= c.seg - d.local_off && d.sym_off <= c.seg && ss <= c.seg - d.sym_off;
+    }
+    return false;
+}
+
+__device__ __forceinline__ void desc_exec(const Ctx &c, const shmem_op_desc &d, size_t rank, size_t size)
+{
+    uint8_t *local = ptr(c, d.local_off, d.pe_self);
+    uint8_t *remote = ptr(c, d.sym_off, d.pe);
+    switch (d.kind) {
+    case SHMEM_OP_PUT: copy(remote, local, d.count, rank, size); break;
+    case SHMEM_OP_GET: copy(local, remote, d.count, rank, size); break;
+    case SHMEM_OP_IPUT: strided(remote, local, d.sym_stride, d.local_stride, d.count, d.elem_bytes, rank, size); break;
+    case SHMEM_OP_IGET: strided(local, remote, d.local_stride, d.sym_stride, d.count, d.elem_bytes, rank, size); break;
+    default: break;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_op_batch(Ctx c, const shmem_op_desc *__restrict__ ops, size_t n,
+                                                  size_t quiet_every, int wgs_per_pe)
+{
+    const uint32_t pe = blockIdx.x / (uint32_t)wgs_per_pe;
+    const uint32_t wg = blockIdx.x % (uint32_t)wgs_per_pe;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves_per_wg = blockDim.x >> 6;
+    const uint32_t team_waves = (uint32_t)wgs_per_pe * waves_per_wg;
+    const uint32_t my_wave = wg * waves_per_wg + wave;
+    const size_t window = quiet_every ? quiet_every : n;
+    for (size_t b = 0; b < n; b += window) {
+        const size_t e = b + window < n ? b + window : n;
+        uint32_t mine = 0;  // small ops of this PE seen so far in the window
+        for (size_t i = b; i < e; ++i) {
+            const shmem_op_desc d = ops[i];
+            if (d.pe_self != pe) {
+                if (d.pe_self >= (uint32_t)c.npes && blockIdx.x == 0 && threadIdx.x == 0) report(c, DEV_ERR_BAD_OP, i);
+                continue;
+            }
+            if (!desc_valid(c, d)) {
+                if (wg == 0 && threadIdx.x == 0) report(c, DEV_ERR_BAD_OP, i);
+                continue;
+            }
+            const uint64_t bytes = (d.kind <= SHMEM_OP_GET) ? d.count : d.count * d.elem_bytes;
+            if (bytes > BIG_OP) {
+                desc_exec(c, d, (size_t)my_wave * 64 + lane, (size_t)team_waves * 64);
+            } else {
+                if (mine % team_waves == my_wave) desc_exec(c, d, lane, 64);
+                ++mine;
+            }
+        }
+        barrier_all(c);  // quiet by every wave, then all teams synchronise
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Bandwidth-sweep cell.  All ops of a PE are independent, so the team's waves
+// share the flattened list of (op, chunk) tasks: a chunk is CHUNK_VECS 16-byte
+// vectors per lane (4 KiB per wave for contiguous ops, 1024 elements for
+// strided ones).  Neighbouring waves take neighbouring chunks, so a workgroup
+// streams 16 KiB of consecutive bytes per step.
+struct SweepArgs {
+    int kind;
+    uint64_t remote_off, local_off;
+    uint64_t count;
+    uint32_t elem_bytes;
+    int64_t remote_stride, local_stride;
+    uint64_t remote_slot, local_slot, nslots;
+    uint32_t ops_per_pe, wgs_per_pe;
+};
+
+constexpr uint64_t CHUNK_BYTES = 4096;  // per wave-task, contiguous ops
+constexpr uint64_t CHUNK_ELEMS = 1024;  // per wave-task, strided ops
+
+__global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
+{
+    const uint32_t pe = blockIdx.x / a.wgs_per_pe;
+    const uint32_t wg = blockIdx.x % a.wgs_per_pe;
+    const uint32_t peer = (pe + 1) % (uint32_t)c.npes;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves_per_wg = blockDim.x >> 6;
+    const uint64_t team_waves = (uint64_t)a.wgs_per_pe * waves_per_wg;
+    const uint64_t my_wave = (uint64_t)wg * waves_per_wg + wave;
+    const bool contiguous = a.kind <= SHMEM_OP_GET;
+    const uint64_t per_chunk = contiguous ? CHUNK_BYTES : CHUNK_ELEMS;
+    const uint64_t chunks = (a.count + per_chunk - 1) / per_chunk;
+    const uint64_t tasks = chunks * a.ops_per_pe;
+    uint8_t *const lbase = ptr(c, a.local_off, pe);
+    uint8_t *const rbase = ptr(c, a.remote_off, peer);
+    for (uint64_t t = my_wave; t < tasks; t += team_waves) {
+        const uint64_t op = t / chunks, ch = t - op * chunks;
+        const uint64_t slot = op % a.nslots;
+        uint8_t *l = lbase + slot * a.local_slot;
+        uint8_t *r = rbase + slot * a.remote_slot;
+        const uint64_t first = ch * per_chunk;
+        const uint64_t cnt = a.count - first < per_chunk ? a.count - first : per_chunk;
+        if (contiguous) {
+            if (a.kind == SHMEM_OP_PUT) copy(r + first, l + first, cnt, lane, 64);
+            else copy(l + first, r + first, cnt, lane, 64);
+        } else {
+            const uint64_t eb = a.elem_bytes;
+            uint8_t *lp = l + first * (uint64_t)a.local_stride * eb;
+            uint8_t *rp = r + first * (uint64_t)a.remote_stride * eb;
+            if (a.kind == SHMEM_OP_IPUT) strided(rp, lp, a.remote_stride, a.local_stride, cnt, a.elem_bytes, lane, 64);
+            else strided(lp, rp, a.local_stride, a.remote_stride, cnt, a.elem_bytes, lane, 64);
+        }
+    }
+}
+
+}  // namespace shmemx

@@ -1,0 +1,83 @@
+// Distributed open-addressing hash table: insert by compare-swap, lookup by get.
+#pragma once
+#include "../../include/mi_shmem.h"
+#include "shmemx.hpp"
+
+namespace shmemx {
+
+struct HashArgs {
+    uint64_t table_off;          // symmetric offset of the table
+    uint32_t slots;              // slots per PE
+    const uint64_t *keys;
+    uint64_t n, per_pe;          // keys in total / keys held per PE (block layout)
+    uint8_t *out;                // status (insert) or found flag (lookup)
+    uint32_t wgs_per_pe;
+};
+
+// SplitMix64 finaliser
+__device__ __forceinline__ uint64_t hash_mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// owner = h mod npes, home = (h / npes) mod slots; shifts and masks when the
+// divisors are powers of two (they are in the benchmark shapes)
+__device__ __forceinline__ void hash_place(const Ctx &c, uint32_t slots, uint64_t key, uint32_t *owner, uint32_t *home)
+{
+    const uint64_t h = hash_mix64(key);
+    const uint32_t np = (uint32_t)c.npes;
+    uint64_t q;
+    if ((np & (np - 1)) == 0) { *owner = (uint32_t)h & (np - 1); q = h >> __builtin_ctz(np); }
+    else { *owner = (uint32_t)(h % np); q = h / np; }
+    *home = (slots & (slots - 1)) == 0 ? (uint32_t)q & (slots - 1) : (uint32_t)(q % slots);
+}
+
+__global__ __launch_bounds__(256) void k_hash_insert(Ctx c, HashArgs g)
+{
+    const uint32_t pe_self = blockIdx.x / g.wgs_per_pe, wg = blockIdx.x % g.wgs_per_pe;
+    const uint64_t begin = (uint64_t)pe_self * g.per_pe;
+    const uint64_t end = begin + g.per_pe < g.n ? begin + g.per_pe : g.n;
+    for (uint64_t i = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i < end; i += (uint64_t)g.wgs_per_pe * blockDim.x) {
+        const uint64_t key = __builtin_nontemporal_load(g.keys + i);
+        if (key == 0) { report(c, DEV_ERR_BAD_OP, i); continue; }
+        uint32_t owner, slot;
+        hash_place(c, g.slots, key, &owner, &slot);
+        uint64_t *table = (uint64_t *)ptr(c, g.table_off, owner);
+        uint8_t st = SHMEM_HASH_FULL;
+        for (uint32_t j = 0; j < g.slots; ++j) {
+            // A non-zero word never changes again, so a plain read that shows one is
+            // final; only an empty-looking slot needs the compare-swap.
+            uint64_t seen = table[slot];
+            if (seen == 0) seen = atomic_compare_swap(&table[slot], 0, key);
+            if (seen == 0) { st = SHMEM_HASH_INSERTED; break; }
+            if (seen == key) { st = SHMEM_HASH_DUPLICATE; break; }
+            slot = slot + 1 == g.slots ? 0 : slot + 1;
+        }
+        if (g.out) g.out[i] = st;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_hash_lookup(Ctx c, HashArgs g)
+{
+    const uint32_t pe_self = blockIdx.x / g.wgs_per_pe, wg = blockIdx.x % g.wgs_per_pe;
+    const uint64_t begin = (uint64_t)pe_self * g.per_pe;
+    const uint64_t end = begin + g.per_pe < g.n ? begin + g.per_pe : g.n;
+    for (uint64_t i = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i < end; i += (uint64_t)g.wgs_per_pe * blockDim.x) {
+        const uint64_t key = __builtin_nontemporal_load(g.keys + i);
+        uint32_t owner, slot;
+        hash_place(c, g.slots, key, &owner, &slot);
+        const uint64_t *table = (const uint64_t *)ptr(c, g.table_off, owner);
+        uint8_t found = 0;
+        for (uint32_t j = 0; j < g.slots; ++j) {
+            const uint64_t seen = table[slot];           // an 8-byte get from the owner
+            if (seen == key) { found = 1; break; }
+            if (seen == 0) break;
+            slot = slot + 1 == g.slots ? 0 : slot + 1;
+        }
+        g.out[i] = found;
+    }
+}
+
+}  // namespace shmemx

@@ -1,0 +1,537 @@
+// mi_shmem: host side of the C ABI declared in include/mi_shmem.h plus the
+// gfx950 kernels it launches.  One translation unit; the kernels live in the
+// headers included below and are built from the primitives in shmemx.hpp.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/mi_shmem.h"
+#include "shmemx.hpp"
+#include "kernels_copy.hpp"
+#include "kernels_amo.hpp"
+#include "kernels_hash.hpp"
+#include "kernels_bfs.hpp"
+
+namespace {
+
+constexpr size_t GRAN = 256;       // allocator granularity / minimum alignment
+constexpr int WG_THREADS = 256;    // 4 wavefronts per workgroup
+
+struct Block { uint64_t off, len; };
+
+struct Host {
+    bool init = false;
+    int npes = 0;
+    size_t seg = 0;
+    uint8_t *heap = nullptr;
+    uint64_t *scratch = nullptr;
+    hipStream_t stream = nullptr;
+    int num_cus = 0;
+    std::vector<Block> free_list;  // address-ordered
+    std::vector<Block> live;
+    uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
+    std::mutex mu;
+} H;
+
+struct BfsGraph {
+    shmemx::BfsState st;
+    int wgs_per_pe;
+    void *allocs[8];
+    int nallocs;
+};
+
+inline shmemx::Ctx ctx() { return shmemx::Ctx{H.heap, (uint64_t)H.seg, H.scratch, H.npes}; }
+inline bool pe_ok(int pe) { return pe >= 0 && pe < H.npes; }
+
+// symmetric address -> offset; checks [off, off+span) lies inside a segment
+inline int sym_off(const void *sym, uint64_t span, uint64_t *off)
+{
+    const uint8_t *p = (const uint8_t *)sym;
+    if (!p || p < H.heap || p >= H.heap + H.seg) return SHMEM_ERR_OUT_OF_RANGE;
+    uint64_t o = (uint64_t)(p - H.heap);
+    if (span > H.seg - o) return SHMEM_ERR_OUT_OF_RANGE;
+    *off = o;
+    return SHMEM_OK;
+}
+
+// bytes spanned by nelems elements of eb bytes at a pitch of stride elements; false on overflow
+inline bool strided_span(size_t nelems, ptrdiff_t stride, size_t eb, uint64_t *span)
+{
+    if (nelems == 0) { *span = 0; return true; }
+    unsigned __int128 last = (unsigned __int128)(nelems - 1) * (unsigned __int128)(uint64_t)stride;
+    unsigned __int128 bytes = last * eb + eb;
+    if (bytes > (unsigned __int128)UINT64_MAX) return false;
+    *span = (uint64_t)bytes;
+    return true;
+}
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? SHMEM_OK : SHMEM_ERR_DEVICE; }
+inline int launched() { return hip_rc(hipGetLastError()); }
+
+// workgroups for a stand-alone copy of n bytes: 16 KiB per workgroup, capped at 8 per CU
+inline int wgs_for_bytes(size_t n)
+{
+    size_t w = (n + 16383) / 16384;
+    size_t cap = (size_t)std::max(1, H.num_cus) * 8;
+    return (int)std::max<size_t>(1, std::min(w, cap));
+}
+
+void free_insert(uint64_t off, uint64_t len)
+{
+    auto it = std::lower_bound(H.free_list.begin(), H.free_list.end(), off,
+                               [](const Block &b, uint64_t o) { return b.off < o; });
+    it = H.free_list.insert(it, Block{off, len});
+    auto nx = it + 1;
+    if (nx != H.free_list.end() && it->off + it->len == nx->off) { it->len += nx->len; it = H.free_list.erase(nx) - 1; }
+    if (it != H.free_list.begin()) {
+        auto pv = it - 1;
+        if (pv->off + pv->len == it->off) { pv->len += it->len; H.free_list.erase(it); }
+    }
+}
+
+// co-residency limit for kernels that contain an in-kernel barrier
+template <typename K>
+int max_resident_wgs(K kernel)
+{
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, WG_THREADS, 0) != hipSuccess) return 0;
+    return per_cu * H.num_cus;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *shmem_strerror(int status)
+{
+    switch (status) {
+    case SHMEM_OK: return "ok";
+    case SHMEM_ERR_NOT_INIT: return "library not initialised";
+    case SHMEM_ERR_ALREADY_INIT: return "library already initialised";
+    case SHMEM_ERR_INVALID_ARG: return "invalid argument";
+    case SHMEM_ERR_INVALID_PE: return "PE out of range";
+    case SHMEM_ERR_OUT_OF_RANGE: return "address or range outside the symmetric segment";
+    case SHMEM_ERR_ALIGN: return "misaligned address or size";
+    case SHMEM_ERR_NOMEM: return "symmetric heap exhausted";
+    case SHMEM_ERR_BAD_FREE: return "not an address returned by shmem_malloc / shmem_align";
+    case SHMEM_ERR_DEVICE: return "a HIP runtime call failed";
+    case SHMEM_ERR_DEVICE_FAULT: return "an operation was rejected on the device";
+    default: return "unknown status";
+    }
+}
+
+size_t shmem_scratch_bytes(int npes)
+{
+    if (npes < 1) return 0;
+    size_t words = shmemx::W_PE_BASE + (size_t)npes * shmemx::W_PE_WORDS;
+    return (words * 8 + 255) / 256 * 256;
+}
+
+int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scratch, void *hip_stream)
+{
+    std::lock_guard<std::mutex> g(H.mu);
+    if (H.init) return SHMEM_ERR_ALREADY_INIT;
+    if (npes < 1 || npes > 65536 || heap_bytes_per_pe == 0 || !dev_heap || !dev_scratch) return SHMEM_ERR_INVALID_ARG;
+    if (heap_bytes_per_pe % GRAN || (uintptr_t)dev_heap % GRAN || (uintptr_t)dev_scratch % GRAN) return SHMEM_ERR_ALIGN;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SHMEM_ERR_DEVICE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (hipMemsetAsync(dev_scratch, 0, shmem_scratch_bytes(npes), s) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return SHMEM_ERR_DEVICE;
+    uint64_t *pinned = nullptr;
+    if (hipHostMalloc((void **)&pinned, 4096, hipHostMallocDefault) != hipSuccess) return SHMEM_ERR_DEVICE;
+    H.npes = npes; H.seg = heap_bytes_per_pe; H.heap = (uint8_t *)dev_heap; H.scratch = (uint64_t *)dev_scratch;
+    H.stream = s; H.num_cus = prop.multiProcessorCount; H.pinned = pinned;
+    H.free_list.assign(1, Block{0, (uint64_t)heap_bytes_per_pe});
+    H.live.clear();
+    H.init = true;
+    return SHMEM_OK;
+}
+
+int shmem_finalize(void)
+{
+    std::lock_guard<std::mutex> g(H.mu);
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    hipError_t e = hipStreamSynchronize(H.stream);
+    if (H.pinned) (void)hipHostFree(H.pinned);
+    H.pinned = nullptr; H.init = false; H.npes = 0; H.heap = nullptr; H.scratch = nullptr;
+    H.free_list.clear(); H.live.clear();
+    return hip_rc(e);
+}
+
+int shmem_n_pes(void) { return H.init ? H.npes : 0; }
+
+void *shmem_align(size_t alignment, size_t nbytes)
+{
+    std::lock_guard<std::mutex> g(H.mu);
+    if (!H.init || nbytes == 0 || alignment == 0 || (alignment & (alignment - 1))) return nullptr;
+    // the alignment is that of the device address, on every PE's copy
+    if (alignment < GRAN) alignment = GRAN;
+    if (H.seg % alignment || nbytes > H.seg) return nullptr;
+    const uint64_t base = (uint64_t)(uintptr_t)H.heap;
+    uint64_t need = ((uint64_t)nbytes + GRAN - 1) / GRAN * GRAN;
+    for (size_t i = 0; i < H.free_list.size(); ++i) {
+        uint64_t b = H.free_list[i].off, e = b + H.free_list[i].len;
+        uint64_t a = (base + b + alignment - 1) / alignment * alignment - base;
+        if (a < b || a + need > e || a + need < a) continue;
+        H.free_list.erase(H.free_list.begin() + (ptrdiff_t)i);
+        if (a > b) free_insert(b, a - b);
+        if (a + need < e) free_insert(a + need, e - (a + need));
+        H.live.push_back(Block{a, need});
+        return H.heap + a;
+    }
+    return nullptr;
+}
+
+void *shmem_malloc(size_t nbytes) { return shmem_align(GRAN, nbytes); }
+
+int shmem_free(void *sym)
+{
+    std::lock_guard<std::mutex> g(H.mu);
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    const uint8_t *p = (const uint8_t *)sym;
+    if (!p || p < H.heap || p >= H.heap + H.seg) return SHMEM_ERR_BAD_FREE;
+    uint64_t off = (uint64_t)(p - H.heap);
+    for (size_t i = 0; i < H.live.size(); ++i)
+        if (H.live[i].off == off) {
+            uint64_t len = H.live[i].len;
+            H.live[i] = H.live.back(); H.live.pop_back();
+            free_insert(off, len);
+            return SHMEM_OK;
+        }
+    return SHMEM_ERR_BAD_FREE;
+}
+
+void *shmem_ptr(const void *sym, int pe)
+{
+    if (!H.init || !pe_ok(pe)) return nullptr;
+    const uint8_t *p = (const uint8_t *)sym;
+    if (!p || p < H.heap || p >= H.heap + H.seg) return nullptr;
+    return (void *)(p + (size_t)pe * H.seg);
+}
+
+// ---------------------------------------------------------------------------
+int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, int pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
+    uint64_t off;
+    if (int rc = sym_off(dst_sym, nbytes, &off)) return rc;
+    if (nbytes == 0) return SHMEM_OK;
+    if (!src_local) return SHMEM_ERR_INVALID_ARG;
+    uint8_t *dst = H.heap + (size_t)pe * H.seg + off;
+    hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(nbytes)), dim3(WG_THREADS), 0, H.stream, dst,
+                       (const uint8_t *)src_local, nbytes);
+    return launched();
+}
+
+int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, int pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
+    uint64_t off;
+    if (int rc = sym_off(src_sym, nbytes, &off)) return rc;
+    if (nbytes == 0) return SHMEM_OK;
+    if (!dst_local) return SHMEM_ERR_INVALID_ARG;
+    const uint8_t *src = H.heap + (size_t)pe * H.seg + off;
+    hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(nbytes)), dim3(WG_THREADS), 0, H.stream,
+                       (uint8_t *)dst_local, src, nbytes);
+    return launched();
+}
+
+static int strided_common(int pe_self, const void *sym, const void *local, ptrdiff_t sym_stride,
+                          ptrdiff_t local_stride, size_t nelems, size_t eb, int pe, uint64_t *off)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
+    if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return SHMEM_ERR_INVALID_ARG;
+    if (sym_stride < 1 || local_stride < 1) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)sym % eb || (uintptr_t)local % eb) return SHMEM_ERR_ALIGN;
+    uint64_t span;
+    if (!strided_span(nelems, sym_stride, eb, &span)) return SHMEM_ERR_OUT_OF_RANGE;
+    if (int rc = sym_off(sym, span, off)) return rc;
+    if (nelems && !local) return SHMEM_ERR_INVALID_ARG;
+    return SHMEM_OK;
+}
+
+int shmem_iput(int pe_self, void *dst_sym, const void *src_local, ptrdiff_t dst_stride, ptrdiff_t src_stride,
+               size_t nelems, size_t elem_bytes, int pe)
+{
+    uint64_t off;
+    if (int rc = strided_common(pe_self, dst_sym, src_local, dst_stride, src_stride, nelems, elem_bytes, pe, &off)) return rc;
+    if (nelems == 0) return SHMEM_OK;
+    uint8_t *dst = H.heap + (size_t)pe * H.seg + off;
+    hipLaunchKernelGGL(shmemx::k_strided, dim3(wgs_for_bytes(nelems * 16)), dim3(WG_THREADS), 0, H.stream, dst,
+                       (const uint8_t *)src_local, (int64_t)dst_stride, (int64_t)src_stride, nelems,
+                       (uint32_t)elem_bytes);
+    return launched();
+}
+
+int shmem_iget(int pe_self, void *dst_local, const void *src_sym, ptrdiff_t dst_stride, ptrdiff_t src_stride,
+               size_t nelems, size_t elem_bytes, int pe)
+{
+    uint64_t off;
+    if (int rc = strided_common(pe_self, src_sym, dst_local, src_stride, dst_stride, nelems, elem_bytes, pe, &off)) return rc;
+    if (nelems == 0) return SHMEM_OK;
+    const uint8_t *src = H.heap + (size_t)pe * H.seg + off;
+    hipLaunchKernelGGL(shmemx::k_strided, dim3(wgs_for_bytes(nelems * 16)), dim3(WG_THREADS), 0, H.stream,
+                       (uint8_t *)dst_local, src, (int64_t)dst_stride, (int64_t)src_stride, nelems,
+                       (uint32_t)elem_bytes);
+    return launched();
+}
+
+static int amo_single(int kind, int pe_self, uint64_t *sym, uint64_t a, uint64_t b, int pe, uint64_t *dev_result)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
+    if ((uintptr_t)sym % 8 || (uintptr_t)dev_result % 8) return SHMEM_ERR_ALIGN;
+    uint64_t off;
+    if (int rc = sym_off(sym, 8, &off)) return rc;
+    uint64_t *target = (uint64_t *)(H.heap + (size_t)pe * H.seg + off);
+    hipLaunchKernelGGL(shmemx::k_amo_single, dim3(1), dim3(64), 0, H.stream, kind, target, a, b, dev_result);
+    return launched();
+}
+
+int shmem_atomic_fetch_add(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result)
+{
+    return amo_single(SHMEM_AMO_FETCH_ADD, pe_self, dst_sym, value, 0, pe, dev_result);
+}
+int shmem_atomic_compare_swap(int pe_self, uint64_t *dst_sym, uint64_t cond, uint64_t value, int pe, uint64_t *dev_result)
+{
+    return amo_single(SHMEM_AMO_COMPARE_SWAP, pe_self, dst_sym, cond, value, pe, dev_result);
+}
+int shmem_atomic_fetch_or(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result)
+{
+    return amo_single(SHMEM_AMO_FETCH_OR, pe_self, dst_sym, value, 0, pe, dev_result);
+}
+
+int shmem_fence(int pe_self)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    return pe_ok(pe_self) ? SHMEM_OK : SHMEM_ERR_INVALID_PE;
+}
+int shmem_quiet(int pe_self)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    return (pe_self == -1 || pe_ok(pe_self)) ? SHMEM_OK : SHMEM_ERR_INVALID_PE;
+}
+int shmem_barrier_all(void) { return H.init ? SHMEM_OK : SHMEM_ERR_NOT_INIT; }
+
+int shmem_stream_sync(uint64_t *first_bad_index)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (hipMemcpyAsync(H.pinned, H.scratch, 16, hipMemcpyDeviceToHost, H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (H.pinned[0] == 0) return SHMEM_OK;
+    if (first_bad_index) *first_bad_index = H.pinned[1];
+    if (hipMemsetAsync(H.scratch, 0, 16, H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    return SHMEM_ERR_DEVICE_FAULT;
+}
+
+// ---------------------------------------------------------------------------
+int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (wgs_per_pe < 1 || (n && !dev_ops) || (uintptr_t)dev_ops % 8) return SHMEM_ERR_INVALID_ARG;
+    if (n == 0) return SHMEM_OK;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_op_batch)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    const shmem_op_desc *ops = (const shmem_op_desc *)dev_ops;
+    void *args[] = {&c, &ops, &n, &quiet_every, &wgs_per_pe};
+    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_op_batch, dim3((unsigned)grid),
+                                             dim3(WG_THREADS), args, 0, H.stream));
+}
+
+int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
+                     ptrdiff_t remote_stride, ptrdiff_t local_stride, size_t remote_slot_bytes,
+                     size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (kind < SHMEM_OP_PUT || kind > SHMEM_OP_IGET || wgs_per_pe < 1 || ops_per_pe < 0 || nslots < 1) return SHMEM_ERR_INVALID_ARG;
+    const bool is_strided = kind >= SHMEM_OP_IPUT;
+    uint64_t rspan = count, lspan = count;
+    if (is_strided) {
+        if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8) return SHMEM_ERR_INVALID_ARG;
+        if (remote_stride < 1 || local_stride < 1) return SHMEM_ERR_INVALID_ARG;
+        if ((uintptr_t)remote_sym % elem_bytes || (uintptr_t)local_sym % elem_bytes ||
+            remote_slot_bytes % elem_bytes || local_slot_bytes % elem_bytes) return SHMEM_ERR_ALIGN;
+        if (!strided_span(count, remote_stride, elem_bytes, &rspan) ||
+            !strided_span(count, local_stride, elem_bytes, &lspan)) return SHMEM_ERR_OUT_OF_RANGE;
+    } else {
+        elem_bytes = 1; remote_stride = local_stride = 1;
+    }
+    if (nslots > 1 && (rspan > remote_slot_bytes || lspan > local_slot_bytes)) return SHMEM_ERR_INVALID_ARG;
+    unsigned __int128 rtot = (unsigned __int128)(nslots - 1) * remote_slot_bytes + rspan;
+    unsigned __int128 ltot = (unsigned __int128)(nslots - 1) * local_slot_bytes + lspan;
+    if (rtot > H.seg || ltot > H.seg) return SHMEM_ERR_OUT_OF_RANGE;
+    uint64_t roff, loff;
+    if (int rc = sym_off(remote_sym, (uint64_t)rtot, &roff)) return rc;
+    if (int rc = sym_off(local_sym, (uint64_t)ltot, &loff)) return rc;
+    // the local and the remote window of one segment must not intersect (PE p's
+    // remote window is written/read by PE p-1 while p uses its local window)
+    if (roff < loff + (uint64_t)ltot && loff < roff + (uint64_t)rtot) return SHMEM_ERR_INVALID_ARG;
+    if (count == 0 || ops_per_pe == 0) return SHMEM_OK;
+    shmemx::SweepArgs a;
+    a.kind = kind; a.remote_off = roff; a.local_off = loff; a.count = count; a.elem_bytes = (uint32_t)elem_bytes;
+    a.remote_stride = remote_stride; a.local_stride = local_stride; a.remote_slot = remote_slot_bytes;
+    a.local_slot = local_slot_bytes; a.nslots = nslots; a.ops_per_pe = (uint32_t)ops_per_pe;
+    a.wgs_per_pe = (uint32_t)wgs_per_pe;
+    hipLaunchKernelGGL(shmemx::k_copy_sweep, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
+                       ctx(), a);
+    return launched();
+}
+
+int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe, const uint32_t *dev_idx,
+                    const uint64_t *dev_a, const uint64_t *dev_b, uint64_t *dev_old, size_t n,
+                    int wgs_per_pe, int aggregate)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (kind < SHMEM_AMO_FETCH_ADD || kind > SHMEM_AMO_MIN_CAS_LOOP || wgs_per_pe < 1 || T == 0) return SHMEM_ERR_INVALID_ARG;
+    if (T > H.seg / 8) return SHMEM_ERR_OUT_OF_RANGE;
+    if ((uintptr_t)ctr_sym % 8) return SHMEM_ERR_ALIGN;
+    uint64_t off;
+    if (int rc = sym_off(ctr_sym, (uint64_t)T * 8, &off)) return rc;
+    if (n == 0) return SHMEM_OK;
+    if (!dev_pe || !dev_idx || !dev_a || (kind == SHMEM_AMO_COMPARE_SWAP && !dev_b)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::AmoArgs a;
+    a.kind = kind; a.ctr_off = off; a.T = T; a.pe = dev_pe; a.idx = dev_idx; a.a = dev_a; a.b = dev_b;
+    a.old = dev_old; a.n = n; a.per_pe = (n + (size_t)H.npes - 1) / (size_t)H.npes; a.wgs_per_pe = (uint32_t)wgs_per_pe;
+    dim3 grid((unsigned)(H.npes * wgs_per_pe)), block(WG_THREADS);
+    // the combining kernel keys its LDS table by pe * T + idx in 32 bits
+    const bool agg = aggregate && kind != SHMEM_AMO_COMPARE_SWAP && (uint64_t)H.npes * T < 0xFFFFFFFFull;
+    if (agg) hipLaunchKernelGGL(shmemx::k_amo_batch_agg, grid, block, 0, H.stream, ctx(), a);
+    else hipLaunchKernelGGL(shmemx::k_amo_batch, grid, block, 0, H.stream, ctx(), a);
+    return launched();
+}
+
+static int hash_common(const uint64_t *table_sym, size_t slots, const uint64_t *keys, size_t n, int wgs, uint64_t *off)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (slots == 0 || wgs < 1 || slots > UINT32_MAX) return SHMEM_ERR_INVALID_ARG;
+    if (slots > H.seg / 8) return SHMEM_ERR_OUT_OF_RANGE;
+    if ((uintptr_t)table_sym % 8) return SHMEM_ERR_ALIGN;
+    if (int rc = sym_off(table_sym, (uint64_t)slots * 8, off)) return rc;
+    if (n && !keys) return SHMEM_ERR_INVALID_ARG;
+    return SHMEM_OK;
+}
+
+int shmem_hash_insert(uint64_t *table_sym, size_t slots_per_pe, const uint64_t *dev_keys, size_t n,
+                      uint8_t *dev_status, int wgs_per_pe)
+{
+    uint64_t off;
+    if (int rc = hash_common(table_sym, slots_per_pe, dev_keys, n, wgs_per_pe, &off)) return rc;
+    if (n == 0) return SHMEM_OK;
+    shmemx::HashArgs a{off, (uint32_t)slots_per_pe, dev_keys, n, (n + (size_t)H.npes - 1) / (size_t)H.npes,
+                       dev_status, (uint32_t)wgs_per_pe};
+    hipLaunchKernelGGL(shmemx::k_hash_insert, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
+                       ctx(), a);
+    return launched();
+}
+
+int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint64_t *dev_keys, size_t n,
+                      uint8_t *dev_found, int wgs_per_pe)
+{
+    uint64_t off;
+    if (int rc = hash_common(table_sym, slots_per_pe, dev_keys, n, wgs_per_pe, &off)) return rc;
+    if (n == 0) return SHMEM_OK;
+    if (!dev_found) return SHMEM_ERR_INVALID_ARG;
+    shmemx::HashArgs a{off, (uint32_t)slots_per_pe, dev_keys, n, (n + (size_t)H.npes - 1) / (size_t)H.npes,
+                       dev_found, (uint32_t)wgs_per_pe};
+    hipLaunchKernelGGL(shmemx::k_hash_lookup, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
+                       ctx(), a);
+    return launched();
+}
+
+// ---------------------------------------------------------------------------
+int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_t *dev_nbr, int wgs_per_pe,
+                     void **graph_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!graph_out || nverts == 0 || !dev_row_off || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    BfsGraph *g = new (std::nothrow) BfsGraph();
+    if (!g) return SHMEM_ERR_NOMEM;
+    const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
+    const uint64_t words = ((uint64_t)vpp + 63) / 64;
+    const size_t sizes[7] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+                             (size_t)vpp * 4, 256};
+    uint64_t offs[7];
+    g->nallocs = 0;
+    for (int i = 0; i < 7; ++i) {
+        void *p = shmem_malloc(sizes[i]);
+        if (!p) {
+            for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
+            delete g;
+            return SHMEM_ERR_NOMEM;
+        }
+        g->allocs[g->nallocs++] = p;
+        offs[i] = (uint64_t)((uint8_t *)p - H.heap);
+    }
+    shmemx::BfsState &s = g->st;
+    s.nverts = nverts; s.vpp = vpp; s.words = words;
+    s.shift = (vpp & (vpp - 1)) == 0 ? (int)__builtin_ctz(vpp) : -1;
+    s.row_off = dev_row_off; s.nbr = dev_nbr;
+    s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
+    s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.hub_off = offs[5]; s.tails_off = offs[6];
+    s.wgs_per_pe = (uint32_t)wgs_per_pe;
+    g->wgs_per_pe = wgs_per_pe;
+    *graph_out = g;
+    return SHMEM_OK;
+}
+
+int shmem_bfs_destroy(void *graph)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!graph) return SHMEM_ERR_INVALID_ARG;
+    BfsGraph *g = (BfsGraph *)graph;
+    int rc = SHMEM_OK;
+    for (int k = 0; k < g->nallocs; ++k) if (shmem_free(g->allocs[k]) != SHMEM_OK) rc = SHMEM_ERR_BAD_FREE;
+    delete g;
+    return rc;
+}
+
+int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!graph) return SHMEM_ERR_INVALID_ARG;
+    BfsGraph *g = (BfsGraph *)graph;
+    const shmemx::BfsState &s = g->st;
+    if (root >= s.nverts) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    dim3 grid((unsigned)(H.npes * g->wgs_per_pe)), block(WG_THREADS);
+    shmem_bfs_stats st;
+    memset(&st, 0, sizeof st);
+    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
+    uint64_t *counts = H.pinned + 16;       // [0] frontier total of the next level, [1] degree sum so far
+    st.frontier_size[0] = 1;
+    uint32_t L = 0;
+    for (;;) {
+        hipLaunchKernelGGL(shmemx::k_bfs_expand, grid, block, 0, H.stream, c, s, L);
+        hipLaunchKernelGGL(shmemx::k_bfs_hubs, grid, block, 0, H.stream, c, s, L);
+        hipLaunchKernelGGL(shmemx::k_bfs_count, dim3(1), dim3(64), 0, H.stream, c, s, L + 1);
+        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 16, hipMemcpyDeviceToHost, H.stream) != hipSuccess)
+            return SHMEM_ERR_DEVICE;
+        if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+        ++L;
+        if (counts[0] == 0) break;
+        if (L >= 64) return SHMEM_ERR_INVALID_ARG;
+        st.frontier_size[L] = counts[0];
+    }
+    st.nlevels = L;
+    for (uint32_t l = 0; l < L; ++l) st.reached += st.frontier_size[l];
+    st.edges_traversed = counts[1] / 2;
+    if (dev_level || dev_parent) {
+        hipLaunchKernelGGL(shmemx::k_bfs_gather, grid, block, 0, H.stream, c, s, dev_level, dev_parent);
+        if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    }
+    if (stats) *stats = st;
+    return launched();
+}
+
+}  // extern "C"

@@ -1,0 +1,234 @@
+// Device-side one-sided primitives for gfx950 (wave64).  Every call takes a
+// cooperation scope -- the (rank, size) of the calling lane among the lanes
+// that perform the operation together (one lane, a wavefront, a workgroup or a
+// whole PE team) -- mirroring the `coop` argument of the paper's device API
+// (Listing 1; Sec. I "cooperation models").
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace shmemx {
+
+// Kernel-argument view of the symmetric heap.
+struct Ctx {
+    uint8_t *heap;      // PE 0's segment
+    uint64_t seg;       // bytes per PE segment
+    uint64_t *scratch;  // library scratch words (layout below)
+    int npes;
+};
+
+// Scratch layout in 64-bit words.  Words that are spun on or hammered by
+// atomics sit alone on a 128-byte line.
+enum : uint32_t {
+    W_ERR_FLAG = 0,     // 0 = no device fault, else a DEV_ERR_* code
+    W_ERR_INDEX = 1,    // index of the first rejected op
+    W_BAR_COUNT = 16,   // world barrier: arrivals
+    W_BAR_GEN = 32,     // world barrier: generation
+    W_WORK = 48,        // 16 general-purpose counters (BFS edge sum, ...)
+    W_PE_BASE = 64,     // per PE: 32 words; +0 team arrivals, +16 team generation
+    W_PE_WORDS = 32
+};
+enum : uint64_t { DEV_ERR_BAD_OP = 1, DEV_ERR_BARRIER_TIMEOUT = 2, DEV_ERR_BAD_TARGET = 3 };
+
+#define SHMEMX_AGENT __HIP_MEMORY_SCOPE_AGENT
+
+__device__ __forceinline__ uint8_t *ptr(const Ctx &c, uint64_t off, uint32_t pe)
+{
+    return c.heap + (uint64_t)pe * c.seg + off;
+}
+
+__device__ __forceinline__ void report(const Ctx &c, uint64_t code, uint64_t index)
+{
+    unsigned long long expect = 0;
+    if (__hip_atomic_compare_exchange_strong((unsigned long long *)&c.scratch[W_ERR_FLAG], &expect,
+                                             (unsigned long long)code, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             SHMEMX_AGENT))
+        __hip_atomic_store(&c.scratch[W_ERR_INDEX], index, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
+
+// ---------------------------------------------------------------------------
+// Atomic memory operations (Table II "memory atomics"): agent scope, so that
+// workgroups on different XCDs (separate L2s) resolve them at one point.
+__device__ __forceinline__ uint64_t atomic_fetch_add(uint64_t *p, uint64_t v)
+{
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
+__device__ __forceinline__ uint64_t atomic_fetch_or(uint64_t *p, uint64_t v)
+{
+    return __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
+__device__ __forceinline__ uint64_t atomic_compare_swap(uint64_t *p, uint64_t cond, uint64_t v)
+{
+    __hip_atomic_compare_exchange_strong(p, &cond, v, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    return cond;  // the previous value, whether or not the swap happened
+}
+__device__ __forceinline__ uint64_t atomic_fetch(const uint64_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
+
+// ---------------------------------------------------------------------------
+// Ordering.  quiet: the calling wave's earlier puts / AMOs are complete and
+// visible device-wide (wait for outstanding stores, write this XCD's L2 back).
+// fence: earlier puts ordered before later ones; on one GPU that is the same
+// release, so both map to it.  acquire: drop stale lines before reading what
+// another PE put (needed after a barrier or after seeing a signal).
+__device__ __forceinline__ void quiet() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+
+// Sense-reversing barrier over `nwg` workgroups that share (count, gen).
+// Implies quiet before and acquire after.  Every participating workgroup must
+// be resident (the host checks the grid against the occupancy limit and uses
+// a cooperative launch).  The wait is bounded: on time-out the fault word is
+// set and the caller continues, so the grid always drains.
+__device__ __forceinline__ void barrier(const Ctx &c, uint64_t *count, uint64_t *gen, uint32_t nwg)
+{
+    quiet();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        uint64_t a = __hip_atomic_fetch_add(count, 1ull, __ATOMIC_ACQ_REL, SHMEMX_AGENT);
+        if (a == nwg - 1) {
+            __hip_atomic_store(count, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            __hip_atomic_store(gen, g + 1, __ATOMIC_RELEASE, SHMEMX_AGENT);
+        } else {
+            uint32_t spins = 0;
+            while (__hip_atomic_load(gen, __ATOMIC_ACQUIRE, SHMEMX_AGENT) == g) {
+                __builtin_amdgcn_s_sleep(4);
+                if (++spins > (1u << 24)) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); break; }
+            }
+        }
+    }
+    __syncthreads();
+    acquire();
+}
+__device__ __forceinline__ void barrier_all(const Ctx &c)
+{
+    barrier(c, &c.scratch[W_BAR_COUNT], &c.scratch[W_BAR_GEN], gridDim.x);
+}
+__device__ __forceinline__ void team_barrier(const Ctx &c, uint32_t pe, uint32_t wgs_per_pe)
+{
+    uint64_t *w = &c.scratch[W_PE_BASE + pe * W_PE_WORDS];
+    barrier(c, w, w + 16, wgs_per_pe);
+}
+
+// ---------------------------------------------------------------------------
+// Contiguous copy by `size` cooperating lanes (rank in [0, size)).  Lane r
+// moves 16-byte vectors r, r+size, ... so that a wavefront's access covers
+// 1 KiB of consecutive bytes; four loads are in flight per lane before the
+// first store.  The widest unit the two addresses share (16/8/4/1 bytes) is
+// used; head and tail bytes are peeled.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename V>
+__device__ __forceinline__ void copy_units(V *__restrict__ d, const V *__restrict__ s, size_t nv,
+                                           size_t rank, size_t size)
+{
+    size_t i = rank;
+    for (; i + 3 * size < nv; i += 4 * size) {
+        V a = __builtin_nontemporal_load(s + i);
+        V b = __builtin_nontemporal_load(s + i + size);
+        V e = __builtin_nontemporal_load(s + i + 2 * size);
+        V f = __builtin_nontemporal_load(s + i + 3 * size);
+        __builtin_nontemporal_store(a, d + i);
+        __builtin_nontemporal_store(b, d + i + size);
+        __builtin_nontemporal_store(e, d + i + 2 * size);
+        __builtin_nontemporal_store(f, d + i + 3 * size);
+    }
+    for (; i < nv; i += size) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+}
+
+__device__ __forceinline__ void copy(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n,
+                                     size_t rank, size_t size)
+{
+    if (n == 0) return;
+    const uintptr_t diff = (uintptr_t)dst ^ (uintptr_t)src;
+    const size_t unit = (diff & 15) == 0 ? 16 : (diff & 7) == 0 ? 8 : (diff & 3) == 0 ? 4 : 1;
+    size_t head = (size_t)(-(uintptr_t)dst) & (unit - 1);
+    if (head > n) head = n;
+    for (size_t j = rank; j < head; j += size) dst[j] = src[j];
+    const size_t body = (n - head) / unit;
+    uint8_t *d = dst + head;
+    const uint8_t *s = src + head;
+    if (unit == 16) copy_units((u32x4 *)d, (const u32x4 *)s, body, rank, size);
+    else if (unit == 8) copy_units((u32x2 *)d, (const u32x2 *)s, body, rank, size);
+    else if (unit == 4) copy_units((uint32_t *)d, (const uint32_t *)s, body, rank, size);
+    else copy_units(d, s, body, rank, size);
+    for (size_t j = head + body * unit + rank; j < n; j += size) dst[j] = src[j];
+}
+
+// put / get are the same copy with the remote side as destination / source
+// (Sec. III-A one-sided semantics; Table II put_nbi / get).
+__device__ __forceinline__ void put(const Ctx &c, uint64_t dst_off, const uint8_t *src, size_t n, uint32_t pe,
+                                    size_t rank, size_t size)
+{
+    copy(ptr(c, dst_off, pe), src, n, rank, size);
+}
+__device__ __forceinline__ void get(const Ctx &c, uint8_t *dst, uint64_t src_off, size_t n, uint32_t pe,
+                                    size_t rank, size_t size)
+{
+    copy(dst, ptr(c, src_off, pe), n, rank, size);
+}
+
+// ---------------------------------------------------------------------------
+// Strided copy: d[i * ds] = s[i * ss], i < nelems, strides in elements.
+// When one side is unit-stride and 16-byte aligned, a lane moves 16 / sizeof(T)
+// consecutive elements so that side uses full 16-byte vectors.
+template <typename T>
+__device__ __forceinline__ void strided_t(T *__restrict__ d, const T *__restrict__ s, int64_t ds, int64_t ss,
+                                          size_t nelems, size_t rank, size_t size)
+{
+    constexpr size_t VE = 16 / sizeof(T);
+    typedef T vec_t __attribute__((ext_vector_type(VE)));
+    if (VE > 1 && ds == 1 && ((uintptr_t)d & 15) == 0) {           // gather into vectors
+        const size_t ng = nelems / VE;
+        for (size_t g = rank; g < ng; g += size) {
+            vec_t v;
+#pragma unroll
+            for (size_t k = 0; k < VE; ++k) v[k] = __builtin_nontemporal_load(s + (g * VE + k) * ss);
+            __builtin_nontemporal_store(v, (vec_t *)d + g);
+        }
+        for (size_t i = ng * VE + rank; i < nelems; i += size) d[i] = s[i * ss];
+    } else if (VE > 1 && ss == 1 && ((uintptr_t)s & 15) == 0) {    // scatter from vectors
+        const size_t ng = nelems / VE;
+        for (size_t g = rank; g < ng; g += size) {
+            vec_t v = __builtin_nontemporal_load((const vec_t *)s + g);
+#pragma unroll
+            for (size_t k = 0; k < VE; ++k) __builtin_nontemporal_store((T)v[k], d + (g * VE + k) * ds);
+        }
+        for (size_t i = ng * VE + rank; i < nelems; i += size) d[i * ds] = s[i];
+    } else {
+        for (size_t i = rank; i < nelems; i += size) d[i * ds] = s[i * ss];
+    }
+}
+
+__device__ __forceinline__ void strided(uint8_t *d, const uint8_t *s, int64_t ds, int64_t ss, size_t nelems,
+                                        uint32_t elem_bytes, size_t rank, size_t size)
+{
+    switch (elem_bytes) {
+    case 8: strided_t((uint64_t *)d, (const uint64_t *)s, ds, ss, nelems, rank, size); break;
+    case 4: strided_t((uint32_t *)d, (const uint32_t *)s, ds, ss, nelems, rank, size); break;
+    case 2: strided_t((uint16_t *)d, (const uint16_t *)s, ds, ss, nelems, rank, size); break;
+    default: strided_t(d, s, ds, ss, nelems, rank, size); break;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront helpers (64 lanes).
+__device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
+__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
+__device__ __forceinline__ uint32_t rank_in(uint64_t mask)  // set bits of mask below this lane
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+__device__ __forceinline__ uint32_t bcast32(uint32_t v, uint32_t lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ uint64_t bcast64(uint64_t v, uint32_t lane)
+{
+    uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
+    uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(v >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+}  // namespace shmemx

@@ -1,0 +1,266 @@
+"""GPU parity for the atomic path, the hash table and BFS.
+
+Where several results are correct (fetched values, compare-swap winners, slot
+placement, BFS parents) the unique part is compared bit-exact with the oracle
+and the rest is checked for validity."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workgen
+
+pytestmark = pytest.mark.gpu
+
+sh = pytest.importorskip("paper_2511_15076_amd")
+from gpu_util import as_np, heaps_of, shmem_world, to_dev  # noqa: E402
+
+
+def counters_of(heap, npes, off, T):
+    h = heaps_of(heap, npes)
+    return np.stack([h[p][off:off + 8 * T].view(np.uint64) for p in range(npes)])
+
+
+def run_amo(kind, npes, T, pe, idx, a, b, wgs, agg, hb):
+    n = len(pe)
+    with shmem_world(npes, hb) as (heap, base):
+        ctr = sh.malloc(T * 8)
+        d_pe, d_idx, d_a = to_dev(pe), to_dev(idx), to_dev(a)
+        d_b = to_dev(b) if b is not None else None
+        d_old = torch.zeros(n, dtype=torch.int64, device="cuda:0")
+        sh.amo_batch(kind, ctr, T, d_pe, d_idx, d_a, d_b, d_old, n, wgs, agg)
+        sh.stream_sync()
+        return counters_of(heap, npes, ctr - base, T), as_np(d_old, np.uint64).copy(), ctr - base
+
+
+def check_prefix_sums(pe, idx, a, old, T):
+    key = pe.astype(np.int64) * T + idx
+    order = np.lexsort((old, key))
+    k, f, aa = key[order], old[order], a[order]
+    first = np.r_[True, k[1:] != k[:-1]]
+    assert (f[first] == 0).all()
+    same = ~first[1:]
+    assert np.array_equal(f[1:][same], (f[:-1] + aa[:-1])[same])
+
+
+@pytest.mark.parametrize("agg", [0, 1])
+@pytest.mark.parametrize("dist,T,npes", [("uniform", 1, 64), ("zipf", 1024, 64), ("uniform", 4096, 16),
+                                         ("zipf", 37, 5)])
+def test_fetch_add_batch(agg, dist, T, npes):
+    n = 200000 + 77                                      # several passes and a ragged tail
+    hb = max(1 << 16, ((T * 8 + 255) // 256 + 1) * 256)
+    for addend in ("one", "rand16"):
+        pe, idx, a = workgen.cfg3_amo_ops(n=n, npes=npes, T=T, dist=dist, addend=addend)
+        final, old, off = run_amo(sh.AMO_FETCH_ADD, npes, T, pe, idx, a, None, 3, agg, hb)
+        w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+        assert w.malloc(T * 8) == off
+        oold = w.amo_batch(oracle.AMO_FETCH_ADD, off, pe, idx, a)
+        ofinal = np.stack([w.heap(p)[off:off + 8 * T].view(np.uint64) for p in range(npes)])
+        assert np.array_equal(final, ofinal)
+        check_prefix_sums(pe, idx, a, old, T)            # a permutation of prefix sums
+        if addend == "one":                              # per counter the same multiset as the oracle
+            key = pe.astype(np.int64) * T + idx
+            assert np.array_equal(old[np.lexsort((old, key))], oold[np.lexsort((oold, key))])
+
+
+@pytest.mark.parametrize("agg", [0, 1])
+def test_fetch_or_and_min_loop_batch(agg):
+    npes, T, n = 16, 64, 150001
+    hb = 1 << 16
+    pe, idx, tag = workgen.cfg3_amo_ops(n=n, npes=npes, T=T, dist="zipf", addend="tag")
+    bits = (np.uint64(1) << (tag % np.uint64(64))).astype(np.uint64)
+    final, old, off = run_amo(sh.AMO_FETCH_OR, npes, T, pe, idx, bits, None, 2, agg, hb)
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    assert w.malloc(T * 8) == off
+    w.amo_batch(oracle.AMO_FETCH_OR, off, pe, idx, bits)
+    assert np.array_equal(final, np.stack([w.heap(p)[off:off + 8 * T].view(np.uint64) for p in range(npes)]))
+    # exactly one op per (word, bit) saw the bit clear
+    clear = (old & bits) == 0
+    key = (pe.astype(np.int64) * T + idx) * 64 + (tag % np.uint64(64)).astype(np.int64)
+    assert len(np.unique(key[clear])) == int(clear.sum()) == len(np.unique(key))
+    # min through a compare-swap loop: closed form min per word
+    tag = np.random.default_rng(2).permutation(tag)
+    final, _, off = run_amo(sh.AMO_MIN_CAS_LOOP, npes, T, pe, idx, tag, None, 2, agg, hb)
+    w2 = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    assert w2.malloc(T * 8) == off
+    w2.amo_batch(oracle.AMO_MIN_CAS_LOOP, off, pe, idx, tag)
+    assert np.array_equal(final, np.stack([w2.heap(p)[off:off + 8 * T].view(np.uint64) for p in range(npes)]))
+
+
+@pytest.mark.parametrize("dist,T", [("uniform", 1), ("zipf", 1024)])
+def test_compare_swap_claim_batch(dist, T):
+    npes, n, hb = 64, 120000, 1 << 16
+    pe, idx, tag = workgen.cfg3_amo_ops(n=n, npes=npes, T=T, dist=dist, addend="tag")
+    zeros = np.zeros(n, dtype=np.uint64)
+    final, old, off = run_amo(sh.AMO_COMPARE_SWAP, npes, T, pe, idx, zeros, tag, 2, 0, hb)
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    assert w.malloc(T * 8) == off
+    w.amo_batch(oracle.AMO_COMPARE_SWAP, off, pe, idx, zeros, tag)
+    ofinal = np.stack([w.heap(p)[off:off + 8 * T].view(np.uint64) for p in range(npes)])
+    assert np.array_equal(final != 0, ofinal != 0)       # the set of claimed slots is unique
+    key = pe.astype(np.int64) * T + idx
+    winners = old == 0
+    assert int(winners.sum()) == len(np.unique(key)) == int((final != 0).sum())
+    assert len(np.unique(key[winners])) == int(winners.sum())   # one winner per slot
+    flat = final.reshape(-1)
+    assert np.array_equal(flat[key[winners]], tag[winners])     # the slot holds its winner's tag
+    assert np.array_equal(old[~winners], flat[key[~winners]])   # losers saw the final value
+
+
+def test_compare_swap_outcomes_are_linearisable():
+    # tiny programs: every outcome the GPU produces must be reachable by some
+    # serial order of the same ops (brute force over all orders)
+    rng = np.random.default_rng(8)
+    npes, hb = 3, 4096
+    for trial in range(12):
+        n = int(rng.integers(2, 7))
+        slot = rng.integers(0, 2, n)
+        cond = rng.integers(0, 3, n).astype(np.uint64)
+        val = rng.integers(1, 4, n).astype(np.uint64)
+        allowed = set()
+        for order in itertools.permutations(range(n)):
+            mem, seen = [0, 0], [0] * n
+            for i in order:
+                seen[i] = mem[slot[i]]
+                if mem[slot[i]] == cond[i]:
+                    mem[slot[i]] = int(val[i])
+            allowed.add((tuple(mem), tuple(seen)))
+        pe = np.full(n, 2, dtype=np.int32)               # all target PE 2; issuers spread over the PEs
+        for rep in range(4):
+            final, old, off = run_amo(sh.AMO_COMPARE_SWAP, npes, 2, pe, slot.astype(np.uint32), cond, val,
+                                      1, 0, hb)
+            got = (tuple(int(x) for x in final[2]), tuple(int(x) for x in old))
+            assert got in allowed, (trial, got)
+
+
+def test_single_amos():
+    npes, hb = 4, 4096
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    with shmem_world(npes, hb) as (heap, base):
+        res = torch.zeros(8, dtype=torch.int64, device="cuda:0")
+        sh.atomic_fetch_add(0, base + 64, 2**64 - 3, 1, res[0:])
+        sh.atomic_fetch_add(2, base + 64, 5, 1, res[1:])
+        sh.atomic_compare_swap(3, base + 72, 0, 9, 1, res[2:])
+        sh.atomic_compare_swap(3, base + 72, 0, 11, 1, res[3:])
+        sh.atomic_compare_swap(0, base + 72, 9, 11, 1, res[4:])
+        sh.atomic_fetch_or(1, base + 80, 5, 3, res[5:])
+        sh.atomic_fetch_or(1, base + 80, 6, 3, None)
+        sh.stream_sync()
+        exp = [w.atomic_fetch_add(0, 64, 2**64 - 3, 1), w.atomic_fetch_add(2, 64, 5, 1),
+               w.atomic_compare_swap(3, 72, 0, 9, 1), w.atomic_compare_swap(3, 72, 0, 11, 1),
+               w.atomic_compare_swap(0, 72, 9, 11, 1), w.atomic_fetch_or(1, 80, 5, 3)]
+        w.atomic_fetch_or(1, 80, 6, 3)
+        assert [int(x) for x in as_np(res, np.uint64)[:6]] == exp
+        assert np.array_equal(heaps_of(heap, npes), w.heaps())
+
+
+# ------------------------------------------------------------------ hash
+@pytest.mark.parametrize("npes,slots,n", [(16, 1 << 12, 30000), (5, 3001, 7000), (16, 64, 1200)])
+def test_hash_insert_lookup(npes, slots, n):
+    keys = workgen.cfg4_keys(n=n)
+    keys = np.concatenate([keys, keys[: n // 8]])        # duplicates; the last shape overfills
+    queries = workgen.cfg4_queries(keys, n=2 * n + 3)
+    hb = ((slots * 8 + 255) // 256 + 2) * 256
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    tab = w.malloc(slots * 8)
+    ost = w.hash_insert(tab, slots, keys)
+    ofound = w.hash_lookup(tab, slots, queries)
+    otab = np.stack([w.heap(p)[tab:tab + 8 * slots].view(np.uint64) for p in range(npes)])
+    with shmem_world(npes, hb) as (heap, base):
+        t = sh.malloc(slots * 8)
+        assert t - base == tab
+        dk, dq = to_dev(keys), to_dev(queries)
+        dst = torch.full((len(keys),), 255, dtype=torch.uint8, device="cuda:0")
+        dfo = torch.full((len(queries),), 255, dtype=torch.uint8, device="cuda:0")
+        sh.hash_insert(t, slots, dk, len(keys), dst, 3)
+        sh.hash_lookup(t, slots, dq, len(queries), dfo, 2)
+        sh.stream_sync()
+        gtab = counters_of(heap, npes, tab, slots)
+        st, found = as_np(dst, np.uint8), as_np(dfo, np.uint8)
+    full = (ost == oracle.HASH_FULL).any()
+    if not full:
+        assert np.array_equal(gtab != 0, otab != 0)      # occupancy does not depend on the order
+        for p in range(npes):
+            assert np.array_equal(np.sort(gtab[p]), np.sort(otab[p]))
+        assert np.array_equal(found, ofound)
+        for code in (0, 1, 2):
+            assert int((st == code).sum()) == int((ost == code).sum())
+        # per key value: inserted exactly once, every other copy reported as duplicate
+        order = np.argsort(keys, kind="stable")
+        ks, ss = keys[order], st[order]
+        firsts = np.r_[True, ks[1:] != ks[:-1]]
+        ins_per_key = np.add.reduceat((ss == 0).astype(np.int64), np.flatnonzero(firsts))
+        assert (ins_per_key == 1).all()
+    else:
+        # an overfull table: which keys fit depends on the order; check validity instead
+        stored = gtab[gtab != 0]
+        assert len(stored) == len(set(stored.tolist()))
+        inserted = set(keys[st == 0].tolist())
+        assert set(stored.tolist()) == inserted
+        assert (st == 2).any()
+        truth = np.array([int(q) in inserted for q in queries])
+        assert np.array_equal(found.astype(bool), truth)
+    # every stored key is reachable from its home slot before an empty one
+    for p in range(npes):
+        for s in np.flatnonzero(gtab[p])[:400]:
+            h = oracle.mix64(int(gtab[p, s]))
+            assert h % npes == p
+            j = (h // npes) % slots
+            while j != s:
+                assert gtab[p, j] != 0
+                j = (j + 1) % slots
+
+
+# ------------------------------------------------------------------ BFS
+def check_tree(row, nbr, root, level, parent):
+    reached = level >= 0
+    assert parent[root] == root
+    assert ((parent == sh.BFS_NONE) == ~reached).all()
+    vs = np.flatnonzero(reached)
+    vs = vs[vs != root]
+    us = parent[vs].astype(np.int64)
+    assert (level[us] == level[vs] - 1).all()
+    for v, u in zip(vs[:3000], us[:3000]):                # the tree edge exists
+        assert v in nbr[row[u]:row[u + 1]]
+
+
+def run_bfs_case(row, nbr, roots, npes, wgs):
+    n = len(row) - 1
+    vpp = -(-n // npes)
+    hb = ((vpp * 24 + vpp // 8 + 16 * 256 + 255) // 256) * 256
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 1)
+    with shmem_world(npes, hb) as (heap, base):
+        drow, dnbr = to_dev(row), to_dev(nbr)
+        g = sh.bfs_create(n, drow, dnbr, wgs)
+        dl = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        dp = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        for root in roots:
+            stats = sh.bfs(g, int(root), dl, dp)
+            sh.stream_sync()
+            level, parent = as_np(dl, np.int32).copy(), as_np(dp, np.uint32).copy()
+            olevel, oparent, ostats = w.bfs(row, nbr, int(root))
+            assert np.array_equal(level, olevel)          # levels are unique
+            assert stats == ostats                        # sizes per level, reached, traversed edges
+            check_tree(row, nbr, int(root), level, parent)
+        sh.bfs_destroy(g)
+        assert sh.malloc(hb) == base                      # everything was returned to the heap
+
+
+@pytest.mark.parametrize("scale,npes,wgs", [(10, 16, 1), (14, 16, 4), (13, 3, 2), (16, 16, 8)])
+def test_bfs_rmat(scale, npes, wgs):
+    row, nbr = workgen.rmat_csr(scale)
+    roots = workgen.bfs_roots(row, 3)
+    run_bfs_case(row, nbr, roots, npes, wgs)
+
+
+def test_bfs_tiny_and_hub_graphs():
+    # a path, an isolated pair, and a star whose centre has more neighbours than
+    # the long-row threshold (exercises the team-wide expansion)
+    hub_deg = 5000
+    src = np.r_[np.arange(0, 9), [20], np.full(hub_deg, 30)].astype(np.uint32)
+    dst = np.r_[np.arange(1, 10), [21], np.arange(31, 31 + hub_deg)].astype(np.uint32)
+    n = 31 + hub_deg + 5
+    row, nbr = workgen.csr_from_edges(n, src, dst)
+    run_bfs_case(row, nbr, [0, 9, 20, 30, 31, 4000, n - 1], 4, 2)

@@ -1,0 +1,223 @@
+"""GPU parity, bit-exact: put / get / iput / iget, the descriptor-table
+executor (configuration 1 at full size) and the bandwidth-sweep cell
+(configuration 2's op shapes at sizes that span several chunks and a ragged
+tail), against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workgen
+
+pytestmark = pytest.mark.gpu
+
+sh = pytest.importorskip("paper_2511_15076_amd")
+from gpu_util import heaps_of, shmem_world, to_dev  # noqa: E402
+
+
+def seeded_heaps(npes, hb, seed):
+    return np.stack([workgen.random_words(seed + p, hb // 8).view(np.uint8) for p in range(npes)])
+
+
+def oracle_world(init, seed=3):
+    npes, hb = init.shape
+    w = oracle.World(npes, hb, oracle.SHUFFLED, seed)
+    for p in range(npes):
+        w.heap(p)[:] = init[p]
+    return w
+
+
+@pytest.mark.parametrize("wgs", [1, 3])
+def test_config1_full_table(wgs):
+    npes, hb = 4, 1 << 20
+    ops = workgen.cfg1_op_table()                       # 10,000 ops, batches of 100
+    init = seeded_heaps(npes, hb, workgen.BASE_SEED + 100)
+    w = oracle_world(init)
+    assert w.op_batch(ops, 100) == 0
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        dops = to_dev(ops)
+        sh.op_batch(dops, len(ops), 100, wgs)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+
+
+def test_table_with_strided_and_large_ops_and_device_fault():
+    npes, hb = 3, 1 << 20
+    init = seeded_heaps(npes, hb, 555)
+    ops = np.zeros(7, dtype=workgen.OP_DESC)
+    # disjoint regions by construction
+    ops[0] = (workgen.OP_PUT, 0, 1, 1, 0, 0, 200000, 1, 1, 0)            # large: whole team
+    ops[1] = (workgen.OP_IPUT, 1, 2, 4, 300000, 300000, 5000, 3, 5, 0)   # local stride 3, remote 5
+    ops[2] = (workgen.OP_IGET, 2, 0, 8, 500000, 600000, 700, 2, 7, 0)
+    ops[3] = (workgen.OP_GET, 0, 2, 1, 800003, 900001, 1237, 1, 1, 0)    # byte-granular, odd alignment
+    ops[4] = (workgen.OP_PUT, 1, 1, 1, 8, 950000, 0, 1, 1, 0)            # zero bytes
+    ops[5] = (workgen.OP_PUT, 2, 7, 1, 0, 0, 8, 1, 1, 0)                 # bad remote PE -> rejected
+    ops[6] = (workgen.OP_IPUT, 0, 1, 2, 1000000, 1000000, 100, 9, 1, 0)
+    w = oracle_world(init)
+    assert w.op_batch(ops, 0) == -4                     # the oracle rejects op 5 too, the rest is done
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.op_batch(to_dev(ops), len(ops), 0, 2)
+        with pytest.raises(sh.ShmemError) as e:
+            sh.stream_sync()
+        assert e.value.status == sh.ERR_DEVICE_FAULT and e.value.first_bad_index == 5
+        sh.stream_sync()                                # the fault word was cleared
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+
+
+def test_single_ops_byte_granular():
+    npes, hb = 3, 1 << 18
+    init = seeded_heaps(npes, hb, 42)
+    w = oracle_world(init)
+    rng = np.random.default_rng(1)
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        # each op works in its own 8 KiB stripe: no conflicts in either model
+        for k in range(30):
+            n = int(rng.choice([0, 1, 3, 7, 8, 15, 16, 17, 63, 64, 100, 255, 1024, 2049, 4000]))
+            a, b = int(rng.integers(0, 96)), int(rng.integers(0, 96))
+            me, pe = int(rng.integers(0, npes)), int(rng.integers(0, npes))
+            lo, so = k * 8192 + a, k * 8192 + 4096 + b
+            if k % 2 == 0:
+                assert w.put(me, so, lo, n, pe) == 0
+                sh.put(me, base + so, sh.ptr(base + lo, me), n, pe)
+            else:
+                assert w.get(me, lo, so, n, pe) == 0
+                sh.get(me, sh.ptr(base + lo, me), base + so, n, pe)
+            sh.quiet(me)
+            w.quiet(me)
+        sh.barrier_all()
+        got = heaps_of(heap, npes)
+    w.barrier_all()
+    assert np.array_equal(got, w.heaps())
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_single_iput_iget(eb):
+    npes, hb = 2, 1 << 20
+    init = seeded_heaps(npes, hb, 77 + eb)
+    w = oracle_world(init)
+    rng = np.random.default_rng(eb)
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        half = hb // 2
+        for k in range(12):
+            ds, ss = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+            if k % 3 == 0:
+                ds = 1
+            if k % 3 == 1:
+                ss = 1
+            n = int(rng.integers(0, 3000))
+            so = int(rng.integers(0, 8)) * eb                    # source in the low half
+            do = half + int(rng.integers(0, 8)) * eb            # destination in the high half
+            if k % 2 == 0:
+                assert w.iput(0, do, so, ds, ss, n, eb, 1) == 0
+                sh.iput(0, base + do, sh.ptr(base + so, 0), ds, ss, n, eb, 1)
+            else:
+                assert w.iget(1, do, so, ds, ss, n, eb, 0) == 0
+                sh.iget(1, sh.ptr(base + do, 1), base + so, ds, ss, n, eb, 0)
+            w.barrier_all()
+            got = heaps_of(heap, npes)
+            assert np.array_equal(got, w.heaps()), (k, ds, ss, n)
+
+
+SWEEP_CASES = [
+    # kind, count, eb, remote_stride, local_stride, ops_per_pe, nslots, wgs
+    (workgen.OP_PUT, 8, 1, 1, 1, 5, 3, 1),
+    (workgen.OP_GET, 64, 1, 1, 1, 7, 2, 2),
+    (workgen.OP_PUT, 4096, 1, 1, 1, 9, 4, 3),
+    (workgen.OP_PUT, 14352, 1, 1, 1, 6, 3, 2),          # the paper's MoE dispatch message size
+    (workgen.OP_GET, 14336, 1, 1, 1, 6, 3, 5),          # ... and its combine message size
+    (workgen.OP_PUT, (1 << 20) + 24, 1, 1, 1, 3, 2, 16),  # several chunks and a ragged tail
+    (workgen.OP_GET, (1 << 20) + 8, 1, 1, 1, 2, 1, 7),
+    (workgen.OP_IPUT, 5000, 4, 1, 2, 3, 2, 3),          # gather (local side strided)
+    (workgen.OP_IPUT, 5000, 4, 64, 1, 3, 2, 4),         # scatter
+    (workgen.OP_IPUT, 3001, 4, 16, 8, 2, 2, 2),         # both strided
+    (workgen.OP_IGET, 5003, 4, 4, 1, 3, 2, 3),          # gather from remote
+    (workgen.OP_IGET, 2000, 4, 1, 32, 2, 1, 1),
+    (workgen.OP_IGET, 1500, 8, 3, 5, 2, 2, 2),
+]
+
+
+@pytest.mark.parametrize("case", SWEEP_CASES)
+def test_copy_sweep_cell(case):
+    kind, count, eb, rs, ls, nops, nslots, wgs = case
+    npes = 8
+    strided = kind >= workgen.OP_IPUT
+    rspan = ((count - 1) * rs + 1) * eb if strided else count
+    lspan = ((count - 1) * ls + 1) * eb if strided else count
+    rslot = (rspan + 255) // 256 * 256
+    lslot = (lspan + 255) // 256 * 256 + 256
+    hb = ((rslot + lslot) * nslots + 4096 + 255) // 256 * 256
+    init = seeded_heaps(npes, hb, 900 + count % 97)
+    w = oracle_world(init)
+    local_off, remote_off = 0, lslot * nslots + 256
+    for p in range(npes):
+        peer = (p + 1) % npes
+        for k in range(nops):
+            s = k % nslots
+            lo, ro = local_off + s * lslot, remote_off + s * rslot
+            if kind == workgen.OP_PUT:
+                rc = w.put(p, ro, lo, count, peer)
+            elif kind == workgen.OP_GET:
+                rc = w.get(p, lo, ro, count, peer)
+            elif kind == workgen.OP_IPUT:
+                rc = w.iput(p, ro, lo, rs, ls, count, eb, peer)
+            else:
+                rc = w.iget(p, lo, ro, ls, rs, count, eb, peer)
+            assert rc == 0
+    w.barrier_all()
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.copy_sweep(kind, base + remote_off, base + local_off, count, eb, rs, ls, rslot, lslot,
+                      nslots, nops, wgs)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+    assert not np.array_equal(got, init)
+
+
+def test_allocator_matches_oracle_and_host_errors():
+    npes, hb = 2, 64 * 256
+    w = oracle.World(npes, hb, oracle.EAGER, 0)
+    rng = np.random.default_rng(11)
+    with shmem_world(npes, hb) as (heap, base):
+        assert sh.n_pes() == npes
+        live = []
+        for step in range(200):
+            if live and rng.random() < 0.45:
+                off = live.pop(int(rng.integers(0, len(live))))
+                assert w.free(off) == 0
+                sh.free(base + off)
+            else:
+                n = int(rng.integers(1, 2000))
+                exp = w.malloc(n)
+                got = sh.malloc(n)
+                assert (got is None) == (exp < 0)
+                if got is not None:
+                    assert got - base == exp            # same policy, same offsets
+                    assert sh.ptr(got, 1) == got + hb
+                    live.append(exp)
+        assert sh.malloc(0) is None and sh.align(3, 8) is None
+        for call, status in [
+            (lambda: sh.free(base + 128), sh.ERR_BAD_FREE),
+            (lambda: sh.put(0, base, base, 8, 2), sh.ERR_INVALID_PE),
+            (lambda: sh.put(-1, base, base, 8, 0), sh.ERR_INVALID_PE),
+            (lambda: sh.put(0, base + hb - 4, base, 8, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.get(0, base, base + hb, 1, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.iput(0, base, base, 0, 1, 4, 4, 1), sh.ERR_INVALID_ARG),
+            (lambda: sh.iput(0, base + 2, base, 1, 1, 4, 4, 1), sh.ERR_ALIGN),
+            (lambda: sh.iput(0, base, base, hb // 4, 1, 2, 4, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.atomic_fetch_add(0, base + 4, 1, 1), sh.ERR_ALIGN),
+            (lambda: sh.op_batch(base, 1, 1, 0), sh.ERR_INVALID_ARG),
+            (lambda: sh.op_batch(base, 1, 1, 100000), sh.ERR_INVALID_ARG),   # cannot be co-resident
+            (lambda: sh.copy_sweep(0, base, base, 64, 1, 1, 1, 256, 256, 1, 1, 1), sh.ERR_INVALID_ARG),
+            (lambda: sh.init(2, hb, heap, heap), sh.ERR_ALREADY_INIT),
+        ]:
+            with pytest.raises(sh.ShmemError) as e:
+                call()
+            assert e.value.status == status
+        assert sh.ptr(base + hb, 0) is None and sh.ptr(base, 2) is None
