@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the one-sided hot path on one MI355X.
+
+Headline (the workload the metric is quoted on): configuration 2, the put / get
+bandwidth sweep over 8 emulated PEs in a ring.  One "step" is one pass over the
+HBM-bound part of the sweep: for every message size in SIZES, one put cell and
+one get cell (every PE issues OPS back-to-back messages to its ring neighbour
+in one launch, rotating over slots so that a launch touches >= 2 GiB).  `value`
+is the payload rate of the whole step; a copy moves two bytes of HBM traffic per
+payload byte, which is what `roofline` prices against the 8 TB/s peak.
+
+Prints ONE JSON line.  Inputs are resident in HBM before the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+NPES = 8
+SEG = 1 << 30                       # 1 GiB per PE
+SIZES = [1 << 20, 1 << 22, 1 << 24, 1 << 26]
+BYTES_PER_PE_PER_CELL = 1 << 28     # 256 MiB of payload per PE per launch (2 GiB per launch)
+
+
+def cells(wgs):
+    out = []
+    for nbytes in SIZES:
+        ops = BYTES_PER_PE_PER_CELL // nbytes
+        nslots = ops                 # every op has its own slot: 256 MiB local + 256 MiB remote per PE
+        for kind in (0, 1):          # put, get
+            out.append(dict(kind=kind, nbytes=nbytes, ops=ops, nslots=nslots, wgs=wgs))
+    return out
+
+
+def cpu_baseline(seconds=12.0):
+    """The oracle as it stands, single-threaded, on a bounded sample of the same
+    workload: put + quiet and get of SIZES between ring neighbours."""
+    import numpy as np
+    import oracle
+    npes, seg = NPES, 160 << 20
+    w = oracle.World(npes, seg, oracle.AT_QUIET, 0)
+    for p in range(npes):
+        w.heap(p)[: 1 << 20] = np.arange(1 << 20, dtype=np.uint8)
+    moved, t0, k = 0, time.perf_counter(), 0
+    while time.perf_counter() - t0 < seconds:
+        nbytes = SIZES[k % len(SIZES)]
+        for p in range(npes):
+            peer = (p + 1) % npes
+            if (k // len(SIZES)) % 2 == 0:
+                w.put(p, 80 << 20, 0, nbytes, peer)
+            else:
+                w.get(p, 0, 80 << 20, nbytes, peer)
+        w.barrier_all()
+        moved += nbytes * npes
+        k += 1
+    dt = time.perf_counter() - t0
+    w.close()
+    return {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{k} ring rounds of put+quiet / get over sizes {SIZES} B, 8 PEs, {dt:.1f} s of CPU time"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--wgs-per-pe", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (PEs are emulated as workgroup teams on one "
+              "MI355X); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_15076_amd as sh
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    heap = torch.empty(NPES * SEG, dtype=torch.uint8, device=dev)
+    heap.view(torch.int64).random_()                    # synthetic payload, resident in HBM
+    scratch = torch.zeros(sh.scratch_bytes(NPES), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    sh.init(NPES, SEG, heap, scratch, stream.cuda_stream)
+    base = heap.data_ptr()
+    local_sym, remote_sym = base, base + (SEG // 2)
+    plan = cells(args.wgs_per_pe)
+
+    def launch(c):
+        sh.copy_sweep(c["kind"], remote_sym, local_sym, c["nbytes"], 1, 1, 1, c["nbytes"], c["nbytes"],
+                      c["nslots"], c["ops"], c["wgs"])
+
+    for _ in range(args.warmup):
+        for c in plan:
+            launch(c)
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` steps; per-launch HIP events on the library's stream
+    evs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for c in plan:
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            launch(c)
+            b.record(stream)
+            evs.append((c, a, b))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    sh.stream_sync()
+
+    per_cell = {}
+    kernel_ms = 0.0
+    for c, a, b in evs:
+        ms = a.elapsed_time(b)
+        kernel_ms += ms
+        per_cell.setdefault((c["kind"], c["nbytes"]), []).append(ms)
+    payload_per_launch = NPES * BYTES_PER_PE_PER_CELL
+    payload_per_step = payload_per_launch * len(plan)
+    ms_per_step = wall * 1e3 / args.steps
+    value = payload_per_step / (wall / args.steps) / 1e9
+    avg_launch_ms = kernel_ms / len(evs)
+    achieved = 2.0 * payload_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    detail = {}
+    for (kind, nbytes), v in sorted(per_cell.items()):
+        v = sorted(v)
+        med = v[len(v) // 2]
+        detail[f"{'put' if kind == 0 else 'get'}_{nbytes >> 20}MiB"] = {
+            "payload_GBs": round(payload_per_launch / (med * 1e-3) / 1e9, 1),
+            "hbm_frac": round(2.0 * payload_per_launch / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    out = {
+        "metric": "put/get payload bandwidth, messages >= 1 MiB (config 2 sweep, 8 emulated PEs)",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "configs[1]: 8 emulated PEs in a ring, contiguous put and get, message sizes "
+                               "1/4/16/64 MiB, 256 MiB payload per PE per launch",
+                   "npes": NPES, "heap_bytes_per_pe": SEG, "wgs_per_pe": args.wgs_per_pe,
+                   "launches_per_step": len(plan)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "k_copy_sweep", "avg_launch_ms": round(avg_launch_ms, 4),
+                     "algorithmic_bytes_per_launch": 2 * payload_per_launch},
+        "cells": detail,
+    }
+    sh.finalize()
+    del heap
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
