@@ -67,6 +67,140 @@ def cpu_baseline(seconds=12.0):
             "sample": f"{k} ring rounds of put+quiet / get over sizes {SIZES} B, 8 PEs, {dt:.1f} s of CPU time"}
 
 
+def _median_ms(fn, reset, reps=5, warm=2):
+    """Median HIP-event time of fn() on the current stream; reset() runs untimed before each rep."""
+    import torch
+    stream = torch.cuda.current_stream()
+    out = []
+    for r in range(warm + reps):
+        reset()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        fn()
+        b.record(stream)
+        b.synchronize()
+        if r >= warm:
+            out.append(a.elapsed_time(b))
+    out.sort()
+    return out[len(out) // 2]
+
+
+def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
+    """Configuration 3: 2^24 AMOs on 64 PEs, T in {1, 1024, 2^20}, uniform / Zipf(1.0)."""
+    import numpy as np
+    import workgen
+    dev = torch.device("cuda:0")
+    seg = 8 << 20
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    res = {}
+    try:
+        d_old = torch.empty(n, dtype=torch.int64, device=dev)
+        d_zero = torch.zeros(n, dtype=torch.int64, device=dev)
+        d_tag = torch.arange(1, n + 1, dtype=torch.int64, device=dev)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).to(dev)
+        for T in (1, 1024, 1 << 20):
+            ctr = sh.malloc(T * 8)
+            off = ctr - heap.data_ptr()
+            view = heap.view(npes, seg)[:, off:off + 8 * T]
+            for dist in ("uniform", "zipf"):
+                pe, idx, a16 = workgen.cfg3_amo_ops(n=n, npes=npes, T=T, dist=dist, addend="rand16")
+                d_pe, d_idx, d_a16 = up(pe), up(idx), up(a16)
+                d_one = torch.ones(n, dtype=torch.int64, device=dev)
+                reset = lambda: view.zero_()
+                cell = {}
+                for name, kind, a, b, agg in (("fadd1", sh.AMO_FETCH_ADD, d_one, None, 0),
+                                              ("fadd1_agg", sh.AMO_FETCH_ADD, d_one, None, 1),
+                                              ("faddv", sh.AMO_FETCH_ADD, d_a16, None, 0),
+                                              ("faddv_agg", sh.AMO_FETCH_ADD, d_a16, None, 1),
+                                              ("cas_claim", sh.AMO_COMPARE_SWAP, d_zero, d_tag, 0),
+                                              ("cas_min", sh.AMO_MIN_CAS_LOOP, d_tag, None, 0),
+                                              ("cas_min_agg", sh.AMO_MIN_CAS_LOOP, d_tag, None, 1)):
+                    ms = _median_ms(lambda: sh.amo_batch(kind, ctr, T, d_pe, d_idx, a, b, d_old, n, wgs, agg),
+                                    reset, reps=3, warm=1)
+                    cell[name] = round(n / ms / 1e3, 1)       # Mops/s
+                res[f"T{T}_{dist}"] = cell
+                del d_pe, d_idx, d_a16
+            sh.free(ctr)
+        sh.stream_sync()
+    finally:
+        sh.finalize()
+    return {"unit": "Mops/s", "ops": n, "npes": npes, "wgs_per_pe": wgs, "cells": res}
+
+
+def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=128):
+    """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
+    import numpy as np
+    import workgen
+    dev = torch.device("cuda:0")
+    slots = 2 * n // npes
+    seg = slots * 8 + (1 << 20)
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        keys = workgen.cfg4_keys(n=n)
+        queries = workgen.cfg4_queries(keys, n=n)
+        d_keys = torch.from_numpy(keys.view(np.int64)).to(dev)
+        d_q = torch.from_numpy(queries.view(np.int64)).to(dev)
+        d_st = torch.empty(n, dtype=torch.uint8, device=dev)
+        d_fo = torch.empty(n, dtype=torch.uint8, device=dev)
+        tab = sh.malloc(slots * 8)
+        ins_ms = _median_ms(lambda: sh.hash_insert(tab, slots, d_keys, n, d_st, wgs), lambda: heap.zero_(), reps=3, warm=1)
+        look_ms = _median_ms(lambda: sh.hash_lookup(tab, slots, d_q, n, d_fo, wgs), lambda: None, reps=3, warm=1)
+        sh.stream_sync()
+        found = float(d_fo.float().mean().item())
+        inserted = int((d_st == 0).sum().item())
+    finally:
+        sh.finalize()
+    # algorithmic bytes: insert = 8 B key + 128 B sector read-modify-write + 1 B status; lookup = 8 + 64 + 1
+    return {"keys": n, "npes": npes, "slots_per_pe": slots, "wgs_per_pe": wgs,
+            "Minserts_per_s": round(n / ins_ms / 1e3, 1), "Mlookups_per_s": round(n / look_ms / 1e3, 1),
+            "insert_eff_GBs": round(n * 137 / ins_ms / 1e6, 1), "lookup_eff_GBs": round(n * 73 / look_ms / 1e6, 1),
+            "inserted": inserted, "found_fraction": round(found, 4)}
+
+
+def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
+    """Configuration 5: level-synchronous BFS on an R-MAT graph, 64 seeded roots."""
+    import numpy as np
+    import workgen
+    dev = torch.device("cuda:0")
+    n = 1 << scale
+    row, nbr = workgen.rmat_csr(scale)
+    roots = workgen.bfs_roots(row, nroots)
+    vpp = n // npes
+    seg = ((vpp * 24 + vpp // 8 + (1 << 16)) + 255) // 256 * 256
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        d_row = torch.from_numpy(row.view(np.int64)).to(dev)
+        d_nbr = torch.from_numpy(nbr.view(np.int32)).to(dev)
+        g = sh.bfs_create(n, d_row, d_nbr, wgs)
+        sh.bfs(g, int(roots[0]))                                   # warm-up
+        teps, times, levels = [], [], []
+        for r in roots:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st = sh.bfs(g, int(r))                                 # blocks until the search is complete
+            dt = time.perf_counter() - t0
+            teps.append(st["edges_traversed"] / dt / 1e9)
+            times.append(dt * 1e3)
+            levels.append(st["nlevels"])
+        sh.bfs_destroy(g)
+        sh.stream_sync()
+    finally:
+        sh.finalize()
+    teps = np.array(teps)
+    return {"scale": scale, "edge_factor": 16, "npes": npes, "wgs_per_pe": wgs, "roots": nroots,
+            "csr_entries": int(len(nbr)),
+            "GTEPS_harmonic_mean": round(float(len(teps) / (1.0 / teps).sum()), 3),
+            "GTEPS_min": round(float(teps.min()), 3), "GTEPS_median": round(float(np.median(teps)), 3),
+            "GTEPS_max": round(float(teps.max()), 3), "ms_median": round(float(np.median(times)), 3),
+            "levels_median": int(np.median(levels))}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +208,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--wgs-per-pe", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", default="amo,hash,bfs",
+                    help="comma list of the other configurations to measure too (amo, hash, bfs) or 'none'")
+    ap.add_argument("--bfs-scale", type=int, default=24)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (PEs are emulated as workgroup teams on one "
@@ -154,6 +291,20 @@ def main():
     }
     sh.finalize()
     del heap
+    torch.cuda.empty_cache()
+    want = [] if args.extras == "none" else args.extras.split(",")
+    extras = {}
+    if "amo" in want:
+        extras["config3_amo"] = extra_amo(sh, torch)
+        torch.cuda.empty_cache()
+    if "hash" in want:
+        extras["config4_hash"] = extra_hash(sh, torch)
+        torch.cuda.empty_cache()
+    if "bfs" in want:
+        extras["config5_bfs"] = extra_bfs(sh, torch, scale=args.bfs_scale)
+        torch.cuda.empty_cache()
+    if extras:
+        out["extras"] = extras
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out), flush=True)

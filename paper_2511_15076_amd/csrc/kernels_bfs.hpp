@@ -17,6 +17,7 @@ struct BfsState {
     const uint32_t *nbr;         // CSR neighbours
     // symmetric offsets of the per-PE state
     uint64_t bitmap_off, level_off, parent_off, queue_off[2], hub_off, tails_off;
+    uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_visit)
     uint32_t wgs_per_pe;
 };
 
@@ -24,6 +25,10 @@ struct BfsState {
 enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_HUBS = 4 };
 
 constexpr uint32_t HUB_DEGREE = 2048;  // rows at least this long are expanded by the whole team
+constexpr uint32_t NXCD = 8;           // accelerator dies, each with a private L2
+
+// Index of the die this wave runs on (XCC_ID hardware register, 4 bits).
+__device__ __forceinline__ uint32_t xcd_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & (NXCD - 1); }
 
 __device__ __forceinline__ uint32_t bfs_owner(const BfsState &s, uint32_t v)
 {
@@ -45,6 +50,8 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
     for (uint64_t w = rank; w < s.words; w += size)
         bm[w] = (pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
+    uint64_t *flt = (uint64_t *)ptr(c, s.filter_off, pe);
+    for (uint64_t w = rank; w < s.words * NXCD; w += size) flt[w] = 0;
     for (uint64_t l = rank; l < s.vpp; l += size) {
         const bool is_root = pe == ro && l == rl;
         lv[l] = is_root ? 0 : -1;
@@ -59,19 +66,35 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
 }
 
 // Visit neighbour v of frontier vertex u (lanes with active == false only take
-// part in the wave-wide steps).  The test before the fetch_or may read a stale
-// "clear" bit -- then the fetch_or decides; a set bit is never stale.
-__device__ __forceinline__ void bfs_visit(const Ctx &c, const BfsState &s, bool active, uint32_t v, uint32_t u,
-                                          uint32_t L)
+// part in the wave-wide steps).
+//
+// Test before set: the fetch_or on the owner's bitmap is the claim, but most
+// probes find a vertex that is already claimed.  Atomics resolve beyond the
+// per-die L2s, and a plain read of the bitmap word may hit a line that this
+// die's L2 fetched before the bit was set, so a plain test of the bitmap itself
+// stays blind to everything claimed during the current level.  Each die
+// therefore keeps a private copy of the bitmap that only its own waves read and
+// write with plain accesses (coherent inside one L2): a bit is set there after
+// a fetch_or has shown the vertex to be claimed, so a set bit is always true
+// and a missing bit (first probe from this die, or a lost racy update) only
+// costs one more fetch_or.
+__device__ __forceinline__ void bfs_visit(const Ctx &c, const BfsState &s, uint32_t xcd, bool active, uint32_t v,
+                                          uint32_t u, uint32_t L)
 {
     bool won = false;
     uint32_t o = 0, l = 0;
     if (active) {
         o = bfs_owner(s, v);
         l = v - o * s.vpp;
-        uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, o) + (l >> 6);
         const uint64_t bit = 1ull << (l & 63);
-        if (!(*w & bit)) won = !(atomic_fetch_or(w, bit) & bit);
+        uint64_t *f = (uint64_t *)ptr(c, s.filter_off, o) + (uint64_t)xcd * s.words + (l >> 6);
+        const uint64_t known = *f;
+        if (!(known & bit)) {
+            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, o) + (l >> 6);
+            const uint64_t old = atomic_fetch_or(w, bit);
+            won = !(old & bit);
+            *f = known | old | bit;      // everything the fetch_or showed to be claimed
+        }
     }
     // winners that share an owner reserve their queue slots with one fetch_add
     uint64_t m = ballot(won);
@@ -102,6 +125,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint32_t xcd = xcd_id();
     uint64_t *tails = bfs_tails(c, s, pe);
     const uint64_t cnt = tails[T_TAIL0 + L % 3];
     const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[L & 1], pe);
@@ -135,7 +159,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
             for (uint32_t t0 = 0; t0 < dj; t0 += 64) {
                 const bool act = t0 + lane < dj;
                 const uint32_t v = act ? s.nbr[rj + t0 + lane] : 0;
-                bfs_visit(c, s, act, v, uj, L);
+                bfs_visit(c, s, xcd, act, v, uj, L);
             }
         }
     }
@@ -150,6 +174,7 @@ __global__ __launch_bounds__(256) void k_bfs_hubs(Ctx c, BfsState s, uint32_t L)
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint32_t xcd = xcd_id();
     const uint64_t nh = bfs_tails(c, s, pe)[T_HUBS];
     const uint32_t *hubs = (const uint32_t *)ptr(c, s.hub_off, pe);
     for (uint64_t h = 0; h < nh; ++h) {
@@ -158,7 +183,7 @@ __global__ __launch_bounds__(256) void k_bfs_hubs(Ctx c, BfsState s, uint32_t L)
         for (uint64_t t0 = my_wave * 64; t0 < deg; t0 += team_waves * 64) {
             const bool act = t0 + lane < deg;
             const uint32_t v = act ? s.nbr[r0 + t0 + lane] : 0;
-            bfs_visit(c, s, act, v, u, L);
+            bfs_visit(c, s, xcd, act, v, u, L);
         }
     }
 }

@@ -459,11 +459,11 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     if (!g) return SHMEM_ERR_NOMEM;
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
     const uint64_t words = ((uint64_t)vpp + 63) / 64;
-    const size_t sizes[7] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
-                             (size_t)vpp * 4, 256};
-    uint64_t offs[7];
+    const size_t sizes[8] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+                             (size_t)vpp * 4, 256, words * 8 * shmemx::NXCD};
+    uint64_t offs[8];
     g->nallocs = 0;
-    for (int i = 0; i < 7; ++i) {
+    for (int i = 0; i < 8; ++i) {
         void *p = shmem_malloc(sizes[i]);
         if (!p) {
             for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
@@ -479,6 +479,7 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.row_off = dev_row_off; s.nbr = dev_nbr;
     s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
     s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.hub_off = offs[5]; s.tails_off = offs[6];
+    s.filter_off = offs[7];
     s.wgs_per_pe = (uint32_t)wgs_per_pe;
     g->wgs_per_pe = wgs_per_pe;
     *graph_out = g;
