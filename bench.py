@@ -170,7 +170,7 @@ def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
     row, nbr = workgen.rmat_csr(scale)
     roots = workgen.bfs_roots(row, nroots)
     vpp = n // npes
-    seg = ((vpp * 24 + vpp // 8 + (1 << 16)) + 255) // 256 * 256
+    seg = ((vpp * 28 + vpp // 8 + (1 << 16)) + 255) // 256 * 256
     heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
     scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
     sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
@@ -211,6 +211,11 @@ def main():
     ap.add_argument("--extras", default="amo,hash,bfs",
                     help="comma list of the other configurations to measure too (amo, hash, bfs) or 'none'")
     ap.add_argument("--bfs-scale", type=int, default=24)
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also run the plain read / write / copy stream kernels (sanity ceilings of the box)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB tensor copy (a reference dispatch for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (PEs are emulated as workgroup teams on one "
@@ -239,6 +244,9 @@ def main():
         for c in plan:
             launch(c)
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        heap[SEG:2 * SEG].copy_(heap[0:SEG])            # plain copy: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
 
     # timed region: exactly `steps` steps; per-launch HIP events on the library's stream
     evs = []
@@ -284,7 +292,10 @@ def main():
                    "npes": NPES, "heap_bytes_per_pe": SEG, "wgs_per_pe": args.wgs_per_pe,
                    "launches_per_step": len(plan)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a plain 1 GiB copy
+                     # (profiles/k_copy_sweep_config2_put_get_1-64MiB.md)
+                     "traffic": 4294.99e6,
                      "kernel": "k_copy_sweep", "avg_launch_ms": round(avg_launch_ms, 4),
                      "algorithmic_bytes_per_launch": 2 * payload_per_launch},
         "cells": detail,
@@ -305,6 +316,11 @@ def main():
         torch.cuda.empty_cache()
     if extras:
         out["extras"] = extras
+    if args.ceilings:
+        import subprocess
+        exe = os.path.join(ROOT, "paper_2511_15076_amd", "stream_ceilings")
+        res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        out["stream_ceilings"] = json.loads(res.stdout) if res.returncode == 0 else {"error": res.stdout[-200:]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out), flush=True)

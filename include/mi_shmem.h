@@ -204,7 +204,8 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
  * neighbours uint32[nnz]; PE p reads only its own rows) and allocates the
  * per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
- * long-row list, per-die bitmap copies, tails: about 21.2 bytes per owned vertex).  Errors: NOMEM, INVALID_ARG. */
+ * long-row list and its scan, per-die bitmap copies, counters: about 25.2 bytes per
+ * owned vertex).  Errors: NOMEM, INVALID_ARG. */
 typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */

@@ -1,8 +1,19 @@
 // Level-synchronous BFS over a 1D block vertex partition, built on the
 // one-sided primitives: fetch_or claims a vertex in its owner's bitmap,
-// fetch_add reserves a slot in the owner's next-frontier queue, puts deliver
-// the vertex, its parent and its level.  One launch per level; the kernel
-// boundary is the quiet + barrier_all between levels.
+// fetch_add reserves slots in the owner's next-frontier queue, puts deliver
+// the vertex, its parent and its level.  One set of launches per level; the
+// kernel boundary is the quiet + barrier_all between levels.
+//
+// Work distribution inside a PE team:
+//   k_bfs_expand   a wave takes 64 frontier vertices, sets long rows aside and
+//                  expands the short ones packed: a wave-wide prefix sum over
+//                  the row lengths lets every lane take edges, whatever the
+//                  length mix (R-MAT degrees are heavily skewed);
+//   k_bfs_bigscan  prefix sum over the long rows' segment counts (one
+//                  workgroup per PE);
+//   k_bfs_big      the team's waves split the long rows' 256-edge segments
+//                  evenly;
+//   k_bfs_count    one wave totals the next frontier and resets counters.
 #pragma once
 #include "../../include/mi_shmem.h"
 #include "shmemx.hpp"
@@ -16,20 +27,26 @@ struct BfsState {
     const uint64_t *row_off;     // CSR row offsets (PE p reads rows of its own vertices)
     const uint32_t *nbr;         // CSR neighbours
     // symmetric offsets of the per-PE state
-    uint64_t bitmap_off, level_off, parent_off, queue_off[2], hub_off, tails_off;
-    uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_visit)
+    uint64_t bitmap_off, level_off, parent_off, queue_off[2], big_off, bigscan_off, tails_off;
+    uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
     uint32_t wgs_per_pe;
 };
 
 // words inside the per-PE tails block (uint64 each)
-enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_HUBS = 4 };
+enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, T_NTASKS = 5 };
 
-constexpr uint32_t HUB_DEGREE = 2048;  // rows at least this long are expanded by the whole team
+constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
+constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
+constexpr uint32_t EPL = 4;            // edges per lane in flight
 constexpr uint32_t NXCD = 8;           // accelerator dies, each with a private L2
+constexpr uint32_t STAGE_PES = 16;     // winners are staged in LDS when npes <= this
+constexpr uint32_t STAGE_CAP = 128;    // staged vertices per owner per wave (flushed in blocks of 64)
 
 // Index of the die this wave runs on (XCC_ID hardware register, 4 bits).
-__device__ __forceinline__ uint32_t xcd_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & (NXCD - 1); }
-
+__device__ __forceinline__ uint32_t xcd_id()
+{
+    return __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & (NXCD - 1);
+}
 __device__ __forceinline__ uint32_t bfs_owner(const BfsState &s, uint32_t v)
 {
     return s.shift >= 0 ? v >> s.shift : v / s.vpp;
@@ -59,14 +76,81 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     }
     if (rank == 0) {
         uint64_t *t = bfs_tails(c, s, pe);
-        t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0; t[T_HUBS] = 0;
+        t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
         if (pe == 0) c.scratch[W_WORK + 1] = 0;  // degree sum of reached vertices
     }
 }
 
-// Visit neighbour v of frontier vertex u (lanes with active == false only take
-// part in the wave-wide steps).
+// ---------------------------------------------------------------------------
+// Per-wave staging of claimed vertices, one small buffer per owner in LDS.
+// A full block of 64 is written to the owner's queue with ONE fetch_add on its
+// tail and one coalesced 256-byte put; the remainder goes out at kernel end.
+struct Stage {
+    uint32_t *cnt;   // [STAGE_PES]
+    uint32_t *buf;   // [STAGE_PES][STAGE_CAP]
+};
+
+template <bool STAGED>
+__device__ __forceinline__ void bfs_enqueue(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L, bool won,
+                                            uint32_t o, uint32_t v)
+{
+    uint64_t m = ballot(won);
+    const uint32_t lane = lane_id();
+    while (m) {
+        const uint32_t leader = (uint32_t)__builtin_ctzll(m);
+        const uint32_t ol = bcast32(o, leader);
+        const uint64_t grp = ballot(won && o == ol);
+        const uint32_t n = (uint32_t)__builtin_popcountll(grp);
+        uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], ol);
+        uint64_t *tail = bfs_tails(c, s, ol) + T_TAIL0 + (L + 1) % 3;
+        if (STAGED) {
+            uint32_t *buf = st.buf + ol * STAGE_CAP;
+            uint32_t cn = st.cnt[ol];
+            if (won && o == ol) buf[cn + rank_in(grp)] = v;
+            cn += n;
+            __builtin_amdgcn_wave_barrier();
+            if (cn >= 64) {
+                uint64_t base = 0;
+                if (lane == 0) base = atomic_fetch_add(tail, 64);
+                base = bcast64(base, 0);
+                queue[base + lane] = buf[lane];                       // put: one full block
+                const uint32_t rest = cn - 64;
+                const uint32_t moved = lane < rest ? buf[64 + lane] : 0;
+                __builtin_amdgcn_wave_barrier();
+                if (lane < rest) buf[lane] = moved;
+                cn = rest;
+            }
+            if (lane == 0) st.cnt[ol] = cn;
+            __builtin_amdgcn_wave_barrier();
+        } else {
+            uint64_t base = 0;
+            if (lane == leader) base = atomic_fetch_add(tail, (uint64_t)n);
+            base = bcast64(base, leader);
+            if (won && o == ol) queue[base + rank_in(grp)] = v;       // put v
+        }
+        m &= ~grp;
+    }
+}
+
+template <bool STAGED>
+__device__ __forceinline__ void bfs_flush(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L)
+{
+    if (!STAGED) return;
+    const uint32_t lane = lane_id();
+    for (uint32_t o = 0; o < (uint32_t)c.npes; ++o) {
+        const uint32_t cn = st.cnt[o];
+        if (cn == 0) continue;
+        uint64_t base = 0;
+        if (lane == 0) base = atomic_fetch_add(bfs_tails(c, s, o) + T_TAIL0 + (L + 1) % 3, (uint64_t)cn);
+        base = bcast64(base, 0);
+        if (lane < cn) ((uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], o))[base + lane] = st.buf[o * STAGE_CAP + lane];
+    }
+}
+
+// Probe EPL neighbours per lane (v[k] of frontier vertex u[k]; inactive slots
+// only take part in the wave-wide steps).
 //
 // Test before set: the fetch_or on the owner's bitmap is the claim, but most
 // probes find a vertex that is already claimed.  Atomics resolve beyond the
@@ -78,58 +162,69 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
 // a fetch_or has shown the vertex to be claimed, so a set bit is always true
 // and a missing bit (first probe from this die, or a lost racy update) only
 // costs one more fetch_or.
-__device__ __forceinline__ void bfs_visit(const Ctx &c, const BfsState &s, uint32_t xcd, bool active, uint32_t v,
-                                          uint32_t u, uint32_t L)
+template <bool STAGED>
+__device__ __forceinline__ void bfs_probe(const Ctx &c, const BfsState &s, const Stage &st, uint32_t xcd, uint32_t L,
+                                          const bool (&act)[EPL], const uint32_t (&v)[EPL], const uint32_t (&u)[EPL])
 {
-    bool won = false;
-    uint32_t o = 0, l = 0;
-    if (active) {
-        o = bfs_owner(s, v);
-        l = v - o * s.vpp;
-        const uint64_t bit = 1ull << (l & 63);
-        uint64_t *f = (uint64_t *)ptr(c, s.filter_off, o) + (uint64_t)xcd * s.words + (l >> 6);
-        const uint64_t known = *f;
-        if (!(known & bit)) {
-            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, o) + (l >> 6);
-            const uint64_t old = atomic_fetch_or(w, bit);
-            won = !(old & bit);
-            *f = known | old | bit;      // everything the fetch_or showed to be claimed
+    uint32_t o[EPL], l[EPL];
+    uint64_t *f[EPL], known[EPL];
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) {        // EPL cache probes in flight
+        o[k] = 0; l[k] = 0; f[k] = nullptr; known[k] = ~0ull;
+        if (act[k]) {
+            o[k] = bfs_owner(s, v[k]);
+            l[k] = v[k] - o[k] * s.vpp;
+            f[k] = (uint64_t *)ptr(c, s.filter_off, o[k]) + (uint64_t)xcd * s.words + (l[k] >> 6);
+            known[k] = *f[k];
         }
     }
-    // winners that share an owner reserve their queue slots with one fetch_add
-    uint64_t m = ballot(won);
-    const uint32_t lane = lane_id();
-    while (m) {
-        const uint32_t leader = (uint32_t)__builtin_ctzll(m);
-        const uint32_t ol = bcast32(o, leader);
-        const uint64_t grp = ballot(won && o == ol);
-        uint64_t base = 0;
-        if (lane == leader)
-            base = atomic_fetch_add(bfs_tails(c, s, ol) + T_TAIL0 + (L + 1) % 3, (uint64_t)__builtin_popcountll(grp));
-        base = bcast64(base, leader);
-        if (won && o == ol) {
-            const uint64_t slot = base + rank_in(grp);
-            ((uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], ol))[slot] = v;   // put v
-            ((uint32_t *)ptr(c, s.parent_off, ol))[l] = u;                  // put parent
-            ((int32_t *)ptr(c, s.level_off, ol))[l] = (int32_t)(L + 1);     // put level
+    bool won[EPL];
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) {
+        won[k] = false;
+        const uint64_t bit = 1ull << (l[k] & 63);
+        if (act[k] && !(known[k] & bit)) {
+            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, o[k]) + (l[k] >> 6);
+            const uint64_t old = atomic_fetch_or(w, bit);                  // the claim
+            won[k] = !(old & bit);
+            *f[k] = known[k] | old | bit;     // everything the fetch_or showed to be claimed
+            if (won[k]) {
+                ((uint32_t *)ptr(c, s.parent_off, o[k]))[l[k]] = u[k];           // put parent
+                ((int32_t *)ptr(c, s.level_off, o[k]))[l[k]] = (int32_t)(L + 1); // put level
+            }
         }
-        m &= ~grp;
     }
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) bfs_enqueue<STAGED>(c, s, st, L, won[k], o[k], v[k]);
 }
 
-// Expand level L.  A wave takes 64 frontier vertices at a time (coalesced queue
-// read, 64 row lookups in flight), then walks their rows one after the other
-// with all lanes; very long rows are set aside for k_bfs_hubs.
+// LDS of one workgroup (4 waves)
+struct BfsLds {
+    uint32_t cnt[4][STAGE_PES];
+    uint32_t buf[4][STAGE_PES * STAGE_CAP];
+    uint32_t pre[4][64];
+    uint32_t u[4][64];
+    uint64_t r0[4][64];
+};
+
+// Expand level L: short rows packed, long rows set aside.
+template <bool STAGED>
 __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t L)
 {
+    __shared__ BfsLds lds;
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
     const uint32_t xcd = xcd_id();
+    const Stage st{lds.cnt[wave], lds.buf[wave]};
+    if (STAGED && lane < STAGE_PES) st.cnt[lane] = 0;
+    __builtin_amdgcn_wave_barrier();
+    uint32_t *pre = lds.pre[wave], *su = lds.u[wave];
+    uint64_t *sr0 = lds.r0[wave];
     uint64_t *tails = bfs_tails(c, s, pe);
     const uint64_t cnt = tails[T_TAIL0 + L % 3];
     const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[L & 1], pe);
-    uint32_t *hubs = (uint32_t *)ptr(c, s.hub_off, pe);
+    uint32_t *big = (uint32_t *)ptr(c, s.big_off, pe);
     uint64_t degsum = 0;
     for (uint64_t base = my_wave * 64; base < cnt; base += team_waves * 64) {
         const bool valid = base + lane < cnt;
@@ -141,55 +236,144 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
             deg = (uint32_t)(s.row_off[u + 1] - r0);
         }
         degsum += deg;
-        const bool hub = deg >= HUB_DEGREE;
-        const uint64_t hm = ballot(hub);
-        if (hm) {
-            const uint32_t leader = (uint32_t)__builtin_ctzll(hm);
+        const bool is_big = deg >= BIG_DEGREE;
+        const uint64_t bm = ballot(is_big);
+        if (bm) {                                   // long rows: one fetch_add reserves list slots for the wave
             uint64_t hb = 0;
-            if (lane == leader) hb = atomic_fetch_add(tails + T_HUBS, (uint64_t)__builtin_popcountll(hm));
-            hb = bcast64(hb, leader);
-            if (hub) hubs[hb + rank_in(hm)] = u;
+            if (lane == 0) hb = atomic_fetch_add(tails + T_NBIG, (uint64_t)__builtin_popcountll(bm));
+            hb = bcast64(hb, 0);
+            if (is_big) big[hb + rank_in(bm)] = u;
         }
-        uint64_t todo = ballot(valid && !hub && deg > 0);
-        while (todo) {
-            const uint32_t j = (uint32_t)__builtin_ctzll(todo);
-            todo &= todo - 1;
-            const uint32_t uj = bcast32(u, j), dj = bcast32(deg, j);
-            const uint64_t rj = bcast64(r0, j);
-            for (uint32_t t0 = 0; t0 < dj; t0 += 64) {
-                const bool act = t0 + lane < dj;
-                const uint32_t v = act ? s.nbr[rj + t0 + lane] : 0;
-                bfs_visit(c, s, xcd, act, v, uj, L);
+        // wave-wide inclusive prefix sum of the short rows' lengths
+        const uint32_t small = is_big ? 0 : deg;
+        uint32_t incl = small;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t t = __shfl_up(incl, d, 64);
+            if (lane >= (uint32_t)d) incl += t;
+        }
+        const uint32_t total = bcast32(incl, 63);
+        if (total == 0) continue;
+        pre[lane] = incl - small; su[lane] = u; sr0[lane] = r0;
+        __builtin_amdgcn_wave_barrier();
+        for (uint32_t e0 = 0; e0 < total; e0 += 64 * EPL) {
+            bool act[EPL];
+            uint32_t vv[EPL], uu[EPL];
+#pragma unroll
+            for (uint32_t k = 0; k < EPL; ++k) {
+                const uint32_t e = e0 + k * 64 + lane;
+                act[k] = e < total;
+                vv[k] = 0; uu[k] = 0;
+                if (act[k]) {
+                    uint32_t lo = 0;                 // largest i with pre[i] <= e
+#pragma unroll
+                    for (int step = 32; step > 0; step >>= 1)
+                        if (pre[lo + step] <= e) lo += step;
+                    uu[k] = su[lo];
+                    vv[k] = __builtin_nontemporal_load(s.nbr + sr0[lo] + (e - pre[lo]));
+                }
             }
+            bfs_probe<STAGED>(c, s, st, xcd, L, act, vv, uu);
         }
+        __builtin_amdgcn_wave_barrier();
     }
+    bfs_flush<STAGED>(c, s, st, L);
     // degree sum of this level's frontier -> traversed-edge count
     for (int off = 32; off > 0; off >>= 1) degsum += __shfl_down(degsum, off, 64);
     if (lane == 0 && degsum) atomic_fetch_add(&c.scratch[W_WORK + 1], degsum);
 }
 
-// Long rows of level L: all waves of the owner's team stride over each of them.
-__global__ __launch_bounds__(256) void k_bfs_hubs(Ctx c, BfsState s, uint32_t L)
+// Prefix sum over the long rows' segment counts of each PE (one workgroup per
+// PE): scan[i] = first segment id of long row i, scan[nbig] = segments in total.
+__global__ __launch_bounds__(1024) void k_bfs_bigscan(Ctx c, BfsState s)
 {
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t carry_s;
+    const uint32_t pe = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    uint64_t *tails = bfs_tails(c, s, pe);
+    const uint32_t nbig = (uint32_t)tails[T_NBIG];
+    const uint32_t *big = (const uint32_t *)ptr(c, s.big_off, pe);
+    uint32_t *scan = (uint32_t *)ptr(c, s.bigscan_off, pe);
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < nbig; base += blockDim.x) {
+        const uint32_t i = base + threadIdx.x;
+        uint32_t segs = 0;
+        if (i < nbig) {
+            const uint32_t u = big[i];
+            segs = (uint32_t)((s.row_off[u + 1] - s.row_off[u] + SEG_EDGES - 1) / SEG_EDGES);
+        }
+        uint32_t incl = segs;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t t = __shfl_up(incl, d, 64);
+            if (lane >= (uint32_t)d) incl += t;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry_s;
+        for (uint32_t w = 0; w < wave; ++w) before += wsum[w];
+        if (i < nbig) scan[i] = before + incl - segs;
+        __syncthreads();
+        if (threadIdx.x == blockDim.x - 1) carry_s = before + incl;
+        __syncthreads();
+    }
+    (void)nw;
+    if (threadIdx.x == 0) { scan[nbig] = carry_s; tails[T_NTASKS] = carry_s; }
+}
+
+// Long rows of level L: every wave of the owner's team takes an equal run of
+// consecutive 256-edge segments.
+template <bool STAGED>
+__global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
+{
+    __shared__ BfsLds lds;
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint64_t *tails = bfs_tails(c, s, pe);
+    const uint32_t nbig = (uint32_t)tails[T_NBIG], ntasks = (uint32_t)tails[T_NTASKS];
+    if (ntasks == 0) return;
     const uint32_t xcd = xcd_id();
-    const uint64_t nh = bfs_tails(c, s, pe)[T_HUBS];
-    const uint32_t *hubs = (const uint32_t *)ptr(c, s.hub_off, pe);
-    for (uint64_t h = 0; h < nh; ++h) {
-        const uint32_t u = hubs[h];
-        const uint64_t r0 = s.row_off[u], deg = s.row_off[u + 1] - r0;
-        for (uint64_t t0 = my_wave * 64; t0 < deg; t0 += team_waves * 64) {
-            const bool act = t0 + lane < deg;
-            const uint32_t v = act ? s.nbr[r0 + t0 + lane] : 0;
-            bfs_visit(c, s, xcd, act, v, u, L);
+    const Stage st{lds.cnt[wave], lds.buf[wave]};
+    if (STAGED && lane < STAGE_PES) st.cnt[lane] = 0;
+    __builtin_amdgcn_wave_barrier();
+    const uint32_t *big = (const uint32_t *)ptr(c, s.big_off, pe);
+    const uint32_t *scan = (const uint32_t *)ptr(c, s.bigscan_off, pe);
+    const uint32_t per = (uint32_t)((ntasks + team_waves - 1) / team_waves);
+    const uint64_t t0 = my_wave * per;
+    const uint32_t t1 = (uint32_t)(t0 + per < ntasks ? t0 + per : ntasks);
+    if (t0 < ntasks) {
+        uint32_t i = 0;                              // long row that holds segment t0
+        for (uint32_t hi = nbig; hi - i > 1;) {
+            const uint32_t mid = i + (hi - i) / 2;
+            if (scan[mid] <= (uint32_t)t0) i = mid; else hi = mid;
+        }
+        uint32_t first = scan[i], next = scan[i + 1], u = big[i];
+        uint64_t r0 = s.row_off[u], deg = s.row_off[u + 1] - r0;
+        for (uint32_t t = (uint32_t)t0; t < t1; ++t) {
+            while (t >= next) {
+                ++i; first = next; next = scan[i + 1]; u = big[i];
+                r0 = s.row_off[u]; deg = s.row_off[u + 1] - r0;
+            }
+            const uint64_t e0 = (uint64_t)(t - first) * SEG_EDGES;
+            bool act[EPL];
+            uint32_t vv[EPL], uu[EPL];
+#pragma unroll
+            for (uint32_t k = 0; k < EPL; ++k) {
+                const uint64_t e = e0 + k * 64 + lane;
+                act[k] = e < deg;
+                uu[k] = u;
+                vv[k] = act[k] ? __builtin_nontemporal_load(s.nbr + r0 + e) : 0;
+            }
+            bfs_probe<STAGED>(c, s, st, xcd, L, act, vv, uu);
         }
     }
+    bfs_flush<STAGED>(c, s, st, L);
 }
 
-// Level epilogue (one wave): total size of frontier `next`, reset of the hub
-// lists and of the count that level next+1 will fill.
+// Level epilogue (one wave): total size of frontier `next`, reset of the long
+// row counters and of the count that level next+1 will fill.
 __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
 {
     uint64_t total = 0;
@@ -197,7 +381,7 @@ __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
         uint64_t *t = bfs_tails(c, s, pe);
         total += t[T_TAIL0 + next % 3];
         t[T_TAIL0 + (next + 1) % 3] = 0;
-        t[T_HUBS] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0;
     }
     for (int off = 32; off > 0; off >>= 1) total += __shfl_down(total, off, 64);
     if (threadIdx.x == 0) c.scratch[W_WORK] = total;

@@ -41,7 +41,7 @@ struct Host {
 struct BfsGraph {
     shmemx::BfsState st;
     int wgs_per_pe;
-    void *allocs[8];
+    void *allocs[9];
     int nallocs;
 };
 
@@ -459,11 +459,12 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     if (!g) return SHMEM_ERR_NOMEM;
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
     const uint64_t words = ((uint64_t)vpp + 63) / 64;
-    const size_t sizes[8] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
-                             (size_t)vpp * 4, 256, words * 8 * shmemx::NXCD};
-    uint64_t offs[8];
+    // bitmap, level, parent, two queues, long-row list, its segment scan, counters, per-die bitmap copies
+    const size_t sizes[9] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+                             (size_t)vpp * 4, ((size_t)vpp + 1) * 4, 256, words * 8 * shmemx::NXCD};
+    uint64_t offs[9];
     g->nallocs = 0;
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 9; ++i) {
         void *p = shmem_malloc(sizes[i]);
         if (!p) {
             for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
@@ -478,8 +479,8 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.shift = (vpp & (vpp - 1)) == 0 ? (int)__builtin_ctz(vpp) : -1;
     s.row_off = dev_row_off; s.nbr = dev_nbr;
     s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
-    s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.hub_off = offs[5]; s.tails_off = offs[6];
-    s.filter_off = offs[7];
+    s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.big_off = offs[5]; s.bigscan_off = offs[6];
+    s.tails_off = offs[7]; s.filter_off = offs[8];
     s.wgs_per_pe = (uint32_t)wgs_per_pe;
     g->wgs_per_pe = wgs_per_pe;
     *graph_out = g;
@@ -509,12 +510,20 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     shmem_bfs_stats st;
     memset(&st, 0, sizeof st);
     hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
+    const bool staged = H.npes <= (int)shmemx::STAGE_PES;   // winners staged in LDS per owner
     uint64_t *counts = H.pinned + 16;       // [0] frontier total of the next level, [1] degree sum so far
     st.frontier_size[0] = 1;
     uint32_t L = 0;
     for (;;) {
-        hipLaunchKernelGGL(shmemx::k_bfs_expand, grid, block, 0, H.stream, c, s, L);
-        hipLaunchKernelGGL(shmemx::k_bfs_hubs, grid, block, 0, H.stream, c, s, L);
+        if (staged) {
+            hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
+            hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
+            hipLaunchKernelGGL(shmemx::k_bfs_big<true>, grid, block, 0, H.stream, c, s, L);
+        } else {
+            hipLaunchKernelGGL(shmemx::k_bfs_expand<false>, grid, block, 0, H.stream, c, s, L);
+            hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
+            hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
+        }
         hipLaunchKernelGGL(shmemx::k_bfs_count, dim3(1), dim3(64), 0, H.stream, c, s, L + 1);
         if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 16, hipMemcpyDeviceToHost, H.stream) != hipSuccess)
             return SHMEM_ERR_DEVICE;

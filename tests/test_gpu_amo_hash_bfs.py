@@ -229,7 +229,7 @@ def check_tree(row, nbr, root, level, parent):
 def run_bfs_case(row, nbr, roots, npes, wgs):
     n = len(row) - 1
     vpp = -(-n // npes)
-    hb = ((vpp * 24 + vpp // 8 + 16 * 256 + 255) // 256) * 256
+    hb = ((vpp * 28 + vpp // 8 + 16 * 256 + 255) // 256) * 256
     w = oracle.World(npes, hb, oracle.SHUFFLED, 1)
     with shmem_world(npes, hb) as (heap, base):
         drow, dnbr = to_dev(row), to_dev(nbr)
