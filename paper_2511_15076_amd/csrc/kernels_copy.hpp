@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void k_op_batch(Ctx c, const shmem_op_desc *__
 // ---------------------------------------------------------------------------
 // Bandwidth-sweep cell.  All ops of a PE are independent, so the team's waves
 // share the flattened list of (op, chunk) tasks: a chunk is CHUNK_VECS 16-byte
-// vectors per lane (4 KiB per wave for contiguous ops, 1024 elements for
+// vectors per lane (4 KiB per wave for contiguous ops, 2048 elements for
 // strided ones).  Neighbouring waves take neighbouring chunks, so a workgroup
 // streams 16 KiB of consecutive bytes per step.
 struct SweepArgs {
@@ -114,7 +114,8 @@ struct SweepArgs {
 };
 
 constexpr uint64_t CHUNK_BYTES = 4096;  // per wave-task, contiguous ops
-constexpr uint64_t CHUNK_ELEMS = 1024;  // per wave-task, strided ops
+constexpr uint64_t CHUNK_ELEMS = 2048;  // per wave-task, strided ops
+constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size are packed into sub-wave groups
 
 __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
 {
@@ -130,6 +131,24 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
     const uint64_t tasks = chunks * a.ops_per_pe;
     uint8_t *const lbase = ptr(c, a.local_off, pe);
     uint8_t *const rbase = ptr(c, a.remote_off, peer);
+    if (contiguous && a.count <= SMALL_MSG && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 7) == 0) {
+        // Small messages: a sub-group of count/8 lanes (rounded up to a power of two)
+        // moves one message, 8 bytes per lane, so a wave issues 64/group messages at once.
+        uint32_t group = 1;
+        while (group * 8 < a.count) group <<= 1;
+        const uint32_t per_wave = 64 / group, sub = lane / group, j = lane % group;
+        for (uint64_t t = my_wave; t * per_wave < a.ops_per_pe; t += team_waves) {
+            const uint64_t op = t * per_wave + sub;
+            if (op < a.ops_per_pe && (uint64_t)j * 8 < a.count) {
+                const uint64_t slot = op % a.nslots;
+                u32x2 *l = (u32x2 *)(lbase + slot * a.local_slot) + j;
+                u32x2 *r = (u32x2 *)(rbase + slot * a.remote_slot) + j;
+                if (a.kind == SHMEM_OP_PUT) __builtin_nontemporal_store(__builtin_nontemporal_load(l), r);
+                else __builtin_nontemporal_store(__builtin_nontemporal_load(r), l);
+            }
+        }
+        return;
+    }
     for (uint64_t t = my_wave; t < tasks; t += team_waves) {
         const uint64_t op = t / chunks, ch = t - op * chunks;
         const uint64_t slot = op % a.nslots;

@@ -137,7 +137,15 @@ __device__ __forceinline__ void copy_units(V *__restrict__ d, const V *__restric
         __builtin_nontemporal_store(e, d + i + 2 * size);
         __builtin_nontemporal_store(f, d + i + 3 * size);
     }
-    for (; i < nv; i += size) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+    // up to three units are left for this lane: all loads first, then the stores
+    const bool p0 = i < nv, p1 = i + size < nv, p2 = i + 2 * size < nv;
+    V a, b, e;
+    if (p0) a = __builtin_nontemporal_load(s + i);
+    if (p1) b = __builtin_nontemporal_load(s + i + size);
+    if (p2) e = __builtin_nontemporal_load(s + i + 2 * size);
+    if (p0) __builtin_nontemporal_store(a, d + i);
+    if (p1) __builtin_nontemporal_store(b, d + i + size);
+    if (p2) __builtin_nontemporal_store(e, d + i + 2 * size);
 }
 
 __device__ __forceinline__ void copy(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n,
@@ -174,34 +182,27 @@ __device__ __forceinline__ void get(const Ctx &c, uint8_t *dst, uint64_t src_off
 
 // ---------------------------------------------------------------------------
 // Strided copy: d[i * ds] = s[i * ss], i < nelems, strides in elements.
-// When one side is unit-stride and 16-byte aligned, a lane moves 16 / sizeof(T)
-// consecutive elements so that side uses full 16-byte vectors.
+// Lane r takes elements r, r + size, ... (lane-major), so one wave access spans
+// 64 * pitch consecutive bytes on a strided side -- for small pitches a handful
+// of cache lines, each fully used by neighbouring lanes -- and 64 consecutive
+// elements on a unit-stride side.  SIF elements are in flight per lane before
+// the first store.  Only the named elements are written: the gaps of a strided
+// destination may belong to somebody else's concurrent iput.
+constexpr int SIF = 8;
+
 template <typename T>
 __device__ __forceinline__ void strided_t(T *__restrict__ d, const T *__restrict__ s, int64_t ds, int64_t ss,
                                           size_t nelems, size_t rank, size_t size)
 {
-    constexpr size_t VE = 16 / sizeof(T);
-    typedef T vec_t __attribute__((ext_vector_type(VE)));
-    if (VE > 1 && ds == 1 && ((uintptr_t)d & 15) == 0) {           // gather into vectors
-        const size_t ng = nelems / VE;
-        for (size_t g = rank; g < ng; g += size) {
-            vec_t v;
+    size_t i = rank;
+    for (; i + (SIF - 1) * size < nelems; i += SIF * size) {
+        T v[SIF];
 #pragma unroll
-            for (size_t k = 0; k < VE; ++k) v[k] = __builtin_nontemporal_load(s + (g * VE + k) * ss);
-            __builtin_nontemporal_store(v, (vec_t *)d + g);
-        }
-        for (size_t i = ng * VE + rank; i < nelems; i += size) d[i] = s[i * ss];
-    } else if (VE > 1 && ss == 1 && ((uintptr_t)s & 15) == 0) {    // scatter from vectors
-        const size_t ng = nelems / VE;
-        for (size_t g = rank; g < ng; g += size) {
-            vec_t v = __builtin_nontemporal_load((const vec_t *)s + g);
+        for (int k = 0; k < SIF; ++k) v[k] = __builtin_nontemporal_load(s + (i + k * size) * ss);
 #pragma unroll
-            for (size_t k = 0; k < VE; ++k) __builtin_nontemporal_store((T)v[k], d + (g * VE + k) * ds);
-        }
-        for (size_t i = ng * VE + rank; i < nelems; i += size) d[i * ds] = s[i];
-    } else {
-        for (size_t i = rank; i < nelems; i += size) d[i * ds] = s[i * ss];
+        for (int k = 0; k < SIF; ++k) __builtin_nontemporal_store(v[k], d + (i + k * size) * ds);
     }
+    for (; i < nelems; i += size) d[i * ds] = s[i * ss];
 }
 
 __device__ __forceinline__ void strided(uint8_t *d, const uint8_t *s, int64_t ds, int64_t ss, size_t nelems,
