@@ -115,7 +115,7 @@ __device__ __forceinline__ void bfs_enqueue(const Ctx &c, const BfsState &s, con
                 uint64_t base = 0;
                 if (lane == 0) base = atomic_fetch_add(tail, 64);
                 base = bcast64(base, 0);
-                queue[base + lane] = buf[lane];                       // put: one full block
+                __builtin_nontemporal_store(buf[lane], queue + base + lane);   // put: one full block
                 const uint32_t rest = cn - 64;
                 const uint32_t moved = lane < rest ? buf[64 + lane] : 0;
                 __builtin_amdgcn_wave_barrier();
@@ -162,40 +162,54 @@ __device__ __forceinline__ void bfs_flush(const Ctx &c, const BfsState &s, const
 // a fetch_or has shown the vertex to be claimed, so a set bit is always true
 // and a missing bit (first probe from this die, or a lost racy update) only
 // costs one more fetch_or.
-template <bool STAGED>
-__device__ __forceinline__ void bfs_probe(const Ctx &c, const BfsState &s, const Stage &st, uint32_t xcd, uint32_t L,
-                                          const bool (&act)[EPL], const uint32_t (&v)[EPL], const uint32_t (&u)[EPL])
-{
+struct Probe {
     uint32_t o[EPL], l[EPL];
-    uint64_t *f[EPL], known[EPL];
+    uint64_t *f[EPL];
+    uint64_t known[EPL];
+};
+
+// first half: owner, local index and the read of this die's bitmap copy (EPL probes in flight)
+__device__ __forceinline__ void bfs_probe_issue(const Ctx &c, const BfsState &s, uint32_t xcd, Probe &p,
+                                                const bool (&act)[EPL], const uint32_t (&v)[EPL])
+{
 #pragma unroll
-    for (uint32_t k = 0; k < EPL; ++k) {        // EPL cache probes in flight
-        o[k] = 0; l[k] = 0; f[k] = nullptr; known[k] = ~0ull;
+    for (uint32_t k = 0; k < EPL; ++k) {
+        p.o[k] = 0; p.l[k] = 0; p.f[k] = nullptr; p.known[k] = ~0ull;
         if (act[k]) {
-            o[k] = bfs_owner(s, v[k]);
-            l[k] = v[k] - o[k] * s.vpp;
-            f[k] = (uint64_t *)ptr(c, s.filter_off, o[k]) + (uint64_t)xcd * s.words + (l[k] >> 6);
-            known[k] = *f[k];
+            p.o[k] = bfs_owner(s, v[k]);
+            p.l[k] = v[k] - p.o[k] * s.vpp;
+            p.f[k] = (uint64_t *)ptr(c, s.filter_off, p.o[k]) + (uint64_t)xcd * s.words + (p.l[k] >> 6);
+            p.known[k] = *p.f[k];
         }
     }
+}
+
+// second half: claim what is not known to be claimed, deliver parent / level, enqueue the winners
+template <bool STAGED>
+__device__ __forceinline__ void bfs_probe_finish(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L,
+                                                 Probe &p, const bool (&act)[EPL], const uint32_t (&v)[EPL],
+                                                 const uint32_t (&u)[EPL])
+{
     bool won[EPL];
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) {
         won[k] = false;
-        const uint64_t bit = 1ull << (l[k] & 63);
-        if (act[k] && !(known[k] & bit)) {
-            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, o[k]) + (l[k] >> 6);
+        const uint64_t bit = 1ull << (p.l[k] & 63);
+        if (act[k] && !(p.known[k] & bit)) {
+            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6);
             const uint64_t old = atomic_fetch_or(w, bit);                  // the claim
             won[k] = !(old & bit);
-            *f[k] = known[k] | old | bit;     // everything the fetch_or showed to be claimed
+            *p.f[k] = p.known[k] | old | bit;   // everything the fetch_or showed to be claimed
             if (won[k]) {
-                ((uint32_t *)ptr(c, s.parent_off, o[k]))[l[k]] = u[k];           // put parent
-                ((int32_t *)ptr(c, s.level_off, o[k]))[l[k]] = (int32_t)(L + 1); // put level
+                // put parent, put level: streaming stores, so the scattered lines do not push the
+                // bitmap copies out of L2
+                __builtin_nontemporal_store(u[k], (uint32_t *)ptr(c, s.parent_off, p.o[k]) + p.l[k]);
+                __builtin_nontemporal_store((int32_t)(L + 1), (int32_t *)ptr(c, s.level_off, p.o[k]) + p.l[k]);
             }
         }
     }
 #pragma unroll
-    for (uint32_t k = 0; k < EPL; ++k) bfs_enqueue<STAGED>(c, s, st, L, won[k], o[k], v[k]);
+    for (uint32_t k = 0; k < EPL; ++k) bfs_enqueue<STAGED>(c, s, st, L, won[k], p.o[k], v[k]);
 }
 
 // LDS of one workgroup (4 waves)
@@ -213,7 +227,8 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
 {
     __shared__ BfsLds lds;
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps wave state in SGPRs
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
     const uint32_t xcd = xcd_id();
     const Stage st{lds.cnt[wave], lds.buf[wave]};
@@ -231,9 +246,9 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
         uint32_t u = 0, deg = 0;
         uint64_t r0 = 0;
         if (valid) {
-            u = queue[base + lane];
-            r0 = s.row_off[u];
-            deg = (uint32_t)(s.row_off[u + 1] - r0);
+            u = __builtin_nontemporal_load(queue + base + lane);
+            r0 = __builtin_nontemporal_load(s.row_off + u);
+            deg = (uint32_t)(__builtin_nontemporal_load(s.row_off + u + 1) - r0);
         }
         degsum += deg;
         const bool is_big = deg >= BIG_DEGREE;
@@ -256,9 +271,8 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
         if (total == 0) continue;
         pre[lane] = incl - small; su[lane] = u; sr0[lane] = r0;
         __builtin_amdgcn_wave_barrier();
-        for (uint32_t e0 = 0; e0 < total; e0 += 64 * EPL) {
-            bool act[EPL];
-            uint32_t vv[EPL], uu[EPL];
+        // edges e0 .. e0 + 64*EPL of the batch: owning row by binary search over the prefix sums
+        auto fetch = [&](uint32_t e0, bool (&act)[EPL], uint32_t (&vv)[EPL], uint32_t (&uu)[EPL]) {
 #pragma unroll
             for (uint32_t k = 0; k < EPL; ++k) {
                 const uint32_t e = e0 + k * 64 + lane;
@@ -273,7 +287,20 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
                     vv[k] = __builtin_nontemporal_load(s.nbr + sr0[lo] + (e - pre[lo]));
                 }
             }
-            bfs_probe<STAGED>(c, s, st, xcd, L, act, vv, uu);
+        };
+        bool act[EPL], nact[EPL];
+        uint32_t vv[EPL], uu[EPL], nvv[EPL], nuu[EPL];
+        fetch(0, act, vv, uu);
+        for (uint32_t e0 = 0; e0 < total; e0 += 64 * EPL) {
+            Probe pr;
+            bfs_probe_issue(c, s, xcd, pr, act, vv);
+            const bool more = e0 + 64 * EPL < total;
+            if (more) fetch(e0 + 64 * EPL, nact, nvv, nuu);   // next neighbours travel while this chunk is probed
+            bfs_probe_finish<STAGED>(c, s, st, L, pr, act, vv, uu);
+            if (more) {
+#pragma unroll
+                for (uint32_t k = 0; k < EPL; ++k) { act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k]; }
+            }
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -329,7 +356,8 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
 {
     __shared__ BfsLds lds;
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wpw = blockDim.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
     const uint64_t *tails = bfs_tails(c, s, pe);
     const uint32_t nbig = (uint32_t)tails[T_NBIG], ntasks = (uint32_t)tails[T_NTASKS];
@@ -351,14 +379,13 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
         }
         uint32_t first = scan[i], next = scan[i + 1], u = big[i];
         uint64_t r0 = s.row_off[u], deg = s.row_off[u + 1] - r0;
-        for (uint32_t t = (uint32_t)t0; t < t1; ++t) {
+        // neighbours of segment t (the row cursor only moves forward)
+        auto fetch = [&](uint32_t t, bool (&act)[EPL], uint32_t (&vv)[EPL], uint32_t (&uu)[EPL]) {
             while (t >= next) {
                 ++i; first = next; next = scan[i + 1]; u = big[i];
                 r0 = s.row_off[u]; deg = s.row_off[u + 1] - r0;
             }
             const uint64_t e0 = (uint64_t)(t - first) * SEG_EDGES;
-            bool act[EPL];
-            uint32_t vv[EPL], uu[EPL];
 #pragma unroll
             for (uint32_t k = 0; k < EPL; ++k) {
                 const uint64_t e = e0 + k * 64 + lane;
@@ -366,7 +393,20 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
                 uu[k] = u;
                 vv[k] = act[k] ? __builtin_nontemporal_load(s.nbr + r0 + e) : 0;
             }
-            bfs_probe<STAGED>(c, s, st, xcd, L, act, vv, uu);
+        };
+        bool act[EPL], nact[EPL];
+        uint32_t vv[EPL], uu[EPL], nvv[EPL], nuu[EPL];
+        fetch((uint32_t)t0, act, vv, uu);
+        for (uint32_t t = (uint32_t)t0; t < t1; ++t) {
+            Probe pr;
+            bfs_probe_issue(c, s, xcd, pr, act, vv);
+            const bool more = t + 1 < t1;
+            if (more) fetch(t + 1, nact, nvv, nuu);          // next segment travels while this one is probed
+            bfs_probe_finish<STAGED>(c, s, st, L, pr, act, vv, uu);
+            if (more) {
+#pragma unroll
+                for (uint32_t k = 0; k < EPL; ++k) { act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k]; }
+            }
         }
     }
     bfs_flush<STAGED>(c, s, st, L);

@@ -34,28 +34,53 @@ __device__ __forceinline__ void hash_place(const Ctx &c, uint32_t slots, uint64_
     *home = (slots & (slots - 1)) == 0 ? (uint32_t)q & (slots - 1) : (uint32_t)(q % slots);
 }
 
+// Keys in flight per lane: the first probe of each is issued before any of them
+// is examined, so a lane keeps HASH_KIF independent random line fetches going.
+constexpr int HASH_KIF = 4;
+
 __global__ __launch_bounds__(256) void k_hash_insert(Ctx c, HashArgs g)
 {
     const uint32_t pe_self = blockIdx.x / g.wgs_per_pe, wg = blockIdx.x % g.wgs_per_pe;
     const uint64_t begin = (uint64_t)pe_self * g.per_pe;
     const uint64_t end = begin + g.per_pe < g.n ? begin + g.per_pe : g.n;
-    for (uint64_t i = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i < end; i += (uint64_t)g.wgs_per_pe * blockDim.x) {
-        const uint64_t key = __builtin_nontemporal_load(g.keys + i);
-        if (key == 0) { report(c, DEV_ERR_BAD_OP, i); continue; }
-        uint32_t owner, slot;
-        hash_place(c, g.slots, key, &owner, &slot);
-        uint64_t *table = (uint64_t *)ptr(c, g.table_off, owner);
-        uint8_t st = SHMEM_HASH_FULL;
-        for (uint32_t j = 0; j < g.slots; ++j) {
-            // A non-zero word never changes again, so a plain read that shows one is
-            // final; only an empty-looking slot needs the compare-swap.
-            uint64_t seen = table[slot];
-            if (seen == 0) seen = atomic_compare_swap(&table[slot], 0, key);
-            if (seen == 0) { st = SHMEM_HASH_INSERTED; break; }
-            if (seen == key) { st = SHMEM_HASH_DUPLICATE; break; }
-            slot = slot + 1 == g.slots ? 0 : slot + 1;
+    const uint64_t stride = (uint64_t)g.wgs_per_pe * blockDim.x;
+    for (uint64_t i0 = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i0 < end; i0 += stride * HASH_KIF) {
+        uint64_t key[HASH_KIF], seen[HASH_KIF], *table[HASH_KIF];
+        uint32_t slot[HASH_KIF];
+        bool live[HASH_KIF];
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            const uint64_t i = i0 + k * stride;
+            live[k] = i < end;
+            key[k] = live[k] ? __builtin_nontemporal_load(g.keys + i) : 1;
         }
-        if (g.out) g.out[i] = st;
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            uint32_t owner;
+            hash_place(c, g.slots, key[k], &owner, &slot[k]);
+            table[k] = (uint64_t *)ptr(c, g.table_off, owner);
+            seen[k] = 1;
+            if (live[k] && key[k] != 0) seen[k] = table[k][slot[k]];      // first probe
+        }
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            if (!live[k]) continue;
+            const uint64_t i = i0 + k * stride;
+            if (key[k] == 0) { report(c, DEV_ERR_BAD_OP, i); continue; }
+            uint8_t st = SHMEM_HASH_FULL;
+            uint64_t cur = seen[k];
+            uint32_t sl = slot[k];
+            for (uint32_t j = 0; j < g.slots; ++j) {
+                // A non-zero word never changes again, so a plain read that shows one is
+                // final; only an empty-looking slot needs the compare-swap.
+                if (j) cur = table[k][sl];
+                if (cur == 0) cur = atomic_compare_swap(&table[k][sl], 0, key[k]);
+                if (cur == 0) { st = SHMEM_HASH_INSERTED; break; }
+                if (cur == key[k]) { st = SHMEM_HASH_DUPLICATE; break; }
+                sl = sl + 1 == g.slots ? 0 : sl + 1;
+            }
+            if (g.out) g.out[i] = st;
+        }
     }
 }
 
@@ -64,19 +89,40 @@ __global__ __launch_bounds__(256) void k_hash_lookup(Ctx c, HashArgs g)
     const uint32_t pe_self = blockIdx.x / g.wgs_per_pe, wg = blockIdx.x % g.wgs_per_pe;
     const uint64_t begin = (uint64_t)pe_self * g.per_pe;
     const uint64_t end = begin + g.per_pe < g.n ? begin + g.per_pe : g.n;
-    for (uint64_t i = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i < end; i += (uint64_t)g.wgs_per_pe * blockDim.x) {
-        const uint64_t key = __builtin_nontemporal_load(g.keys + i);
-        uint32_t owner, slot;
-        hash_place(c, g.slots, key, &owner, &slot);
-        const uint64_t *table = (const uint64_t *)ptr(c, g.table_off, owner);
-        uint8_t found = 0;
-        for (uint32_t j = 0; j < g.slots; ++j) {
-            const uint64_t seen = table[slot];           // an 8-byte get from the owner
-            if (seen == key) { found = 1; break; }
-            if (seen == 0) break;
-            slot = slot + 1 == g.slots ? 0 : slot + 1;
+    const uint64_t stride = (uint64_t)g.wgs_per_pe * blockDim.x;
+    for (uint64_t i0 = begin + (uint64_t)wg * blockDim.x + threadIdx.x; i0 < end; i0 += stride * HASH_KIF) {
+        uint64_t key[HASH_KIF], seen[HASH_KIF];
+        const uint64_t *table[HASH_KIF];
+        uint32_t slot[HASH_KIF];
+        bool live[HASH_KIF];
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            const uint64_t i = i0 + k * stride;
+            live[k] = i < end;
+            key[k] = live[k] ? __builtin_nontemporal_load(g.keys + i) : 0;
         }
-        g.out[i] = found;
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            uint32_t owner;
+            hash_place(c, g.slots, key[k], &owner, &slot[k]);
+            table[k] = (const uint64_t *)ptr(c, g.table_off, owner);
+            seen[k] = 0;
+            if (live[k]) seen[k] = table[k][slot[k]];                     // an 8-byte get from the owner
+        }
+#pragma unroll
+        for (int k = 0; k < HASH_KIF; ++k) {
+            if (!live[k]) continue;
+            uint8_t found = 0;
+            uint64_t cur = seen[k];
+            uint32_t sl = slot[k];
+            for (uint32_t j = 0; j < g.slots; ++j) {
+                if (j) cur = table[k][sl];
+                if (cur == key[k]) { found = 1; break; }
+                if (cur == 0) break;
+                sl = sl + 1 == g.slots ? 0 : sl + 1;
+            }
+            g.out[i0 + k * stride] = found;
+        }
     }
 }
 
