@@ -129,6 +129,60 @@ def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
     return {"unit": "Mops/s", "ops": n, "npes": npes, "wgs_per_pe": wgs, "cells": res}
 
 
+def extra_config1(sh, torch, wgs=2):
+    """Configuration 1: 10,000 random puts/gets (8 B..4 KiB) on 4 PEs, barrier every 100, one launch."""
+    import numpy as np
+    import workgen
+    dev = torch.device("cuda:0")
+    npes, seg = 4, 1 << 20
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    heap.view(torch.int64).random_()
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    ops = workgen.cfg1_op_table()
+    d_ops = torch.from_numpy(ops.view(np.uint8).reshape(-1)).to(dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        res = {}
+        for w in (1, wgs, 8):
+            ms = _median_ms(lambda: sh.op_batch(d_ops, len(ops), 100, w), lambda: None, reps=5, warm=2)
+            res[f"wgs{w}"] = {"ms": round(ms, 4), "us_per_batch_of_100": round(ms * 10, 3),
+                             "Mops_per_s": round(len(ops) / ms / 1e3, 2)}
+        sh.stream_sync()
+    finally:
+        sh.finalize()
+    return {"ops": int(len(ops)), "payload_bytes": int(ops["count"].sum()), "npes": npes, "cells": res}
+
+
+def extra_latency(sh, torch):
+    """Put-with-signal ping-pong between two PEs on different dies (the paper's latency experiment,
+    Sec. V-A, here inside one GPU) and the in-kernel world barrier."""
+    dev = torch.device("cuda:0")
+    npes, seg = 16, 16 << 20
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        base = heap.data_ptr()
+        sig = base + (8 << 20) + 4096
+        hv = heap.view(npes, seg)
+        pp = {}
+        for nbytes in (8, 128, 4096, 65536, 1 << 20, 4 << 20):
+            iters = 2000 if nbytes <= 65536 else 200
+            ms = _median_ms(lambda: sh.pingpong(base, nbytes, sig, iters),
+                            lambda: hv[:2, (8 << 20) + 4096:(8 << 20) + 4104].zero_(), reps=3, warm=1)
+            pp[str(nbytes)] = round(ms * 1e3 / iters, 3)            # us per round trip
+        slots = base + (12 << 20)
+        bar = {}
+        for wgs in (1, 4, 16):
+            rounds = 2000
+            ms = _median_ms(lambda: sh.barrier_epochs(slots, rounds, wgs, None), lambda: None, reps=3, warm=1)
+            bar[f"{npes}x{wgs}_wgs"] = round(ms * 1e3 / rounds, 3)  # us per put-all + barrier_all round
+        sh.stream_sync()
+    finally:
+        sh.finalize()
+    return {"pingpong_round_trip_us": pp, "barrier_round_us": bar}
+
+
 def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=128):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
@@ -270,8 +324,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--wgs-per-pe", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="amo,hash,bfs",
-                    help="comma list of the other configurations to measure too (amo, hash, bfs) or 'none'")
+    ap.add_argument("--extras", default="cfg1,latency,amo,hash,bfs",
+                    help="comma list of the other measurements to run too (cfg1, latency, amo, hash, bfs) or 'none'")
     ap.add_argument("--bfs-scale", type=int, default=24)
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="run the whole configuration-2 sweep instead of the headline and write its cells to FILE")
@@ -372,6 +426,10 @@ def main():
     torch.cuda.empty_cache()
     want = [] if args.extras == "none" else args.extras.split(",")
     extras = {}
+    if "cfg1" in want:
+        extras["config1_optable"] = extra_config1(sh, torch)
+    if "latency" in want:
+        extras["latency"] = extra_latency(sh, torch)
     if "amo" in want:
         extras["config3_amo"] = extra_amo(sh, torch)
         torch.cuda.empty_cache()

@@ -223,6 +223,40 @@ int shmem_bfs_destroy(void *graph);
  * than 64 levels), DEVICE. */
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
 
+/* ---- in-kernel ordering: put -> signal, waitSignal, barrier (Sec. III-A, III-B) ---- */
+
+/* The unidirectional ring exchange of Listing 2, `rounds` times in one
+ * persistent launch of npes * wgs_per_pe workgroups.  In each round PE r puts
+ * bytes [peer*slot_bytes, +slot_bytes) of its send buffer (peer = (r+1) mod
+ * npes) into bytes [r*slot_bytes, +slot_bytes) of the peer's receive buffer,
+ * then adds 1 to the peer's signal word -- an atomic add that lands only after
+ * the put is visible -- and waits until its own signal word shows that round's
+ * arrival.  After the last round all PEs meet in a barrier and reset their
+ * signal word to 0.  send_sym / recv_sym: symmetric, npes * slot_bytes each, not
+ * overlapping; signal_sym: symmetric uint64, 0 before the call.  The waits are
+ * bounded; a time-out sets the device fault word.
+ * Errors: NOT_INIT, INVALID_ARG (also: more workgroups than can be
+ * co-resident), ALIGN, OUT_OF_RANGE, DEVICE. */
+int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, uint64_t *signal_sym, int rounds,
+                        int wgs_per_pe);
+
+/* Put-with-signal ping-pong (the latency experiment of Sec. V-A) between PE 0
+ * and PE 1, one workgroup each: PE 0 puts nbytes from its copy of buf_sym into
+ * PE 1's copy and signals; PE 1 waits, puts what it received into PE 0's second
+ * buffer (buf_sym + nbytes rounded up to 256) and signals back; `iters` round
+ * trips.  Both signal words (signal_sym on PE 0 and PE 1) must be 0 before the
+ * call and hold `iters` after it.  buf_sym spans 2 * roundup(nbytes, 256) bytes.
+ * Errors as above. */
+int shmem_pingpong(void *buf_sym, size_t nbytes, uint64_t *signal_sym, int iters);
+
+/* Barrier epochs: in round e = 1..rounds every PE puts the value e into word
+ * `pe` of slots_sym (uint64[npes], symmetric) on EVERY PE, all PEs meet in the
+ * in-kernel barrier_all (quiet + synchronisation), and every PE checks that each
+ * word of its own copy is at least e.  *dev_errors (DEVICE uint64, may be NULL)
+ * is incremented once per violation; afterwards every word equals `rounds`.
+ * Errors as above. */
+int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors);
+
 #ifdef __cplusplus
 }
 #endif

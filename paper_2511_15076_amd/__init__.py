@@ -69,6 +69,9 @@ _SIG = {
     "shmem_bfs_create": (_i, [C.c_uint32, _vp, _vp, _i, C.POINTER(_vp)]),
     "shmem_bfs_destroy": (_i, [_vp]),
     "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
+    "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i]),
+    "shmem_pingpong": (_i, [_vp, _sz, _vp, _i]),
+    "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_L, _name)
@@ -229,3 +232,17 @@ def bfs(graph, root, dev_level=None, dev_parent=None):
     _check(_L.shmem_bfs(graph, int(root), _addr(dev_level), _addr(dev_parent), C.byref(st)), "shmem_bfs")
     return {"nlevels": st.nlevels, "reached": st.reached, "edges_traversed": st.edges_traversed,
             "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}
+
+
+def ring_exchange(recv_sym, send_sym, slot_bytes, signal_sym, rounds=1, wgs_per_pe=1):
+    return _check(_L.shmem_ring_exchange(_addr(recv_sym), _addr(send_sym), slot_bytes, _addr(signal_sym),
+                                         rounds, wgs_per_pe), "shmem_ring_exchange")
+
+
+def pingpong(buf_sym, nbytes, signal_sym, iters):
+    return _check(_L.shmem_pingpong(_addr(buf_sym), nbytes, _addr(signal_sym), iters), "shmem_pingpong")
+
+
+def barrier_epochs(slots_sym, rounds, wgs_per_pe, dev_errors=None):
+    return _check(_L.shmem_barrier_epochs(_addr(slots_sym), rounds, wgs_per_pe, _addr(dev_errors)),
+                  "shmem_barrier_epochs")

@@ -68,32 +68,46 @@ __global__ __launch_bounds__(256) void k_op_batch(Ctx c, const shmem_op_desc *__
 {
     const uint32_t pe = blockIdx.x / (uint32_t)wgs_per_pe;
     const uint32_t wg = blockIdx.x % (uint32_t)wgs_per_pe;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves_per_wg = blockDim.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, waves_per_wg = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t team_waves = (uint32_t)wgs_per_pe * waves_per_wg;
     const uint32_t my_wave = wg * waves_per_wg + wave;
     const size_t window = quiet_every ? quiet_every : n;
     for (size_t b = 0; b < n; b += window) {
         const size_t e = b + window < n ? b + window : n;
         uint32_t mine = 0;  // small ops of this PE seen so far in the window
-        for (size_t i = b; i < e; ++i) {
-            const shmem_op_desc d = ops[i];
-            if (d.pe_self != pe) {
-                if (d.pe_self >= (uint32_t)c.npes && blockIdx.x == 0 && threadIdx.x == 0) report(c, DEV_ERR_BAD_OP, i);
-                continue;
-            }
-            if (!desc_valid(c, d)) {
-                if (wg == 0 && threadIdx.x == 0) report(c, DEV_ERR_BAD_OP, i);
-                continue;
-            }
-            const uint64_t bytes = (d.kind <= SHMEM_OP_GET) ? d.count : d.count * d.elem_bytes;
-            if (bytes > BIG_OP) {
-                desc_exec(c, d, (size_t)my_wave * 64 + lane, (size_t)team_waves * 64);
-            } else {
-                if (mine % team_waves == my_wave) desc_exec(c, d, lane, 64);
-                ++mine;
+        // 64 descriptors at a time: lane j reads descriptor j (one coalesced 4 KiB read), a ballot
+        // finds this PE's ones, and their fields are broadcast from the lane that holds them
+        for (size_t i0 = b; i0 < e; i0 += 64) {
+            shmem_op_desc d;
+            d.kind = ~0u; d.pe_self = ~0u; d.pe = 0; d.elem_bytes = 0; d.local_off = d.sym_off = d.count = 0;
+            d.local_stride = d.sym_stride = 0; d.value = 0;
+            const bool have = i0 + lane < e;
+            if (have) d = ops[i0 + lane];
+            if (have && d.pe_self >= (uint32_t)c.npes && blockIdx.x == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
+            const bool ok = have && d.pe_self == pe && desc_valid(c, d);
+            if (have && d.pe_self == pe && !ok && wg == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
+            uint64_t todo = ballot(ok);
+            while (todo) {
+                const uint32_t j = (uint32_t)__builtin_ctzll(todo);
+                todo &= todo - 1;
+                shmem_op_desc u;                      // descriptor j, now uniform across the wave
+                u.kind = bcast32(d.kind, j); u.pe_self = pe; u.pe = bcast32(d.pe, j);
+                u.elem_bytes = bcast32(d.elem_bytes, j);
+                u.local_off = bcast64(d.local_off, j); u.sym_off = bcast64(d.sym_off, j);
+                u.count = bcast64(d.count, j);
+                u.local_stride = (int64_t)bcast64((uint64_t)d.local_stride, j);
+                u.sym_stride = (int64_t)bcast64((uint64_t)d.sym_stride, j);
+                const uint64_t bytes = (u.kind <= SHMEM_OP_GET) ? u.count : u.count * u.elem_bytes;
+                if (bytes > BIG_OP) {
+                    desc_exec(c, u, (size_t)my_wave * 64 + lane, (size_t)team_waves * 64);
+                } else {
+                    if (mine % team_waves == my_wave) desc_exec(c, u, lane, 64);
+                    ++mine;
+                }
             }
         }
-        barrier_all(c);  // quiet by every wave, then all teams synchronise
+        barrier_all(c, pe, (uint32_t)wgs_per_pe);  // quiet by every wave, then all teams synchronise
     }
 }
 

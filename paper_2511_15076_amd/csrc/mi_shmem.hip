@@ -16,6 +16,7 @@
 #include "kernels_amo.hpp"
 #include "kernels_hash.hpp"
 #include "kernels_bfs.hpp"
+#include "kernels_sync.hpp"
 
 namespace {
 
@@ -542,6 +543,69 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     }
     if (stats) *stats = st;
     return launched();
+}
+
+// ---------------------------------------------------------------------------
+int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, uint64_t *signal_sym, int rounds,
+                        int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)signal_sym % 8) return SHMEM_ERR_ALIGN;
+    unsigned __int128 span = (unsigned __int128)slot_bytes * (unsigned)H.npes;
+    if (span > H.seg) return SHMEM_ERR_OUT_OF_RANGE;
+    uint64_t roff, soff, goff;
+    if (int rc = sym_off(recv_sym, (uint64_t)span, &roff)) return rc;
+    if (int rc = sym_off(send_sym, (uint64_t)span, &soff)) return rc;
+    if (int rc = sym_off(signal_sym, 8, &goff)) return rc;
+    if (roff < soff + (uint64_t)span && soff < roff + (uint64_t)span && span) return SHMEM_ERR_INVALID_ARG;
+    if (rounds == 0) return SHMEM_OK;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_ring_exchange)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    uint64_t ds = slot_bytes;
+    uint32_t r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
+    void *args[] = {&c, &roff, &soff, &ds, &goff, &r, &w};
+    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_ring_exchange, dim3((unsigned)grid),
+                                             dim3(WG_THREADS), args, 0, H.stream));
+}
+
+int shmem_pingpong(void *buf_sym, size_t nbytes, uint64_t *signal_sym, int iters)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (H.npes < 2 || iters < 0) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)signal_sym % 8) return SHMEM_ERR_ALIGN;
+    const uint64_t padded = ((uint64_t)nbytes + 255) / 256 * 256;
+    if (padded > H.seg / 2) return SHMEM_ERR_OUT_OF_RANGE;
+    uint64_t boff, goff;
+    if (int rc = sym_off(buf_sym, 2 * padded, &boff)) return rc;
+    if (int rc = sym_off(signal_sym, 8, &goff)) return rc;
+    if (goff < boff + 2 * padded && boff < goff + 8) return SHMEM_ERR_INVALID_ARG;
+    if (iters == 0) return SHMEM_OK;
+    if (2 > max_resident_wgs(shmemx::k_pingpong)) return SHMEM_ERR_DEVICE;
+    shmemx::Ctx c = ctx();
+    uint64_t nb = nbytes;
+    uint32_t it = (uint32_t)iters;
+    void *args[] = {&c, &boff, &nb, &goff, &it};
+    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_pingpong, dim3(2), dim3(WG_THREADS), args, 0,
+                                             H.stream));
+}
+
+int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)slots_sym % 8 || (uintptr_t)dev_errors % 8) return SHMEM_ERR_ALIGN;
+    uint64_t off;
+    if (int rc = sym_off(slots_sym, 8ull * (uint64_t)H.npes, &off)) return rc;
+    if (rounds == 0) return SHMEM_OK;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_barrier_epochs)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    uint32_t r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
+    void *args[] = {&c, &off, &r, &w, &dev_errors};
+    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid),
+                                             dim3(WG_THREADS), args, 0, H.stream));
 }
 
 }  // extern "C"

@@ -25,8 +25,8 @@ enum : uint32_t {
     W_BAR_COUNT = 16,   // world barrier: arrivals
     W_BAR_GEN = 32,     // world barrier: generation
     W_WORK = 48,        // 16 general-purpose counters (BFS edge sum, ...)
-    W_PE_BASE = 64,     // per PE: 32 words; +0 team arrivals, +16 team generation
-    W_PE_WORDS = 32
+    W_PE_BASE = 64,     // per PE: 64 words; +0 / +16 team barrier arrivals / generation,
+    W_PE_WORDS = 64     //               +32 / +48 the team's stage of the world barrier
 };
 enum : uint64_t { DEV_ERR_BAD_OP = 1, DEV_ERR_BARRIER_TIMEOUT = 2, DEV_ERR_BAD_TARGET = 3 };
 
@@ -44,6 +44,14 @@ __device__ __forceinline__ void report(const Ctx &c, uint64_t code, uint64_t ind
                                              (unsigned long long)code, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                              SHMEMX_AGENT))
         __hip_atomic_store(&c.scratch[W_ERR_INDEX], index, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
+
+constexpr uint32_t SPIN_LIMIT = 1u << 20;  // polls before a device-side wait gives up
+
+// true once some wait of this launch has timed out
+__device__ __forceinline__ bool timed_out(const Ctx &c)
+{
+    return __hip_atomic_load(&c.scratch[W_ERR_FLAG], __ATOMIC_RELAXED, SHMEMX_AGENT) == DEV_ERR_BARRIER_TIMEOUT;
 }
 
 // ---------------------------------------------------------------------------
@@ -77,40 +85,90 @@ __device__ __forceinline__ void quiet() { __builtin_amdgcn_fence(__ATOMIC_RELEAS
 __device__ __forceinline__ void fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 __device__ __forceinline__ void acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
-// Sense-reversing barrier over `nwg` workgroups that share (count, gen).
-// Implies quiet before and acquire after.  Every participating workgroup must
-// be resident (the host checks the grid against the occupancy limit and uses
-// a cooperative launch).  The wait is bounded: on time-out the fault word is
-// set and the caller continues, so the grid always drains.
-__device__ __forceinline__ void barrier(const Ctx &c, uint64_t *count, uint64_t *gen, uint32_t nwg)
+// The device-scope release and acquire around a barrier are cache maintenance
+// on the die's L2 (write back dirty lines / drop stale ones), so one wave per
+// workgroup performs them: every wave first completes its own stores
+// (workgroup-scope release) and meets the others; wave 0 then releases at
+// device scope, synchronises with the other workgroups and acquires at device
+// scope -- the L1 it invalidates is the one all waves of the workgroup share --
+// before the workgroup continues.
+__device__ __forceinline__ void wg_release()
 {
-    quiet();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint64_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT);
-        uint64_t a = __hip_atomic_fetch_add(count, 1ull, __ATOMIC_ACQ_REL, SHMEMX_AGENT);
-        if (a == nwg - 1) {
-            __hip_atomic_store(count, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
-            __hip_atomic_store(gen, g + 1, __ATOMIC_RELEASE, SHMEMX_AGENT);
-        } else {
-            uint32_t spins = 0;
-            while (__hip_atomic_load(gen, __ATOMIC_ACQUIRE, SHMEMX_AGENT) == g) {
-                __builtin_amdgcn_s_sleep(4);
-                if (++spins > (1u << 24)) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); break; }
-            }
-        }
+}
+__device__ __forceinline__ void wg_acquire()
+{
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// One arrival at a sense-reversing barrier word pair (thread 0 of a workgroup).
+// Returns true for the last of `n` arrivals, which must call barrier_open when
+// it is ready to let the others go; everybody else returns after the wait.
+// Waits are bounded (about a second); once any wait of a launch has timed out
+// the fault word is set and every later wait gives up at once, so a broken
+// launch still drains quickly.
+__device__ __forceinline__ bool barrier_arrive(const Ctx &c, uint64_t *count, uint64_t *gen, uint32_t n,
+                                               uint64_t *my_gen)
+{
+    // All atomics here are relaxed: the caller's quiet() before and acquire() after are the
+    // fences.  (An acquire on every poll would invalidate the die's L2 once per poll.)
+    const uint64_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    *my_gen = g;
+    const uint64_t a = __hip_atomic_fetch_add(count, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    if (a == n - 1) {
+        __hip_atomic_store(count, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        return true;
     }
-    __syncthreads();
-    acquire();
+    uint32_t spins = 0;
+    while (!timed_out(c) && __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT) == g) {
+        __builtin_amdgcn_s_sleep(2);
+        if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); break; }
+    }
+    return false;
 }
-__device__ __forceinline__ void barrier_all(const Ctx &c)
+// The last arriver has read every other arrival; the fence makes what they released part of
+// what the waiters acquire when they see the new generation.
+__device__ __forceinline__ void barrier_open(uint64_t *gen, uint64_t my_gen)
 {
-    barrier(c, &c.scratch[W_BAR_COUNT], &c.scratch[W_BAR_GEN], gridDim.x);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "agent");
+    __hip_atomic_store(gen, my_gen + 1, __ATOMIC_RELAXED, SHMEMX_AGENT);
 }
+
+// Team barrier: the workgroups of one PE.  Implies a PE-wide quiet before and
+// an acquire after.  Every participating workgroup must be resident (the host checks the
+// grid against the occupancy limit and uses a cooperative launch).
 __device__ __forceinline__ void team_barrier(const Ctx &c, uint32_t pe, uint32_t wgs_per_pe)
 {
-    uint64_t *w = &c.scratch[W_PE_BASE + pe * W_PE_WORDS];
-    barrier(c, w, w + 16, wgs_per_pe);
+    wg_release();
+    if (threadIdx.x == 0) {
+        quiet();
+        uint64_t *w = &c.scratch[W_PE_BASE + pe * W_PE_WORDS], g;
+        if (barrier_arrive(c, w, w + 16, wgs_per_pe, &g)) barrier_open(w + 16, g);
+        acquire();
+    }
+    wg_acquire();
+}
+
+// World barrier (barrier_all): quiet by every wave, then two stages so that no
+// word is hammered by more than max(wgs_per_pe, npes) workgroups -- the
+// workgroups of a team meet on the team's words, the last one of each team
+// meets the other teams on the world words and then releases its team.
+__device__ __forceinline__ void barrier_all(const Ctx &c, uint32_t pe, uint32_t wgs_per_pe)
+{
+    wg_release();
+    if (threadIdx.x == 0) {
+        quiet();
+        uint64_t *t = &c.scratch[W_PE_BASE + pe * W_PE_WORDS + 32], tg, wg_;
+        if (barrier_arrive(c, t, t + 16, wgs_per_pe, &tg)) {
+            if (barrier_arrive(c, &c.scratch[W_BAR_COUNT], &c.scratch[W_BAR_GEN], (uint32_t)c.npes, &wg_))
+                barrier_open(&c.scratch[W_BAR_GEN], wg_);
+            barrier_open(t + 16, tg);
+        }
+        acquire();
+    }
+    wg_acquire();
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,116 @@
+"""GPU parity for in-kernel ordering: put -> signal (the ring exchange of
+Listing 2), the put-with-signal ping-pong, and barrier epochs.  These run as
+persistent launches with teams on different dies, so a reader only sees fresh
+data if quiet / signal / barrier really release and acquire at device scope."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workgen
+
+pytestmark = pytest.mark.gpu
+
+sh = pytest.importorskip("paper_2511_15076_amd")
+from gpu_util import as_np, heaps_of, shmem_world  # noqa: E402
+
+
+def golden_ring_cases(golden_dir):
+    return [tuple(map(int, l.split())) for l in open(f"{golden_dir}/ring_exchange.txt")
+            if l.strip() and not l.startswith("#")]
+
+
+@pytest.mark.parametrize("wgs,rounds", [(1, 1), (3, 1), (2, 25)])
+def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
+    for n, ds in golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000)]:
+        span = n * ds
+        send, recv = 0, (span + 255) // 256 * 256
+        sig = 2 * recv
+        hb = (sig + 256 + 255) // 256 * 256
+        init = np.stack([workgen.random_words(300 + p + ds, hb // 8).view(np.uint8) for p in range(n)])
+        init[:, sig:sig + 8] = 0
+        w = oracle.World(n, hb, oracle.SHUFFLED, 2)
+        for p in range(n):
+            w.heap(p)[:] = init[p]
+        for _ in range(rounds):
+            for r in range(n):
+                peer = (r + 1) % n
+                assert w.put(r, recv + r * ds, send + peer * ds, ds, peer) == 0
+                assert w.signal_add(r, sig, 1, peer) == 0
+            for p in range(n):
+                assert int(w.heap(p)[sig:sig + 8].view(np.uint64)[0]) >= 1
+        for p in range(n):
+            w.heap(p)[sig:sig + 8] = 0                        # reset for the next use
+        with shmem_world(n, hb) as (heap, base):
+            heap.copy_(torch.from_numpy(init.reshape(-1)))
+            sh.ring_exchange(base + recv, base + send, ds, base + sig, rounds, wgs)
+            sh.stream_sync()
+            got = heaps_of(heap, n)
+        assert np.array_equal(got, w.heaps()), (n, ds)
+        for p in range(n):                                    # the worked example, spelled out
+            q = (p - 1 + n) % n
+            assert np.array_equal(got[p][recv + q * ds: recv + (q + 1) * ds],
+                                  init[q][send + p * ds: send + (p + 1) * ds])
+
+
+@pytest.mark.parametrize("nbytes", [8, 128, 4096, 14352, 1 << 20])
+def test_pingpong(nbytes):
+    npes, iters = 4, 200
+    pad = (nbytes + 255) // 256 * 256
+    buf, sig = 0, 2 * pad
+    hb = (sig + 512 + 255) // 256 * 256
+    init = np.stack([workgen.random_words(900 + p, hb // 8).view(np.uint8) for p in range(npes)])
+    init[:, sig:sig + 8] = 0
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 3)
+    for p in range(npes):
+        w.heap(p)[:] = init[p]
+    for _ in range(3):                                        # the result is the same after any number of trips
+        w.put(0, buf, buf, nbytes, 1); w.signal_add(0, sig, 1, 1)
+        w.put(1, buf + pad, buf, nbytes, 0); w.signal_add(1, sig, 1, 0)
+    w.heap(0)[sig:sig + 8].view(np.uint64)[0] = iters
+    w.heap(1)[sig:sig + 8].view(np.uint64)[0] = iters
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.pingpong(base + buf, nbytes, base + sig, iters)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+    assert np.array_equal(got[0][pad:pad + nbytes], init[0][:nbytes])   # the payload came back
+
+
+@pytest.mark.parametrize("npes,wgs,rounds", [(16, 2, 10000), (64, 1, 2000), (5, 3, 3000)])
+def test_barrier_epochs(npes, wgs, rounds):
+    hb = 4096
+    with shmem_world(npes, hb) as (heap, base):
+        slots = sh.malloc(8 * npes)
+        err = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        sh.barrier_epochs(slots, rounds, wgs, err)
+        sh.stream_sync()
+        assert int(err.item()) == 0                            # nobody left a barrier early
+        got = heaps_of(heap, npes)
+        off = slots - base
+    w = oracle.World(npes, hb, oracle.AT_QUIET, 0)
+    assert w.malloc(8 * npes) == off
+    for p in range(npes):                                     # the last round decides the final state
+        for q in range(npes):
+            w.put_value(p, off + 8 * p, rounds, 8, q)
+    w.barrier_all()
+    assert np.array_equal(got, w.heaps())
+
+
+def test_sync_entry_point_errors():
+    with shmem_world(4, 1 << 16) as (heap, base):
+        for call, status in [
+            (lambda: sh.ring_exchange(base, base + 128, 256, base + 8192, 1, 1), sh.ERR_INVALID_ARG),   # overlap
+            (lambda: sh.ring_exchange(base + 4096, base, 256, base + 8196, 1, 1), sh.ERR_ALIGN),
+            (lambda: sh.ring_exchange(base + 4096, base, 1 << 15, base + 8192, 1, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.ring_exchange(base + 4096, base, 256, base + 8192, 1, 100000), sh.ERR_INVALID_ARG),
+            (lambda: sh.pingpong(base, 1 << 16, base + 8192, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.pingpong(base, 4096, base + 4096, 1), sh.ERR_INVALID_ARG),                     # signal inside
+            (lambda: sh.barrier_epochs(base + 4, 1, 1), sh.ERR_ALIGN),
+            (lambda: sh.barrier_epochs(base, 1, 0), sh.ERR_INVALID_ARG),
+        ]:
+            with pytest.raises(sh.ShmemError) as e:
+                call()
+            assert e.value.status == status
+        sh.stream_sync()
