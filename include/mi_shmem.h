@@ -29,6 +29,11 @@
  * device can see (a bad descriptor inside a device-resident table) set a
  * device error word, skip that op and surface at shmem_stream_sync().
  * No exceptions, no abort(), nothing printed.
+ *
+ * The library keeps ONE context per process (init ... finalize).  The allocator
+ * calls take a lock; everything else expects one calling thread at a time.
+ * All entry points are stream-ordered except shmem_bfs, shmem_stream_sync,
+ * shmem_init and shmem_finalize, which block the host.
  */
 #ifndef MI_SHMEM_H
 #define MI_SHMEM_H

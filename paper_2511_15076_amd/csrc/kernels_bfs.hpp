@@ -12,7 +12,7 @@
 //   k_bfs_bigscan  prefix sum over the long rows' segment counts (one
 //                  workgroup per PE);
 //   k_bfs_big      the team's waves split the long rows' 256-edge segments
-//                  evenly;
+//                  evenly (each wave takes a run of consecutive segments);
 //   k_bfs_count    one wave totals the next frontier and resets counters.
 #pragma once
 #include "../../include/mi_shmem.h"
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(1024) void k_bfs_bigscan(Ctx c, BfsState s)
 {
     __shared__ uint32_t wsum[16];
     __shared__ uint32_t carry_s;
-    const uint32_t pe = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    const uint32_t pe = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint64_t *tails = bfs_tails(c, s, pe);
     const uint32_t nbig = (uint32_t)tails[T_NBIG];
     const uint32_t *big = (const uint32_t *)ptr(c, s.big_off, pe);
@@ -345,7 +345,6 @@ __global__ __launch_bounds__(1024) void k_bfs_bigscan(Ctx c, BfsState s)
         if (threadIdx.x == blockDim.x - 1) carry_s = before + incl;
         __syncthreads();
     }
-    (void)nw;
     if (threadIdx.x == 0) { scan[nbig] = carry_s; tails[T_NTASKS] = carry_s; }
 }
 

@@ -244,16 +244,11 @@ def test_config1_table_every_delivery_order_and_byte_model(nops, npes, hb):
 def test_racy_table_is_detected_by_shuffle():
     # two puts to one target range inside one quiet window: the result depends
     # on the delivery seed, which is how a racy generator would be caught
-    ops = np.zeros(2, dtype=workgen.OP_DESC)
-    ops["kind"] = workgen.OP_PUT
-    ops["pe_self"] = [0, 1]; ops["pe"] = 2
-    ops["local_off"] = 0; ops["sym_off"] = 64; ops["count"] = 8
     seen = set()
     for seed in range(32):
         w = oracle.World(3, HB, oracle.SHUFFLED, seed)
-        w.heap(0)[0:8] = 1; w.heap(1)[0:8] = 2
-        # one initiator per put: order across initiators follows the PE loop,
-        # so race two puts of the same initiator instead
+        w.heap(0)[0:8] = 1
+        # two puts of one initiator to the same target bytes, no fence between them
         w.put(0, 64, 0, 8, 2)
         w.heap(0)[0:8] = 3
         w.put(0, 64, 0, 8, 2)
