@@ -67,6 +67,49 @@ def cpu_baseline(seconds=12.0):
             "sample": f"{k} ring rounds of put+quiet / get over sizes {SIZES} B, 8 PEs, {dt:.1f} s of CPU time"}
 
 
+def cpu_baseline_extras():
+    """The oracle timed (one core) on bounded samples of the other configurations, in each one's unit."""
+    import numpy as np
+    import oracle
+    import workgen
+    out = {}
+    # config 1: the whole table (it is small)
+    ops = workgen.cfg1_op_table()
+    w = oracle.World(4, 1 << 20, oracle.AT_QUIET, 0)
+    t0 = time.perf_counter(); w.op_batch(ops, 100); dt = time.perf_counter() - t0
+    out["config1_optable"] = {"Mops_per_s": round(len(ops) / dt / 1e6, 3), "sample": "all 10,000 ops"}
+    w.close()
+    # config 3: 2^22 fetch-adds, T = 1024, uniform
+    n = 1 << 22
+    pe, idx, a = workgen.cfg3_amo_ops(n=n, npes=64, T=1024, dist="uniform", addend="rand16")
+    w = oracle.World(64, 1 << 16, oracle.AT_QUIET, 0)
+    t0 = time.perf_counter(); w.amo_batch(oracle.AMO_FETCH_ADD, 0, pe, idx, a); dt = time.perf_counter() - t0
+    out["config3_amo"] = {"Mops_per_s": round(n / dt / 1e6, 2), "sample": "2^22 fetch-adds, T=1024, uniform"}
+    w.close()
+    # config 4: 2^21 inserts at load 0.5 and 2^21 lookups
+    n, npes = 1 << 21, 16
+    slots = 2 * n // npes
+    keys = workgen.cfg4_keys(n=n)
+    q = workgen.cfg4_queries(keys, n=n)
+    w = oracle.World(npes, slots * 8 + 4096, oracle.AT_QUIET, 0)
+    tab = w.malloc(slots * 8)
+    t0 = time.perf_counter(); w.hash_insert(tab, slots, keys); t1 = time.perf_counter()
+    w.hash_lookup(tab, slots, q); t2 = time.perf_counter()
+    out["config4_hash"] = {"Minserts_per_s": round(n / (t1 - t0) / 1e6, 2), "Mlookups_per_s": round(n / (t2 - t1) / 1e6, 2),
+                           "sample": "2^21 keys into 2^22 slots, 2^21 lookups"}
+    w.close()
+    # config 5: one search on an R-MAT graph of scale 20
+    scale = 20
+    row, nbr = workgen.rmat_csr(scale)
+    root = int(workgen.bfs_roots(row, 1)[0])
+    vpp = (1 << scale) // 16
+    w = oracle.World(16, ((vpp * 28 + vpp // 8 + (1 << 16)) + 255) // 256 * 256, oracle.AT_QUIET, 0)
+    t0 = time.perf_counter(); _, _, st = w.bfs(row, nbr, root); dt = time.perf_counter() - t0
+    out["config5_bfs"] = {"GTEPS": round(st["edges_traversed"] / dt / 1e9, 4), "sample": "one root, R-MAT scale 20, edge factor 16"}
+    w.close()
+    return {"cores": 1, "kind": "oracle", "cells": out}
+
+
 def _median_ms(fn, reset, reps=5, warm=2):
     """Median HIP-event time of fn() on the current stream; reset() runs untimed before each rep."""
     import torch
@@ -448,6 +491,8 @@ def main():
         out["stream_ceilings"] = json.loads(res.stdout) if res.returncode == 0 else {"error": res.stdout[-200:]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
+        if extras:
+            out["cpu_baseline_extras"] = cpu_baseline_extras()
     print(json.dumps(out), flush=True)
 
 
