@@ -206,15 +206,17 @@ def extra_latency(sh, torch):
     sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
     try:
         base = heap.data_ptr()
-        sig = base + (8 << 20) + 4096
+        buf = sh.malloc(9 << 20)                                    # 2 x 4 MiB payload buffers
+        gin = sh.gin_create(1, 0)
+        sig_off = sh.gin_signal_sym(gin, 0) - base
         hv = heap.view(npes, seg)
         pp = {}
         for nbytes in (8, 128, 4096, 65536, 1 << 20, 4 << 20):
             iters = 2000 if nbytes <= 65536 else 200
-            ms = _median_ms(lambda: sh.pingpong(base, nbytes, sig, iters),
-                            lambda: hv[:2, (8 << 20) + 4096:(8 << 20) + 4104].zero_(), reps=3, warm=1)
+            ms = _median_ms(lambda: sh.pingpong(buf, nbytes, gin, 0, iters),
+                            lambda: hv[:2, sig_off:sig_off + 8].zero_(), reps=3, warm=1)
             pp[str(nbytes)] = round(ms * 1e3 / iters, 3)            # us per round trip
-        slots = base + (12 << 20)
+        slots = sh.malloc(8 * npes)
         bar = {}
         for wgs in (1, 4, 16):
             rounds = 2000

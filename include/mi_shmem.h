@@ -228,31 +228,47 @@ int shmem_bfs_destroy(void *graph);
  * than 64 levels), DEVICE. */
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
 
-/* ---- in-kernel ordering: put -> signal, waitSignal, barrier (Sec. III-A, III-B) ---- */
+/* ---- the paper's device API shape: signals, counters, put with actions (Sec. III-A, III-B) ---- */
+
+/* A Gin object owns `nsignals` signals (symmetric uint64, remotely incremented:
+ * remote completion) and `ncounters` counters (uint64 local to each PE: local
+ * completion), addressed by integer ID as in Listing 1.  Both arrays are taken
+ * from the symmetric heap and cleared on every PE (stream-ordered).  Kernels
+ * built into the library use them through the device-side Gin interface
+ * (put with SignalInc / SignalAdd / CounterInc actions, putValue, signal, flush,
+ * read/wait/reset of signals and counters, barrier session).
+ * Errors: NOT_INIT, INVALID_ARG, NOMEM, DEVICE. */
+int shmem_gin_create(int nsignals, int ncounters, void **gin_out /* HOST */);
+int shmem_gin_destroy(void *gin);
+/* Symmetric address of signal / counter `id` (for inspection with shmem_ptr +
+ * a device read); NULL if out of range. */
+void *shmem_gin_signal_sym(void *gin, int id);
+void *shmem_gin_counter_sym(void *gin, int id);
 
 /* The unidirectional ring exchange of Listing 2, `rounds` times in one
  * persistent launch of npes * wgs_per_pe workgroups.  In each round PE r puts
  * bytes [peer*slot_bytes, +slot_bytes) of its send buffer (peer = (r+1) mod
- * npes) into bytes [r*slot_bytes, +slot_bytes) of the peer's receive buffer,
- * then adds 1 to the peer's signal word -- an atomic add that lands only after
- * the put is visible -- and waits until its own signal word shows that round's
- * arrival.  After the last round all PEs meet in a barrier and reset their
- * signal word to 0.  send_sym / recv_sym: symmetric, npes * slot_bytes each, not
- * overlapping; signal_sym: symmetric uint64, 0 before the call.  The waits are
- * bounded; a time-out sets the device fault word.
- * Errors: NOT_INIT, INVALID_ARG (also: more workgroups than can be
- * co-resident), ALIGN, OUT_OF_RANGE, DEVICE. */
-int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, uint64_t *signal_sym, int rounds,
-                        int wgs_per_pe);
+ * npes) into bytes [r*slot_bytes, +slot_bytes) of the peer's receive buffer with
+ * the actions SignalInc{signal_id} -- an atomic increment of the peer's signal
+ * that lands only after the put is visible -- and CounterInc{counter_id}; then it
+ * waits until its own signal reads 1 and its counter reads the round number,
+ * resets the signal, and all PEs meet in the barrier session.  Afterwards every
+ * signal and counter involved reads 0 again.  send_sym / recv_sym: symmetric,
+ * npes * slot_bytes each, not overlapping.  The waits are bounded; a time-out
+ * sets the device fault word.
+ * Errors: NOT_INIT, INVALID_ARG (also: bad IDs, more workgroups than can be
+ * co-resident), OUT_OF_RANGE, DEVICE. */
+int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, void *gin, int signal_id,
+                        int counter_id, int rounds, int wgs_per_pe);
 
 /* Put-with-signal ping-pong (the latency experiment of Sec. V-A) between PE 0
  * and PE 1, one workgroup each: PE 0 puts nbytes from its copy of buf_sym into
- * PE 1's copy and signals; PE 1 waits, puts what it received into PE 0's second
- * buffer (buf_sym + nbytes rounded up to 256) and signals back; `iters` round
- * trips.  Both signal words (signal_sym on PE 0 and PE 1) must be 0 before the
- * call and hold `iters` after it.  buf_sym spans 2 * roundup(nbytes, 256) bytes.
- * Errors as above. */
-int shmem_pingpong(void *buf_sym, size_t nbytes, uint64_t *signal_sym, int iters);
+ * PE 1's copy with SignalInc{signal_id}; PE 1 waits, puts what it received into
+ * PE 0's second buffer (buf_sym + nbytes rounded up to 256) with the same
+ * action; `iters` round trips.  Signal `signal_id` must read 0 on PE 0 and PE 1
+ * before the call and reads `iters` on both after it.  buf_sym spans
+ * 2 * roundup(nbytes, 256) bytes.  Errors as above. */
+int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int iters);
 
 /* Barrier epochs: in round e = 1..rounds every PE puts the value e into word
  * `pe` of slots_sym (uint64[npes], symmetric) on EVERY PE, all PEs meet in the

@@ -69,8 +69,12 @@ _SIG = {
     "shmem_bfs_create": (_i, [C.c_uint32, _vp, _vp, _i, C.POINTER(_vp)]),
     "shmem_bfs_destroy": (_i, [_vp]),
     "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
-    "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i]),
-    "shmem_pingpong": (_i, [_vp, _sz, _vp, _i]),
+    "shmem_gin_create": (_i, [_i, _i, C.POINTER(_vp)]),
+    "shmem_gin_destroy": (_i, [_vp]),
+    "shmem_gin_signal_sym": (_vp, [_vp, _i]),
+    "shmem_gin_counter_sym": (_vp, [_vp, _i]),
+    "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i, _i, _i]),
+    "shmem_pingpong": (_i, [_vp, _sz, _vp, _i, _i]),
     "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
 }
 for _name, (_res, _args) in _SIG.items():
@@ -234,13 +238,31 @@ def bfs(graph, root, dev_level=None, dev_parent=None):
             "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}
 
 
-def ring_exchange(recv_sym, send_sym, slot_bytes, signal_sym, rounds=1, wgs_per_pe=1):
-    return _check(_L.shmem_ring_exchange(_addr(recv_sym), _addr(send_sym), slot_bytes, _addr(signal_sym),
+def gin_create(nsignals, ncounters):
+    g = _vp(0)
+    _check(_L.shmem_gin_create(nsignals, ncounters, C.byref(g)), "shmem_gin_create")
+    return g
+
+
+def gin_destroy(gin):
+    return _check(_L.shmem_gin_destroy(gin), "shmem_gin_destroy")
+
+
+def gin_signal_sym(gin, signal_id):
+    return _L.shmem_gin_signal_sym(gin, signal_id)
+
+
+def gin_counter_sym(gin, counter_id):
+    return _L.shmem_gin_counter_sym(gin, counter_id)
+
+
+def ring_exchange(recv_sym, send_sym, slot_bytes, gin, signal_id=0, counter_id=0, rounds=1, wgs_per_pe=1):
+    return _check(_L.shmem_ring_exchange(_addr(recv_sym), _addr(send_sym), slot_bytes, gin, signal_id, counter_id,
                                          rounds, wgs_per_pe), "shmem_ring_exchange")
 
 
-def pingpong(buf_sym, nbytes, signal_sym, iters):
-    return _check(_L.shmem_pingpong(_addr(buf_sym), nbytes, _addr(signal_sym), iters), "shmem_pingpong")
+def pingpong(buf_sym, nbytes, gin, signal_id, iters):
+    return _check(_L.shmem_pingpong(_addr(buf_sym), nbytes, gin, signal_id, iters), "shmem_pingpong")
 
 
 def barrier_epochs(slots_sym, rounds, wgs_per_pe, dev_errors=None):

@@ -1,86 +1,70 @@
-// Kernels that exercise in-kernel ordering: put followed by a signal (a remote
-// atomic add that makes the earlier puts visible), waiting on a signal, and
-// barrier epochs.  They are the device forms of the paper's ring exchange
-// (Listing 2) and put-with-signal ping-pong (Sec. V-A).
+// Kernels that exercise in-kernel ordering through the GIN-shaped device API
+// (gin.hpp): put with a signal action, waitSignal, counters, the barrier
+// session, and barrier epochs.  They are the device forms of the paper's ring
+// exchange (Listing 2) and put-with-signal ping-pong (Sec. V-A).
 #pragma once
 #include "../../include/mi_shmem.h"
+#include "gin.hpp"
 #include "shmemx.hpp"
 
 namespace shmemx {
 
-// signal: remote atomic add on a 64-bit signal word of PE pe.  Called by one
-// lane after the wave (or, behind a team barrier, the team) has issued its
-// puts: the release makes every earlier put of the caller visible before the
-// add lands (Sec. III-A "Ordering semantics").
-__device__ __forceinline__ void signal_add(const Ctx &c, uint64_t sig_off, uint64_t value, uint32_t pe)
-{
-    __hip_atomic_fetch_add((uint64_t *)ptr(c, sig_off, pe), value, __ATOMIC_RELEASE, SHMEMX_AGENT);
-}
-
-// waitSignal: spin (relaxed polls) until the local signal word reaches `expected`;
-// the caller then acquires so that the data the signal announces is read fresh.  Bounded; returns false
-// on time-out (the fault word is set and the caller carries on).
-__device__ __forceinline__ bool wait_signal(const Ctx &c, uint64_t sig_off, uint64_t expected, uint32_t pe_self)
-{
-    const uint64_t *w = (const uint64_t *)ptr(c, sig_off, pe_self);
-    bool ok = true;
-    uint32_t spins = 0;
-    while (__hip_atomic_load(w, __ATOMIC_RELAXED, SHMEMX_AGENT) < expected) {   // the caller acquires afterwards
-        if (timed_out(c)) { ok = false; break; }
-        __builtin_amdgcn_s_sleep(1);
-        if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, pe_self); ok = false; break; }
-    }
-    return ok;
-}
-
-// Ring exchange: PE r puts its send slot `peer` into slot r of the receive
-// buffer of peer = (r+1) mod n, increments the peer's signal, waits for its own
-// signal to show this round's arrival, and after the last round resets it.
-__global__ __launch_bounds__(256) void k_ring_exchange(Ctx c, uint64_t recv_off, uint64_t send_off, uint64_t ds,
-                                                       uint64_t sig_off, uint32_t rounds, uint32_t wgs_per_pe)
+// Ring exchange (Listing 2) through the GIN-shaped device API: PE r puts its
+// send slot `peer` into slot r of the receive buffer of peer = (r+1) mod n with
+// a SignalInc on signal `sig` (and a CounterInc on counter `ctr`), waits until
+// its own signal shows the predecessor's arrival and resets it.  Rounds are
+// separated by the barrier session, so a reset cannot swallow the next round's
+// increment.
+__global__ __launch_bounds__(256) void k_ring_exchange(Ctx c, GinState gs, uint64_t recv_off, uint64_t send_off,
+                                                       uint64_t ds, uint32_t sig, uint32_t ctr, uint32_t rounds,
+                                                       uint32_t wgs_per_pe)
 {
     const uint32_t pe = blockIdx.x / wgs_per_pe, wg = blockIdx.x % wgs_per_pe;
-    const uint32_t npes = (uint32_t)c.npes, peer = (pe + 1) % npes;
-    const size_t rank = (size_t)wg * blockDim.x + threadIdx.x, size = (size_t)wgs_per_pe * blockDim.x;
+    const Gin gin{c, gs, pe, wgs_per_pe};
+    const uint32_t peer = (pe + 1) % (uint32_t)c.npes;
     for (uint32_t r = 1; r <= rounds; ++r) {
-        put(c, recv_off + (uint64_t)pe * ds, ptr(c, send_off + (uint64_t)peer * ds, pe), ds, peer, rank, size);
-        team_barrier(c, pe, wgs_per_pe);                 // every wave's puts are complete and visible
-        if (wg == 0 && threadIdx.x == 0) signal_add(c, sig_off, 1, peer);
-        if (threadIdx.x == 0) wait_signal(c, sig_off, r, pe);
-        __syncthreads();
-        acquire();
+        GinActions act;
+        act.signal_id = (int32_t)sig;               // SignalInc{sig}
+        act.counter_id = (int32_t)ctr;              // CounterInc{ctr}
+        gin.put(peer, recv_off + (uint64_t)pe * ds, send_off + (uint64_t)peer * ds, ds, act);
+        gin.wait_signal(sig, 1);                    // the predecessor's data has arrived and is visible
+        gin.wait_counter(ctr, r);                   // our own send slot is reusable
+        team_barrier(c, pe, wgs_per_pe);            // every workgroup of the team has seen the signal ...
+        if (wg == 0 && threadIdx.x == 0) gin.reset_signal(sig);   // ... so it can be reset
+        gin.barrier_sync();
     }
-    barrier_all(c, pe, wgs_per_pe);                      // nobody still waits on a signal ...
-    if (wg == 0 && threadIdx.x == 0)                     // ... so it can be reset for the next use
-        __hip_atomic_store((uint64_t *)ptr(c, sig_off, pe), 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    if (wg == 0 && threadIdx.x == 0) gin.reset_counter(ctr);
 }
 
 // Ping-pong between PE 0 and PE 1, one workgroup each (they run on different
-// dies): PE 0 puts nbytes into PE 1's buffer and signals; PE 1 waits, puts the
-// bytes it received back into PE 0's second buffer and signals; `iters` times.
-// Signals count up; the host resets them.
-__global__ __launch_bounds__(256) void k_pingpong(Ctx c, uint64_t buf_off, uint64_t nbytes, uint64_t sig_off,
+// dies): PE 0 puts nbytes into PE 1's buffer with a SignalInc; PE 1 waits, puts
+// the bytes it received back into PE 0's second buffer with a SignalInc;
+// `iters` round trips.  The signal counts up; the host resets it.
+__global__ __launch_bounds__(256) void k_pingpong(Ctx c, GinState gs, uint64_t buf_off, uint64_t nbytes, uint32_t sig,
                                                   uint32_t iters)
 {
     const uint32_t pe = blockIdx.x;  // 0 or 1
+    const Gin gin{c, gs, pe, 1};
     const uint64_t back_off = buf_off + ((nbytes + 255) / 256) * 256;
+    GinActions act;
+    act.signal_id = (int32_t)sig;
     for (uint32_t i = 1; i <= iters; ++i) {
         if (pe == 0) {
-            put(c, buf_off, ptr(c, buf_off, 0), nbytes, 1, threadIdx.x, blockDim.x);
-            quiet();
-            __syncthreads();
-            if (threadIdx.x == 0) { signal_add(c, sig_off, 1, 1); wait_signal(c, sig_off, i, 0); }
-            __syncthreads();
-            acquire();
+            gin.put(1, buf_off, buf_off, nbytes, act);
+            gin.wait_signal(sig, i);
         } else {
-            if (threadIdx.x == 0) wait_signal(c, sig_off, i, 1);
-            __syncthreads();
-            acquire();
-            put(c, back_off, ptr(c, buf_off, 1), nbytes, 0, threadIdx.x, blockDim.x);
-            quiet();
-            __syncthreads();
-            if (threadIdx.x == 0) signal_add(c, sig_off, 1, 0);
+            gin.wait_signal(sig, i);
+            gin.put(0, back_off, buf_off, nbytes, act);
         }
+    }
+}
+
+// Clears the signal and counter arrays of a new Gin object on every PE.
+__global__ void k_gin_zero(Ctx c, GinState gs)
+{
+    for (uint32_t pe = blockIdx.x; pe < (uint32_t)c.npes; pe += gridDim.x) {
+        for (uint32_t i = threadIdx.x; i < gs.nsignals; i += blockDim.x) *(uint64_t *)ptr(c, gs.signals_off + 8ull * i, pe) = 0;
+        for (uint32_t i = threadIdx.x; i < gs.ncounters; i += blockDim.x) *(uint64_t *)ptr(c, gs.counters_off + 8ull * i, pe) = 0;
     }
 }
 

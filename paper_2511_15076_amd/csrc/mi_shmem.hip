@@ -546,47 +546,95 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
 }
 
 // ---------------------------------------------------------------------------
-int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, uint64_t *signal_sym, int rounds,
-                        int wgs_per_pe)
+struct GinObj { shmemx::GinState st; void *alloc; };
+
+int shmem_gin_create(int nsignals, int ncounters, void **gin_out)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
-    if ((uintptr_t)signal_sym % 8) return SHMEM_ERR_ALIGN;
+    if (!gin_out || nsignals < 1 || ncounters < 0 || nsignals > (1 << 20) || ncounters > (1 << 20)) return SHMEM_ERR_INVALID_ARG;
+    GinObj *g = new (std::nothrow) GinObj();
+    if (!g) return SHMEM_ERR_NOMEM;
+    const size_t sig_bytes = ((size_t)nsignals * 8 + 255) / 256 * 256;
+    g->alloc = shmem_malloc(sig_bytes + (size_t)std::max(ncounters, 1) * 8);
+    if (!g->alloc) { delete g; return SHMEM_ERR_NOMEM; }
+    g->st.signals_off = (uint64_t)((uint8_t *)g->alloc - H.heap);
+    g->st.counters_off = g->st.signals_off + sig_bytes;
+    g->st.nsignals = (uint32_t)nsignals; g->st.ncounters = (uint32_t)ncounters;
+    hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), g->st);
+    if (int rc = launched()) { shmem_free(g->alloc); delete g; return rc; }
+    *gin_out = g;
+    return SHMEM_OK;
+}
+
+int shmem_gin_destroy(void *gin)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!gin) return SHMEM_ERR_INVALID_ARG;
+    GinObj *g = (GinObj *)gin;
+    int rc = shmem_free(g->alloc);
+    delete g;
+    return rc;
+}
+
+void *shmem_gin_signal_sym(void *gin, int id)
+{
+    if (!H.init || !gin) return nullptr;
+    GinObj *g = (GinObj *)gin;
+    if (id < 0 || (uint32_t)id >= g->st.nsignals) return nullptr;
+    return H.heap + g->st.signals_off + 8ull * (uint32_t)id;
+}
+
+void *shmem_gin_counter_sym(void *gin, int id)
+{
+    if (!H.init || !gin) return nullptr;
+    GinObj *g = (GinObj *)gin;
+    if (id < 0 || (uint32_t)id >= g->st.ncounters) return nullptr;
+    return H.heap + g->st.counters_off + 8ull * (uint32_t)id;
+}
+
+int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, void *gin, int signal_id,
+                        int counter_id, int rounds, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!gin || rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    GinObj *g = (GinObj *)gin;
+    if (signal_id < 0 || (uint32_t)signal_id >= g->st.nsignals || counter_id < 0 ||
+        (uint32_t)counter_id >= g->st.ncounters) return SHMEM_ERR_INVALID_ARG;
     unsigned __int128 span = (unsigned __int128)slot_bytes * (unsigned)H.npes;
     if (span > H.seg) return SHMEM_ERR_OUT_OF_RANGE;
-    uint64_t roff, soff, goff;
+    uint64_t roff, soff;
     if (int rc = sym_off(recv_sym, (uint64_t)span, &roff)) return rc;
     if (int rc = sym_off(send_sym, (uint64_t)span, &soff)) return rc;
-    if (int rc = sym_off(signal_sym, 8, &goff)) return rc;
     if (roff < soff + (uint64_t)span && soff < roff + (uint64_t)span && span) return SHMEM_ERR_INVALID_ARG;
     if (rounds == 0) return SHMEM_OK;
     long grid = (long)H.npes * wgs_per_pe;
     if (grid > max_resident_wgs(shmemx::k_ring_exchange)) return SHMEM_ERR_INVALID_ARG;
     shmemx::Ctx c = ctx();
+    shmemx::GinState gs = g->st;
     uint64_t ds = slot_bytes;
-    uint32_t r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
-    void *args[] = {&c, &roff, &soff, &ds, &goff, &r, &w};
+    uint32_t sig = (uint32_t)signal_id, ctr = (uint32_t)counter_id, r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
+    void *args[] = {&c, &gs, &roff, &soff, &ds, &sig, &ctr, &r, &w};
     return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_ring_exchange, dim3((unsigned)grid),
                                              dim3(WG_THREADS), args, 0, H.stream));
 }
 
-int shmem_pingpong(void *buf_sym, size_t nbytes, uint64_t *signal_sym, int iters)
+int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int iters)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (H.npes < 2 || iters < 0) return SHMEM_ERR_INVALID_ARG;
-    if ((uintptr_t)signal_sym % 8) return SHMEM_ERR_ALIGN;
+    if (!gin || H.npes < 2 || iters < 0) return SHMEM_ERR_INVALID_ARG;
+    GinObj *g = (GinObj *)gin;
+    if (signal_id < 0 || (uint32_t)signal_id >= g->st.nsignals) return SHMEM_ERR_INVALID_ARG;
     const uint64_t padded = ((uint64_t)nbytes + 255) / 256 * 256;
     if (padded > H.seg / 2) return SHMEM_ERR_OUT_OF_RANGE;
-    uint64_t boff, goff;
+    uint64_t boff;
     if (int rc = sym_off(buf_sym, 2 * padded, &boff)) return rc;
-    if (int rc = sym_off(signal_sym, 8, &goff)) return rc;
-    if (goff < boff + 2 * padded && boff < goff + 8) return SHMEM_ERR_INVALID_ARG;
     if (iters == 0) return SHMEM_OK;
     if (2 > max_resident_wgs(shmemx::k_pingpong)) return SHMEM_ERR_DEVICE;
     shmemx::Ctx c = ctx();
+    shmemx::GinState gs = g->st;
     uint64_t nb = nbytes;
-    uint32_t it = (uint32_t)iters;
-    void *args[] = {&c, &boff, &nb, &goff, &it};
+    uint32_t sig = (uint32_t)signal_id, it = (uint32_t)iters;
+    void *args[] = {&c, &gs, &boff, &nb, &sig, &it};
     return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_pingpong, dim3(2), dim3(WG_THREADS), args, 0,
                                              H.stream));
 }

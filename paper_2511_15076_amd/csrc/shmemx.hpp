@@ -144,9 +144,11 @@ __device__ __forceinline__ void team_barrier(const Ctx &c, uint32_t pe, uint32_t
     wg_release();
     if (threadIdx.x == 0) {
         quiet();
-        uint64_t *w = &c.scratch[W_PE_BASE + pe * W_PE_WORDS], g;
-        if (barrier_arrive(c, w, w + 16, wgs_per_pe, &g)) barrier_open(w + 16, g);
-        acquire();
+        if (wgs_per_pe > 1) {   // a one-workgroup team has nobody else to meet
+            uint64_t *w = &c.scratch[W_PE_BASE + pe * W_PE_WORDS], g;
+            if (barrier_arrive(c, w, w + 16, wgs_per_pe, &g)) barrier_open(w + 16, g);
+            acquire();
+        }
     }
     wg_acquire();
 }

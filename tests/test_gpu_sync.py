@@ -20,33 +20,49 @@ def golden_ring_cases(golden_dir):
             if l.strip() and not l.startswith("#")]
 
 
+def gin_offsets(hb_payload, nsig, nctr):
+    """Where the library will place a Gin object's arrays when it is the first allocation after
+    `hb_payload` bytes reserved by the test (first fit, 256-byte granules)."""
+    sig_bytes = (nsig * 8 + 255) // 256 * 256
+    return hb_payload, hb_payload + sig_bytes
+
+
 @pytest.mark.parametrize("wgs,rounds", [(1, 1), (3, 1), (2, 25)])
 def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
     for n, ds in golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000)]:
         span = n * ds
         send, recv = 0, (span + 255) // 256 * 256
-        sig = 2 * recv
-        hb = (sig + 256 + 255) // 256 * 256
+        payload = 2 * recv                                    # bytes the test reserves with shmem_malloc
+        nsig, nctr, sig_id, ctr_id = 4, 3, 2, 1
+        sig_base, ctr_base = gin_offsets(payload, nsig, nctr)
+        hb = (ctr_base + 256 + 255) // 256 * 256
         init = np.stack([workgen.random_words(300 + p + ds, hb // 8).view(np.uint8) for p in range(n)])
-        init[:, sig:sig + 8] = 0
+        init[:, sig_base:] = 0                                # what gin_create clears
         w = oracle.World(n, hb, oracle.SHUFFLED, 2)
         for p in range(n):
             w.heap(p)[:] = init[p]
+        sig = sig_base + 8 * sig_id
         for _ in range(rounds):
-            for r in range(n):
+            for r in range(n):                                # put with SignalInc{sig_id}
                 peer = (r + 1) % n
                 assert w.put(r, recv + r * ds, send + peer * ds, ds, peer) == 0
                 assert w.signal_add(r, sig, 1, peer) == 0
-            for p in range(n):
-                assert int(w.heap(p)[sig:sig + 8].view(np.uint64)[0]) >= 1
-        for p in range(n):
-            w.heap(p)[sig:sig + 8] = 0                        # reset for the next use
+            for p in range(n):                                # waitSignal(sig_id, 1); resetSignal(sig_id)
+                assert int(w.heap(p)[sig:sig + 8].view(np.uint64)[0]) == 1
+                w.heap(p)[sig:sig + 8] = 0
+            w.barrier_all()
         with shmem_world(n, hb) as (heap, base):
             heap.copy_(torch.from_numpy(init.reshape(-1)))
-            sh.ring_exchange(base + recv, base + send, ds, base + sig, rounds, wgs)
+            assert sh.malloc(payload) == base
+            gin = sh.gin_create(nsig, nctr)
+            assert sh.gin_signal_sym(gin, sig_id) == base + sig
+            assert sh.gin_counter_sym(gin, ctr_id) == base + ctr_base + 8 * ctr_id
+            assert sh.gin_signal_sym(gin, nsig) is None and sh.gin_counter_sym(gin, -1) is None
+            sh.ring_exchange(base + recv, base + send, ds, gin, sig_id, ctr_id, rounds, wgs)
             sh.stream_sync()
             got = heaps_of(heap, n)
-        assert np.array_equal(got, w.heaps()), (n, ds)
+            sh.gin_destroy(gin)
+        assert np.array_equal(got, w.heaps()), (n, ds)       # data delivered, signals and counters back to 0
         for p in range(n):                                    # the worked example, spelled out
             q = (p - 1 + n) % n
             assert np.array_equal(got[p][recv + q * ds: recv + (q + 1) * ds],
@@ -57,24 +73,26 @@ def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
 def test_pingpong(nbytes):
     npes, iters = 4, 200
     pad = (nbytes + 255) // 256 * 256
-    buf, sig = 0, 2 * pad
-    hb = (sig + 512 + 255) // 256 * 256
+    buf, payload = 0, 2 * pad
+    sig_base, ctr_base = gin_offsets(payload, 1, 0)
+    hb = (ctr_base + 256 + 255) // 256 * 256
     init = np.stack([workgen.random_words(900 + p, hb // 8).view(np.uint8) for p in range(npes)])
-    init[:, sig:sig + 8] = 0
+    init[:, sig_base:] = 0
     w = oracle.World(npes, hb, oracle.SHUFFLED, 3)
     for p in range(npes):
         w.heap(p)[:] = init[p]
-    for _ in range(3):                                        # the result is the same after any number of trips
-        w.put(0, buf, buf, nbytes, 1); w.signal_add(0, sig, 1, 1)
-        w.put(1, buf + pad, buf, nbytes, 0); w.signal_add(1, sig, 1, 0)
-    w.heap(0)[sig:sig + 8].view(np.uint64)[0] = iters
-    w.heap(1)[sig:sig + 8].view(np.uint64)[0] = iters
+    for _ in range(iters):
+        w.put(0, buf, buf, nbytes, 1); w.signal_add(0, sig_base, 1, 1)
+        w.put(1, buf + pad, buf, nbytes, 0); w.signal_add(1, sig_base, 1, 0)
     with shmem_world(npes, hb) as (heap, base):
         heap.copy_(torch.from_numpy(init.reshape(-1)))
-        sh.pingpong(base + buf, nbytes, base + sig, iters)
+        assert sh.malloc(payload) == base
+        gin = sh.gin_create(1, 0)
+        sh.pingpong(base + buf, nbytes, gin, 0, iters)
         sh.stream_sync()
         got = heaps_of(heap, npes)
-    assert np.array_equal(got, w.heaps())
+        sh.gin_destroy(gin)
+    assert np.array_equal(got, w.heaps())                     # both signals read `iters`
     assert np.array_equal(got[0][pad:pad + nbytes], init[0][:nbytes])   # the payload came back
 
 
@@ -100,17 +118,22 @@ def test_barrier_epochs(npes, wgs, rounds):
 
 def test_sync_entry_point_errors():
     with shmem_world(4, 1 << 16) as (heap, base):
+        gin = sh.gin_create(2, 1)
         for call, status in [
-            (lambda: sh.ring_exchange(base, base + 128, 256, base + 8192, 1, 1), sh.ERR_INVALID_ARG),   # overlap
-            (lambda: sh.ring_exchange(base + 4096, base, 256, base + 8196, 1, 1), sh.ERR_ALIGN),
-            (lambda: sh.ring_exchange(base + 4096, base, 1 << 15, base + 8192, 1, 1), sh.ERR_OUT_OF_RANGE),
-            (lambda: sh.ring_exchange(base + 4096, base, 256, base + 8192, 1, 100000), sh.ERR_INVALID_ARG),
-            (lambda: sh.pingpong(base, 1 << 16, base + 8192, 1), sh.ERR_OUT_OF_RANGE),
-            (lambda: sh.pingpong(base, 4096, base + 4096, 1), sh.ERR_INVALID_ARG),                     # signal inside
+            (lambda: sh.ring_exchange(base, base + 128, 256, gin, 0, 0, 1, 1), sh.ERR_INVALID_ARG),     # overlap
+            (lambda: sh.ring_exchange(base + 4096, base, 256, gin, 2, 0, 1, 1), sh.ERR_INVALID_ARG),    # signal id
+            (lambda: sh.ring_exchange(base + 4096, base, 256, gin, 0, 1, 1, 1), sh.ERR_INVALID_ARG),    # counter id
+            (lambda: sh.ring_exchange(base + 4096, base, 1 << 15, gin, 0, 0, 1, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.ring_exchange(base + 4096, base, 256, gin, 0, 0, 1, 100000), sh.ERR_INVALID_ARG),
+            (lambda: sh.pingpong(base, 1 << 16, gin, 0, 1), sh.ERR_OUT_OF_RANGE),
+            (lambda: sh.pingpong(base, 4096, gin, 5, 1), sh.ERR_INVALID_ARG),
+            (lambda: sh.gin_create(0, 0), sh.ERR_INVALID_ARG),
+            (lambda: sh.gin_create(1 << 19, 0), sh.ERR_NOMEM),
             (lambda: sh.barrier_epochs(base + 4, 1, 1), sh.ERR_ALIGN),
             (lambda: sh.barrier_epochs(base, 1, 0), sh.ERR_INVALID_ARG),
         ]:
             with pytest.raises(sh.ShmemError) as e:
                 call()
             assert e.value.status == status
+        sh.gin_destroy(gin)
         sh.stream_sync()
