@@ -209,8 +209,8 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
  * neighbours uint32[nnz]; PE p reads only its own rows) and allocates the
  * per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
- * long-row list and its scan, per-die bitmap copies, counters: about 25.2 bytes per
- * owned vertex).  Errors: NOMEM, INVALID_ARG. */
+ * long-row list and its scan, per-die bitmap copies, frontier and previous-level
+ * bitmaps, counters: about 25.4 bytes per owned vertex).  Errors: NOMEM, INVALID_ARG. */
 typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */
@@ -221,6 +221,18 @@ typedef struct {
 int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_t *dev_nbr,
                      int wgs_per_pe, void **graph_out /* HOST */);
 int shmem_bfs_destroy(void *graph);
+/* Direction of the levels.  TOP_DOWN (the default) is the method as stated above
+ * on every level.  DIRECTION_OPTIMIZING switches a level to bottom-up -- every
+ * owner scans its own unvisited vertices and looks for a neighbour in the current
+ * frontier with one-sided gets of the owners' frontier bitmaps; claim, parent,
+ * level and queue entry are then local writes -- when the frontier's row lengths
+ * add up to more than 1/14 of those of the unvisited vertices, and back to
+ * top-down when the frontier is below nverts/24 and shrinking.  BOTTOM_UP forces
+ * bottom-up on every level (for tests).  Levels, frontier sizes and counts are
+ * the same in every mode; parents may differ (all are valid).
+ * Errors: NOT_INIT, INVALID_ARG. */
+enum { SHMEM_BFS_TOP_DOWN = 0, SHMEM_BFS_DIRECTION_OPTIMIZING = 1, SHMEM_BFS_BOTTOM_UP = 2 };
+int shmem_bfs_configure(void *graph, int mode);
 /* Runs one search; blocks the host (one stream sync per level).  dev_level
  * (int32[nverts], -1 = unreached) and dev_parent (uint32[nverts],
  * SHMEM_BFS_NONE = unreached; parent[root] = root) are DEVICE and may be NULL;

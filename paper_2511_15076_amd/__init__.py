@@ -20,6 +20,7 @@ OP_PUT, OP_GET, OP_IPUT, OP_IGET = 0, 1, 2, 3
 AMO_FETCH_ADD, AMO_COMPARE_SWAP, AMO_FETCH_OR, AMO_MIN_CAS_LOOP = 0, 1, 2, 3
 HASH_INSERTED, HASH_DUPLICATE, HASH_FULL = 0, 1, 2
 BFS_NONE = 0xFFFFFFFF
+BFS_TOP_DOWN, BFS_DIRECTION_OPTIMIZING, BFS_BOTTOM_UP = 0, 1, 2
 
 
 class ShmemError(RuntimeError):
@@ -68,6 +69,7 @@ _SIG = {
     "shmem_hash_lookup": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
     "shmem_bfs_create": (_i, [C.c_uint32, _vp, _vp, _i, C.POINTER(_vp)]),
     "shmem_bfs_destroy": (_i, [_vp]),
+    "shmem_bfs_configure": (_i, [_vp, _i]),
     "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
     "shmem_gin_create": (_i, [_i, _i, C.POINTER(_vp)]),
     "shmem_gin_destroy": (_i, [_vp]),
@@ -225,6 +227,10 @@ def bfs_create(nverts, dev_row_off, dev_nbr, wgs_per_pe):
     _check(_L.shmem_bfs_create(nverts, _addr(dev_row_off), _addr(dev_nbr), wgs_per_pe, C.byref(g)),
            "shmem_bfs_create")
     return g
+
+
+def bfs_configure(graph, mode):
+    return _check(_L.shmem_bfs_configure(graph, mode), "shmem_bfs_configure")
 
 
 def bfs_destroy(graph):

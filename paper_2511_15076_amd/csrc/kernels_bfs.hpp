@@ -29,6 +29,7 @@ struct BfsState {
     // symmetric offsets of the per-PE state
     uint64_t bitmap_off, level_off, parent_off, queue_off[2], big_off, bigscan_off, tails_off;
     uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
+    uint64_t front_off, prev_off; // frontier bitmap and the bitmap as of the previous level (bottom-up levels)
     uint32_t wgs_per_pe;
 };
 
@@ -69,6 +70,8 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
         bm[w] = (pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
     uint64_t *flt = (uint64_t *)ptr(c, s.filter_off, pe);
     for (uint64_t w = rank; w < s.words * NXCD; w += size) flt[w] = 0;
+    uint64_t *prev = (uint64_t *)ptr(c, s.prev_off, pe);
+    for (uint64_t w = rank; w < s.words; w += size) prev[w] = 0;
     for (uint64_t l = rank; l < s.vpp; l += size) {
         const bool is_root = pe == ro && l == rl;
         lv[l] = is_root ? 0 : -1;
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
-        if (pe == 0) c.scratch[W_WORK + 1] = 0;  // degree sum of reached vertices
+        if (pe == 0) { c.scratch[W_WORK + 1] = 0; c.scratch[W_WORK + 2] = 0; }  // degree sums (reached / next frontier)
     }
 }
 
@@ -411,6 +414,94 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
     bfs_flush<STAGED>(c, s, st, L);
 }
 
+// ---------------------------------------------------------------------------
+// Direction-optimising levels (optional).  A bottom-up level turns the search
+// round: every owner scans ITS OWN unvisited vertices and looks for a neighbour
+// in the current frontier with one-sided gets of the frontier bitmap; the
+// claim, parent, level and queue entry are then local (owner computes, no
+// atomics on the bitmap).  It examines far fewer edges than top-down once the
+// frontier holds most of the remaining edges.
+
+// frontier bitmap of the level about to be expanded = newly set bits; runs after init and each level
+__global__ __launch_bounds__(256) void k_bfs_make_front(Ctx c, BfsState s)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
+    const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
+    uint64_t *front = (uint64_t *)ptr(c, s.front_off, pe), *prev = (uint64_t *)ptr(c, s.prev_off, pe);
+    for (uint64_t w = rank; w < s.words; w += size) {
+        const uint64_t v = vis[w];
+        front[w] = v & ~prev[w];
+        prev[w] = v;
+    }
+}
+
+// sum of the row lengths of frontier `next` (decides the direction of the next level)
+__global__ __launch_bounds__(256) void k_bfs_front_degree(Ctx c, BfsState s, uint32_t next)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
+    const uint64_t cnt = bfs_tails(c, s, pe)[T_TAIL0 + next % 3];
+    const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[next & 1], pe);
+    uint64_t sum = 0;
+    for (uint64_t k = rank; k < cnt; k += size) {
+        const uint32_t u = queue[k];
+        sum += s.row_off[u + 1] - s.row_off[u];
+    }
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(&c.scratch[W_WORK + 2], sum);
+}
+
+// Bottom-up level L -> L+1.  A wave owns one bitmap word (64 consecutive local
+// vertices, lane = bit) at a time.
+__global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_t L)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint64_t first = (uint64_t)pe * s.vpp;
+    if (first >= s.nverts) return;
+    const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
+    uint64_t *vis = (uint64_t *)ptr(c, s.bitmap_off, pe);
+    int32_t *lv = (int32_t *)ptr(c, s.level_off, pe);
+    uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
+    uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], pe);
+    uint64_t *tail = bfs_tails(c, s, pe) + T_TAIL0 + (L + 1) % 3;
+    uint64_t mf = 0;
+    for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
+        const uint64_t visw = vis[w];
+        if (visw == ~0ull) continue;
+        const uint64_t l = w * 64 + lane;
+        uint32_t par = SHMEM_BFS_NONE, deg = 0;
+        if (l < count && !((visw >> lane) & 1)) {
+            const uint64_t r0 = s.row_off[first + l], r1 = s.row_off[first + l + 1];
+            deg = (uint32_t)(r1 - r0);
+            for (uint64_t e = r0; e < r1; ++e) {
+                const uint32_t u = s.nbr[e];
+                const uint32_t o = bfs_owner(s, u), lu = u - o * s.vpp;
+                const uint64_t fw = ((const uint64_t *)ptr(c, s.front_off, o))[lu >> 6];   // get from u's owner
+                if ((fw >> (lu & 63)) & 1) { par = u; break; }
+            }
+        }
+        const bool found = par != SHMEM_BFS_NONE;
+        const uint64_t fm = ballot(found);
+        if (fm == 0) continue;
+        if (lane == 0) vis[w] = visw | fm;               // this wave is the only writer of the word
+        uint64_t base = 0;
+        if (lane == 0) base = atomic_fetch_add(tail, (uint64_t)__builtin_popcountll(fm));
+        base = bcast64(base, 0);
+        if (found) {
+            queue[base + rank_in(fm)] = (uint32_t)(first + l);
+            lv[l] = (int32_t)(L + 1);
+            pr[l] = par;
+            mf += deg;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) mf += __shfl_down(mf, off, 64);
+    if (lane == 0 && mf) atomic_fetch_add(&c.scratch[W_WORK + 2], mf);
+}
+
 // Level epilogue (one wave): total size of frontier `next`, reset of the long
 // row counters and of the count that level next+1 will fill.
 __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
@@ -425,6 +516,9 @@ __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
     for (int off = 32; off > 0; off >>= 1) total += __shfl_down(total, off, 64);
     if (threadIdx.x == 0) c.scratch[W_WORK] = total;
 }
+
+// clears the next-frontier degree sum once the host has read it
+__global__ void k_bfs_clear_front_degree(Ctx c) { if (threadIdx.x == 0) c.scratch[W_WORK + 2] = 0; }
 
 // Every owner copies its level / parent slice into the caller's flat arrays.
 __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, int32_t *level, uint32_t *parent)

@@ -42,7 +42,9 @@ struct Host {
 struct BfsGraph {
     shmemx::BfsState st;
     int wgs_per_pe;
-    void *allocs[9];
+    int mode;          // SHMEM_BFS_TOP_DOWN / DIRECTION_OPTIMIZING / BOTTOM_UP
+    uint64_t nnz;      // CSR entries (sum of all row lengths)
+    void *allocs[11];
     int nallocs;
 };
 
@@ -460,12 +462,14 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     if (!g) return SHMEM_ERR_NOMEM;
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
     const uint64_t words = ((uint64_t)vpp + 63) / 64;
-    // bitmap, level, parent, two queues, long-row list, its segment scan, counters, per-die bitmap copies
-    const size_t sizes[9] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
-                             (size_t)vpp * 4, ((size_t)vpp + 1) * 4, 256, words * 8 * shmemx::NXCD};
-    uint64_t offs[9];
+    // bitmap, level, parent, two queues, long-row list, its segment scan, counters, per-die bitmap copies,
+    // frontier bitmap, previous-level bitmap
+    const size_t sizes[11] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+                              (size_t)vpp * 4, ((size_t)vpp + 1) * 4, 256, words * 8 * shmemx::NXCD, words * 8,
+                              words * 8};
+    uint64_t offs[11];
     g->nallocs = 0;
-    for (int i = 0; i < 9; ++i) {
+    for (int i = 0; i < 11; ++i) {
         void *p = shmem_malloc(sizes[i]);
         if (!p) {
             for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
@@ -481,7 +485,16 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.row_off = dev_row_off; s.nbr = dev_nbr;
     s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
     s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.big_off = offs[5]; s.bigscan_off = offs[6];
-    s.tails_off = offs[7]; s.filter_off = offs[8];
+    s.tails_off = offs[7]; s.filter_off = offs[8]; s.front_off = offs[9]; s.prev_off = offs[10];
+    g->mode = SHMEM_BFS_TOP_DOWN;
+    g->nnz = 0;
+    if (hipMemcpyAsync(H.pinned + 32, dev_row_off + nverts, 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
+        hipStreamSynchronize(H.stream) != hipSuccess) {
+        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
+        delete g;
+        return SHMEM_ERR_DEVICE;
+    }
+    g->nnz = H.pinned[32];
     s.wgs_per_pe = (uint32_t)wgs_per_pe;
     g->wgs_per_pe = wgs_per_pe;
     *graph_out = g;
@@ -499,6 +512,14 @@ int shmem_bfs_destroy(void *graph)
     return rc;
 }
 
+int shmem_bfs_configure(void *graph, int mode)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!graph || mode < SHMEM_BFS_TOP_DOWN || mode > SHMEM_BFS_BOTTOM_UP) return SHMEM_ERR_INVALID_ARG;
+    ((BfsGraph *)graph)->mode = mode;
+    return SHMEM_OK;
+}
+
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
@@ -510,13 +531,35 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     dim3 grid((unsigned)(H.npes * g->wgs_per_pe)), block(WG_THREADS);
     shmem_bfs_stats st;
     memset(&st, 0, sizeof st);
-    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
     const bool staged = H.npes <= (int)shmemx::STAGE_PES;   // winners staged in LDS per owner
-    uint64_t *counts = H.pinned + 16;       // [0] frontier total of the next level, [1] degree sum so far
+    const bool hybrid = g->mode != SHMEM_BFS_TOP_DOWN;
+    // [0] size of the next frontier, [1] degree sum of the expanded frontiers (top-down only mode),
+    // [2] running degree sum of every frontier discovered so far (direction-optimising modes)
+    uint64_t *counts = H.pinned + 16;
+    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
+    uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;
+    if (hybrid) {
+        hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, 0u);
+        hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
+        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 24, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
+            hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+        m_f = cum_mf = counts[2];
+    }
     st.frontier_size[0] = 1;
+    bool bottom_up = false;
     uint32_t L = 0;
     for (;;) {
-        if (staged) {
+        if (g->mode == SHMEM_BFS_BOTTOM_UP) bottom_up = true;
+        else if (g->mode == SHMEM_BFS_DIRECTION_OPTIMIZING) {
+            // switch when the frontier's edges outweigh a fraction of the edges still hanging off
+            // unvisited vertices; switch back when the frontier is small and shrinking
+            const uint64_t m_u = g->nnz > cum_mf ? g->nnz - cum_mf : 0;
+            if (!bottom_up) bottom_up = m_f > m_u / 14;
+            else if (n_f < s.nverts / 24 && n_f < n_f_prev) bottom_up = false;
+        }
+        if (bottom_up) {
+            hipLaunchKernelGGL(shmemx::k_bfs_bottomup, grid, block, 0, H.stream, c, s, L);
+        } else if (staged) {
             hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
             hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
             hipLaunchKernelGGL(shmemx::k_bfs_big<true>, grid, block, 0, H.stream, c, s, L);
@@ -526,17 +569,23 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
         }
         hipLaunchKernelGGL(shmemx::k_bfs_count, dim3(1), dim3(64), 0, H.stream, c, s, L + 1);
-        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 16, hipMemcpyDeviceToHost, H.stream) != hipSuccess)
+        if (hybrid) {
+            if (!bottom_up) hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, L + 1);
+            hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
+        }
+        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 24, hipMemcpyDeviceToHost, H.stream) != hipSuccess)
             return SHMEM_ERR_DEVICE;
         if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
         ++L;
         if (counts[0] == 0) break;
         if (L >= 64) return SHMEM_ERR_INVALID_ARG;
         st.frontier_size[L] = counts[0];
+        n_f_prev = n_f; n_f = counts[0];
+        if (hybrid) { m_f = counts[2] - cum_mf; cum_mf = counts[2]; }
     }
     st.nlevels = L;
     for (uint32_t l = 0; l < L; ++l) st.reached += st.frontier_size[l];
-    st.edges_traversed = counts[1] / 2;
+    st.edges_traversed = (hybrid ? counts[2] : counts[1]) / 2;
     if (dev_level || dev_parent) {
         hipLaunchKernelGGL(shmemx::k_bfs_gather, grid, block, 0, H.stream, c, s, dev_level, dev_parent);
         if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;

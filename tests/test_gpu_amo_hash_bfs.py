@@ -226,7 +226,7 @@ def check_tree(row, nbr, root, level, parent):
         assert v in nbr[row[u]:row[u + 1]]
 
 
-def run_bfs_case(row, nbr, roots, npes, wgs):
+def run_bfs_case(row, nbr, roots, npes, wgs, mode=0):
     n = len(row) - 1
     vpp = -(-n // npes)
     hb = ((vpp * 28 + vpp // 8 + 16 * 256 + 255) // 256) * 256
@@ -234,6 +234,7 @@ def run_bfs_case(row, nbr, roots, npes, wgs):
     with shmem_world(npes, hb) as (heap, base):
         drow, dnbr = to_dev(row), to_dev(nbr)
         g = sh.bfs_create(n, drow, dnbr, wgs)
+        sh.bfs_configure(g, mode)
         dl = torch.empty(n, dtype=torch.int32, device="cuda:0")
         dp = torch.empty(n, dtype=torch.int32, device="cuda:0")
         for root in roots:
@@ -248,14 +249,16 @@ def run_bfs_case(row, nbr, roots, npes, wgs):
         assert sh.malloc(hb) == base                      # everything was returned to the heap
 
 
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP])
 @pytest.mark.parametrize("scale,npes,wgs", [(10, 16, 1), (14, 16, 4), (13, 3, 2), (16, 16, 8)])
-def test_bfs_rmat(scale, npes, wgs):
+def test_bfs_rmat(scale, npes, wgs, mode):
     row, nbr = workgen.rmat_csr(scale)
     roots = workgen.bfs_roots(row, 3)
-    run_bfs_case(row, nbr, roots, npes, wgs)
+    run_bfs_case(row, nbr, roots, npes, wgs, mode)
 
 
-def test_bfs_tiny_and_hub_graphs():
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP])
+def test_bfs_tiny_and_hub_graphs(mode):
     # a path, an isolated pair, and a star whose centre has more neighbours than
     # the long-row threshold (exercises the team-wide expansion)
     hub_deg = 5000
@@ -263,4 +266,4 @@ def test_bfs_tiny_and_hub_graphs():
     dst = np.r_[np.arange(1, 10), [21], np.arange(31, 31 + hub_deg)].astype(np.uint32)
     n = 31 + hub_deg + 5
     row, nbr = workgen.csr_from_edges(n, src, dst)
-    run_bfs_case(row, nbr, [0, 9, 20, 30, 31, 4000, n - 1], 4, 2)
+    run_bfs_case(row, nbr, [0, 9, 20, 30, 31, 4000, n - 1], 4, 2, mode)

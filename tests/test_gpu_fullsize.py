@@ -170,20 +170,22 @@ def test_config5_full_two_roots():
         dl = torch.empty(n, dtype=torch.int32, device="cuda:0")
         dp = torch.empty(n, dtype=torch.int32, device="cuda:0")
         for root in roots:
-            stats = sh.bfs(g, int(root), dl, dp)
-            level, parent = as_np(dl, np.int32).copy(), as_np(dp, np.uint32).copy()
             olevel, oparent, ostats = w.bfs(row, nbr, int(root))
             print("oracle search done", flush=True)
-            assert np.array_equal(level, olevel)
-            assert stats == ostats
-            reached = level >= 0
-            assert parent[root] == root and ((parent == sh.BFS_NONE) == ~reached).all()
-            vs = np.flatnonzero(reached)
-            vs = vs[vs != root]
-            us = parent[vs].astype(np.int64)
-            assert (level[us] == level[vs] - 1).all()             # every tree edge spans one level
-            assert stats["edges_traversed"] == int(deg[reached].sum()) // 2
-            for v in vs[:: max(1, len(vs) // 2000)]:              # sampled: the tree edge exists
-                u = int(parent[v])
-                assert v in nbr[row[u]:row[u + 1]]
+            for mode in (sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING):
+                sh.bfs_configure(g, mode)
+                stats = sh.bfs(g, int(root), dl, dp)
+                level, parent = as_np(dl, np.int32).copy(), as_np(dp, np.uint32).copy()
+                assert np.array_equal(level, olevel)
+                assert stats == ostats
+                reached = level >= 0
+                assert parent[root] == root and ((parent == sh.BFS_NONE) == ~reached).all()
+                vs = np.flatnonzero(reached)
+                vs = vs[vs != root]
+                us = parent[vs].astype(np.int64)
+                assert (level[us] == level[vs] - 1).all()             # every tree edge spans one level
+                assert stats["edges_traversed"] == int(deg[reached].sum()) // 2
+                for v in vs[:: max(1, len(vs) // 2000)]:              # sampled: the tree edge exists
+                    u = int(parent[v])
+                    assert v in nbr[row[u]:row[u + 1]]
         sh.bfs_destroy(g)
