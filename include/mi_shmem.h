@@ -226,13 +226,15 @@ int shmem_bfs_destroy(void *graph);
  * owner scans its own unvisited vertices and looks for a neighbour in the current
  * frontier with one-sided gets of the owners' frontier bitmaps; claim, parent,
  * level and queue entry are then local writes -- when the frontier's row lengths
- * add up to more than 1/14 of those of the unvisited vertices, and back to
- * top-down when the frontier is below nverts/24 and shrinking.  BOTTOM_UP forces
+ * add up to more than 1/alpha of those of the unvisited vertices, and back to
+ * top-down when the frontier is below nverts/beta and shrinking (alpha, beta = 0:
+ * the
+ * defaults, 30 and 24).  BOTTOM_UP forces
  * bottom-up on every level (for tests).  Levels, frontier sizes and counts are
  * the same in every mode; parents may differ (all are valid).
  * Errors: NOT_INIT, INVALID_ARG. */
 enum { SHMEM_BFS_TOP_DOWN = 0, SHMEM_BFS_DIRECTION_OPTIMIZING = 1, SHMEM_BFS_BOTTOM_UP = 2 };
-int shmem_bfs_configure(void *graph, int mode);
+int shmem_bfs_configure(void *graph, int mode, int alpha, int beta);
 /* Runs one search; blocks the host (one stream sync per level).  dev_level
  * (int32[nverts], -1 = unreached) and dev_parent (uint32[nverts],
  * SHMEM_BFS_NONE = unreached; parent[root] = root) are DEVICE and may be NULL;

@@ -69,7 +69,7 @@ _SIG = {
     "shmem_hash_lookup": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
     "shmem_bfs_create": (_i, [C.c_uint32, _vp, _vp, _i, C.POINTER(_vp)]),
     "shmem_bfs_destroy": (_i, [_vp]),
-    "shmem_bfs_configure": (_i, [_vp, _i]),
+    "shmem_bfs_configure": (_i, [_vp, _i, _i, _i]),
     "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
     "shmem_gin_create": (_i, [_i, _i, C.POINTER(_vp)]),
     "shmem_gin_destroy": (_i, [_vp]),
@@ -229,8 +229,8 @@ def bfs_create(nverts, dev_row_off, dev_nbr, wgs_per_pe):
     return g
 
 
-def bfs_configure(graph, mode):
-    return _check(_L.shmem_bfs_configure(graph, mode), "shmem_bfs_configure")
+def bfs_configure(graph, mode, alpha=0, beta=0):
+    return _check(_L.shmem_bfs_configure(graph, mode, alpha, beta), "shmem_bfs_configure")
 
 
 def bfs_destroy(graph):

@@ -30,6 +30,7 @@ struct BfsState {
     uint64_t bitmap_off, level_off, parent_off, queue_off[2], big_off, bigscan_off, tails_off;
     uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
     uint64_t front_off, prev_off; // frontier bitmap and the bitmap as of the previous level (bottom-up levels)
+    uint64_t linked_off;          // bit set = the vertex has at least one neighbour (never changes)
     uint32_t wgs_per_pe;
 };
 
@@ -422,6 +423,23 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
 // atomics on the bitmap).  It examines far fewer edges than top-down once the
 // frontier holds most of the remaining edges.
 
+// Once per graph: bit l of the owner's `linked` bitmap = local vertex l has a non-empty row.
+__global__ __launch_bounds__(256) void k_bfs_mark_linked(Ctx c, BfsState s)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6, wave = threadIdx.x >> 6;
+    const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint64_t first = (uint64_t)pe * s.vpp;
+    const uint64_t count = first >= s.nverts ? 0 : (s.nverts - first < s.vpp ? s.nverts - first : s.vpp);
+    uint64_t *linked = (uint64_t *)ptr(c, s.linked_off, pe);
+    for (uint64_t w = my_wave; w < s.words; w += team_waves) {
+        const uint64_t l = w * 64 + lane;
+        const bool has = l < count && s.row_off[first + l + 1] > s.row_off[first + l];
+        const uint64_t m = ballot(has);
+        if (lane == 0) linked[w] = m;
+    }
+}
+
 // frontier bitmap of the level about to be expanded = newly set bits; runs after init and each level
 __global__ __launch_bounds__(256) void k_bfs_make_front(Ctx c, BfsState s)
 {
@@ -452,6 +470,15 @@ __global__ __launch_bounds__(256) void k_bfs_front_degree(Ctx c, BfsState s, uin
     if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(&c.scratch[W_WORK + 2], sum);
 }
 
+// is u in the current frontier?  (an 8-byte get from u's owner)
+__device__ __forceinline__ bool bfs_in_front(const Ctx &c, const BfsState &s, uint32_t u)
+{
+    const uint32_t o = bfs_owner(s, u), lu = u - o * s.vpp;
+    return (((const uint64_t *)ptr(c, s.front_off, o))[lu >> 6] >> (lu & 63)) & 1;
+}
+
+constexpr uint32_t BU_LANE_EDGES = 16;  // neighbours a lane scans on its own before the wave helps
+
 // Bottom-up level L -> L+1.  A wave owns one bitmap word (64 consecutive local
 // vertices, lane = bit) at a time.
 __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_t L)
@@ -464,6 +491,7 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     if (first >= s.nverts) return;
     const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
     uint64_t *vis = (uint64_t *)ptr(c, s.bitmap_off, pe);
+    const uint64_t *linked = (const uint64_t *)ptr(c, s.linked_off, pe);
     int32_t *lv = (int32_t *)ptr(c, s.level_off, pe);
     uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
     uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], pe);
@@ -471,18 +499,35 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     uint64_t mf = 0;
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
         const uint64_t visw = vis[w];
-        if (visw == ~0ull) continue;
+        const uint64_t todo = ~visw & linked[w];         // unvisited vertices that have neighbours
+        if (todo == 0) continue;
         const uint64_t l = w * 64 + lane;
         uint32_t par = SHMEM_BFS_NONE, deg = 0;
-        if (l < count && !((visw >> lane) & 1)) {
-            const uint64_t r0 = s.row_off[first + l], r1 = s.row_off[first + l + 1];
-            deg = (uint32_t)(r1 - r0);
-            for (uint64_t e = r0; e < r1; ++e) {
-                const uint32_t u = s.nbr[e];
-                const uint32_t o = bfs_owner(s, u), lu = u - o * s.vpp;
-                const uint64_t fw = ((const uint64_t *)ptr(c, s.front_off, o))[lu >> 6];   // get from u's owner
-                if ((fw >> (lu & 63)) & 1) { par = u; break; }
+        uint64_t r0 = 0;
+        if ((todo >> lane) & 1) {
+            r0 = s.row_off[first + l];
+            deg = (uint32_t)(s.row_off[first + l + 1] - r0);
+            const uint32_t own = deg < BU_LANE_EDGES ? deg : BU_LANE_EDGES;   // the lane's own share of the row
+            for (uint32_t j = 0; j < own; ++j) {
+                const uint32_t u = s.nbr[r0 + j];
+                if (bfs_in_front(c, s, u)) { par = u; break; }
             }
+        }
+        // rows longer than a lane's share: the whole wave scans the rest, 64 neighbours at a time
+        uint64_t longrows = ballot(par == SHMEM_BFS_NONE && deg > BU_LANE_EDGES);
+        while (longrows) {
+            const uint32_t j = (uint32_t)__builtin_ctzll(longrows);
+            longrows &= longrows - 1;
+            const uint32_t dj = bcast32(deg, j);
+            const uint64_t rj = bcast64(r0, j);
+            uint32_t hit = SHMEM_BFS_NONE;
+            for (uint32_t e0 = BU_LANE_EDGES; e0 < dj && hit == SHMEM_BFS_NONE; e0 += 64) {
+                const bool act = e0 + lane < dj;
+                const uint32_t u = act ? s.nbr[rj + e0 + lane] : 0;
+                const uint64_t hm = ballot(act && bfs_in_front(c, s, u));
+                if (hm) hit = bcast32(u, (uint32_t)__builtin_ctzll(hm));
+            }
+            if (lane == j) par = hit;
         }
         const bool found = par != SHMEM_BFS_NONE;
         const uint64_t fm = ballot(found);

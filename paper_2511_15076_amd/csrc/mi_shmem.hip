@@ -22,6 +22,7 @@ namespace {
 
 constexpr size_t GRAN = 256;       // allocator granularity / minimum alignment
 constexpr int WG_THREADS = 256;    // 4 wavefronts per workgroup
+constexpr uint32_t BFS_ALPHA = 30, BFS_BETA = 24;  // default direction thresholds (measured best on R-MAT scale 24)
 
 struct Block { uint64_t off, len; };
 
@@ -43,8 +44,9 @@ struct BfsGraph {
     shmemx::BfsState st;
     int wgs_per_pe;
     int mode;          // SHMEM_BFS_TOP_DOWN / DIRECTION_OPTIMIZING / BOTTOM_UP
+    uint32_t alpha, beta;  // direction thresholds
     uint64_t nnz;      // CSR entries (sum of all row lengths)
-    void *allocs[11];
+    void *allocs[12];
     int nallocs;
 };
 
@@ -463,13 +465,13 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
     const uint64_t words = ((uint64_t)vpp + 63) / 64;
     // bitmap, level, parent, two queues, long-row list, its segment scan, counters, per-die bitmap copies,
-    // frontier bitmap, previous-level bitmap
-    const size_t sizes[11] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+    // frontier bitmap, previous-level bitmap, has-neighbours bitmap
+    const size_t sizes[12] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
                               (size_t)vpp * 4, ((size_t)vpp + 1) * 4, 256, words * 8 * shmemx::NXCD, words * 8,
-                              words * 8};
-    uint64_t offs[11];
+                              words * 8, words * 8};
+    uint64_t offs[12];
     g->nallocs = 0;
-    for (int i = 0; i < 11; ++i) {
+    for (int i = 0; i < 12; ++i) {
         void *p = shmem_malloc(sizes[i]);
         if (!p) {
             for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
@@ -485,8 +487,8 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.row_off = dev_row_off; s.nbr = dev_nbr;
     s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
     s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.big_off = offs[5]; s.bigscan_off = offs[6];
-    s.tails_off = offs[7]; s.filter_off = offs[8]; s.front_off = offs[9]; s.prev_off = offs[10];
-    g->mode = SHMEM_BFS_TOP_DOWN;
+    s.tails_off = offs[7]; s.filter_off = offs[8]; s.front_off = offs[9]; s.prev_off = offs[10]; s.linked_off = offs[11];
+    g->mode = SHMEM_BFS_TOP_DOWN; g->alpha = BFS_ALPHA; g->beta = BFS_BETA;
     g->nnz = 0;
     if (hipMemcpyAsync(H.pinned + 32, dev_row_off + nverts, 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
         hipStreamSynchronize(H.stream) != hipSuccess) {
@@ -495,8 +497,10 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
         return SHMEM_ERR_DEVICE;
     }
     g->nnz = H.pinned[32];
-    s.wgs_per_pe = (uint32_t)wgs_per_pe;
+    s.wgs_per_pe = (uint32_t)wgs_per_pe;     // before any launch that takes the state
     g->wgs_per_pe = wgs_per_pe;
+    hipLaunchKernelGGL(shmemx::k_bfs_mark_linked, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
+                       ctx(), g->st);
     *graph_out = g;
     return SHMEM_OK;
 }
@@ -512,11 +516,14 @@ int shmem_bfs_destroy(void *graph)
     return rc;
 }
 
-int shmem_bfs_configure(void *graph, int mode)
+int shmem_bfs_configure(void *graph, int mode, int alpha, int beta)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!graph || mode < SHMEM_BFS_TOP_DOWN || mode > SHMEM_BFS_BOTTOM_UP) return SHMEM_ERR_INVALID_ARG;
-    ((BfsGraph *)graph)->mode = mode;
+    if (!graph || mode < SHMEM_BFS_TOP_DOWN || mode > SHMEM_BFS_BOTTOM_UP || alpha < 0 || beta < 0) return SHMEM_ERR_INVALID_ARG;
+    BfsGraph *g = (BfsGraph *)graph;
+    g->mode = mode;
+    g->alpha = alpha ? (uint32_t)alpha : BFS_ALPHA;
+    g->beta = beta ? (uint32_t)beta : BFS_BETA;
     return SHMEM_OK;
 }
 
@@ -554,11 +561,14 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             // switch when the frontier's edges outweigh a fraction of the edges still hanging off
             // unvisited vertices; switch back when the frontier is small and shrinking
             const uint64_t m_u = g->nnz > cum_mf ? g->nnz - cum_mf : 0;
-            if (!bottom_up) bottom_up = m_f > m_u / 14;
-            else if (n_f < s.nverts / 24 && n_f < n_f_prev) bottom_up = false;
+            if (!bottom_up) bottom_up = m_f > m_u / g->alpha;
+            else if (n_f < s.nverts / g->beta && n_f < n_f_prev) bottom_up = false;
         }
         if (bottom_up) {
-            hipLaunchKernelGGL(shmemx::k_bfs_bottomup, grid, block, 0, H.stream, c, s, L);
+            // no LDS and few registers: twice the workgroups per PE fill the CUs' wave slots
+            shmemx::BfsState s2 = s;
+            s2.wgs_per_pe = s.wgs_per_pe * 2;
+            hipLaunchKernelGGL(shmemx::k_bfs_bottomup, dim3(grid.x * 2), block, 0, H.stream, c, s2, L);
         } else if (staged) {
             hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
             hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
