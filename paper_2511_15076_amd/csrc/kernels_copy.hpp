@@ -131,12 +131,74 @@ constexpr uint64_t CHUNK_BYTES = 4096;  // per wave-task, contiguous ops
 constexpr uint64_t CHUNK_ELEMS = 2048;  // per wave-task, strided ops
 constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size are packed into sub-wave groups
 
+// Contiguous messages whose size and placement are multiples of 1 KiB (the bandwidth cells): every
+// wave-task is VPL full 16-byte vectors per lane, so nothing is predicated, and the loop is software-
+// pipelined over two register sets: the loads of a wave's next task are issued before the stores of
+// its current one, which keeps reads in flight behind the writes.  (Predicated or conditional loads
+// inside the loop would make the compiler wait for every outstanding access before each store.)
+template <int VPL>
+__device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint8_t *lbase, uint8_t *rbase, uint64_t my_wave,
+                                                uint64_t team_waves, uint32_t lane)
+{
+    constexpr uint64_t TASK_VECS = 64 * VPL;
+    const uint64_t chunks = a.count / (TASK_VECS * 16);
+    const uint64_t tasks = chunks * a.ops_per_pe;
+    if (my_wave >= tasks) return;
+    // task t = (op, chunk) with slot = op % nslots; the walk t -> t + team_waves needs no division
+    const uint64_t step_ch = team_waves % chunks, step_slot = (team_waves / chunks) % a.nslots;
+    uint64_t ch = my_wave % chunks, slot = (my_wave / chunks) % a.nslots;
+    uint64_t left = (tasks - 1 - my_wave) / team_waves;  // tasks of this wave after its first
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    // wave-uniform bases plus one constant per-lane byte offset: the addresses live in scalar registers
+    const uint8_t *const sbase = is_put ? lbase : rbase;
+    uint8_t *const dbase = is_put ? rbase : lbase;
+    const uint64_t sslot = is_put ? a.local_slot : a.remote_slot, dslot = is_put ? a.remote_slot : a.local_slot;
+    const uint32_t lane_off = lane * 16;
+    auto locate = [&](const uint8_t *&src, uint8_t *&dst) {
+        src = sbase + slot * sslot + ch * (TASK_VECS * 16);
+        dst = dbase + slot * dslot + ch * (TASK_VECS * 16);
+    };
+    auto advance = [&]() {
+        ch += step_ch;
+        slot += step_slot;
+        if (ch >= chunks) { ch -= chunks; slot += 1; }
+        if (slot >= a.nslots) slot -= a.nslots;
+    };
+    auto load = [&](u32x4 (&v)[VPL], const uint8_t *src) {
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) v[j] = __builtin_nontemporal_load((const u32x4 *)(src + lane_off) + 64 * j);
+    };
+    auto store = [&](const u32x4 (&v)[VPL], uint8_t *dst) {
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(v[j], (u32x4 *)(dst + lane_off) + 64 * j);
+    };
+    u32x4 va[VPL], vb[VPL];
+    const uint8_t *src;
+    uint8_t *da, *db;
+    locate(src, da);
+    load(va, src);
+    for (;;) {
+        if (left == 0) { store(va, da); break; }
+        advance();
+        locate(src, db);
+        load(vb, src);
+        store(va, da);
+        if (left == 1) { store(vb, db); break; }
+        advance();
+        locate(src, da);
+        load(va, src);
+        store(vb, db);
+        left -= 2;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
 {
     const uint32_t pe = blockIdx.x / a.wgs_per_pe;
     const uint32_t wg = blockIdx.x % a.wgs_per_pe;
     const uint32_t peer = (pe + 1) % (uint32_t)c.npes;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves_per_wg = blockDim.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, waves_per_wg = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t team_waves = (uint64_t)a.wgs_per_pe * waves_per_wg;
     const uint64_t my_wave = (uint64_t)wg * waves_per_wg + wave;
     const bool contiguous = a.kind <= SHMEM_OP_GET;
@@ -161,6 +223,12 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
                 else __builtin_nontemporal_store(__builtin_nontemporal_load(r), l);
             }
         }
+        return;
+    }
+    if (contiguous && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 1023) == 0) {
+        if (a.count % 4096 == 0) sweep_pipelined<4>(a, lbase, rbase, my_wave, team_waves, lane);
+        else if (a.count % 2048 == 0) sweep_pipelined<2>(a, lbase, rbase, my_wave, team_waves, lane);
+        else sweep_pipelined<1>(a, lbase, rbase, my_wave, team_waves, lane);
         return;
     }
     for (uint64_t t = my_wave; t < tasks; t += team_waves) {
