@@ -405,7 +405,7 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a plain 1 GiB copy
                      # (profiles/k_copy_sweep_config2_put_get_1-64MiB.md)
-                     "traffic": 4294.99e6,
+                     "traffic": 4295.11e6,
                      "kernel": "k_copy_sweep", "avg_launch_ms": round(avg_launch_ms, 4),
                      "algorithmic_bytes_per_launch": 2 * payload_per_launch},
         "cells": detail,
