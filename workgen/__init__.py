@@ -162,6 +162,44 @@ def cfg4_queries(keys: np.ndarray, seed: int = BASE_SEED + 4, n: int | None = No
 # --------------------------------------------------------------------------
 # config 5: R-MAT graph in CSR form, BFS roots
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# MoE-shaped all-to-all traffic (small token batches, top-k routing)
+# --------------------------------------------------------------------------
+def moe_routing(seed: int = BASE_SEED + 60, npes: int = 8, num_experts: int = 288, max_tokens: int = 128,
+                topk: int = 8, ntok=None, dist: str = "uniform", drop: float = 0.0) -> tuple[np.ndarray, np.ndarray]:
+    """Routing tables of a decode-sized expert-parallel batch.
+
+    Returns (topk_idx, ntok): topk_idx is int32 [npes, max_tokens, topk], the experts of
+    each token (distinct within a token, -1 = unused entry; rows at or beyond a PE's ntok are
+    all -1); ntok is int32 [npes].  ``dist`` is "uniform" or "zipf" (expert popularity
+    proportional to 1/(rank+1)); ``drop`` is the probability that an entry is replaced by -1.
+    """
+    rng = rng_for(seed)
+    if ntok is None:
+        ntok = np.full(npes, max_tokens, dtype=np.int32)
+    ntok = np.broadcast_to(np.asarray(ntok, dtype=np.int32), (npes,)).copy()
+    assert ntok.min() >= 0 and ntok.max() <= max_tokens and topk <= num_experts
+    if dist == "uniform":
+        score = rng.random((npes, max_tokens, num_experts))
+    elif dist == "zipf":
+        w = 1.0 / (1.0 + rng.permutation(num_experts))
+        score = rng.random((npes, max_tokens, num_experts)) ** (1.0 / w)      # weighted sampling without replacement
+    else:
+        raise ValueError(dist)
+    idx = np.argsort(-score, axis=2)[:, :, :topk].astype(np.int32)
+    if drop > 0:
+        idx[rng.random(idx.shape) < drop] = -1
+    for p in range(npes):
+        idx[p, ntok[p]:] = -1
+    return np.ascontiguousarray(idx), ntok
+
+
+def moe_tokens(seed: int = BASE_SEED + 61, npes: int = 8, max_tokens: int = 128, hidden_bytes: int = 14336) -> np.ndarray:
+    """Token payloads: uint8 [npes, max_tokens, hidden_bytes] of uniform random bytes."""
+    words = rng_for(seed).integers(0, 2**32 - 1, size=(npes, max_tokens, hidden_bytes // 4), dtype=np.uint32, endpoint=True)
+    return words.view(np.uint8).reshape(npes, max_tokens, hidden_bytes)
+
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libworkgen.so")
 _lib = None
