@@ -292,6 +292,68 @@ int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int i
  * Errors as above. */
 int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors);
 
+/* -------------------------------------------------------------------------
+ * MoE-shaped all-to-all in traffic shape: the low-latency dispatch / combine
+ * of Sec. IV-B ("Low-Latency Kernel Integration") with the message sizes of
+ * Sec. V-A (dispatch: 16 bytes of source-index metadata + the token; combine:
+ * the token alone).  Payloads are opaque bytes; no quantisation, compression
+ * or weighted floating-point reduction.
+ *
+ * num_experts experts are spread evenly over the PEs (expert e lives on PE
+ * e / (num_experts / npes)).  Every PE holds up to max_tokens tokens of
+ * hidden_bytes bytes, each routed to up to topk distinct experts.
+ *
+ * shmem_moe_create allocates, in the symmetric heap, the dispatch receive slots
+ * ((num_experts/npes) * npes * max_tokens messages per PE), the combine slots
+ * (max_tokens * topk tokens per PE) and the signals (one per (local expert,
+ * sender) pair for the counts, one per expert for the combine flags), and
+ * clears the signals.  Limits: num_experts a multiple of npes and <= 1024,
+ * max_tokens <= 128, topk <= 64, npes <= 256, hidden_bytes a positive
+ * multiple of 16.  *moe_out is owned by the library until shmem_moe_destroy.
+ * Errors: NOT_INIT, INVALID_ARG, NOMEM (heap too small), DEVICE. */
+typedef struct shmem_moe *shmem_moe_t;
+int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_bytes, shmem_moe_t *moe_out);
+int shmem_moe_destroy(shmem_moe_t moe);
+
+/* One dispatch, asynchronous on the library's stream.  All arrays are DEVICE
+ * memory owned by the caller, 16-byte aligned, with the PE as leading index:
+ *   dev_x        const uint8 [npes][max_tokens][hidden_bytes]   tokens
+ *   dev_topk     const int32 [npes][max_tokens][topk]  expert ids, < 0 = unused entry
+ *   dev_ntok     const int32 [npes]                    tokens held by each PE
+ *   dev_recv_x   uint8 [npes][E/npes][npes*max_tokens][hidden_bytes]  tokens received per local expert
+ *   dev_recv_info int32 [npes][E/npes][npes*max_tokens][4]  per received token: source token
+ *                index, source PE, position in the token's top-k list, expert id
+ *   dev_recv_range int32 [npes][E/npes][npes][2]  (begin, count) of each sender's rows
+ *   dev_recv_count int32 [npes][E/npes]           rows in use per local expert
+ * Each sender writes one (metadata + token) message per route directly into a
+ * slot at the expert's owner and then delivers the count of the (sender,
+ * expert) pair with a zero-byte put + SignalAdd (release, then remote atomic
+ * add of count + 1); receivers poll the signals, reset them and pack the
+ * messages: senders in ascending PE order, a sender's tokens in ascending
+ * order.  Rows beyond dev_recv_count are not written.  An expert id >=
+ * num_experts or repeated within a token sets the device fault word
+ * (shmem_stream_sync: BAD_TARGET / BAD_OP); that entry is skipped.  The waits
+ * are bounded.  wgs_per_pe workgroups per PE must all be co-resident.
+ * Errors: NOT_INIT, INVALID_ARG, ALIGN, DEVICE. */
+int shmem_moe_dispatch(shmem_moe_t moe, const void *dev_x, const int32_t *dev_topk, const int32_t *dev_ntok,
+                       void *dev_recv_x, int32_t *dev_recv_info, int32_t *dev_recv_range, int32_t *dev_recv_count,
+                       int wgs_per_pe);
+
+/* One combine, asynchronous on the library's stream: row i of local expert le
+ * on PE r in dev_expert_out (uint8, shaped like dev_recv_x) is sent to slot
+ * (token, position) of the source PE named by dev_recv_info; after an expert's
+ * rows one flag signal per destination follows the data (zero-byte put +
+ * SignalAdd); each PE waits for the flags of a token's experts and writes
+ *   dev_combined uint8 [npes][max_tokens][hidden_bytes]
+ * = per token the sum, modulo 2^32 per 32-bit word, of the rows returned for
+ * its valid routes (tokens at or beyond dev_ntok are not written).
+ * dev_recv_info / dev_recv_range are the outputs of the matching dispatch;
+ * dev_topk / dev_ntok are its inputs.  Flags count calls and are never reset.
+ * Errors: as shmem_moe_dispatch. */
+int shmem_moe_combine(shmem_moe_t moe, const void *dev_expert_out, const int32_t *dev_recv_info,
+                      const int32_t *dev_recv_range, const int32_t *dev_topk, const int32_t *dev_ntok,
+                      void *dev_combined, int wgs_per_pe);
+
 #ifdef __cplusplus
 }
 #endif

@@ -78,6 +78,10 @@ _SIG = {
     "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i, _i, _i]),
     "shmem_pingpong": (_i, [_vp, _sz, _vp, _i, _i]),
     "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
+    "shmem_moe_create": (_i, [_i, _i, _i, _sz, C.POINTER(_vp)]),
+    "shmem_moe_destroy": (_i, [_vp]),
+    "shmem_moe_dispatch": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i]),
+    "shmem_moe_combine": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_L, _name)
@@ -274,3 +278,26 @@ def pingpong(buf_sym, nbytes, gin, signal_id, iters):
 def barrier_epochs(slots_sym, rounds, wgs_per_pe, dev_errors=None):
     return _check(_L.shmem_barrier_epochs(_addr(slots_sym), rounds, wgs_per_pe, _addr(dev_errors)),
                   "shmem_barrier_epochs")
+
+
+def moe_create(num_experts, max_tokens, topk, hidden_bytes):
+    m = _vp(0)
+    _check(_L.shmem_moe_create(num_experts, max_tokens, topk, hidden_bytes, C.byref(m)), "shmem_moe_create")
+    return m
+
+
+def moe_destroy(moe):
+    return _check(_L.shmem_moe_destroy(moe), "shmem_moe_destroy")
+
+
+def moe_dispatch(moe, dev_x, dev_topk, dev_ntok, dev_recv_x, dev_recv_info, dev_recv_range, dev_recv_count,
+                 wgs_per_pe):
+    return _check(_L.shmem_moe_dispatch(moe, _addr(dev_x), _addr(dev_topk), _addr(dev_ntok), _addr(dev_recv_x),
+                                        _addr(dev_recv_info), _addr(dev_recv_range), _addr(dev_recv_count),
+                                        wgs_per_pe), "shmem_moe_dispatch")
+
+
+def moe_combine(moe, dev_expert_out, dev_recv_info, dev_recv_range, dev_topk, dev_ntok, dev_combined, wgs_per_pe):
+    return _check(_L.shmem_moe_combine(moe, _addr(dev_expert_out), _addr(dev_recv_info), _addr(dev_recv_range),
+                                       _addr(dev_topk), _addr(dev_ntok), _addr(dev_combined), wgs_per_pe),
+                  "shmem_moe_combine")

@@ -1,0 +1,263 @@
+// MoE-shaped all-to-all in traffic shape: the low-latency dispatch and combine
+// of Sec. IV-B ("Low-Latency Kernel Integration") at the message sizes of
+// Sec. V-A (16 bytes of source-index metadata + the token; the token alone on
+// the way back), on emulated PEs.  No quantisation, compression or weighted
+// floating-point reduction: payloads are opaque bytes and the combine reduction
+// is a wrapping sum of 32-bit words.
+//
+// Dispatch: every (token, expert) route is one message written straight into a
+// receive slot at the expert's owner.  When all messages of one (sender,
+// expert) pair are complete the sender delivers the pair's token count with a
+// zero-byte put + SignalAdd (here: release, then a remote atomic add of
+// count + 1 on signal le * npes + sender), so the count is only visible after
+// the data.  Receivers poll their signals (readSignal), then pack what arrived
+// per local expert: senders in ascending PE order, each sender's tokens in
+// ascending token order.
+// Combine: every expert output goes back to slot (token, top-k position) at the
+// token's source PE; one flag signal per (expert, destination) pair follows the
+// data; the destination waits for the flags of a token's experts and sums the
+// copies.
+//
+// Work split: workgroup w of a PE's team owns the experts e = w (mod team size)
+// when sending and the local experts / tokens with the same residue when
+// receiving, so one workgroup-level release covers all messages of a pair.
+// Both kernels are launched cooperatively (all workgroups resident): every
+// workgroup finishes sending before it starts to wait.
+#pragma once
+#include "gin.hpp"
+#include "shmemx.hpp"
+
+namespace shmemx {
+
+constexpr uint32_t MOE_MAX_EXPERTS = 1024;  // per-expert token masks live in LDS
+constexpr uint32_t MOE_MAX_TOKENS = 128;    // two 64-bit mask words per expert
+constexpr uint32_t MOE_MAX_TOPK = 64;       // one lane per top-k position
+constexpr uint32_t MOE_MAX_PES = 256;
+constexpr uint32_t MOE_META_BYTES = 16;
+
+struct MoeState {
+    uint32_t num_experts, epp, max_tokens, topk;
+    uint64_t hidden, msg;    // token bytes (multiple of 16); dispatch message bytes = 16 + hidden
+    uint64_t recv_off;       // symmetric: [epp][npes][max_tokens] dispatch messages
+    uint64_t comb_off;       // symmetric: [max_tokens][topk] returned tokens
+    GinState gin;            // signals [0, epp*npes): dispatch counts; then num_experts combine flags
+};
+
+struct MoeDispatchArgs {
+    const uint8_t *x;        // [npes][max_tokens][hidden]
+    const int32_t *topk;     // [npes][max_tokens][topk]
+    const int32_t *ntok;     // [npes]
+    uint8_t *recv_x;         // [npes][epp][npes*max_tokens][hidden]
+    int32_t *recv_info;      // [npes][epp][npes*max_tokens][4]
+    int32_t *recv_range;     // [npes][epp][npes][2]
+    int32_t *recv_count;     // [npes][epp]
+    uint32_t wgs_per_pe;
+};
+
+struct MoeCombineArgs {
+    const uint8_t *expert_out;  // [npes][epp][npes*max_tokens][hidden]
+    const int32_t *recv_info, *recv_range, *topk, *ntok;
+    uint8_t *combined;          // [npes][max_tokens][hidden]
+    uint64_t epoch;             // number of this combine on the object (flags count calls)
+    uint32_t wgs_per_pe;
+};
+
+// One wave copies nv 16-byte vectors, eight loads per lane in flight.
+__device__ __forceinline__ void wave_copy16(u32x4 *__restrict__ d, const u32x4 *__restrict__ s, uint32_t nv, uint32_t lane)
+{
+    constexpr int IF = 8;
+    uint32_t i = lane;
+    for (; i + (IF - 1) * 64 < nv; i += IF * 64) {
+        u32x4 v[IF];
+#pragma unroll
+        for (int k = 0; k < IF; ++k) v[k] = __builtin_nontemporal_load(s + i + 64 * k);
+#pragma unroll
+        for (int k = 0; k < IF; ++k) __builtin_nontemporal_store(v[k], d + i + 64 * k);
+    }
+    u32x4 v[IF - 1];
+#pragma unroll
+    for (int k = 0; k < IF - 1; ++k) if (i + 64 * k < nv) v[k] = __builtin_nontemporal_load(s + i + 64 * k);
+#pragma unroll
+    for (int k = 0; k < IF - 1; ++k) if (i + 64 * k < nv) __builtin_nontemporal_store(v[k], d + i + 64 * k);
+}
+
+// position of the n-th (0-based) set bit of the 128-bit mask (m0 = tokens 0..63, m1 = 64..127)
+__device__ __forceinline__ uint32_t moe_nth_token(uint64_t m0, uint64_t m1, uint32_t n)
+{
+    const uint32_t c0 = (uint32_t)__popcll(m0);
+    uint64_t m = n < c0 ? m0 : m1;
+    uint32_t k = n < c0 ? n : n - c0;
+    for (; k; --k) m &= m - 1;
+    return (uint32_t)__builtin_ctzll(m) + (n < c0 ? 0u : 64u);
+}
+
+// bounded poll of one of the caller's own signals until it is at least `expected`
+__device__ __forceinline__ uint64_t moe_poll(const Gin &gin, uint32_t id, uint64_t expected)
+{
+    uint32_t spins = 0;
+    uint64_t v;
+    while ((v = gin.read_signal(id)) < expected) {
+        if (timed_out(gin.c)) break;
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > SPIN_LIMIT) { report(gin.c, DEV_ERR_BARRIER_TIMEOUT, gin.pe); break; }
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
+{
+    __shared__ uint64_t mask[MOE_MAX_EXPERTS][2];   // per expert: which of this PE's tokens go there
+    __shared__ uint32_t begin[MOE_MAX_PES + 1];
+    const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
+    const uint32_t P = (uint32_t)c.npes, E = m.num_experts, T = m.max_tokens, K = m.topk;
+    const uint32_t lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Gin gin{c, m.gin, pe, W};
+    const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
+    const int32_t *topk = a.topk + (size_t)pe * T * K;
+    const uint32_t hvecs = (uint32_t)(m.hidden / 16);
+
+    // ---- routing masks (every workgroup builds its own copy: at most 128 x topk entries) ----
+    for (uint32_t i = threadIdx.x; i < 2 * E; i += blockDim.x) (&mask[0][0])[i] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < ntok * K; i += blockDim.x) {
+        const int32_t e = topk[i];
+        if (e < 0) continue;                          // unused entry
+        const uint32_t t = i / K;
+        if ((uint32_t)e >= E) { report(c, DEV_ERR_BAD_TARGET, (uint64_t)pe * T * K + i); continue; }
+        const uint64_t bit = 1ull << (t & 63);
+        const uint64_t old = __hip_atomic_fetch_or(&mask[e][t >> 6], bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (old & bit) report(c, DEV_ERR_BAD_OP, (uint64_t)pe * T * K + i);   // an expert twice in one token
+    }
+    __syncthreads();
+
+    // ---- send: the routes of this workgroup's experts, dealt round-robin to its waves ----
+    uint32_t q = 0;                                                          // running route number (same in every wave)
+    for (uint32_t e = wg; e < E; e += W) {
+        const uint32_t owner = e / m.epp, le = e % m.epp;
+        const uint64_t m0 = mask[e][0], m1 = mask[e][1];
+        const uint32_t n = (uint32_t)(__popcll(m0) + __popcll(m1));
+        for (uint32_t i = 0; i < n; ++i, ++q) {                              // slot i = i-th token in ascending order
+            if (q % nwaves != wave) continue;
+            const uint32_t t = moe_nth_token(m0, m1, i);
+            const uint64_t hit = ballot(lane < K && topk[t * K + min(lane, K - 1)] == (int32_t)e);
+            const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
+            uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
+            if (lane == 0) {
+                u32x4 meta = {t, pe, j, e};
+                __builtin_nontemporal_store(meta, (u32x4 *)slot);
+            }
+            wave_copy16((u32x4 *)(slot + MOE_META_BYTES), (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden), hvecs, lane);
+        }
+    }
+    // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
+    // complete and one release has made them visible, so a count is never seen before its data
+    wg_release();
+    if (threadIdx.x < 64) {
+        quiet();
+        for (uint32_t e = wg + lane * W; e < E; e += 64 * W) {
+            const uint32_t n = (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+            __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)n + 1, __ATOMIC_RELAXED,
+                                   SHMEMX_AGENT);
+        }
+    }
+
+    // ---- receive: this workgroup's local experts ----
+    for (uint32_t le = wg; le < m.epp; le += W) {
+        __syncthreads();                                                     // begin[] of the previous expert is done with
+        for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+            const uint64_t v = moe_poll(gin, le * P + s, 1);
+            begin[s + 1] = v ? (uint32_t)min(v - 1, (uint64_t)T) : 0;        // 0 only after a time-out
+            gin.reset_signal(le * P + s);                                    // nobody else reads it; next dispatch starts clean
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) acquire();                                     // what the signals released is now readable
+        wg_acquire();
+        if (threadIdx.x == 0) {
+            begin[0] = 0;
+            for (uint32_t s = 0; s < P; ++s) begin[s + 1] += begin[s];
+        }
+        __syncthreads();
+        const uint32_t total = begin[P];
+        const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
+        for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+            a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)begin[s];
+            a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(begin[s + 1] - begin[s]);
+        }
+        if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
+        for (uint32_t i = wave; i < total; i += nwaves) {
+            uint32_t s = 0;
+            while (begin[s + 1] <= i) ++s;
+            const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[s])) * m.msg, pe);
+            if (lane == 0) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = *(const u32x4 *)slot;
+            wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden), (const u32x4 *)(slot + MOE_META_BYTES), hvecs, lane);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_moe_combine(Ctx c, MoeState m, MoeCombineArgs a)
+{
+    __shared__ uint32_t begin[MOE_MAX_PES + 1];
+    __shared__ int32_t experts[MOE_MAX_TOPK];
+    const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
+    const uint32_t P = (uint32_t)c.npes, T = m.max_tokens, K = m.topk;
+    const uint32_t lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const Gin gin{c, m.gin, pe, W};
+    const uint32_t flag0 = m.epp * P;                                        // first combine flag ID
+    const uint32_t hvecs = (uint32_t)(m.hidden / 16);
+
+    // ---- send: the outputs of this workgroup's local experts go back to the tokens' sources ----
+    for (uint32_t le = wg; le < m.epp; le += W) {
+        __syncthreads();
+        const size_t pair0 = ((size_t)pe * m.epp + le) * P;
+        if (threadIdx.x == 0) {
+            begin[0] = 0;
+            for (uint32_t s = 0; s < P; ++s) {
+                const int32_t n = a.recv_range[(pair0 + s) * 2 + 1];
+                begin[s + 1] = begin[s] + (uint32_t)min(max(n, 0), (int32_t)T);
+            }
+        }
+        __syncthreads();
+        const uint32_t total = begin[P];
+        const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
+        for (uint32_t i = wave; i < total; i += nwaves) {
+            const u32x4 info = *(const u32x4 *)(a.recv_info + (row0 + i) * 4);   // token, source PE, position, expert
+            const uint32_t t = info.x, s = info.y, j = info.z;
+            if (t >= T || s >= P || j >= K) { if (lane == 0) report(c, DEV_ERR_BAD_OP, row0 + i); continue; }
+            wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s),
+                        (const u32x4 *)(a.expert_out + (row0 + i) * m.hidden), hvecs, lane);
+        }
+        // flags: zero-byte put + SignalAdd to every destination, after one release for the whole expert
+        wg_release();
+        if (threadIdx.x < 64) {
+            quiet();
+            for (uint32_t s = lane; s < P; s += 64)
+                __hip_atomic_fetch_add(gin.signal_word(flag0 + pe * m.epp + le, s), 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        }
+    }
+
+    // ---- receive: this workgroup's tokens ----
+    const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
+    for (uint32_t t = wg; t < ntok; t += W) {
+        __syncthreads();
+        if (threadIdx.x < K) {
+            const int32_t e = a.topk[((size_t)pe * T + t) * K + threadIdx.x];
+            const bool ok = e >= 0 && (uint32_t)e < m.num_experts;
+            experts[threadIdx.x] = ok ? e : -1;
+            if (ok) moe_poll(gin, flag0 + (uint32_t)e, a.epoch);             // that expert's outputs for this PE are in
+        }
+        if (threadIdx.x < 64) acquire();
+        wg_acquire();
+        const u32x4 *slots = (const u32x4 *)ptr(c, m.comb_off + (uint64_t)t * K * m.hidden, pe);
+        u32x4 *out = (u32x4 *)(a.combined + ((size_t)pe * T + t) * m.hidden);
+        for (uint32_t v = threadIdx.x; v < hvecs; v += blockDim.x) {
+            u32x4 acc = {0, 0, 0, 0};
+            for (uint32_t j = 0; j < K; ++j)
+                if (experts[j] >= 0) acc += __builtin_nontemporal_load(slots + (size_t)j * hvecs + v);
+            __builtin_nontemporal_store(acc, out + v);
+        }
+    }
+}
+
+}  // namespace shmemx

@@ -17,6 +17,7 @@
 #include "kernels_hash.hpp"
 #include "kernels_bfs.hpp"
 #include "kernels_sync.hpp"
+#include "kernels_moe.hpp"
 
 namespace {
 
@@ -713,6 +714,102 @@ int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64
     void *args[] = {&c, &off, &r, &w, &dev_errors};
     return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid),
                                              dim3(WG_THREADS), args, 0, H.stream));
+}
+
+// ---------------------------------------------------------------------------
+struct shmem_moe {
+    shmemx::MoeState st;
+    void *recv_alloc, *comb_alloc, *sig_alloc;
+    uint64_t combines;   // combine calls so far (the flags count them)
+};
+
+int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_bytes, shmem_moe_t *moe_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!moe_out || num_experts < 1 || max_tokens < 1 || topk < 1 || hidden_bytes == 0) return SHMEM_ERR_INVALID_ARG;
+    if (num_experts % H.npes || (uint32_t)num_experts > shmemx::MOE_MAX_EXPERTS || (uint32_t)max_tokens > shmemx::MOE_MAX_TOKENS ||
+        (uint32_t)topk > shmemx::MOE_MAX_TOPK || topk > num_experts || (uint32_t)H.npes > shmemx::MOE_MAX_PES ||
+        hidden_bytes % 16 || hidden_bytes > (1u << 30)) return SHMEM_ERR_INVALID_ARG;
+    shmem_moe *m = new (std::nothrow) shmem_moe();
+    if (!m) return SHMEM_ERR_NOMEM;
+    shmemx::MoeState &st = m->st;
+    st.num_experts = (uint32_t)num_experts; st.epp = (uint32_t)(num_experts / H.npes);
+    st.max_tokens = (uint32_t)max_tokens; st.topk = (uint32_t)topk;
+    st.hidden = hidden_bytes; st.msg = hidden_bytes + shmemx::MOE_META_BYTES;
+    const uint32_t nsig = st.epp * (uint32_t)H.npes + st.num_experts;
+    unsigned __int128 recv_bytes = (unsigned __int128)st.epp * (unsigned)H.npes * (unsigned)max_tokens * st.msg;
+    unsigned __int128 comb_bytes = (unsigned __int128)max_tokens * (unsigned)topk * st.hidden;
+    if (recv_bytes > H.seg || comb_bytes > H.seg) { delete m; return SHMEM_ERR_NOMEM; }
+    m->recv_alloc = shmem_malloc((size_t)recv_bytes);
+    m->comb_alloc = m->recv_alloc ? shmem_malloc((size_t)comb_bytes) : nullptr;
+    m->sig_alloc = m->comb_alloc ? shmem_malloc((size_t)nsig * 8) : nullptr;
+    if (!m->sig_alloc) {
+        if (m->comb_alloc) shmem_free(m->comb_alloc);
+        if (m->recv_alloc) shmem_free(m->recv_alloc);
+        delete m;
+        return SHMEM_ERR_NOMEM;
+    }
+    st.recv_off = (uint64_t)((uint8_t *)m->recv_alloc - H.heap);
+    st.comb_off = (uint64_t)((uint8_t *)m->comb_alloc - H.heap);
+    st.gin.signals_off = (uint64_t)((uint8_t *)m->sig_alloc - H.heap);
+    st.gin.counters_off = st.gin.signals_off;
+    st.gin.nsignals = nsig; st.gin.ncounters = 0;
+    m->combines = 0;
+    hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), st.gin);
+    if (int rc = launched()) { shmem_moe_destroy(m); return rc; }
+    *moe_out = m;
+    return SHMEM_OK;
+}
+
+int shmem_moe_destroy(shmem_moe_t m)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!m) return SHMEM_ERR_INVALID_ARG;
+    int rc = shmem_free(m->sig_alloc);
+    int rc2 = shmem_free(m->comb_alloc);
+    int rc3 = shmem_free(m->recv_alloc);
+    delete m;
+    return rc ? rc : rc2 ? rc2 : rc3;
+}
+
+int shmem_moe_dispatch(shmem_moe_t m, const void *dev_x, const int32_t *dev_topk, const int32_t *dev_ntok,
+                       void *dev_recv_x, int32_t *dev_recv_info, int32_t *dev_recv_range, int32_t *dev_recv_count,
+                       int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!m || !dev_x || !dev_topk || !dev_ntok || !dev_recv_x || !dev_recv_info || !dev_recv_range || !dev_recv_count ||
+        wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_x | (uintptr_t)dev_recv_x | (uintptr_t)dev_recv_info | (uintptr_t)dev_topk) % 16) return SHMEM_ERR_ALIGN;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_moe_dispatch)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    shmemx::MoeState st = m->st;
+    shmemx::MoeDispatchArgs a{(const uint8_t *)dev_x, dev_topk, dev_ntok, (uint8_t *)dev_recv_x, dev_recv_info,
+                              dev_recv_range, dev_recv_count, (uint32_t)wgs_per_pe};
+    void *args[] = {&c, &st, &a};
+    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_moe_dispatch, dim3((unsigned)grid), dim3(WG_THREADS),
+                                             args, 0, H.stream));
+}
+
+int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *dev_recv_info,
+                      const int32_t *dev_recv_range, const int32_t *dev_topk, const int32_t *dev_ntok,
+                      void *dev_combined, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!m || !dev_expert_out || !dev_recv_info || !dev_recv_range || !dev_topk || !dev_ntok || !dev_combined ||
+        wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_expert_out | (uintptr_t)dev_combined | (uintptr_t)dev_recv_info) % 16) return SHMEM_ERR_ALIGN;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_moe_combine)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    shmemx::MoeState st = m->st;
+    shmemx::MoeCombineArgs a{(const uint8_t *)dev_expert_out, dev_recv_info, dev_recv_range, dev_topk, dev_ntok,
+                             (uint8_t *)dev_combined, m->combines + 1, (uint32_t)wgs_per_pe};
+    void *args[] = {&c, &st, &a};
+    int rc = hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(WG_THREADS),
+                                               args, 0, H.stream));
+    if (rc == SHMEM_OK) m->combines += 1;
+    return rc;
 }
 
 }  // extern "C"
