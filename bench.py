@@ -107,6 +107,18 @@ def cpu_baseline_extras():
     t0 = time.perf_counter(); _, _, st = w.bfs(row, nbr, root); dt = time.perf_counter() - t0
     out["config5_bfs"] = {"GTEPS": round(st["edges_traversed"] / dt / 1e9, 4), "sample": "one root, R-MAT scale 20, edge factor 16"}
     w.close()
+    # MoE-shaped dispatch + combine: one batch of 128 tokens per PE at the paper's sizes
+    from oracle import moe as omoe
+    P, E, T, K, Hb = 8, 288, 128, 8, 14336
+    topk, ntok = workgen.moe_routing(npes=P, num_experts=E, max_tokens=T, topk=K, ntok=T)
+    x = workgen.moe_tokens(npes=P, max_tokens=T, hidden_bytes=Hb)
+    lay = omoe.MoeLayout(P, E, T, K, Hb)
+    w = oracle.World(P, lay.end, oracle.AT_QUIET, 0)
+    t0 = time.perf_counter(); d = omoe.dispatch(w, lay, x, topk, ntok); t1 = time.perf_counter()
+    omoe.combine(w, lay, d[0], d[1], d[2], topk, ntok); t2 = time.perf_counter()
+    out["moe_low_latency"] = {"dispatch_us": round((t1 - t0) * 1e6), "combine_us": round((t2 - t1) * 1e6),
+                              "sample": "one dispatch and one combine, 8 PEs x 128 tokens, 288 experts, top-8"}
+    w.close()
     return {"cores": 1, "kind": "oracle", "cells": out}
 
 
@@ -228,6 +240,48 @@ def extra_latency(sh, torch):
     return {"pingpong_round_trip_us": pp, "barrier_round_us": bar}
 
 
+def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=36):
+    """MoE-shaped low-latency dispatch / combine (Sec. IV-B, sizes of Sec. V-A): 8 emulated PEs,
+    288 experts, top-8 routing, 14,336-byte tokens (14,352-byte dispatch messages), 1-128 tokens
+    per PE.  Per launch: microseconds, and payload bytes moved between PEs per second."""
+    import numpy as np
+    import workgen
+    dev = torch.device("cuda:0")
+    epp = num_experts // npes
+    seg = (epp * npes * max_tokens * (hidden + 16) + max_tokens * topk * hidden + (1 << 20) + 255) // 256 * 256
+    heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    res = {}
+    try:
+        moe = sh.moe_create(num_experts, max_tokens, topk, hidden)
+        x = torch.from_numpy(workgen.moe_tokens(npes=npes, max_tokens=max_tokens, hidden_bytes=hidden)).to(dev)
+        recv_x = torch.zeros((npes, epp, npes * max_tokens, hidden), dtype=torch.uint8, device=dev)
+        recv_info = torch.zeros((npes, epp, npes * max_tokens, 4), dtype=torch.int32, device=dev)
+        recv_range = torch.zeros((npes, epp, npes, 2), dtype=torch.int32, device=dev)
+        recv_count = torch.zeros((npes, epp), dtype=torch.int32, device=dev)
+        combined = torch.zeros((npes, max_tokens, hidden), dtype=torch.uint8, device=dev)
+        for ntok in (1, 8, 32, 128):
+            topk_np, ntok_np = workgen.moe_routing(npes=npes, num_experts=num_experts, max_tokens=max_tokens, topk=topk,
+                                                   ntok=ntok)
+            tk, nt = torch.from_numpy(topk_np).to(dev), torch.from_numpy(ntok_np).to(dev)
+            routes = int((topk_np >= 0).sum())
+            d_ms = _median_ms(lambda: sh.moe_dispatch(moe, x, tk, nt, recv_x, recv_info, recv_range, recv_count, wgs),
+                              lambda: None, reps=20, warm=3)
+            c_ms = _median_ms(lambda: sh.moe_combine(moe, recv_x, recv_info, recv_range, tk, nt, combined, wgs),
+                              lambda: None, reps=20, warm=3)
+            sh.stream_sync()
+            assert int(recv_count.sum().item()) == routes
+            res[str(ntok)] = {"dispatch_us": round(d_ms * 1e3, 2), "combine_us": round(c_ms * 1e3, 2),
+                              "dispatch_GBs": round(routes * (hidden + 16) / d_ms / 1e6, 1),
+                              "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes}
+        sh.moe_destroy(moe)
+    finally:
+        sh.finalize()
+    return {"npes": npes, "num_experts": num_experts, "topk": topk, "hidden_bytes": hidden, "wgs_per_pe": wgs,
+            "tokens_per_pe": res}
+
+
 def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=128):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
@@ -313,7 +367,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--wgs-per-pe", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="cfg1,latency,amo,hash,bfs",
+    ap.add_argument("--extras", default="cfg1,latency,moe,amo,hash,bfs",
                     help="comma list of the other measurements to run too (cfg1, latency, amo, hash, bfs) or 'none'")
     ap.add_argument("--bfs-scale", type=int, default=24)
     ap.add_argument("--sweep", metavar="FILE", default=None,
@@ -419,6 +473,9 @@ def main():
         extras["config1_optable"] = extra_config1(sh, torch)
     if "latency" in want:
         extras["latency"] = extra_latency(sh, torch)
+    if "moe" in want:
+        extras["moe_low_latency"] = extra_moe(sh, torch)
+        torch.cuda.empty_cache()
     if "amo" in want:
         extras["config3_amo"] = extra_amo(sh, torch)
         torch.cuda.empty_cache()

@@ -21,8 +21,9 @@
 // Work split: workgroup w of a PE's team owns the experts e = w (mod team size)
 // when sending and the local experts / tokens with the same residue when
 // receiving, so one workgroup-level release covers all messages of a pair.
-// Both kernels are launched cooperatively (all workgroups resident): every
-// workgroup finishes sending before it starts to wait.
+// All workgroups of a launch are resident at once (the host checks the grid
+// against the occupancy limit) and every workgroup finishes sending before it
+// starts to wait, so the waits end; they are bounded besides.
 #pragma once
 #include "gin.hpp"
 #include "shmemx.hpp"
@@ -34,6 +35,7 @@ constexpr uint32_t MOE_MAX_TOKENS = 128;    // two 64-bit mask words per expert
 constexpr uint32_t MOE_MAX_TOPK = 64;       // one lane per top-k position
 constexpr uint32_t MOE_MAX_PES = 256;
 constexpr uint32_t MOE_META_BYTES = 16;
+constexpr int MOE_THREADS = 512;              // eight waves per workgroup: more copies in flight per team
 
 struct MoeState {
     uint32_t num_experts, epp, max_tokens, topk;
@@ -104,7 +106,7 @@ __device__ __forceinline__ uint64_t moe_poll(const Gin &gin, uint32_t id, uint64
     return v;
 }
 
-__global__ __launch_bounds__(256) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
+__global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
 {
     __shared__ uint64_t mask[MOE_MAX_EXPERTS][2];   // per expert: which of this PE's tokens go there
     __shared__ uint32_t begin[MOE_MAX_PES + 1];
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void k_moe_dispatch(Ctx c, MoeState m, MoeDisp
     }
 }
 
-__global__ __launch_bounds__(256) void k_moe_combine(Ctx c, MoeState m, MoeCombineArgs a)
+__global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, MoeCombineArgs a)
 {
     __shared__ uint32_t begin[MOE_MAX_PES + 1];
     __shared__ int32_t experts[MOE_MAX_TOPK];

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -35,6 +36,7 @@ struct Host {
     uint64_t *scratch = nullptr;
     hipStream_t stream = nullptr;
     int num_cus = 0;
+    bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
     std::vector<Block> free_list;  // address-ordered
     std::vector<Block> live;
     uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
@@ -102,11 +104,22 @@ void free_insert(uint64_t off, uint64_t len)
 
 // co-residency limit for kernels that contain an in-kernel barrier
 template <typename K>
-int max_resident_wgs(K kernel)
+int max_resident_wgs(K kernel, int threads = WG_THREADS)
 {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, WG_THREADS, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) return 0;
     return per_cu * H.num_cus;
+}
+
+// Launch of a kernel whose workgroups wait for one another (in-kernel barriers, signals): the callers
+// have checked that the whole grid fits the device at once (max_resident_wgs), the stream runs one
+// kernel at a time, and every in-kernel wait is bounded.  An ordinary launch is used by default: a
+// cooperative launch gives the same residency as a formal guarantee but measured about 16 us more per
+// launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
+int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
+{
+    if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
+    return hip_rc(hipLaunchKernel(kernel, grid, block, args, 0, H.stream));
 }
 
 }  // namespace
@@ -154,6 +167,8 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     if (hipHostMalloc((void **)&pinned, 4096, hipHostMallocDefault) != hipSuccess) return SHMEM_ERR_DEVICE;
     H.npes = npes; H.seg = heap_bytes_per_pe; H.heap = (uint8_t *)dev_heap; H.scratch = (uint64_t *)dev_scratch;
     H.stream = s; H.num_cus = prop.multiProcessorCount; H.pinned = pinned;
+    const char *coop = getenv("MI_SHMEM_COOPERATIVE_LAUNCH");
+    H.cooperative = coop && coop[0] == '1';
     H.free_list.assign(1, Block{0, (uint64_t)heap_bytes_per_pe});
     H.live.clear();
     H.init = true;
@@ -351,8 +366,7 @@ int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_pe
     shmemx::Ctx c = ctx();
     const shmem_op_desc *ops = (const shmem_op_desc *)dev_ops;
     void *args[] = {&c, &ops, &n, &quiet_every, &wgs_per_pe};
-    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_op_batch, dim3((unsigned)grid),
-                                             dim3(WG_THREADS), args, 0, H.stream));
+    return launch_resident((const void *)shmemx::k_op_batch, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
@@ -674,8 +688,7 @@ int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes,
     uint64_t ds = slot_bytes;
     uint32_t sig = (uint32_t)signal_id, ctr = (uint32_t)counter_id, r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
     void *args[] = {&c, &gs, &roff, &soff, &ds, &sig, &ctr, &r, &w};
-    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_ring_exchange, dim3((unsigned)grid),
-                                             dim3(WG_THREADS), args, 0, H.stream));
+    return launch_resident((const void *)shmemx::k_ring_exchange, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
 int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int iters)
@@ -695,8 +708,7 @@ int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int i
     uint64_t nb = nbytes;
     uint32_t sig = (uint32_t)signal_id, it = (uint32_t)iters;
     void *args[] = {&c, &gs, &boff, &nb, &sig, &it};
-    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_pingpong, dim3(2), dim3(WG_THREADS), args, 0,
-                                             H.stream));
+    return launch_resident((const void *)shmemx::k_pingpong, dim3(2), dim3(WG_THREADS), args);
 }
 
 int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors)
@@ -712,8 +724,7 @@ int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64
     shmemx::Ctx c = ctx();
     uint32_t r = (uint32_t)rounds, w = (uint32_t)wgs_per_pe;
     void *args[] = {&c, &off, &r, &w, &dev_errors};
-    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid),
-                                             dim3(WG_THREADS), args, 0, H.stream));
+    return launch_resident((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
 // ---------------------------------------------------------------------------
@@ -781,14 +792,13 @@ int shmem_moe_dispatch(shmem_moe_t m, const void *dev_x, const int32_t *dev_topk
         wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
     if (((uintptr_t)dev_x | (uintptr_t)dev_recv_x | (uintptr_t)dev_recv_info | (uintptr_t)dev_topk) % 16) return SHMEM_ERR_ALIGN;
     long grid = (long)H.npes * wgs_per_pe;
-    if (grid > max_resident_wgs(shmemx::k_moe_dispatch)) return SHMEM_ERR_INVALID_ARG;
+    if (grid > max_resident_wgs(shmemx::k_moe_dispatch, shmemx::MOE_THREADS)) return SHMEM_ERR_INVALID_ARG;
     shmemx::Ctx c = ctx();
     shmemx::MoeState st = m->st;
     shmemx::MoeDispatchArgs a{(const uint8_t *)dev_x, dev_topk, dev_ntok, (uint8_t *)dev_recv_x, dev_recv_info,
                               dev_recv_range, dev_recv_count, (uint32_t)wgs_per_pe};
     void *args[] = {&c, &st, &a};
-    return hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_moe_dispatch, dim3((unsigned)grid), dim3(WG_THREADS),
-                                             args, 0, H.stream));
+    return launch_resident((const void *)shmemx::k_moe_dispatch, dim3((unsigned)grid), dim3(shmemx::MOE_THREADS), args);
 }
 
 int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *dev_recv_info,
@@ -800,14 +810,13 @@ int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *
         wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
     if (((uintptr_t)dev_expert_out | (uintptr_t)dev_combined | (uintptr_t)dev_recv_info) % 16) return SHMEM_ERR_ALIGN;
     long grid = (long)H.npes * wgs_per_pe;
-    if (grid > max_resident_wgs(shmemx::k_moe_combine)) return SHMEM_ERR_INVALID_ARG;
+    if (grid > max_resident_wgs(shmemx::k_moe_combine, shmemx::MOE_THREADS)) return SHMEM_ERR_INVALID_ARG;
     shmemx::Ctx c = ctx();
     shmemx::MoeState st = m->st;
     shmemx::MoeCombineArgs a{(const uint8_t *)dev_expert_out, dev_recv_info, dev_recv_range, dev_topk, dev_ntok,
                              (uint8_t *)dev_combined, m->combines + 1, (uint32_t)wgs_per_pe};
     void *args[] = {&c, &st, &a};
-    int rc = hip_rc(hipLaunchCooperativeKernel((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(WG_THREADS),
-                                               args, 0, H.stream));
+    int rc = launch_resident((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(shmemx::MOE_THREADS), args);
     if (rc == SHMEM_OK) m->combines += 1;
     return rc;
 }

@@ -169,3 +169,20 @@ def test_argument_checks():
         with pytest.raises(sh.ShmemError):
             sh.moe_dispatch(m, t, t, t, t, t, t, t, 100000)     # cannot be co-resident
         sh.moe_destroy(m)
+
+
+def test_full_size_batch_as_benchmarked():
+    # the largest cell bench.py times: 8 PEs, 288 experts, top-8, 128 tokens of 14,336 bytes per PE,
+    # 36 workgroups per PE; the oracle affords the whole batch (8192 messages)
+    P, E, T, K, Hb, wgs = 8, 288, 128, 8, 14336, 36
+    topk, ntok = workgen.moe_routing(npes=P, num_experts=E, max_tokens=T, topk=K, ntok=T)
+    x = workgen.moe_tokens(npes=P, max_tokens=T, hidden_bytes=Hb)
+    want = oracle_run(P, E, T, K, Hb, x, topk, ntok, rounds=1, mutate=bump)
+    with shmem_world(P, heap_bytes_for(P, E, T, K, Hb)):
+        dm = DevMoe(P, E, T, K, Hb)
+        for _ in range(2):
+            got = dm.dispatch(x, topk, ntok, wgs)
+            check_dispatch(got, want[0][0])
+            comb = dm.combine(bump(got[0], got[3]), wgs)
+            assert np.array_equal(comb, want[0][2])
+        dm.close()
