@@ -241,7 +241,7 @@ def extra_latency(sh, torch):
 
 
 def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=36):
-    """MoE-shaped low-latency dispatch / combine (Sec. IV-B, sizes of Sec. V-A): 8 emulated PEs,
+    """MoE-shaped low-latency dispatch / combine (Sec. IV-E, sizes of Sec. V-C): 8 emulated PEs,
     288 experts, top-8 routing, 14,336-byte tokens (14,352-byte dispatch messages), 1-128 tokens
     per PE.  Per launch: microseconds, and payload bytes moved between PEs per second."""
     import numpy as np

@@ -294,8 +294,8 @@ int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64
 
 /* -------------------------------------------------------------------------
  * MoE-shaped all-to-all in traffic shape: the low-latency dispatch / combine
- * of Sec. IV-B ("Low-Latency Kernel Integration") with the message sizes of
- * Sec. V-A (dispatch: 16 bytes of source-index metadata + the token; combine:
+ * of Sec. IV-E ("Low-Latency Kernel Integration") with the message sizes of
+ * Sec. V-C (dispatch: 16 bytes of source-index metadata + the token; combine:
  * the token alone).  Payloads are opaque bytes; no quantisation, compression
  * or weighted floating-point reduction.
  *

@@ -3,13 +3,13 @@
 TEST INFRASTRUCTURE ONLY, like the rest of this package: imported by tests and by the
 benchmark's cpu_baseline leg, never by the GPU package.
 
-What is modelled (Sec. IV-B "Low-Latency Kernel Integration", Sec. V-A "Low-Latency Kernels"):
+What is modelled (Sec. IV-E "Low-Latency Kernel Integration", Sec. V-C "Low-Latency Kernels"):
 every PE holds a small batch of tokens, each routed to up to top-k experts; experts are spread
 evenly over the PEs.  Dispatch sends, for every (token, expert) route, one message of 16 bytes of
 source-index metadata followed by the token's bytes straight into a receive slot at the expert's
 owner; once all messages of one (sender, expert) pair are on their way the sender delivers the
 pair's token count with a zero-byte put carrying a SignalAdd, so the count can only be seen after
-the data (the release/acquire idiom of Sec. IV-A).  The receiver reads the signals and packs what
+the data (the release/acquire idiom of Sec. IV-B).  The receiver reads the signals and packs what
 arrived per local expert.  Combine sends every expert output back to the token's source PE and
 raises one flag signal per (expert, destination) pair; the destination then reduces the copies of
 each token.  Quantisation, compression and the weighted floating-point reduction are not part of

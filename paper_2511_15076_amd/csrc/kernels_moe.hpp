@@ -1,6 +1,6 @@
 // MoE-shaped all-to-all in traffic shape: the low-latency dispatch and combine
-// of Sec. IV-B ("Low-Latency Kernel Integration") at the message sizes of
-// Sec. V-A (16 bytes of source-index metadata + the token; the token alone on
+// of Sec. IV-E ("Low-Latency Kernel Integration") at the message sizes of
+// Sec. V-C (16 bytes of source-index metadata + the token; the token alone on
 // the way back), on emulated PEs.  No quantisation, compression or weighted
 // floating-point reduction: payloads are opaque bytes and the combine reduction
 // is a wrapping sum of 32-bit words.

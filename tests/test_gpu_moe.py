@@ -118,7 +118,7 @@ def test_dispatch_and_combine_match_oracle(P, E, T, K, Hb, ntok, dist, drop, wgs
 
 
 def test_paper_message_size_single_token():
-    # one token per PE, 7168 16-bit values = 14,336 bytes, 14,352-byte messages (Sec. V-A)
+    # one token per PE, 7168 16-bit values = 14,336 bytes, 14,352-byte messages (Sec. V-C)
     P, E, T, K, Hb = 8, 288, 1, 8, 14336
     topk, ntok = workgen.moe_routing(7, P, E, T, K)
     x = workgen.moe_tokens(8, P, T, Hb)

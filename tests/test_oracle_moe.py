@@ -99,7 +99,7 @@ def test_dispatch_matches_sorted_routes(P, E, T, K, Hb, dist, drop, mode):
 
 
 def test_message_is_metadata_plus_token_at_paper_sizes():
-    # hidden 7168 in 16-bit words = 14,336 bytes of token data; message = 14,352 bytes (Sec. V-A)
+    # hidden 7168 in 16-bit words = 14,336 bytes of token data; message = 14,352 bytes (Sec. V-C)
     P, E, T, K, Hb = 2, 2, 2, 1, 14336
     topk = np.array([[[1], [1]], [[-1], [-1]]], dtype=np.int32)     # PE 0 sends both tokens to expert 1
     ntok = np.array([2, 0], dtype=np.int32)
