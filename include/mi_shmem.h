@@ -354,6 +354,42 @@ int shmem_moe_combine(shmem_moe_t moe, const void *dev_expert_out, const int32_t
                       const int32_t *dev_recv_range, const int32_t *dev_topk, const int32_t *dev_ntok,
                       void *dev_combined, int wgs_per_pe);
 
+/* -------------------------------------------------------------------------
+ * Proxy-style executor (Sec. III-C, "Proxy Backend"): GPU threads enqueue the
+ * 64-byte descriptors into a lock-free ring in pinned host memory with
+ * fire-and-forget stores; one host thread per proxy object polls the ring,
+ * validates each descriptor and carries it out on a stream of its own
+ * (contiguous ops through the copy engine, strided ops with the library's
+ * strided kernel), and publishes in GPU-visible memory how far it has got.
+ * It is the second backend of the same descriptor format and a debugging twin
+ * of shmem_op_batch: same table, same heap contents afterwards.
+ *
+ * shmem_proxy_create: queue_entries is a power of two in [2, 2^20]; starts the
+ * thread.  shmem_proxy_submit: asynchronous; launches `workgroups` workgroups
+ * (all must be co-resident) on the library's stream that enqueue dev_ops[0..n)
+ * (DEVICE table, 16-byte aligned); descriptor i takes ticket (descriptors
+ * submitted before) + i, so the ring order is the table order; producers wait
+ * (bounded) while the ring is full.  The proxy carries descriptors out in
+ * ticket order on one stream, i.e. in order -- stronger than the unordered
+ * default of shmem_op_batch.  Work issued on the library's stream before the
+ * submit happens before the proxy's copies of that submission; nothing orders
+ * later work on the library's stream behind them except shmem_proxy_quiet.
+ * shmem_proxy_quiet: blocks the calling host thread until every submitted
+ * descriptor has been carried out and its copy is complete; returns
+ * DEVICE_FAULT (and the ticket in *first_bad_index, may be NULL) if the proxy
+ * rejected a descriptor (bad kind / PE / range / stride / alignment: skipped),
+ * DEVICE if a producer timed out or a HIP call failed.
+ * shmem_proxy_stats: counters so far (any pointer may be NULL).
+ * shmem_proxy_destroy: waits for the library's stream, stops the thread, frees
+ * the ring.  One caller thread per proxy object.
+ * Errors: NOT_INIT, INVALID_ARG, ALIGN, NOMEM, DEVICE, DEVICE_FAULT. */
+typedef struct shmem_proxy *shmem_proxy_t;
+int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out);
+int shmem_proxy_submit(shmem_proxy_t proxy, const void *dev_ops, size_t n, int workgroups);
+int shmem_proxy_quiet(shmem_proxy_t proxy, uint64_t *first_bad_index);
+int shmem_proxy_stats(shmem_proxy_t proxy, uint64_t *submitted, uint64_t *executed, uint64_t *rejected);
+int shmem_proxy_destroy(shmem_proxy_t proxy);
+
 #ifdef __cplusplus
 }
 #endif

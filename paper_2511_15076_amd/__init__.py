@@ -82,6 +82,11 @@ _SIG = {
     "shmem_moe_destroy": (_i, [_vp]),
     "shmem_moe_dispatch": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i]),
     "shmem_moe_combine": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i]),
+    "shmem_proxy_create": (_i, [_sz, C.POINTER(_vp)]),
+    "shmem_proxy_submit": (_i, [_vp, _vp, _sz, _i]),
+    "shmem_proxy_quiet": (_i, [_vp, C.POINTER(C.c_uint64)]),
+    "shmem_proxy_stats": (_i, [_vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
+    "shmem_proxy_destroy": (_i, [_vp]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_L, _name)
@@ -301,3 +306,35 @@ def moe_combine(moe, dev_expert_out, dev_recv_info, dev_recv_range, dev_topk, de
     return _check(_L.shmem_moe_combine(moe, _addr(dev_expert_out), _addr(dev_recv_info), _addr(dev_recv_range),
                                        _addr(dev_topk), _addr(dev_ntok), _addr(dev_combined), wgs_per_pe),
                   "shmem_moe_combine")
+
+
+def proxy_create(queue_entries):
+    p = _vp(0)
+    _check(_L.shmem_proxy_create(queue_entries, C.byref(p)), "shmem_proxy_create")
+    return p
+
+
+def proxy_submit(proxy, dev_ops, n, workgroups=4):
+    return _check(_L.shmem_proxy_submit(proxy, _addr(dev_ops), n, workgroups), "shmem_proxy_submit")
+
+
+def proxy_quiet(proxy):
+    """Waits until the proxy has carried out everything submitted; raises ShmemError(ERR_DEVICE_FAULT)
+    with the first rejected ticket if it skipped a descriptor."""
+    bad = C.c_uint64(0)
+    rc = _L.shmem_proxy_quiet(proxy, C.byref(bad))
+    if rc == ERR_DEVICE_FAULT:
+        e = ShmemError(rc, f"shmem_proxy_quiet (first rejected ticket {bad.value})")
+        e.first_bad_index = bad.value
+        raise e
+    return _check(rc, "shmem_proxy_quiet")
+
+
+def proxy_stats(proxy):
+    a, b, c = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    _check(_L.shmem_proxy_stats(proxy, C.byref(a), C.byref(b), C.byref(c)), "shmem_proxy_stats")
+    return {"submitted": a.value, "executed": b.value, "rejected": c.value}
+
+
+def proxy_destroy(proxy):
+    return _check(_L.shmem_proxy_destroy(proxy), "shmem_proxy_destroy")

@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <thread>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -19,6 +22,7 @@
 #include "kernels_bfs.hpp"
 #include "kernels_sync.hpp"
 #include "kernels_moe.hpp"
+#include "proxy.hpp"
 
 namespace {
 
@@ -819,6 +823,199 @@ int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *
     int rc = launch_resident((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(shmemx::MOE_THREADS), args);
     if (rc == SHMEM_OK) m->combines += 1;
     return rc;
+}
+
+// ---------------------------------------------------------------------------
+// Proxy-style executor (Sec. III-C, "Proxy Backend"): the host half.  One thread per proxy object
+// polls the descriptor ring in pinned memory, takes descriptors out in ticket order, validates them
+// on the host and carries them out on a stream of its own: contiguous ops through the copy engine
+// (hipMemcpyAsync), strided ops with the library's strided kernel.  `head` (GPU-visible) tells the
+// producers which slots are free again; `executed` counts descriptors handed to the stream.
+struct shmem_proxy {
+    shmemx::ProxyQueue q;
+    uint64_t entries;
+    uint64_t *head;                     // pinned, written by the thread, read by the GPU
+    hipStream_t stream;
+    hipEvent_t ready;                   // orders the proxy stream behind the library's stream at submit
+    int device;
+    std::thread worker;
+    std::atomic<bool> stop{false};
+    std::atomic<uint64_t> executed{0};  // descriptors taken out and handed to the stream
+    std::atomic<uint64_t> rejected{0};
+    std::atomic<uint64_t> first_bad{UINT64_MAX};
+    std::atomic<int> hip_error{0};
+    uint64_t submitted = 0;             // descriptors given to shmem_proxy_submit so far (caller's thread)
+    // captured at creation: the heap the descriptors refer to
+    uint8_t *heap; uint64_t seg; int npes;
+};
+
+namespace {
+
+bool proxy_desc_valid(const shmem_proxy *p, const shmem_op_desc &d)
+{
+    const uint64_t seg = p->seg;
+    if (d.pe >= (uint32_t)p->npes || d.pe_self >= (uint32_t)p->npes) return false;
+    if (d.kind == SHMEM_OP_PUT || d.kind == SHMEM_OP_GET)
+        return d.local_off <= seg && d.count <= seg - d.local_off && d.sym_off <= seg && d.count <= seg - d.sym_off;
+    if (d.kind == SHMEM_OP_IPUT || d.kind == SHMEM_OP_IGET) {
+        const uint32_t eb = d.elem_bytes;
+        if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return false;
+        if (d.local_stride < 1 || d.sym_stride < 1 || d.local_off % eb || d.sym_off % eb) return false;
+        if (d.count == 0) return d.local_off <= seg && d.sym_off <= seg;
+        if (d.count > seg || (uint64_t)d.local_stride > seg || (uint64_t)d.sym_stride > seg) return false;
+        const unsigned __int128 ls = (unsigned __int128)(d.count - 1) * (uint64_t)d.local_stride * eb + eb;
+        const unsigned __int128 ss = (unsigned __int128)(d.count - 1) * (uint64_t)d.sym_stride * eb + eb;
+        return d.local_off <= seg && ls <= seg - d.local_off && d.sym_off <= seg && ss <= seg - d.sym_off;
+    }
+    return false;
+}
+
+void proxy_execute(shmem_proxy *p, const shmem_op_desc &d)
+{
+    uint8_t *local = p->heap + (uint64_t)d.pe_self * p->seg + d.local_off;
+    uint8_t *remote = p->heap + (uint64_t)d.pe * p->seg + d.sym_off;
+    hipError_t e = hipSuccess;
+    if (d.count == 0) return;
+    switch (d.kind) {
+    case SHMEM_OP_PUT: e = hipMemcpyAsync(remote, local, d.count, hipMemcpyDeviceToDevice, p->stream); break;
+    case SHMEM_OP_GET: e = hipMemcpyAsync(local, remote, d.count, hipMemcpyDeviceToDevice, p->stream); break;
+    case SHMEM_OP_IPUT:
+        hipLaunchKernelGGL(shmemx::k_strided, dim3(wgs_for_bytes(d.count * 16)), dim3(WG_THREADS), 0, p->stream, remote,
+                           (const uint8_t *)local, d.sym_stride, d.local_stride, (size_t)d.count, d.elem_bytes);
+        e = hipGetLastError();
+        break;
+    case SHMEM_OP_IGET:
+        hipLaunchKernelGGL(shmemx::k_strided, dim3(wgs_for_bytes(d.count * 16)), dim3(WG_THREADS), 0, p->stream, local,
+                           (const uint8_t *)remote, d.local_stride, d.sym_stride, (size_t)d.count, d.elem_bytes);
+        e = hipGetLastError();
+        break;
+    }
+    if (e != hipSuccess) p->hip_error.store((int)e);
+}
+
+void proxy_main(shmem_proxy *p)
+{
+    if (hipSetDevice(p->device) != hipSuccess) { p->hip_error.store(1); return; }
+    uint64_t next = 0, idle = 0;
+    while (!p->stop.load(std::memory_order_acquire)) {
+        const uint64_t slot = next & p->q.mask;
+        if (__atomic_load_n(p->q.flags + slot, __ATOMIC_ACQUIRE) != next + 1) {
+            if (++idle > 2000) std::this_thread::sleep_for(std::chrono::microseconds(20));   // nothing for a while
+            continue;
+        }
+        idle = 0;
+        const shmem_op_desc d = p->q.ring[slot];                 // take the descriptor out ...
+        __atomic_store_n(p->head, next + 1, __ATOMIC_RELEASE);   // ... and hand the slot back to the producers
+        if (proxy_desc_valid(p, d)) {
+            proxy_execute(p, d);
+        } else {
+            p->rejected.fetch_add(1);
+            uint64_t expect = UINT64_MAX;
+            p->first_bad.compare_exchange_strong(expect, next);
+        }
+        ++next;
+        p->executed.store(next, std::memory_order_release);
+    }
+}
+
+}  // namespace
+
+int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!proxy_out || queue_entries < 2 || queue_entries > (1u << 20) || (queue_entries & (queue_entries - 1)))
+        return SHMEM_ERR_INVALID_ARG;
+    shmem_proxy *p = new (std::nothrow) shmem_proxy();
+    if (!p) return SHMEM_ERR_NOMEM;
+    p->entries = queue_entries;
+    p->heap = H.heap; p->seg = H.seg; p->npes = H.npes;
+    void *ring = nullptr, *flags = nullptr, *head = nullptr;
+    const unsigned fl = hipHostMallocMapped | hipHostMallocCoherent;
+    bool ok = hipGetDevice(&p->device) == hipSuccess &&
+              hipHostMalloc(&ring, queue_entries * sizeof(shmem_op_desc), fl) == hipSuccess &&
+              hipHostMalloc(&flags, queue_entries * sizeof(uint64_t), fl) == hipSuccess &&
+              hipHostMalloc(&head, 256, fl) == hipSuccess &&
+              hipStreamCreateWithFlags(&p->stream, hipStreamNonBlocking) == hipSuccess;
+    if (ok && hipEventCreateWithFlags(&p->ready, hipEventDisableTiming) != hipSuccess) { (void)hipStreamDestroy(p->stream); ok = false; }
+    if (!ok) {
+        if (ring) (void)hipHostFree(ring);
+        if (flags) (void)hipHostFree(flags);
+        if (head) (void)hipHostFree(head);
+        delete p;
+        return SHMEM_ERR_DEVICE;
+    }
+    memset(ring, 0, queue_entries * sizeof(shmem_op_desc));
+    memset(flags, 0, queue_entries * sizeof(uint64_t));
+    memset(head, 0, 256);
+    p->q.ring = (shmem_op_desc *)ring; p->q.flags = (uint64_t *)flags; p->q.head = (const uint64_t *)head;
+    p->q.mask = queue_entries - 1;
+    p->head = (uint64_t *)head;
+    p->worker = std::thread(proxy_main, p);
+    *proxy_out = p;
+    return SHMEM_OK;
+}
+
+int shmem_proxy_submit(shmem_proxy_t p, const void *dev_ops, size_t n, int workgroups)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!p || (!dev_ops && n) || workgroups < 1) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)dev_ops % 16) return SHMEM_ERR_ALIGN;
+    if (n == 0) return SHMEM_OK;
+    // every producer must be resident: a waiting producer of a high ticket must not keep a low one off the device
+    if (workgroups > max_resident_wgs(shmemx::k_proxy_submit)) return SHMEM_ERR_INVALID_ARG;
+    // what the library's stream has done so far happens before the proxy's copies of this submission
+    if (hipEventRecord(p->ready, H.stream) != hipSuccess || hipStreamWaitEvent(p->stream, p->ready, 0) != hipSuccess)
+        return SHMEM_ERR_DEVICE;
+    hipLaunchKernelGGL(shmemx::k_proxy_submit, dim3((unsigned)workgroups), dim3(WG_THREADS), 0, H.stream, ctx(), p->q,
+                       (const shmem_op_desc *)dev_ops, (uint64_t)n, p->submitted);
+    if (int rc = launched()) return rc;
+    p->submitted += n;
+    return SHMEM_OK;
+}
+
+int shmem_proxy_quiet(shmem_proxy_t p, uint64_t *first_bad_index)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!p) return SHMEM_ERR_INVALID_ARG;
+    const auto t0 = std::chrono::steady_clock::now();
+    while (p->executed.load(std::memory_order_acquire) < p->submitted) {
+        if (p->hip_error.load()) return SHMEM_ERR_DEVICE;
+        if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(20)) return SHMEM_ERR_DEVICE;   // a producer gave up
+        std::this_thread::yield();
+    }
+    if (hipStreamSynchronize(p->stream) != hipSuccess || p->hip_error.load()) return SHMEM_ERR_DEVICE;
+    if (p->rejected.load()) {
+        if (first_bad_index) *first_bad_index = p->first_bad.load();
+        return SHMEM_ERR_DEVICE_FAULT;
+    }
+    return SHMEM_OK;
+}
+
+int shmem_proxy_stats(shmem_proxy_t p, uint64_t *submitted, uint64_t *executed, uint64_t *rejected)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!p) return SHMEM_ERR_INVALID_ARG;
+    if (submitted) *submitted = p->submitted;
+    if (executed) *executed = p->executed.load();
+    if (rejected) *rejected = p->rejected.load();
+    return SHMEM_OK;
+}
+
+int shmem_proxy_destroy(shmem_proxy_t p)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!p) return SHMEM_ERR_INVALID_ARG;
+    (void)hipStreamSynchronize(H.stream);            // no producer is still writing into the ring
+    p->stop.store(true, std::memory_order_release);
+    if (p->worker.joinable()) p->worker.join();
+    (void)hipStreamSynchronize(p->stream);
+    (void)hipEventDestroy(p->ready);
+    (void)hipStreamDestroy(p->stream);
+    (void)hipHostFree(p->q.ring);
+    (void)hipHostFree(p->q.flags);
+    (void)hipHostFree(p->head);
+    delete p;
+    return SHMEM_OK;
 }
 
 }  // extern "C"
