@@ -203,6 +203,19 @@ def extra_config1(sh, torch, wgs=2):
             res[f"wgs{w}"] = {"ms": round(ms, 4), "us_per_batch_of_100": round(ms * 10, 3),
                              "Mops_per_s": round(len(ops) / ms / 1e3, 2)}
         sh.stream_sync()
+        # the same table through the proxy-style executor (descriptor ring in host memory, host thread)
+        px = sh.proxy_create(1 << 12)
+        times = []
+        for _ in range(4):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            sh.proxy_submit(px, d_ops, len(ops), 4)
+            sh.proxy_quiet(px)
+            times.append(time.perf_counter() - t0)
+        sh.proxy_destroy(px)
+        dt = sorted(times[1:])[1]
+        res["proxy"] = {"ms": round(dt * 1e3, 3), "us_per_op": round(dt * 1e6 / len(ops), 3),
+                        "Mops_per_s": round(len(ops) / dt / 1e6, 3)}
     finally:
         sh.finalize()
     return {"ops": int(len(ops)), "payload_bytes": int(ops["count"].sum()), "npes": npes, "cells": res}
