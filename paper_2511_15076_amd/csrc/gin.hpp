@@ -89,7 +89,7 @@ struct Gin {
         if (threadIdx.x == 0) {
             uint32_t spins = 0;
             while (__hip_atomic_load(w, __ATOMIC_RELAXED, SHMEMX_AGENT) < expected) {
-                if (timed_out(c)) break;
+                if (timed_out(c, spins)) break;
                 __builtin_amdgcn_s_sleep(1);
                 if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, pe); break; }
             }

@@ -93,13 +93,22 @@ __device__ __forceinline__ uint32_t moe_nth_token(uint64_t m0, uint64_t m1, uint
     return (uint32_t)__builtin_ctzll(m) + (n < c0 ? 0u : 64u);
 }
 
+// A workgroup with fewer messages than waves splits each message into 2, 4 or 8 pieces, one per
+// wave, so that a batch of a few tokens is not carried by a single wave while the others idle.
+__device__ __forceinline__ uint32_t moe_parts(uint32_t nwaves, uint32_t messages)
+{
+    uint32_t parts = 1;
+    while (messages && parts * 2 * messages <= nwaves) parts *= 2;   // ends: parts doubles, nwaves is fixed
+    return parts;
+}
+
 // bounded poll of one of the caller's own signals until it is at least `expected`
 __device__ __forceinline__ uint64_t moe_poll(const Gin &gin, uint32_t id, uint64_t expected)
 {
     uint32_t spins = 0;
     uint64_t v;
     while ((v = gin.read_signal(id)) < expected) {
-        if (timed_out(gin.c)) break;
+        if (timed_out(gin.c, spins)) break;
         __builtin_amdgcn_s_sleep(1);
         if (++spins > SPIN_LIMIT) { report(gin.c, DEV_ERR_BARRIER_TIMEOUT, gin.pe); break; }
     }
@@ -134,22 +143,31 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     __syncthreads();
 
     // ---- send: the routes of this workgroup's experts, dealt round-robin to its waves ----
-    uint32_t q = 0;                                                          // running route number (same in every wave)
+    uint32_t routes = 0;
+    for (uint32_t e = wg; e < E; e += W) routes += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+    const uint32_t sparts = moe_parts(nwaves, routes), sper = (hvecs + sparts - 1) / sparts;
+    uint32_t q = 0;                                                          // running piece number (same in every wave)
     for (uint32_t e = wg; e < E; e += W) {
         const uint32_t owner = e / m.epp, le = e % m.epp;
         const uint64_t m0 = mask[e][0], m1 = mask[e][1];
         const uint32_t n = (uint32_t)(__popcll(m0) + __popcll(m1));
-        for (uint32_t i = 0; i < n; ++i, ++q) {                              // slot i = i-th token in ascending order
-            if (q % nwaves != wave) continue;
-            const uint32_t t = moe_nth_token(m0, m1, i);
-            const uint64_t hit = ballot(lane < K && topk[t * K + min(lane, K - 1)] == (int32_t)e);
-            const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
-            uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
-            if (lane == 0) {
-                u32x4 meta = {t, pe, j, e};
-                __builtin_nontemporal_store(meta, (u32x4 *)slot);
+        for (uint32_t i = 0; i < n; ++i) {                                   // slot i = i-th token in ascending order
+            for (uint32_t part = 0; part < sparts; ++part, ++q) {
+                if (q % nwaves != wave) continue;
+                const uint32_t t = moe_nth_token(m0, m1, i);
+                uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
+                if (part == 0) {
+                    const uint64_t hit = ballot(lane < K && topk[t * K + min(lane, K - 1)] == (int32_t)e);
+                    const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
+                    if (lane == 0) {
+                        u32x4 meta = {t, pe, j, e};
+                        __builtin_nontemporal_store(meta, (u32x4 *)slot);
+                    }
+                }
+                const uint32_t lo = part * sper, cnt = lo < hvecs ? min(sper, hvecs - lo) : 0;
+                wave_copy16((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo,
+                            cnt, lane);
             }
-            wave_copy16((u32x4 *)(slot + MOE_META_BYTES), (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden), hvecs, lane);
         }
     }
     // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
@@ -187,12 +205,15 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(begin[s + 1] - begin[s]);
         }
         if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
-        for (uint32_t i = wave; i < total; i += nwaves) {
+        const uint32_t rparts = moe_parts(nwaves, total), rper = (hvecs + rparts - 1) / rparts;
+        for (uint32_t u = wave; u < total * rparts; u += nwaves) {
+            const uint32_t i = u / rparts, part = u % rparts;
             uint32_t s = 0;
             while (begin[s + 1] <= i) ++s;
             const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[s])) * m.msg, pe);
-            if (lane == 0) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = *(const u32x4 *)slot;
-            wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden), (const u32x4 *)(slot + MOE_META_BYTES), hvecs, lane);
+            if (part == 0 && lane == 0) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = *(const u32x4 *)slot;
+            const uint32_t lo = part * rper, cnt = lo < hvecs ? min(rper, hvecs - lo) : 0;
+            wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
         }
     }
 }
@@ -223,12 +244,15 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
         __syncthreads();
         const uint32_t total = begin[P];
         const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
-        for (uint32_t i = wave; i < total; i += nwaves) {
+        const uint32_t cparts = moe_parts(nwaves, total), cper = (hvecs + cparts - 1) / cparts;
+        for (uint32_t u = wave; u < total * cparts; u += nwaves) {
+            const uint32_t i = u / cparts, part = u % cparts;
             const u32x4 info = *(const u32x4 *)(a.recv_info + (row0 + i) * 4);   // token, source PE, position, expert
             const uint32_t t = info.x, s = info.y, j = info.z;
-            if (t >= T || s >= P || j >= K) { if (lane == 0) report(c, DEV_ERR_BAD_OP, row0 + i); continue; }
-            wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s),
-                        (const u32x4 *)(a.expert_out + (row0 + i) * m.hidden), hvecs, lane);
+            if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row0 + i); continue; }
+            const uint32_t lo = part * cper, cnt = lo < hvecs ? min(cper, hvecs - lo) : 0;
+            wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
+                        (const u32x4 *)(a.expert_out + (row0 + i) * m.hidden) + lo, cnt, lane);
         }
         // flags: zero-byte put + SignalAdd to every destination, after one release for the whole expert
         wg_release();

@@ -53,6 +53,12 @@ __device__ __forceinline__ bool timed_out(const Ctx &c)
 {
     return __hip_atomic_load(&c.scratch[W_ERR_FLAG], __ATOMIC_RELAXED, SHMEMX_AGENT) == DEV_ERR_BARRIER_TIMEOUT;
 }
+// The same, looked at only on every 64th poll of a wait loop: the fault word costs a round trip to
+// memory like the polled word itself, and the two cannot overlap.
+__device__ __forceinline__ bool timed_out(const Ctx &c, uint32_t spins)
+{
+    return (spins & 63) == 63 && timed_out(c);
+}
 
 // ---------------------------------------------------------------------------
 // Atomic memory operations (Table II "memory atomics"): agent scope, so that
@@ -122,7 +128,8 @@ __device__ __forceinline__ bool barrier_arrive(const Ctx &c, uint64_t *count, ui
         return true;
     }
     uint32_t spins = 0;
-    while (!timed_out(c) && __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT) == g) {
+    while (__hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT) == g) {
+        if (timed_out(c, spins)) break;
         __builtin_amdgcn_s_sleep(2);
         if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); break; }
     }
