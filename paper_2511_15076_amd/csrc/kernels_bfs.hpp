@@ -42,7 +42,8 @@ constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes 
 constexpr uint32_t EPL = 4;            // edges per lane in flight
 constexpr uint32_t NXCD = 8;           // accelerator dies, each with a private L2
 constexpr uint32_t STAGE_PES = 16;     // winners are staged in LDS when npes <= this
-constexpr uint32_t STAGE_CAP = 128;    // staged vertices per owner per wave (flushed in blocks of 64)
+constexpr uint32_t STAGE_BLOCK = 64;   // staged vertices leave in blocks of this many (one 256-byte put)
+constexpr uint32_t STAGE_CAP = STAGE_BLOCK + 64;   // per owner per wave: a partial block plus one entry per lane
 
 // Index of the die this wave runs on (XCC_ID hardware register, 4 bits).
 __device__ __forceinline__ uint32_t xcd_id()
@@ -89,8 +90,8 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
 
 // ---------------------------------------------------------------------------
 // Per-wave staging of claimed vertices, one small buffer per owner in LDS.
-// A full block of 64 is written to the owner's queue with ONE fetch_add on its
-// tail and one coalesced 256-byte put; the remainder goes out at kernel end.
+// A full block of STAGE_BLOCK is written to the owner's queue with ONE fetch_add
+// on its tail and one coalesced 128-byte put; the remainder goes out at kernel end.
 struct Stage {
     uint32_t *cnt;   // [STAGE_PES]
     uint32_t *buf;   // [STAGE_PES][STAGE_CAP]
@@ -115,15 +116,16 @@ __device__ __forceinline__ void bfs_enqueue(const Ctx &c, const BfsState &s, con
             if (won && o == ol) buf[cn + rank_in(grp)] = v;
             cn += n;
             __builtin_amdgcn_wave_barrier();
-            if (cn >= 64) {
+            while (cn >= STAGE_BLOCK) {
                 uint64_t base = 0;
-                if (lane == 0) base = atomic_fetch_add(tail, 64);
+                if (lane == 0) base = atomic_fetch_add(tail, (uint64_t)STAGE_BLOCK);
                 base = bcast64(base, 0);
-                __builtin_nontemporal_store(buf[lane], queue + base + lane);   // put: one full block
-                const uint32_t rest = cn - 64;
-                const uint32_t moved = lane < rest ? buf[64 + lane] : 0;
+                if (lane < STAGE_BLOCK) __builtin_nontemporal_store(buf[lane], queue + base + lane);   // put: one full block
+                const uint32_t rest = cn - STAGE_BLOCK;
+                const uint32_t moved = lane < rest ? buf[STAGE_BLOCK + lane] : 0;
                 __builtin_amdgcn_wave_barrier();
                 if (lane < rest) buf[lane] = moved;
+                __builtin_amdgcn_wave_barrier();
                 cn = rest;
             }
             if (lane == 0) st.cnt[ol] = cn;
@@ -194,16 +196,29 @@ __device__ __forceinline__ void bfs_probe_finish(const Ctx &c, const BfsState &s
                                                  Probe &p, const bool (&act)[EPL], const uint32_t (&v)[EPL],
                                                  const uint32_t (&u)[EPL])
 {
-    bool won[EPL];
+    // all claims of the chunk are issued before the first result is used: a fetch_or resolves at the
+    // memory side, so one round trip then covers EPL of them instead of one each
+    bool won[EPL], need[EPL];
+    uint64_t old[EPL];
+    bool any = false;
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) {
+        need[k] = act[k] && !(p.known[k] & (1ull << (p.l[k] & 63)));
+        any |= need[k];
         won[k] = false;
+        old[k] = 0;
+    }
+    if (!ballot(any)) return;   // every probe of the chunk hit a vertex known to be claimed (the common case late in a search)
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k)
+        if (need[k])
+            old[k] = atomic_fetch_or((uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6), 1ull << (p.l[k] & 63));   // the claim
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) {
         const uint64_t bit = 1ull << (p.l[k] & 63);
-        if (act[k] && !(p.known[k] & bit)) {
-            uint64_t *w = (uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6);
-            const uint64_t old = atomic_fetch_or(w, bit);                  // the claim
-            won[k] = !(old & bit);
-            *p.f[k] = p.known[k] | old | bit;   // everything the fetch_or showed to be claimed
+        won[k] = need[k] && !(old[k] & bit);
+        if (need[k]) {
+            *p.f[k] = p.known[k] | old[k] | bit;   // everything the fetch_or showed to be claimed
             if (won[k]) {
                 // put parent, put level: streaming stores, so the scattered lines do not push the
                 // bitmap copies out of L2
