@@ -381,7 +381,8 @@ int shmem_moe_combine(shmem_moe_t moe, const void *dev_expert_out, const int32_t
  * DEVICE if a producer timed out or a HIP call failed.
  * shmem_proxy_stats: counters so far (any pointer may be NULL).
  * shmem_proxy_destroy: waits for the library's stream, stops the thread, frees
- * the ring.  One caller thread per proxy object.
+ * the ring; shmem_finalize does the same for every proxy still alive.  One
+ * caller thread per proxy object.
  * Errors: NOT_INIT, INVALID_ARG, ALIGN, NOMEM, DEVICE, DEVICE_FAULT. */
 typedef struct shmem_proxy *shmem_proxy_t;
 int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out);

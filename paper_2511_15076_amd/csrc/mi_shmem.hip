@@ -45,6 +45,7 @@ struct Host {
     std::vector<Block> live;
     uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
     std::mutex mu;
+    std::vector<struct shmem_proxy *> proxies;   // live proxy objects (their threads are stopped at finalize)
 } H;
 
 struct BfsGraph {
@@ -120,6 +121,8 @@ int max_resident_wgs(K kernel, int threads = WG_THREADS)
 // kernel at a time, and every in-kernel wait is bounded.  An ordinary launch is used by default: a
 // cooperative launch gives the same residency as a formal guarantee but measured about 16 us more per
 // launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
+void proxy_stop_and_free(struct shmem_proxy *p);   // defined with the proxy executor below
+
 int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
 {
     if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
@@ -184,6 +187,7 @@ int shmem_finalize(void)
     std::lock_guard<std::mutex> g(H.mu);
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     hipError_t e = hipStreamSynchronize(H.stream);
+    while (!H.proxies.empty()) proxy_stop_and_free(H.proxies.back());   // no thread outlives the heap it serves
     if (H.pinned) (void)hipHostFree(H.pinned);
     H.pinned = nullptr; H.init = false; H.npes = 0; H.heap = nullptr; H.scratch = nullptr;
     H.free_list.clear(); H.live.clear();
@@ -918,6 +922,20 @@ void proxy_main(shmem_proxy *p)
     }
 }
 
+void proxy_stop_and_free(shmem_proxy *p)
+{
+    p->stop.store(true, std::memory_order_release);
+    if (p->worker.joinable()) p->worker.join();
+    (void)hipStreamSynchronize(p->stream);
+    (void)hipEventDestroy(p->ready);
+    (void)hipStreamDestroy(p->stream);
+    (void)hipHostFree(p->q.ring);
+    (void)hipHostFree(p->q.flags);
+    (void)hipHostFree(p->head);
+    H.proxies.erase(std::remove(H.proxies.begin(), H.proxies.end(), p), H.proxies.end());
+    delete p;
+}
+
 }  // namespace
 
 int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out)
@@ -951,6 +969,7 @@ int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out)
     p->q.mask = queue_entries - 1;
     p->head = (uint64_t *)head;
     p->worker = std::thread(proxy_main, p);
+    H.proxies.push_back(p);
     *proxy_out = p;
     return SHMEM_OK;
 }
@@ -1004,17 +1023,9 @@ int shmem_proxy_stats(shmem_proxy_t p, uint64_t *submitted, uint64_t *executed, 
 int shmem_proxy_destroy(shmem_proxy_t p)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!p) return SHMEM_ERR_INVALID_ARG;
+    if (!p || std::find(H.proxies.begin(), H.proxies.end(), p) == H.proxies.end()) return SHMEM_ERR_INVALID_ARG;
     (void)hipStreamSynchronize(H.stream);            // no producer is still writing into the ring
-    p->stop.store(true, std::memory_order_release);
-    if (p->worker.joinable()) p->worker.join();
-    (void)hipStreamSynchronize(p->stream);
-    (void)hipEventDestroy(p->ready);
-    (void)hipStreamDestroy(p->stream);
-    (void)hipHostFree(p->q.ring);
-    (void)hipHostFree(p->q.flags);
-    (void)hipHostFree(p->head);
-    delete p;
+    proxy_stop_and_free(p);
     return SHMEM_OK;
 }
 

@@ -117,3 +117,6 @@ def test_proxy_argument_checks():
         sh.proxy_submit(px, t, 0, 1)                               # nothing to do
         sh.proxy_quiet(px)
         sh.proxy_destroy(px)
+        with pytest.raises(sh.ShmemError):
+            sh.proxy_destroy(px)                                   # not a live proxy any more
+        sh.proxy_create(8)                                         # left alive: finalize stops its thread
