@@ -373,6 +373,68 @@ def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
     return out
 
 
+def run_sweep(path):
+    """Configuration 2 in full: contiguous put/get 8 B..64 MiB (plus the paper's 14,336 / 14,352-byte
+    MoE message sizes) x 1..256 workgroups per PE, and strided uint32 iput/iget.  Writes one JSON
+    record per cell to `path` and prints a one-line summary."""
+    import torch
+    import paper_2511_15076_amd as sh
+    dev = torch.device("cuda:0")
+    heap = torch.empty(NPES * SEG, dtype=torch.uint8, device=dev)
+    heap.view(torch.int64).random_()
+    scratch = torch.zeros(sh.scratch_bytes(NPES), dtype=torch.uint8, device=dev)
+    sh.init(NPES, SEG, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    base = heap.data_ptr()
+    local_sym, remote_sym, window = base, base + SEG // 2, SEG // 2
+    cells_out = []
+
+    def time_cell(kind, count, eb, rs, ls, rslot, lslot, nslots, ops, wgs):
+        fn = lambda: sh.copy_sweep(kind, remote_sym, local_sym, count, eb, rs, ls, rslot, lslot, nslots, ops, wgs)
+        return _median_ms(fn, lambda: None, reps=3, warm=1)
+
+    sizes = sorted([1 << k for k in range(3, 27)] + [14336, 14352])
+    for nbytes in sizes:
+        slot = (nbytes + 255) // 256 * 256
+        nslots = max(1, min(window // slot, (1 << 28) // slot))
+        ops = max(1, min((1 << 28) // nbytes, 1 << 16))
+        for wgs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+            for kind, name in ((sh.OP_PUT, "put"), (sh.OP_GET, "get")):
+                ms = time_cell(kind, nbytes, 1, 1, 1, slot, slot, nslots, ops, wgs)
+                payload = NPES * ops * nbytes
+                cells_out.append({"op": name, "bytes": nbytes, "wgs_per_pe": wgs, "ops_per_pe": ops,
+                                  "touched_bytes": 2 * NPES * min(ops, nslots) * nbytes, "ms": round(ms, 4),
+                                  "payload_GBs": round(payload / ms / 1e6, 2),
+                                  "traffic_GBs": round(2 * payload / ms / 1e6, 2),
+                                  "hbm_frac": round(2 * payload / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                  "us_per_op": round(ms * 1e3 / ops, 4)})
+    # strided: uint32 elements, stride on the local side (gather for iput), the remote side (scatter) or both
+    for payload_bytes in (4096, 1 << 20, 1 << 22):
+        nelems = payload_bytes // 4
+        for stride in (2, 4, 8, 16, 32, 64):
+            for mode, ls, rs in (("local", stride, 1), ("remote", 1, stride), ("both", stride, stride)):
+                lspan, rspan = ((nelems - 1) * ls + 1) * 4, ((nelems - 1) * rs + 1) * 4
+                lslot, rslot = (lspan + 255) // 256 * 256, (rspan + 255) // 256 * 256
+                nslots = max(1, min(window // max(lslot, rslot), (1 << 26) // payload_bytes))
+                ops = max(1, (1 << 26) // payload_bytes)
+                for wgs in (16, 64, 256):
+                    for kind, name in ((sh.OP_IPUT, "iput"), (sh.OP_IGET, "iget")):
+                        ms = time_cell(kind, nelems, 4, rs, ls, rslot, lslot, nslots, ops, wgs)
+                        payload = NPES * ops * payload_bytes
+                        sect = lambda st_: min(st_ * 4, 64) if st_ > 1 else 4   # bytes of memory sectors per element
+                        traffic = NPES * ops * nelems * (sect(ls) + sect(rs))
+                        cells_out.append({"op": name, "bytes": payload_bytes, "stride_mode": mode, "stride": stride,
+                                          "wgs_per_pe": wgs, "ops_per_pe": ops, "ms": round(ms, 4),
+                                          "payload_GBs": round(payload / ms / 1e6, 2),
+                                          "traffic_GBs": round(traffic / ms / 1e6, 2),
+                                          "hbm_frac": round(traffic / ms / 1e6 / HBM_PEAK_GBS, 4)})
+    sh.stream_sync()
+    sh.finalize()
+    with open(path, "w") as f:
+        json.dump({"npes": NPES, "heap_bytes_per_pe": SEG, "cells": cells_out}, f)
+    best = max((c for c in cells_out if c["op"] in ("put", "get") and c["bytes"] >= 1 << 20), key=lambda c: c["hbm_frac"])
+    print(json.dumps({"sweep_cells": len(cells_out), "file": path, "best_contiguous_ge_1MiB": best}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
