@@ -131,17 +131,18 @@ constexpr uint64_t CHUNK_BYTES = 4096;  // per wave-task, contiguous ops
 constexpr uint64_t CHUNK_ELEMS = 2048;  // per wave-task, strided ops
 constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size are packed into sub-wave groups
 
-// Contiguous messages whose size and placement are multiples of 1 KiB (the bandwidth cells): every
+// Contiguous 16-byte aligned messages of at least 1 KiB (the bandwidth cells), their leading multiple of
+// 1 KiB: every
 // wave-task is VPL full 16-byte vectors per lane, so nothing is predicated, and the loop is software-
 // pipelined over two register sets: the loads of a wave's next task are issued before the stores of
 // its current one, which keeps reads in flight behind the writes.  (Predicated or conditional loads
 // inside the loop would make the compiler wait for every outstanding access before each store.)
 template <int VPL>
-__device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint8_t *lbase, uint8_t *rbase, uint64_t my_wave,
-                                                uint64_t team_waves, uint32_t lane)
+__device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t body, uint8_t *lbase, uint8_t *rbase,
+                                                uint64_t my_wave, uint64_t team_waves, uint32_t lane)
 {
     constexpr uint64_t TASK_VECS = 64 * VPL;
-    const uint64_t chunks = a.count / (TASK_VECS * 16);
+    const uint64_t chunks = body / (TASK_VECS * 16);   // body: the leading bytes of every message that this path moves
     const uint64_t tasks = chunks * a.ops_per_pe;
     if (my_wave >= tasks) return;
     // task t = (op, chunk) with slot = op % nslots; the walk t -> t + team_waves needs no division
@@ -225,10 +226,25 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
         }
         return;
     }
-    if (contiguous && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 1023) == 0) {
-        if (a.count % 4096 == 0) sweep_pipelined<4>(a, lbase, rbase, my_wave, team_waves, lane);
-        else if (a.count % 2048 == 0) sweep_pipelined<2>(a, lbase, rbase, my_wave, team_waves, lane);
-        else sweep_pipelined<1>(a, lbase, rbase, my_wave, team_waves, lane);
+    if (contiguous && a.count >= 1024 && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0) {
+        // the leading multiple of 1 KiB of every message goes through the pipelined loop ...
+        const uint64_t body = a.count & ~1023ull, tail_vecs = (a.count - body) / 16;
+        if (body % 4096 == 0) sweep_pipelined<4>(a, body, lbase, rbase, my_wave, team_waves, lane);
+        else if (body % 2048 == 0) sweep_pipelined<2>(a, body, lbase, rbase, my_wave, team_waves, lane);
+        else sweep_pipelined<1>(a, body, lbase, rbase, my_wave, team_waves, lane);
+        // ... and what is left of each (under 1 KiB, e.g. the 16 metadata bytes of a 14,352-byte MoE
+        // message) with one vector per lane
+        if (tail_vecs) {
+            for (uint64_t op = my_wave; op < a.ops_per_pe; op += team_waves) {
+                const uint64_t slot = op % a.nslots;
+                u32x4 *l = (u32x4 *)(lbase + slot * a.local_slot + body) + lane;
+                u32x4 *r = (u32x4 *)(rbase + slot * a.remote_slot + body) + lane;
+                if (lane < tail_vecs) {
+                    if (a.kind == SHMEM_OP_PUT) __builtin_nontemporal_store(__builtin_nontemporal_load(l), r);
+                    else __builtin_nontemporal_store(__builtin_nontemporal_load(r), l);
+                }
+            }
+        }
         return;
     }
     for (uint64_t t = my_wave; t < tasks; t += team_waves) {

@@ -131,6 +131,9 @@ SWEEP_CASES = [
     (workgen.OP_PUT, 4096, 1, 1, 1, 9, 4, 3),
     (workgen.OP_PUT, 14352, 1, 1, 1, 6, 3, 2),          # the paper's MoE dispatch message size
     (workgen.OP_GET, 14336, 1, 1, 1, 6, 3, 5),          # ... and its combine message size
+    (workgen.OP_GET, 1040, 1, 1, 1, 37, 5, 3),          # one full KiB and one 16-byte vector
+    (workgen.OP_PUT, 3 * 1024 + 80, 1, 1, 1, 21, 21, 2),
+    (workgen.OP_PUT, (1 << 20) + 48, 1, 1, 1, 3, 3, 16),  # many chunks and a 48-byte tail
     (workgen.OP_PUT, (1 << 20) + 24, 1, 1, 1, 3, 2, 16),  # several chunks and a ragged tail
     (workgen.OP_GET, (1 << 20) + 8, 1, 1, 1, 2, 1, 7),
     (workgen.OP_IPUT, 5000, 4, 1, 2, 3, 2, 3),          # gather (local side strided)
