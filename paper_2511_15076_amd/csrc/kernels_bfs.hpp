@@ -577,6 +577,20 @@ __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
     if (threadIdx.x == 0) c.scratch[W_WORK] = total;
 }
 
+// Last kernel of a level: hands the three level counters to the host through GPU-mapped pinned
+// memory, then a sequence number behind a system-scope release.  The host polls the sequence word
+// instead of paying for a device-to-host copy and a stream synchronisation per level.
+__global__ void k_bfs_publish(Ctx c, uint64_t *host_counts, uint64_t seq)
+{
+    if (threadIdx.x == 0) {
+        host_counts[0] = c.scratch[W_WORK];
+        host_counts[1] = c.scratch[W_WORK + 1];
+        host_counts[2] = c.scratch[W_WORK + 2];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
+        __hip_atomic_store(host_counts + 3, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
 // clears the next-frontier degree sum once the host has read it
 __global__ void k_bfs_clear_front_degree(Ctx c) { if (threadIdx.x == 0) c.scratch[W_WORK + 2] = 0; }
 

@@ -123,6 +123,27 @@ int max_resident_wgs(K kernel, int threads = WG_THREADS)
 // launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
 void proxy_stop_and_free(struct shmem_proxy *p);   // defined with the proxy executor below
 
+// End of a BFS level: a one-thread kernel writes the level counters and a fresh sequence number into
+// the pinned page; the host spins on the sequence word (no copy, no stream synchronisation), looking
+// at the stream every so often so that a failed launch cannot make it wait for ever.
+int bfs_level_counts(uint64_t *counts)
+{
+    static uint64_t seq = 0;
+    ++seq;
+    hipLaunchKernelGGL(shmemx::k_bfs_publish, dim3(1), dim3(64), 0, H.stream, ctx(), counts, seq);
+    if (int rc = launched()) return rc;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint32_t spins = 0; __atomic_load_n(counts + 3, __ATOMIC_ACQUIRE) != seq; ++spins) {
+        if ((spins & 0xFFFF) == 0xFFFF) {
+            const hipError_t q = hipStreamQuery(H.stream);
+            if (q != hipSuccess && q != hipErrorNotReady) return SHMEM_ERR_DEVICE;
+            if (q == hipSuccess && __atomic_load_n(counts + 3, __ATOMIC_ACQUIRE) != seq) return SHMEM_ERR_DEVICE;
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(30)) return SHMEM_ERR_DEVICE;
+        }
+    }
+    return SHMEM_OK;
+}
+
 int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
 {
     if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
@@ -171,7 +192,8 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     if (hipMemsetAsync(dev_scratch, 0, shmem_scratch_bytes(npes), s) != hipSuccess) return SHMEM_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess) return SHMEM_ERR_DEVICE;
     uint64_t *pinned = nullptr;
-    if (hipHostMalloc((void **)&pinned, 4096, hipHostMallocDefault) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (hipHostMalloc((void **)&pinned, 4096, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return SHMEM_ERR_DEVICE;
+    memset(pinned, 0, 4096);
     H.npes = npes; H.seg = heap_bytes_per_pe; H.heap = (uint8_t *)dev_heap; H.scratch = (uint64_t *)dev_scratch;
     H.stream = s; H.num_cus = prop.multiProcessorCount; H.pinned = pinned;
     const char *coop = getenv("MI_SHMEM_COOPERATIVE_LAUNCH");
@@ -571,8 +593,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     if (hybrid) {
         hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, 0u);
         hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
-        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 24, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
-            hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+        if (int rc = bfs_level_counts(counts)) return rc;
         m_f = cum_mf = counts[2];
     }
     st.frontier_size[0] = 1;
@@ -606,9 +627,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             if (!bottom_up) hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, L + 1);
             hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
         }
-        if (hipMemcpyAsync(counts, &H.scratch[shmemx::W_WORK], 24, hipMemcpyDeviceToHost, H.stream) != hipSuccess)
-            return SHMEM_ERR_DEVICE;
-        if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+        if (int rc = bfs_level_counts(counts)) return rc;
         ++L;
         if (counts[0] == 0) break;
         if (L >= 64) return SHMEM_ERR_INVALID_ARG;
