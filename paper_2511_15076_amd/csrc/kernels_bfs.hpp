@@ -493,6 +493,7 @@ __device__ __forceinline__ bool bfs_in_front(const Ctx &c, const BfsState &s, ui
 }
 
 constexpr uint32_t BU_LANE_EDGES = 16;  // neighbours a lane scans on its own before the wave helps
+constexpr uint32_t BU_BATCH = 4;        // ... this many at a time
 
 // Bottom-up level L -> L+1.  A wave owns one bitmap word (64 consecutive local
 // vertices, lane = bit) at a time.
@@ -523,9 +524,16 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
             r0 = s.row_off[first + l];
             deg = (uint32_t)(s.row_off[first + l + 1] - r0);
             const uint32_t own = deg < BU_LANE_EDGES ? deg : BU_LANE_EDGES;   // the lane's own share of the row
-            for (uint32_t j = 0; j < own; ++j) {
-                const uint32_t u = s.nbr[r0 + j];
-                if (bfs_in_front(c, s, u)) { par = u; break; }
+            // four neighbours and their four frontier words travel together; the first hit in row order wins
+            for (uint32_t j = 0; j < own && par == SHMEM_BFS_NONE; j += BU_BATCH) {
+                uint32_t u[BU_BATCH];
+                bool in[BU_BATCH];
+#pragma unroll
+                for (uint32_t k = 0; k < BU_BATCH; ++k) u[k] = j + k < own ? s.nbr[r0 + j + k] : 0;
+#pragma unroll
+                for (uint32_t k = 0; k < BU_BATCH; ++k) in[k] = j + k < own && bfs_in_front(c, s, u[k]);
+#pragma unroll
+                for (uint32_t k = BU_BATCH; k-- > 0;) if (in[k]) par = u[k];
             }
         }
         // rows longer than a lane's share: the whole wave scans the rest, 64 neighbours at a time
