@@ -1,6 +1,9 @@
 // Plain-stream ceilings of the box: read-only, write-only and copy kernels with
 // 16 bytes per lane over 2 GiB buffers, plus the runtime's own memcpy / memset.
-// These are the sanity ceilings the put/get kernels are held against; this
+// These are the sanity ceilings the put/get kernels are held against.  Also the
+// random-access ceilings the AMO, hash and BFS kernels are held against: random
+// 8-byte reads over footprints from L2-resident to HBM-sized, returning 64-bit
+// atomics to distinct lines (R_indep) and to one address (R_same).  This
 // program is a measurement aid, not part of the library.
 #include <hip/hip_runtime.h>
 
@@ -47,6 +50,42 @@ __global__ __launch_bounds__(256) void k_copy(const u32x4 *s, u32x4 *d, uint64_t
     }
 }
 
+
+// counter-based index stream (SplitMix64 finaliser of the global op number)
+__device__ __forceinline__ uint64_t mix(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// n random 8-byte reads over `words` uint64 words (a power of two), PER independent reads in flight per lane
+template <int PER>
+__global__ __launch_bounds__(256) void k_randread(const uint64_t *a, uint64_t words, uint64_t n, uint32_t *out)
+{
+    uint64_t acc = 0;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride * PER) {
+        uint64_t v[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) v[k] = a[mix(i + k * stride) & (words - 1)];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) acc ^= v[k];
+    }
+    if (acc == 0x12345u) out[0] = 1;
+}
+
+// n returning 64-bit fetch-adds (agent scope): word = 16 * (random line index) so that every op has its
+// own 128-byte line when `lines` is large, or all ops hit word 0 when lines == 1
+__global__ __launch_bounds__(256) void k_atomics(uint64_t *a, uint64_t lines, uint64_t n, uint32_t *out)
+{
+    uint64_t acc = 0;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        acc ^= __hip_atomic_fetch_add(a + 16 * (mix(i) & (lines - 1)), 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (acc == 0x12345u) out[0] = 1;
+}
+
 template <typename F>
 static float median_ms(F f, int reps = 9)
 {
@@ -86,6 +125,22 @@ int main()
     float ms = median_ms([&] { CK(hipMemcpyAsync(d, s, bytes, hipMemcpyDeviceToDevice, 0)); });
     printf("\"hipMemcpyDtoD_GBs\": %.0f, ", 2.0 * bytes / ms / 1e6);
     ms = median_ms([&] { CK(hipMemsetAsync(d, 7, bytes, 0)); });
-    printf("\"hipMemset_GBs\": %.0f, \"bytes_per_buffer\": %llu}\n", bytes / ms / 1e6, (unsigned long long)bytes);
+    printf("\"hipMemset_GBs\": %.0f, \"bytes_per_buffer\": %llu, ", bytes / ms / 1e6, (unsigned long long)bytes);
+    // random 8-byte reads: 2 MiB (one die's L2 holds it), 16 MiB, 1 GiB and 2 GiB footprints
+    const uint64_t nops = 1ull << 28;
+    for (uint64_t fp : {2ull << 20, 16ull << 20, 1ull << 30, 2ull << 30}) {
+        ms = median_ms([&] { hipLaunchKernelGGL(k_randread<4>, dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, fp / 8, nops, flag); }, 5);
+        printf("\"randread8_%lluMiB_Gops\": %.1f, ", (unsigned long long)(fp >> 20), nops / ms / 1e6);
+    }
+    // returning atomics: distinct 128-byte lines over 1 GiB, over 8 MiB (64 Ki lines), and one address
+    const uint64_t natom = 1ull << 26;
+    CK(hipMemset(buf, 0, bytes));
+    ms = median_ms([&] { hipLaunchKernelGGL(k_atomics, dim3(4096), dim3(256), 0, 0, (uint64_t *)buf, (1ull << 30) / 128, natom, flag); }, 5);
+    printf("\"atomic_indep_1GiB_Gops\": %.2f, ", natom / ms / 1e6);
+    ms = median_ms([&] { hipLaunchKernelGGL(k_atomics, dim3(4096), dim3(256), 0, 0, (uint64_t *)buf, 1ull << 16, natom, flag); }, 5);
+    printf("\"atomic_indep_8MiB_Gops\": %.2f, ", natom / ms / 1e6);
+    const uint64_t nsame = 1ull << 22;
+    ms = median_ms([&] { hipLaunchKernelGGL(k_atomics, dim3(1024), dim3(256), 0, 0, (uint64_t *)buf, 1ull, nsame, flag); }, 5);
+    printf("\"atomic_same_address_Gops\": %.3f}\n", nsame / ms / 1e6);
     return 0;
 }
