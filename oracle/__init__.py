@@ -222,3 +222,21 @@ class World:
                  "edges_traversed": st.edges_traversed,
                  "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}
         return level, parent, stats
+
+
+def canonical_parents(row_off, nbr, level, root):
+    """Canonical BFS tree for given levels: parent[v] = the smallest neighbour u of v with
+    level[u] == level[v] - 1 (parent[root] = root, unreached vertices keep BFS_NONE).  The levels of
+    a BFS are unique, so this tree is too -- unlike the first-claimer tree, it can be compared
+    vertex by vertex."""
+    row_off = np.asarray(row_off, dtype=np.int64)
+    nbr = np.asarray(nbr, dtype=np.int64)
+    level = np.asarray(level, dtype=np.int64)
+    n = len(row_off) - 1
+    src = np.repeat(np.arange(n, dtype=np.int64), np.diff(row_off))
+    good = (level[src] > 0) & (level[nbr] == level[src] - 1)
+    parent = np.full(n, BFS_NONE, dtype=np.int64)
+    np.minimum.at(parent, src[good], nbr[good])
+    parent[root] = root
+    return parent.astype(np.uint32)
+

@@ -205,3 +205,27 @@ def test_zipf_and_amo_generators():
     assert pe.min() >= 0 and pe.max() == 63 and (ix == 0).all() and (a == 1).all()
     keys = workgen.cfg4_keys(n=1000)
     assert keys.dtype == np.uint64 and keys.min() >= 1
+
+
+def test_canonical_parents_against_loops():
+    # the numpy form against the definition written as loops, on small R-MAT graphs
+    for scale, seed in ((6, 1), (8, 2), (9, 3)):
+        row, nbr = workgen.rmat_csr(scale, edge_factor=4, seed=seed)
+        n = len(row) - 1
+        root = int(workgen.bfs_roots(row, 1, seed=seed)[0])
+        w = oracle.World(4, ((n // 4 + 1) * 40 + 8192 + 255) // 256 * 256, oracle.EAGER, 1)
+        level, parent, _ = w.bfs(row, nbr, root)
+        got = oracle.canonical_parents(row, nbr, level, root)
+        for v in range(n):
+            if v == root:
+                assert got[v] == root
+                continue
+            want = oracle.BFS_NONE
+            if level[v] > 0:
+                for u in nbr[int(row[v]):int(row[v + 1])]:
+                    if level[u] == level[v] - 1:
+                        want = min(want, int(u))
+            assert got[v] == want, (scale, v)
+            if level[v] > 0:                    # and it is a valid tree edge, like the first-claimer parent
+                assert level[parent[v]] == level[v] - 1 and level[got[v]] == level[v] - 1
+
