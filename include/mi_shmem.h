@@ -228,12 +228,15 @@ int shmem_bfs_destroy(void *graph);
  * level and queue entry are then local writes -- when the frontier's row lengths
  * add up to more than 1/alpha of those of the unvisited vertices, and back to
  * top-down when the frontier is below nverts/beta and shrinking (alpha, beta = 0:
- * the
- * defaults, 30 and 24).  BOTTOM_UP forces
- * bottom-up on every level (for tests).  Levels, frontier sizes and counts are
- * the same in every mode; parents may differ (all are valid).
+ * the defaults, 30 and 24).  BOTTOM_UP forces bottom-up on every level (for
+ * tests).  Levels, frontier sizes and counts are the same in every mode; parents
+ * may differ (all are valid).  OR-ing SHMEM_BFS_CANONICAL_PARENTS into the mode
+ * adds a pass after the search that rewrites every parent to the smallest
+ * neighbour one level up (one-sided 4-byte gets of the neighbours' levels): the
+ * one tree that does not depend on who claimed a vertex first.
  * Errors: NOT_INIT, INVALID_ARG. */
-enum { SHMEM_BFS_TOP_DOWN = 0, SHMEM_BFS_DIRECTION_OPTIMIZING = 1, SHMEM_BFS_BOTTOM_UP = 2 };
+enum { SHMEM_BFS_TOP_DOWN = 0, SHMEM_BFS_DIRECTION_OPTIMIZING = 1, SHMEM_BFS_BOTTOM_UP = 2,
+       SHMEM_BFS_CANONICAL_PARENTS = 0x100 };
 int shmem_bfs_configure(void *graph, int mode, int alpha, int beta);
 /* Runs one search; blocks the host (one stream sync per level).  dev_level
  * (int32[nverts], -1 = unreached) and dev_parent (uint32[nverts],

@@ -21,6 +21,7 @@ AMO_FETCH_ADD, AMO_COMPARE_SWAP, AMO_FETCH_OR, AMO_MIN_CAS_LOOP = 0, 1, 2, 3
 HASH_INSERTED, HASH_DUPLICATE, HASH_FULL = 0, 1, 2
 BFS_NONE = 0xFFFFFFFF
 BFS_TOP_DOWN, BFS_DIRECTION_OPTIMIZING, BFS_BOTTOM_UP = 0, 1, 2
+BFS_CANONICAL_PARENTS = 0x100
 
 
 class ShmemError(RuntimeError):

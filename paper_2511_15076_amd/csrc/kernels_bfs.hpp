@@ -570,6 +570,64 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     if (lane == 0 && mf) atomic_fetch_add(&c.scratch[W_WORK + 2], mf);
 }
 
+// Optional post-pass: canonical parents.  parent[v] = the smallest neighbour of v whose level is one
+// less than v's (levels are unique, so this tree is too and can be compared vertex by vertex).  Every
+// owner rewrites the parents of its own vertices; a neighbour's level is a 4-byte get from its owner.
+constexpr uint32_t CANON_LANE_EDGES = 32;   // rows up to this long are scanned by one lane
+
+__device__ __forceinline__ int32_t bfs_level_of(const Ctx &c, const BfsState &s, uint32_t u)
+{
+    const uint32_t o = bfs_owner(s, u);
+    return ((const int32_t *)ptr(c, s.level_off, o))[u - o * s.vpp];
+}
+
+__global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint64_t first = (uint64_t)pe * s.vpp;
+    if (first >= s.nverts) return;
+    const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
+    const int32_t *lv = (const int32_t *)ptr(c, s.level_off, pe);
+    uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
+    for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
+        const uint64_t l = w * 64 + lane;
+        const int32_t lvl = l < count ? lv[l] : -1;
+        const bool need = lvl > 0;                       // reached and not the root
+        uint32_t best = SHMEM_BFS_NONE, deg = 0;
+        uint64_t r0 = 0;
+        if (need) {
+            r0 = s.row_off[first + l];
+            deg = (uint32_t)(s.row_off[first + l + 1] - r0);
+            if (deg <= CANON_LANE_EDGES)
+                for (uint32_t j = 0; j < deg; ++j) {
+                    const uint32_t u = s.nbr[r0 + j];
+                    if (bfs_level_of(c, s, u) == lvl - 1 && u < best) best = u;
+                }
+        }
+        uint64_t longrows = ballot(need && deg > CANON_LANE_EDGES);   // the wave scans these together
+        while (longrows) {
+            const uint32_t j = (uint32_t)__builtin_ctzll(longrows);
+            longrows &= longrows - 1;
+            const uint32_t dj = bcast32(deg, j);
+            const uint64_t rj = bcast64(r0, j);
+            const int32_t lj = (int32_t)bcast32((uint32_t)lvl, j);
+            uint32_t mn = SHMEM_BFS_NONE;
+            for (uint32_t e0 = 0; e0 < dj; e0 += 64) {
+                if (e0 + lane < dj) {
+                    const uint32_t u = s.nbr[rj + e0 + lane];
+                    if (bfs_level_of(c, s, u) == lj - 1 && u < mn) mn = u;
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off, 64));
+            if (lane == j) best = mn;
+        }
+        if (need) pr[l] = best;
+    }
+}
+
 // Level epilogue (one wave): total size of frontier `next`, reset of the long
 // row counters and of the count that level next+1 will fill.
 __global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)

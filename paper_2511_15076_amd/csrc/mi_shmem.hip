@@ -52,6 +52,7 @@ struct BfsGraph {
     shmemx::BfsState st;
     int wgs_per_pe;
     int mode;          // SHMEM_BFS_TOP_DOWN / DIRECTION_OPTIMIZING / BOTTOM_UP
+    bool canonical;    // rewrite the parents into the canonical tree after the search
     uint32_t alpha, beta;  // direction thresholds
     uint64_t nnz;      // CSR entries (sum of all row lengths)
     void *allocs[12];
@@ -533,7 +534,7 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
     s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.big_off = offs[5]; s.bigscan_off = offs[6];
     s.tails_off = offs[7]; s.filter_off = offs[8]; s.front_off = offs[9]; s.prev_off = offs[10]; s.linked_off = offs[11];
-    g->mode = SHMEM_BFS_TOP_DOWN; g->alpha = BFS_ALPHA; g->beta = BFS_BETA;
+    g->mode = SHMEM_BFS_TOP_DOWN; g->canonical = false; g->alpha = BFS_ALPHA; g->beta = BFS_BETA;
     g->nnz = 0;
     if (hipMemcpyAsync(H.pinned + 32, dev_row_off + nverts, 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
         hipStreamSynchronize(H.stream) != hipSuccess) {
@@ -564,9 +565,12 @@ int shmem_bfs_destroy(void *graph)
 int shmem_bfs_configure(void *graph, int mode, int alpha, int beta)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!graph || mode < SHMEM_BFS_TOP_DOWN || mode > SHMEM_BFS_BOTTOM_UP || alpha < 0 || beta < 0) return SHMEM_ERR_INVALID_ARG;
+    const int direction = mode & ~SHMEM_BFS_CANONICAL_PARENTS;
+    if (!graph || direction < SHMEM_BFS_TOP_DOWN || direction > SHMEM_BFS_BOTTOM_UP || alpha < 0 || beta < 0)
+        return SHMEM_ERR_INVALID_ARG;
     BfsGraph *g = (BfsGraph *)graph;
-    g->mode = mode;
+    g->mode = direction;
+    g->canonical = (mode & SHMEM_BFS_CANONICAL_PARENTS) != 0;
     g->alpha = alpha ? (uint32_t)alpha : BFS_ALPHA;
     g->beta = beta ? (uint32_t)beta : BFS_BETA;
     return SHMEM_OK;
@@ -638,6 +642,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     st.nlevels = L;
     for (uint32_t l = 0; l < L; ++l) st.reached += st.frontier_size[l];
     st.edges_traversed = (hybrid ? counts[2] : counts[1]) / 2;
+    if (g->canonical) hipLaunchKernelGGL(shmemx::k_bfs_canonical, grid, block, 0, H.stream, c, s);
     if (dev_level || dev_parent) {
         hipLaunchKernelGGL(shmemx::k_bfs_gather, grid, block, 0, H.stream, c, s, dev_level, dev_parent);
         if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;

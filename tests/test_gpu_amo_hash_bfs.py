@@ -245,11 +245,15 @@ def run_bfs_case(row, nbr, roots, npes, wgs, mode=0):
             assert np.array_equal(level, olevel)          # levels are unique
             assert stats == ostats                        # sizes per level, reached, traversed edges
             check_tree(row, nbr, int(root), level, parent)
+            if mode & sh.BFS_CANONICAL_PARENTS:           # the one tree that can be compared vertex by vertex
+                assert np.array_equal(parent, oracle.canonical_parents(row, nbr, olevel, int(root)))
         sh.bfs_destroy(g)
         assert sh.malloc(hb) == base                      # everything was returned to the heap
 
 
-@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP])
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP,
+                                  sh.BFS_TOP_DOWN | sh.BFS_CANONICAL_PARENTS,
+                                  sh.BFS_DIRECTION_OPTIMIZING | sh.BFS_CANONICAL_PARENTS])
 @pytest.mark.parametrize("scale,npes,wgs", [(10, 16, 1), (14, 16, 4), (13, 3, 2), (16, 16, 8)])
 def test_bfs_rmat(scale, npes, wgs, mode):
     row, nbr = workgen.rmat_csr(scale)

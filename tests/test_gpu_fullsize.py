@@ -188,4 +188,17 @@ def test_config5_full_two_roots():
                 for v in vs[:: max(1, len(vs) // 2000)]:              # sampled: the tree edge exists
                     u = int(parent[v])
                     assert v in nbr[row[u]:row[u + 1]]
+            # canonical parents at full size: sampled vertices, each computed from the oracle's levels
+            sh.bfs_configure(g, sh.BFS_DIRECTION_OPTIMIZING | sh.BFS_CANONICAL_PARENTS)
+            sh.bfs(g, int(root), dl, dp)
+            parent = as_np(dp, np.uint32).copy()
+            reached = olevel >= 0
+            assert parent[root] == root and ((parent == sh.BFS_NONE) == ~reached).all()
+            vs = np.flatnonzero(reached)
+            hubs = np.argsort(deg)[-3:]                               # the longest rows go through the wave-wide scan
+            for v in list(vs[:: max(1, len(vs) // 3000)]) + [int(h) for h in hubs if reached[h]]:
+                if v == root:
+                    continue
+                adj = nbr[row[v]:row[v + 1]]
+                assert parent[v] == adj[olevel[adj] == olevel[v] - 1].min(), v
         sh.bfs_destroy(g)
