@@ -73,17 +73,28 @@ __global__ __launch_bounds__(256) void k_op_batch(Ctx c, const shmem_op_desc *__
     const uint32_t team_waves = (uint32_t)wgs_per_pe * waves_per_wg;
     const uint32_t my_wave = wg * waves_per_wg + wave;
     const size_t window = quiet_every ? quiet_every : n;
-    for (size_t b = 0; b < n; b += window) {
-        const size_t e = b + window < n ? b + window : n;
-        uint32_t mine = 0;  // small ops of this PE seen so far in the window
-        // 64 descriptors at a time: lane j reads descriptor j (one coalesced 4 KiB read), a ballot
-        // finds this PE's ones, and their fields are broadcast from the lane that holds them
-        for (size_t i0 = b; i0 < e; i0 += 64) {
-            shmem_op_desc d;
-            d.kind = ~0u; d.pe_self = ~0u; d.pe = 0; d.elem_bytes = 0; d.local_off = d.sym_off = d.count = 0;
-            d.local_stride = d.sym_stride = 0; d.value = 0;
+    // 64 descriptors at a time: lane j reads descriptor j (one coalesced 4 KiB read), a ballot finds
+    // this PE's ones, and their fields are broadcast from the lane that holds them.  The next batch
+    // is requested before the current one is executed -- also across a window end, so the read of the
+    // next window's first descriptors travels during the barrier (the table is read-only).
+    auto load = [&](size_t i0, size_t e) {
+        shmem_op_desc d;
+        d.kind = ~0u; d.pe_self = ~0u; d.pe = 0; d.elem_bytes = 0; d.local_off = d.sym_off = d.count = 0;
+        d.local_stride = d.sym_stride = 0; d.value = 0;
+        if (i0 + lane < e) d = ops[i0 + lane];
+        return d;
+    };
+    size_t b = 0, e = window < n ? window : n, i0 = 0;
+    shmem_op_desc d = n ? load(0, e) : shmem_op_desc();
+    uint32_t mine = 0;  // small ops of this PE seen so far in the window
+    while (i0 < n) {
+        // position of the batch after this one
+        const bool last_of_window = i0 + 64 >= e;
+        const size_t nb = last_of_window ? e : b, ni0 = last_of_window ? e : i0 + 64;
+        const size_t ne = last_of_window ? (e + window < n ? e + window : n) : e;
+        shmem_op_desc dn = load(ni0, ni0 < n ? ne : ni0);                      // nothing to load past the end
+        {
             const bool have = i0 + lane < e;
-            if (have) d = ops[i0 + lane];
             if (have && d.pe_self >= (uint32_t)c.npes && blockIdx.x == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
             const bool ok = have && d.pe_self == pe && desc_valid(c, d);
             if (have && d.pe_self == pe && !ok && wg == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
@@ -107,7 +118,11 @@ __global__ __launch_bounds__(256) void k_op_batch(Ctx c, const shmem_op_desc *__
                 }
             }
         }
-        barrier_all(c, pe, (uint32_t)wgs_per_pe);  // quiet by every wave, then all teams synchronise
+        if (last_of_window) {
+            barrier_all(c, pe, (uint32_t)wgs_per_pe);  // quiet by every wave, then all teams synchronise
+            mine = 0;
+        }
+        d = dn; b = nb; i0 = ni0; e = ne;
     }
 }
 
