@@ -544,22 +544,27 @@ def main():
     torch.cuda.empty_cache()
     want = [] if args.extras == "none" else args.extras.split(",")
     extras = {}
-    if "cfg1" in want:
-        extras["config1_optable"] = extra_config1(sh, torch)
-    if "latency" in want:
-        extras["latency"] = extra_latency(sh, torch)
-    if "moe" in want:
-        extras["moe_low_latency"] = extra_moe(sh, torch)
+
+    def run_extra(key, name, fn, **kw):
+        # an extra that fails is reported as such; it never costs the headline line
+        if key not in want:
+            return
+        try:
+            extras[name] = fn(sh, torch, **kw)
+        except Exception as ex:  # noqa: BLE001
+            extras[name] = {"error": f"{type(ex).__name__}: {ex}"}
+            try:
+                sh.finalize()
+            except Exception:  # noqa: BLE001
+                pass
         torch.cuda.empty_cache()
-    if "amo" in want:
-        extras["config3_amo"] = extra_amo(sh, torch)
-        torch.cuda.empty_cache()
-    if "hash" in want:
-        extras["config4_hash"] = extra_hash(sh, torch)
-        torch.cuda.empty_cache()
-    if "bfs" in want:
-        extras["config5_bfs"] = extra_bfs(sh, torch, scale=args.bfs_scale)
-        torch.cuda.empty_cache()
+
+    run_extra("cfg1", "config1_optable", extra_config1)
+    run_extra("latency", "latency", extra_latency)
+    run_extra("moe", "moe_low_latency", extra_moe)
+    run_extra("amo", "config3_amo", extra_amo)
+    run_extra("hash", "config4_hash", extra_hash)
+    run_extra("bfs", "config5_bfs", extra_bfs, scale=args.bfs_scale)
     if extras:
         out["extras"] = extras
     if args.ceilings:
@@ -570,7 +575,10 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
         if extras:
-            out["cpu_baseline_extras"] = cpu_baseline_extras()
+            try:
+                out["cpu_baseline_extras"] = cpu_baseline_extras()
+            except Exception as ex:  # noqa: BLE001
+                out["cpu_baseline_extras"] = {"error": f"{type(ex).__name__}: {ex}"}
     print(json.dumps(out), flush=True)
 
 
