@@ -13,7 +13,8 @@
 //                  workgroup per PE);
 //   k_bfs_big      the team's waves split the long rows' 256-edge segments
 //                  evenly (each wave takes a run of consecutive segments);
-//   k_bfs_count    one wave totals the next frontier and resets counters.
+//   k_bfs_level_end  frontier bitmap / degree sum (direction-optimising modes); its last workgroup
+//                  totals the next frontier, resets counters and hands the counts to the host.
 #pragma once
 #include "../../include/mi_shmem.h"
 #include "shmemx.hpp"
@@ -35,7 +36,8 @@ struct BfsState {
 };
 
 // words inside the per-PE tails block (uint64 each)
-enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, T_NTASKS = 5 };
+enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, T_NTASKS = 5,
+                  T_ARRIVE = 6 /* workgroups of this PE that have finished the level-end kernel */ };
 
 constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
 constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
@@ -82,9 +84,9 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     if (rank == 0) {
         uint64_t *t = bfs_tails(c, s, pe);
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
-        t[T_NBIG] = 0; t[T_NTASKS] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
-        if (pe == 0) { c.scratch[W_WORK + 1] = 0; c.scratch[W_WORK + 2] = 0; }  // degree sums (reached / next frontier)
+        if (pe == 0) { c.scratch[W_WORK + 1] = 0; c.scratch[W_WORK + 2] = 0; c.scratch[W_WORK + 4] = 0; }  // degree sums, arrival count
     }
 }
 
@@ -455,36 +457,6 @@ __global__ __launch_bounds__(256) void k_bfs_mark_linked(Ctx c, BfsState s)
     }
 }
 
-// frontier bitmap of the level about to be expanded = newly set bits; runs after init and each level
-__global__ __launch_bounds__(256) void k_bfs_make_front(Ctx c, BfsState s)
-{
-    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
-    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
-    const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
-    uint64_t *front = (uint64_t *)ptr(c, s.front_off, pe), *prev = (uint64_t *)ptr(c, s.prev_off, pe);
-    for (uint64_t w = rank; w < s.words; w += size) {
-        const uint64_t v = vis[w];
-        front[w] = v & ~prev[w];
-        prev[w] = v;
-    }
-}
-
-// sum of the row lengths of frontier `next` (decides the direction of the next level)
-__global__ __launch_bounds__(256) void k_bfs_front_degree(Ctx c, BfsState s, uint32_t next)
-{
-    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
-    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
-    const uint64_t cnt = bfs_tails(c, s, pe)[T_TAIL0 + next % 3];
-    const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[next & 1], pe);
-    uint64_t sum = 0;
-    for (uint64_t k = rank; k < cnt; k += size) {
-        const uint32_t u = queue[k];
-        sum += s.row_off[u + 1] - s.row_off[u];
-    }
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
-    if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(&c.scratch[W_WORK + 2], sum);
-}
-
 // is u in the current frontier?  (an 8-byte get from u's owner)
 __device__ __forceinline__ bool bfs_in_front(const Ctx &c, const BfsState &s, uint32_t u)
 {
@@ -628,37 +600,74 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
     }
 }
 
-// Level epilogue (one wave): total size of frontier `next`, reset of the long
-// row counters and of the count that level next+1 will fill.
-__global__ void k_bfs_count(Ctx c, BfsState s, uint32_t next)
+// End of a level in one launch: (optionally) the frontier bitmap of the level about to be expanded and
+// the sum of its row lengths, then -- by whichever workgroup finishes last -- the level epilogue of
+// level epilogue (total size of frontier `next`, reset of the long-row counters and of the count that
+// level next+1 will fill) and the hand-over to the host: the three level counters go into GPU-mapped
+// pinned memory, then a sequence number behind a system-scope release; the host polls the sequence word
+// instead of paying for a copy and a stream synchronisation per level.  Nobody waits inside the kernel:
+// every workgroup counts itself in, and only the one that finds all others counted goes on.
+__global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32_t next, int do_front, int do_degree,
+                                                       uint64_t *host_counts, uint64_t seq)
 {
+    __shared__ bool last;
+    const uint32_t teams_wgs = gridDim.x / (uint32_t)c.npes;           // workgroups per PE in this launch
+    const uint32_t pe = blockIdx.x / teams_wgs, wg = blockIdx.x % teams_wgs;
+    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)teams_wgs * blockDim.x;
+    if (do_front) {
+        const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
+        uint64_t *front = (uint64_t *)ptr(c, s.front_off, pe), *prev = (uint64_t *)ptr(c, s.prev_off, pe);
+        for (uint64_t w = rank; w < s.words; w += size) {
+            const uint64_t v = vis[w];
+            front[w] = v & ~prev[w];
+            prev[w] = v;
+        }
+    }
+    if (do_degree) {
+        const uint64_t cnt = bfs_tails(c, s, pe)[T_TAIL0 + next % 3];
+        const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[next & 1], pe);
+        uint64_t sum = 0;
+        for (uint64_t k = rank; k < cnt; k += size) {
+            const uint32_t u = queue[k];
+            sum += s.row_off[u + 1] - s.row_off[u];
+        }
+        for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+        if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(&c.scratch[W_WORK + 2], sum);
+    }
+    // Everything the last workgroup reads below is an atomically updated counter, and those resolve at
+    // the memory side: each wave's adds are complete (workgroup-scope release = wait for their
+    // acknowledgement) before thread 0 counts the workgroup in, so no cache write-back or invalidate is
+    // needed here; the plain stores above are for the next kernel and leave with this one's end.
+    wg_release();
+    if (threadIdx.x == 0) {
+        // two stages (per PE, then across PEs): arrivals on one word serialise at the memory side
+        last = false;
+        uint64_t *mine = bfs_tails(c, s, pe) + T_ARRIVE;
+        if (atomic_fetch_add(mine, 1) == teams_wgs - 1) {
+            __hip_atomic_store(mine, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);                     // all of this PE have arrived
+            last = atomic_fetch_add(&c.scratch[W_WORK + 4], 1) == (uint64_t)c.npes - 1;
+            if (last) __hip_atomic_store(&c.scratch[W_WORK + 4], 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        }
+    }
+    __syncthreads();
+    if (!last || threadIdx.x >= 64) return;
     uint64_t total = 0;
-    for (uint32_t pe = threadIdx.x; pe < (uint32_t)c.npes; pe += blockDim.x) {
-        uint64_t *t = bfs_tails(c, s, pe);
-        total += t[T_TAIL0 + next % 3];
+    for (uint32_t q = threadIdx.x; q < (uint32_t)c.npes; q += 64) {
+        uint64_t *t = bfs_tails(c, s, q);
+        total += __hip_atomic_load(&t[T_TAIL0 + next % 3], __ATOMIC_RELAXED, SHMEMX_AGENT);
         t[T_TAIL0 + (next + 1) % 3] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0;
     }
     for (int off = 32; off > 0; off >>= 1) total += __shfl_down(total, off, 64);
-    if (threadIdx.x == 0) c.scratch[W_WORK] = total;
-}
-
-// Last kernel of a level: hands the three level counters to the host through GPU-mapped pinned
-// memory, then a sequence number behind a system-scope release.  The host polls the sequence word
-// instead of paying for a device-to-host copy and a stream synchronisation per level.
-__global__ void k_bfs_publish(Ctx c, uint64_t *host_counts, uint64_t seq)
-{
     if (threadIdx.x == 0) {
-        host_counts[0] = c.scratch[W_WORK];
-        host_counts[1] = c.scratch[W_WORK + 1];
-        host_counts[2] = c.scratch[W_WORK + 2];
+        c.scratch[W_WORK] = total;
+        host_counts[0] = total;
+        host_counts[1] = __hip_atomic_load(&c.scratch[W_WORK + 1], __ATOMIC_RELAXED, SHMEMX_AGENT);
+        host_counts[2] = __hip_atomic_load(&c.scratch[W_WORK + 2], __ATOMIC_RELAXED, SHMEMX_AGENT);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
         __hip_atomic_store(host_counts + 3, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
-
-// clears the next-frontier degree sum once the host has read it
-__global__ void k_bfs_clear_front_degree(Ctx c) { if (threadIdx.x == 0) c.scratch[W_WORK + 2] = 0; }
 
 // Every owner copies its level / parent slice into the caller's flat arrays.
 __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, int32_t *level, uint32_t *parent)

@@ -124,14 +124,19 @@ int max_resident_wgs(K kernel, int threads = WG_THREADS)
 // launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
 void proxy_stop_and_free(struct shmem_proxy *p);   // defined with the proxy executor below
 
-// End of a BFS level: a one-thread kernel writes the level counters and a fresh sequence number into
-// the pinned page; the host spins on the sequence word (no copy, no stream synchronisation), looking
-// at the stream every so often so that a failed launch cannot make it wait for ever.
-int bfs_level_counts(uint64_t *counts)
+// End of a BFS level: one launch builds the next frontier's bitmap and degree sum (direction-optimising
+// modes), and its last workgroup sums the frontier size, resets the per-level counters and writes the
+// level counters plus a fresh sequence number into the pinned page.  The host spins on the sequence word
+// (no copy, no stream synchronisation), looking at the stream every so often so that a failed launch
+// cannot make it wait for ever.
+int bfs_level_end(const shmemx::BfsState &s, uint32_t next, bool do_front, bool do_degree, int wgs_per_pe,
+                  uint64_t *counts)
 {
     static uint64_t seq = 0;
     ++seq;
-    hipLaunchKernelGGL(shmemx::k_bfs_publish, dim3(1), dim3(64), 0, H.stream, ctx(), counts, seq);
+    const unsigned grid = (unsigned)H.npes * (unsigned)((do_front || do_degree) ? wgs_per_pe : 1);
+    hipLaunchKernelGGL(shmemx::k_bfs_level_end, dim3(grid), dim3(WG_THREADS), 0, H.stream, ctx(), s, next,
+                       (int)do_front, (int)do_degree, counts, seq);
     if (int rc = launched()) return rc;
     const auto t0 = std::chrono::steady_clock::now();
     for (uint32_t spins = 0; __atomic_load_n(counts + 3, __ATOMIC_ACQUIRE) != seq; ++spins) {
@@ -595,9 +600,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
     uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;
     if (hybrid) {
-        hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, 0u);
-        hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
-        if (int rc = bfs_level_counts(counts)) return rc;
+        if (int rc = bfs_level_end(s, 0u, true, true, g->wgs_per_pe, counts)) return rc;
         m_f = cum_mf = counts[2];
     }
     st.frontier_size[0] = 1;
@@ -626,12 +629,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
             hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
         }
-        hipLaunchKernelGGL(shmemx::k_bfs_count, dim3(1), dim3(64), 0, H.stream, c, s, L + 1);
-        if (hybrid) {
-            if (!bottom_up) hipLaunchKernelGGL(shmemx::k_bfs_front_degree, grid, block, 0, H.stream, c, s, L + 1);
-            hipLaunchKernelGGL(shmemx::k_bfs_make_front, grid, block, 0, H.stream, c, s);
-        }
-        if (int rc = bfs_level_counts(counts)) return rc;
+        if (int rc = bfs_level_end(s, L + 1, hybrid, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
         ++L;
         if (counts[0] == 0) break;
         if (L >= 64) return SHMEM_ERR_INVALID_ARG;
