@@ -96,6 +96,9 @@ CASES = [
     (3, 9, 5, 9, 48, None, "uniform", 0.0, 2),                  # every token to every expert
     (8, 8, 128, 1, 2064, None, "zipf", 0.0, 16),                # one expert per PE, more workgroups than experts
     (16, 64, 33, 6, 528, None, "zipf", 0.1, 4),
+    (1, 4, 9, 2, 16, None, "uniform", 0.0, 2),                 # a single PE talks to itself; smallest token
+    (4, 64, 128, 64, 32, [128, 1, 77, 128], "uniform", 0.3, 5),  # widest top-k, every expert, ragged batches
+    (2, 1024, 16, 8, 64, None, "zipf", 0.0, 7),                # the largest expert count
 ]
 
 
