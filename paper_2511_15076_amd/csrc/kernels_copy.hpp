@@ -208,6 +208,53 @@ __device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t bod
     }
 }
 
+// One large contiguous put or get with 16-byte aligned ends: the leading multiple of 4 KiB streams
+// through a software-pipelined loop over two register sets (the whole grid is the initiator's team,
+// wave-tasks of 4 KiB dealt round robin, a wave's next task requested before its current one is
+// stored); the rest goes through the generic copy.
+__global__ __launch_bounds__(256) void k_copy_stream(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n)
+{
+    constexpr int VPL = 4;
+    constexpr uint64_t TASK = 1024ull * VPL;
+    const uint32_t lane = threadIdx.x & 63, waves_per_wg = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t my = (uint64_t)blockIdx.x * waves_per_wg + wave, tw = (uint64_t)gridDim.x * waves_per_wg;
+    const uint64_t tasks = n / TASK;
+    if (blockIdx.x == 0 && n > tasks * TASK) copy(dst + tasks * TASK, src + tasks * TASK, n - tasks * TASK, threadIdx.x, blockDim.x);
+    if (my >= tasks) return;
+    uint64_t left = (tasks - 1 - my) / tw;               // tasks of this wave after its first
+    const uint32_t lane_off = lane * 16;
+    uint64_t t = my;
+    u32x4 va[VPL], vb[VPL];
+    const uint8_t *s = src + t * TASK;
+    uint8_t *da = dst + t * TASK, *db = nullptr;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) va[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
+    for (;;) {
+        if (left == 0) {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(va[j], (u32x4 *)(da + lane_off) + 64 * j);
+            break;
+        }
+        t += tw; s = src + t * TASK; db = dst + t * TASK;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) vb[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(va[j], (u32x4 *)(da + lane_off) + 64 * j);
+        if (left == 1) {
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(vb[j], (u32x4 *)(db + lane_off) + 64 * j);
+            break;
+        }
+        t += tw; s = src + t * TASK; da = dst + t * TASK;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) va[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(vb[j], (u32x4 *)(db + lane_off) + 64 * j);
+        left -= 2;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
 {
     const uint32_t pe = blockIdx.x / a.wgs_per_pe;

@@ -87,12 +87,29 @@ inline bool strided_span(size_t nelems, ptrdiff_t stride, size_t eb, uint64_t *s
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? SHMEM_OK : SHMEM_ERR_DEVICE; }
 inline int launched() { return hip_rc(hipGetLastError()); }
 
+// A stand-alone put / get: large copies with 16-byte aligned ends stream through the pipelined loop on
+// two workgroups per CU (the shape that measured best for one stream), everything else takes the
+// generic wave copy.
+int launch_copy(uint8_t *dst, const uint8_t *src, size_t n);
+
 // workgroups for a stand-alone copy of n bytes: 16 KiB per workgroup, capped at 8 per CU
 inline int wgs_for_bytes(size_t n)
 {
     size_t w = (n + 16383) / 16384;
     size_t cap = (size_t)std::max(1, H.num_cus) * 8;
     return (int)std::max<size_t>(1, std::min(w, cap));
+}
+
+int launch_copy(uint8_t *dst, const uint8_t *src, size_t n)
+{
+    if (n >= (1u << 20) && (((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
+        const size_t want = (n + 16383) / 16384;
+        const size_t grid = std::min<size_t>(want, (size_t)std::max(1, H.num_cus) * 2);
+        hipLaunchKernelGGL(shmemx::k_copy_stream, dim3((unsigned)grid), dim3(WG_THREADS), 0, H.stream, dst, src, n);
+    } else {
+        hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(n)), dim3(WG_THREADS), 0, H.stream, dst, src, n);
+    }
+    return launched();
 }
 
 void free_insert(uint64_t off, uint64_t len)
@@ -283,9 +300,7 @@ int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, 
     if (nbytes == 0) return SHMEM_OK;
     if (!src_local) return SHMEM_ERR_INVALID_ARG;
     uint8_t *dst = H.heap + (size_t)pe * H.seg + off;
-    hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(nbytes)), dim3(WG_THREADS), 0, H.stream, dst,
-                       (const uint8_t *)src_local, nbytes);
-    return launched();
+    return launch_copy(dst, (const uint8_t *)src_local, nbytes);
 }
 
 int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, int pe)
@@ -297,9 +312,7 @@ int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, 
     if (nbytes == 0) return SHMEM_OK;
     if (!dst_local) return SHMEM_ERR_INVALID_ARG;
     const uint8_t *src = H.heap + (size_t)pe * H.seg + off;
-    hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(nbytes)), dim3(WG_THREADS), 0, H.stream,
-                       (uint8_t *)dst_local, src, nbytes);
-    return launched();
+    return launch_copy((uint8_t *)dst_local, src, nbytes);
 }
 
 static int strided_common(int pe_self, const void *sym, const void *local, ptrdiff_t sym_stride,

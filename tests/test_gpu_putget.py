@@ -95,6 +95,31 @@ def test_single_ops_byte_granular():
     assert np.array_equal(got, w.heaps())
 
 
+def test_single_large_put_get():
+    # stand-alone puts / gets of 1 MiB and more: 16-byte aligned ends take the streaming kernel (whole
+    # 4 KiB tasks plus a generic tail), anything else the generic copy; several sizes around the task and
+    # grid boundaries, neighbouring bytes checked through the whole-heap comparison
+    npes, hb = 2, 40 << 20
+    init = seeded_heaps(npes, hb, 77)
+    w = oracle_world(init)
+    half = hb // 2
+    cases = [(1 << 20, 0, 0), ((1 << 20) + 4096 + 48, 256, 512), ((5 << 20) + 8, 16, 16), ((3 << 20) + 16, 8, 16),
+             ((2 << 20) + 4095, 32, 4096), (16 << 20, 0, 0), ((16 << 20) - 4096 + 16, 4096, 16)]
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        for k, (n, a, b) in enumerate(cases):
+            lo, so = a, half + b
+            if k % 2 == 0:
+                assert w.put(0, so, lo, n, 1) == 0
+                sh.put(0, base + so, sh.ptr(base + lo, 0), n, 1)
+            else:
+                assert w.get(1, lo, so, n, 0) == 0
+                sh.get(1, sh.ptr(base + lo, 1), base + so, n, 0)
+            sh.barrier_all()
+            w.barrier_all()
+            assert np.array_equal(heaps_of(heap, npes), w.heaps()), (k, n, a, b)
+
+
 @pytest.mark.parametrize("eb", [1, 2, 4, 8])
 def test_single_iput_iget(eb):
     npes, hb = 2, 1 << 20
