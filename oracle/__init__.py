@@ -240,3 +240,21 @@ def canonical_parents(row_off, nbr, level, root):
     parent[root] = root
     return parent.astype(np.uint32)
 
+
+def transpose(w: "World", out_sym: int, in_sym: int, n: int, elem_bytes: int):
+    """Distributed transpose of an n x n matrix by one-sided strided gets (a variant the method invites;
+    the paper has no such operation, so this is the ordinary OpenSHMEM idiom): PE p holds rows
+    [p*R, (p+1)*R) of A (R = n / npes, row-major at in_sym) and produces the same rows of B = A^T at
+    out_sym.  Row i of B on PE p = column p*R + i of A: one iget per source PE q fetches
+    A_q[0..R)[p*R + i] (source stride n) into B_p[i][q*R .. (q+1)*R) (unit stride)."""
+    P = w.npes
+    assert n % P == 0
+    R = n // P
+    for p in range(P):
+        for i in range(R):
+            for q in range(P):
+                rc = w.iget(p, out_sym + (i * n + q * R) * elem_bytes, in_sym + (p * R + i) * elem_bytes,
+                            1, n, R, elem_bytes, q)
+                if rc:
+                    raise RuntimeError(f"iget failed: {rc}")
+

@@ -255,3 +255,23 @@ def test_racy_table_is_detected_by_shuffle():
         w.quiet(0)
         seen.add(int(w.heap(2)[64]))
     assert seen == {1, 3}
+
+
+@pytest.mark.parametrize("npes,n,eb", [(1, 5, 4), (2, 6, 8), (4, 12, 4), (3, 9, 2), (4, 64, 4)])
+def test_transpose_by_igets_is_the_matrix_transpose(npes, n, eb):
+    # the iget formulation against numpy's transpose of the assembled matrix
+    R = n // npes
+    blk = (R * n * eb + 255) // 256 * 256
+    w = oracle.World(npes, 2 * blk + 256, oracle.SHUFFLED, 3)
+    dt = {2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    A = (np.arange(n * n, dtype=np.uint64) * 2654435761 % (1 << (8 * eb - 1))).astype(dt).reshape(n, n)
+    for p in range(npes):
+        w.heap(p)[:] = 0xA5
+        w.heap(p)[:R * n * eb] = A[p * R:(p + 1) * R].reshape(-1).view(np.uint8)
+    oracle.transpose(w, blk, 0, n, eb)
+    B = np.concatenate([w.heap(p)[blk:blk + R * n * eb].view(dt).reshape(R, n) for p in range(npes)])
+    assert np.array_equal(B, A.T)
+    for p in range(npes):                                   # nothing outside the output block was touched
+        assert np.array_equal(w.heap(p)[:R * n * eb].view(dt).reshape(R, n), A[p * R:(p + 1) * R])
+        assert (w.heap(p)[blk + R * n * eb:] == 0xA5).all() and (w.heap(p)[R * n * eb:blk] == 0xA5).all()
+
