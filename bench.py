@@ -295,6 +295,27 @@ def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_toke
             "tokens_per_pe": res}
 
 
+def extra_transpose(sh, torch, npes=8, n=16384, wgs=256):
+    """Distributed transpose by one-sided gets (an iget-shaped variant): 16384 x 16384 uint32 over 8 PEs."""
+    dev = torch.device("cuda:0")
+    blk = (n // npes) * n * 4
+    heap = torch.empty(npes * 2 * blk, dtype=torch.uint8, device=dev)
+    heap.view(torch.int64).random_()
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, 2 * blk, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        base = heap.data_ptr()
+        res = {}
+        for w in (64, wgs):
+            ms = _median_ms(lambda: sh.transpose(base + blk, base, n, 4, w), lambda: None, reps=9, warm=2)
+            res[f"wgs{w}"] = {"ms": round(ms, 4), "traffic_GBs": round(2 * n * n * 4 / ms / 1e6, 1),
+                             "hbm_frac": round(2 * n * n * 4 / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        sh.stream_sync()
+    finally:
+        sh.finalize()
+    return {"n": n, "elem_bytes": 4, "npes": npes, "matrix_bytes": n * n * 4, "cells": res}
+
+
 def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=128):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
@@ -442,7 +463,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--wgs-per-pe", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extras", default="cfg1,latency,moe,amo,hash,bfs",
+    ap.add_argument("--extras", default="cfg1,latency,moe,transpose,amo,hash,bfs",
                     help="comma list of the other measurements to run too (cfg1, latency, amo, hash, bfs) or 'none'")
     ap.add_argument("--bfs-scale", type=int, default=24)
     ap.add_argument("--sweep", metavar="FILE", default=None,
@@ -562,6 +583,7 @@ def main():
     run_extra("cfg1", "config1_optable", extra_config1)
     run_extra("latency", "latency", extra_latency)
     run_extra("moe", "moe_low_latency", extra_moe)
+    run_extra("transpose", "transpose_by_gets", extra_transpose)
     run_extra("amo", "config3_amo", extra_amo)
     run_extra("hash", "config4_hash", extra_hash)
     run_extra("bfs", "config5_bfs", extra_bfs, scale=args.bfs_scale)

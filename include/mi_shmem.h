@@ -394,6 +394,19 @@ int shmem_proxy_quiet(shmem_proxy_t proxy, uint64_t *first_bad_index);
 int shmem_proxy_stats(shmem_proxy_t proxy, uint64_t *submitted, uint64_t *executed, uint64_t *rejected);
 int shmem_proxy_destroy(shmem_proxy_t proxy);
 
+/* Distributed transpose by one-sided gets (an iget-shaped variant; not in the
+ * paper).  PE p holds rows [p*R, (p+1)*R), R = n / npes, of an n x n matrix of
+ * elem_bytes-byte elements (4 or 8), row-major at in_sym; the call writes the
+ * same rows of the transposed matrix at out_sym: B_p[i][j] = A_(j / R)[j % R][p*R + i].
+ * The result is what npes * R * npes igets (source stride n, unit destination
+ * stride) would produce; the kernel fetches 64 x 64 tiles with contiguous gets
+ * and transposes them in LDS.  in_sym / out_sym: symmetric, R * n * elem_bytes
+ * bytes each, not overlapping.  n must be a multiple of npes.  Asynchronous on
+ * the library's stream; complete after shmem_quiet(-1) / shmem_barrier_all /
+ * shmem_stream_sync.
+ * Errors: NOT_INIT, INVALID_ARG, ALIGN, OUT_OF_RANGE, DEVICE. */
+int shmem_transpose(void *out_sym, const void *in_sym, size_t n, size_t elem_bytes, int wgs_per_pe);
+
 #ifdef __cplusplus
 }
 #endif

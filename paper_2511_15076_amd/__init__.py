@@ -88,6 +88,7 @@ _SIG = {
     "shmem_proxy_quiet": (_i, [_vp, C.POINTER(C.c_uint64)]),
     "shmem_proxy_stats": (_i, [_vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "shmem_proxy_destroy": (_i, [_vp]),
+    "shmem_transpose": (_i, [_vp, _vp, _sz, _sz, _i]),
 }
 for _name, (_res, _args) in _SIG.items():
     _fn = getattr(_L, _name)
@@ -339,3 +340,8 @@ def proxy_stats(proxy):
 
 def proxy_destroy(proxy):
     return _check(_L.shmem_proxy_destroy(proxy), "shmem_proxy_destroy")
+
+
+def transpose(out_sym, in_sym, n, elem_bytes, wgs_per_pe):
+    return _check(_L.shmem_transpose(_addr(out_sym), _addr(in_sym), n, elem_bytes, wgs_per_pe), "shmem_transpose")
+

@@ -1,0 +1,60 @@
+// Distributed matrix transpose by one-sided gets (an iget-shaped variant of the
+// path; the paper has no such operation).  PE p holds rows [p*R, (p+1)*R) of an
+// n x n matrix A and produces the same rows of B = A^T.  Row i of B on PE p is
+// column p*R + i of A, spread over every PE: as plain igets that is one element
+// per 4*n-byte pitch -- a full memory sector per element.  Here a workgroup
+// moves a 64 x 64 tile through LDS instead: each tile row is a contiguous get of
+// 64 elements from the row's owner, and the transposed tile leaves as 64
+// contiguous local stores, so both sides move whole lines.
+#pragma once
+#include "shmemx.hpp"
+
+namespace shmemx {
+
+constexpr uint32_t TR_TILE = 64;
+
+struct TransposeArgs {
+    uint64_t in_off, out_off;   // symmetric offsets of A's and B's row blocks
+    uint64_t n, rows;           // matrix order; rows per PE (n / npes)
+    uint32_t wgs_per_pe;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose(Ctx c, TransposeArgs a)
+{
+    __shared__ T tile[TR_TILE][TR_TILE + 1];       // +1: conflict-free column reads
+    const uint32_t pe = blockIdx.x / a.wgs_per_pe, wg = blockIdx.x % a.wgs_per_pe;
+    constexpr uint32_t WAVES = 4, PER = TR_TILE / WAVES;    // launched with 256 threads: 16 tile rows per thread
+    const uint32_t tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TR_TILE - 1) / TR_TILE;
+    T *out = (T *)ptr(c, a.out_off, pe);
+    for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
+        const uint64_t i0 = (t / tiles_j) * TR_TILE;        // first local output row of the tile
+        const uint64_t j0 = (t % tiles_j) * TR_TILE;        // first output column = first source row (global)
+        // tile row r = source row j0 + r, columns p*R + i0 .. + 64: a contiguous get from the row's owner;
+        // a thread's sixteen gets are all requested before the first one is used
+        T v[PER];
+#pragma unroll
+        for (uint32_t k = 0; k < PER; ++k) {
+            const uint64_t j = j0 + ty + k * WAVES, col = i0 + tx;
+            v[k] = 0;
+            if (j < a.n && col < a.rows) {
+                const uint32_t q = (uint32_t)(j / a.rows);
+                const T *src = (const T *)ptr(c, a.in_off, q) + (j - (uint64_t)q * a.rows) * a.n + (uint64_t)pe * a.rows + col;
+                v[k] = __builtin_nontemporal_load(src);
+            }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < PER; ++k) tile[ty + k * WAVES][tx] = v[k];
+        __syncthreads();
+#pragma unroll
+        for (uint32_t k = 0; k < PER; ++k) {
+            const uint32_t r = ty + k * WAVES;
+            const uint64_t i = i0 + r, j = j0 + tx;
+            if (i < a.rows && j < a.n) __builtin_nontemporal_store(tile[tx][r], out + i * a.n + j);
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace shmemx

@@ -23,6 +23,7 @@
 #include "kernels_sync.hpp"
 #include "kernels_moe.hpp"
 #include "proxy.hpp"
+#include "kernels_transpose.hpp"
 
 namespace {
 
@@ -1062,6 +1063,28 @@ int shmem_proxy_destroy(shmem_proxy_t p)
     (void)hipStreamSynchronize(H.stream);            // no producer is still writing into the ring
     proxy_stop_and_free(p);
     return SHMEM_OK;
+}
+
+// ---------------------------------------------------------------------------
+int shmem_transpose(void *out_sym, const void *in_sym, size_t n, size_t elem_bytes, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (wgs_per_pe < 1 || (elem_bytes != 4 && elem_bytes != 8)) return SHMEM_ERR_INVALID_ARG;
+    if (n % (size_t)H.npes) return SHMEM_ERR_INVALID_ARG;
+    if (((uintptr_t)out_sym | (uintptr_t)in_sym) % elem_bytes) return SHMEM_ERR_ALIGN;
+    const size_t rows = n / (size_t)H.npes;
+    unsigned __int128 span = (unsigned __int128)rows * n * elem_bytes;
+    if (span > H.seg) return SHMEM_ERR_OUT_OF_RANGE;
+    uint64_t ooff, ioff;
+    if (int rc = sym_off(out_sym, (uint64_t)span, &ooff)) return rc;
+    if (int rc = sym_off(in_sym, (uint64_t)span, &ioff)) return rc;
+    if (span && ooff < ioff + (uint64_t)span && ioff < ooff + (uint64_t)span) return SHMEM_ERR_INVALID_ARG;   // not in place
+    if (n == 0) return SHMEM_OK;
+    shmemx::TransposeArgs a{ioff, ooff, (uint64_t)n, (uint64_t)rows, (uint32_t)wgs_per_pe};
+    dim3 grid((unsigned)(H.npes * wgs_per_pe)), block(WG_THREADS);
+    if (elem_bytes == 4) hipLaunchKernelGGL(shmemx::k_transpose<uint32_t>, grid, block, 0, H.stream, ctx(), a);
+    else hipLaunchKernelGGL(shmemx::k_transpose<uint64_t>, grid, block, 0, H.stream, ctx(), a);
+    return launched();
 }
 
 }  // extern "C"
