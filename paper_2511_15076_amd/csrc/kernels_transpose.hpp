@@ -57,4 +57,54 @@ __global__ __launch_bounds__(256) void k_transpose(Ctx c, TransposeArgs a)
     }
 }
 
+// The same with 16-byte gets and 16-byte stores (four uint32 or two uint64 per lane): a tile row is then
+// 16 or 32 lanes wide, so one wave instruction covers four or two tile rows.  Needs rows, i.e. n / npes,
+// to be a multiple of the vector length (every vector then lies inside one row block and is 16-byte
+// aligned); the host falls back to the element-wise kernel otherwise.
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
+{
+    constexpr uint32_t E = 16 / sizeof(T);                 // elements per vector
+    constexpr uint32_t LANES = TR_TILE / E;                // lanes per tile row
+    constexpr uint32_t ROWS = 256 / LANES;                 // tile rows per step of the workgroup
+    constexpr uint32_t STEPS = TR_TILE / ROWS;
+    typedef T vec __attribute__((ext_vector_type(E)));
+    __shared__ T tile[TR_TILE][TR_TILE + 1];
+    const uint32_t pe = blockIdx.x / a.wgs_per_pe, wg = blockIdx.x % a.wgs_per_pe;
+    const uint32_t vx = threadIdx.x % LANES, ry = threadIdx.x / LANES;
+    const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TR_TILE - 1) / TR_TILE;
+    T *out = (T *)ptr(c, a.out_off, pe);
+    for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
+        const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TR_TILE;
+        vec v[STEPS];
+#pragma unroll
+        for (uint32_t k = 0; k < STEPS; ++k) {
+            const uint64_t j = j0 + ry + k * ROWS, col = i0 + vx * E;      // source row; first local column of the vector
+            v[k] = vec(0);
+            if (j < a.n && col < a.rows) {                                 // rows % E == 0: a vector is in or out as a whole
+                const uint32_t q = (uint32_t)(j / a.rows);
+                const T *src = (const T *)ptr(c, a.in_off, q) + (j - (uint64_t)q * a.rows) * a.n + (uint64_t)pe * a.rows + col;
+                v[k] = __builtin_nontemporal_load((const vec *)src);
+            }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < STEPS; ++k)
+#pragma unroll
+            for (uint32_t e = 0; e < E; ++e) tile[ry + k * ROWS][vx * E + e] = v[k][e];
+        __syncthreads();
+#pragma unroll
+        for (uint32_t k = 0; k < STEPS; ++k) {
+            const uint32_t r = ry + k * ROWS;                              // tile column = local output row
+            const uint64_t i = i0 + r, j = j0 + vx * E;
+            if (i < a.rows && j < a.n) {                                   // n % E == 0 as well
+                vec o;
+#pragma unroll
+                for (uint32_t e = 0; e < E; ++e) o[e] = tile[vx * E + e][r];
+                __builtin_nontemporal_store(o, (vec *)(out + i * a.n + j));
+            }
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace shmemx
