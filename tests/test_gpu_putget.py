@@ -43,6 +43,27 @@ def test_config1_full_table(wgs):
     assert np.array_equal(got, w.heaps())
 
 
+@pytest.mark.parametrize("batch,nops,wgs", [(1, 70, 2), (7, 203, 1), (64, 640, 3), (65, 650, 2), (129, 1000, 4),
+                                            (1000, 1000, 2), (0, 300, 2)])
+def test_table_window_sizes(batch, nops, wgs):
+    # windows shorter than, equal to and longer than the 64 descriptors a wave reads at a time, a last
+    # window that is not full, and a single window (quiet_every = 0): the executor prefetches the next
+    # batch of descriptors across window ends, so every boundary shape is exercised
+    npes, hb = 4, 1 << 18
+    gen_batch = batch if batch else nops
+    ops = workgen.cfg1_op_table(seed=workgen.BASE_SEED + 7 + batch, npes=npes, heap_bytes=hb, nops=nops,
+                                batch=gen_batch, max_log2=10)
+    init = seeded_heaps(npes, hb, 31 + batch)
+    w = oracle_world(init)
+    assert w.op_batch(ops, batch) == 0
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.op_batch(to_dev(ops), len(ops), batch, wgs)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+
+
 def test_table_with_strided_and_large_ops_and_device_fault():
     npes, hb = 3, 1 << 20
     init = seeded_heaps(npes, hb, 555)
