@@ -89,6 +89,30 @@ def test_table_with_strided_and_large_ops_and_device_fault():
     assert np.array_equal(got, w.heaps())
 
 
+@pytest.mark.parametrize("wgs", [1, 5, 16])
+def test_table_large_ops_take_the_streaming_copy(wgs):
+    # ops above 64 KiB are done by the whole team; with 16-byte aligned ends through the pipelined loop
+    # (whole 4 KiB tasks + a tail), otherwise through the generic copy -- sizes on both sides of each rule
+    npes, hb = 4, 8 << 20
+    init = seeded_heaps(npes, hb, 808)
+    M = 1 << 20
+    ops = np.zeros(6, dtype=workgen.OP_DESC)
+    ops[0] = (workgen.OP_PUT, 0, 1, 1, 0, 4 * M, 65536 + 16, 1, 1, 0)
+    ops[1] = (workgen.OP_GET, 1, 2, 1, 16, 5 * M + 256, M + 4096 + 48, 1, 1, 0)
+    ops[2] = (workgen.OP_PUT, 2, 3, 1, 8, 6 * M + 8, 300000, 1, 1, 0)          # 8-byte aligned only: generic copy
+    ops[3] = (workgen.OP_GET, 3, 0, 1, 2 * M, 7 * M, 4096 * 37, 1, 1, 0)       # whole tasks, no tail
+    ops[4] = (workgen.OP_PUT, 1, 1, 1, 2 * M, 6 * M, 70000, 1, 1, 0)           # to itself
+    ops[5] = (workgen.OP_PUT, 3, 2, 1, 4 * M, 2 * M + 4096, 4096 * 16 + 4080, 1, 1, 0)
+    w = oracle_world(init)
+    assert w.op_batch(ops, 0) == 0
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.op_batch(to_dev(ops), len(ops), 0, wgs)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+
+
 def test_single_ops_byte_granular():
     npes, hb = 3, 1 << 18
     init = seeded_heaps(npes, hb, 42)
