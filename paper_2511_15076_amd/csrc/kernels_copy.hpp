@@ -27,51 +27,11 @@ __global__ __launch_bounds__(256) void k_strided(uint8_t *__restrict__ dst, cons
 // small ops go round-robin to single waves (wave-cooperative put / get), ops
 // above BIG_OP bytes are done by all waves of the team together.  At a window
 // end every wave performs quiet and the teams meet in the world barrier.
-// A large contiguous copy with 16-byte aligned ends by `waves` cooperating waves (this one is number
-// `my`): the leading multiple of 4 KiB streams through a software-pipelined loop over two register sets
-// (wave-tasks of 4 KiB dealt round robin, a wave's next task requested before its current one is stored);
-// wave 0 moves the rest through the generic copy.
-__device__ __forceinline__ void copy_stream(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n,
-                                            uint64_t my, uint64_t waves, uint32_t lane)
-{
-    constexpr int VPL = 4;
-    constexpr uint64_t TASK = 1024ull * VPL;
-    const uint64_t tasks = n / TASK;
-    if (my == 0 && n > tasks * TASK) copy(dst + tasks * TASK, src + tasks * TASK, n - tasks * TASK, lane, 64);
-    if (my >= tasks) return;
-    uint64_t left = (tasks - 1 - my) / waves;            // tasks of this wave after its first
-    const uint32_t lane_off = lane * 16;
-    uint64_t t = my;
-    u32x4 va[VPL], vb[VPL];
-    const uint8_t *s = src + t * TASK;
-    uint8_t *da = dst + t * TASK, *db = nullptr;
-#pragma unroll
-    for (int j = 0; j < VPL; ++j) va[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
-    for (;;) {
-        if (left == 0) {
-#pragma unroll
-            for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(va[j], (u32x4 *)(da + lane_off) + 64 * j);
-            break;
-        }
-        t += waves; s = src + t * TASK; db = dst + t * TASK;
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) vb[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(va[j], (u32x4 *)(da + lane_off) + 64 * j);
-        if (left == 1) {
-#pragma unroll
-            for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(vb[j], (u32x4 *)(db + lane_off) + 64 * j);
-            break;
-        }
-        t += waves; s = src + t * TASK; da = dst + t * TASK;
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) va[j] = __builtin_nontemporal_load((const u32x4 *)(s + lane_off) + 64 * j);
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(vb[j], (u32x4 *)(db + lane_off) + 64 * j);
-        left -= 2;
-    }
-}
-
+// STREAM selects how a large aligned put / get is moved: through the pipelined
+// streaming copy (teams of many workgroups, where it is worth 6 % of bandwidth)
+// or through the generic copy, which keeps the kernel a third of the size -- the
+// variant for small teams, whose tables of small ops are latency-bound.
+// ---------------------------------------------------------------------------
 constexpr uint64_t BIG_OP = 64 * 1024;
 
 __device__ __forceinline__ bool desc_valid(const Ctx &c, const shmem_op_desc &d)
@@ -108,6 +68,7 @@ __device__ __forceinline__ void desc_exec(const Ctx &c, const shmem_op_desc &d, 
     }
 }
 
+template <bool STREAM>
 __global__ __launch_bounds__(256, 4) void k_op_batch(Ctx c, const shmem_op_desc *__restrict__ ops, size_t n,
                                                   size_t quiet_every, int wgs_per_pe)
 {
@@ -157,7 +118,7 @@ __global__ __launch_bounds__(256, 4) void k_op_batch(Ctx c, const shmem_op_desc 
                 const uint64_t bytes = (u.kind <= SHMEM_OP_GET) ? u.count : u.count * u.elem_bytes;
                 if (bytes > BIG_OP) {
                     uint8_t *local = ptr(c, u.local_off, pe), *remote = ptr(c, u.sym_off, u.pe);
-                    if (u.kind <= SHMEM_OP_GET && (((uintptr_t)local | (uintptr_t)remote) & 15) == 0) {
+                    if (STREAM && u.kind <= SHMEM_OP_GET && (((uintptr_t)local | (uintptr_t)remote) & 15) == 0) {
                         if (u.kind == SHMEM_OP_PUT) copy_stream(remote, local, u.count, my_wave, team_waves, lane);
                         else copy_stream(local, remote, u.count, my_wave, team_waves, lane);
                     } else {

@@ -412,11 +412,13 @@ int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_pe
     if (wgs_per_pe < 1 || (n && !dev_ops) || (uintptr_t)dev_ops % 8) return SHMEM_ERR_INVALID_ARG;
     if (n == 0) return SHMEM_OK;
     long grid = (long)H.npes * wgs_per_pe;
-    if (grid > max_resident_wgs(shmemx::k_op_batch)) return SHMEM_ERR_INVALID_ARG;
+    // teams of 16 workgroups and more are bandwidth configurations: their large ops stream
+    auto kernel = wgs_per_pe >= 16 ? shmemx::k_op_batch<true> : shmemx::k_op_batch<false>;
+    if (grid > max_resident_wgs(kernel)) return SHMEM_ERR_INVALID_ARG;
     shmemx::Ctx c = ctx();
     const shmem_op_desc *ops = (const shmem_op_desc *)dev_ops;
     void *args[] = {&c, &ops, &n, &quiet_every, &wgs_per_pe};
-    return launch_resident((const void *)shmemx::k_op_batch, dim3((unsigned)grid), dim3(WG_THREADS), args);
+    return launch_resident((const void *)kernel, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,

@@ -89,10 +89,11 @@ def test_table_with_strided_and_large_ops_and_device_fault():
     assert np.array_equal(got, w.heaps())
 
 
-@pytest.mark.parametrize("wgs", [1, 5, 16])
+@pytest.mark.parametrize("wgs", [1, 5, 16, 33])
 def test_table_large_ops_take_the_streaming_copy(wgs):
-    # ops above 64 KiB are done by the whole team; with 16-byte aligned ends through the pipelined loop
-    # (whole 4 KiB tasks + a tail), otherwise through the generic copy -- sizes on both sides of each rule
+    # ops above 64 KiB are done by the whole team; in teams of 16 workgroups and more those with 16-byte
+    # aligned ends go through the pipelined loop (whole 4 KiB tasks + a tail), everything else through
+    # the generic copy -- team sizes and op sizes on both sides of each rule
     npes, hb = 4, 8 << 20
     init = seeded_heaps(npes, hb, 808)
     M = 1 << 20

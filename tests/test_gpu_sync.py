@@ -29,7 +29,7 @@ def gin_offsets(hb_payload, nsig, nctr):
 
 @pytest.mark.parametrize("wgs,rounds", [(1, 1), (3, 1), (2, 25)])
 def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
-    for n, ds in golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000)]:
+    for n, ds in golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000), (4, (1 << 20) + 4096 + 32)]:
         span = n * ds
         send, recv = 0, (span + 255) // 256 * 256
         payload = 2 * recv                                    # bytes the test reserves with shmem_malloc
