@@ -28,7 +28,8 @@
  * heap exhausted) are returned at once and enqueue nothing.  Errors only the
  * device can see (a bad descriptor inside a device-resident table) set a
  * device error word, skip that op and surface at shmem_stream_sync().
- * No exceptions, no abort(), nothing printed.
+ * No exceptions, no abort(), nothing printed.  Every wgs_per_pe argument must
+ * be at least 1 and npes * wgs_per_pe at most 2^22 (INVALID_ARG otherwise).
  *
  * The library keeps ONE context per process (init ... finalize).  The allocator
  * calls take a lock; everything else expects one calling thread at a time.

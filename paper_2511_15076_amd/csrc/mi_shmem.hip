@@ -85,6 +85,10 @@ inline bool strided_span(size_t nelems, ptrdiff_t stride, size_t eb, uint64_t *s
     return true;
 }
 
+// npes * wgs_per_pe workgroups must be a sane grid (the product is formed in 64 bits)
+constexpr uint64_t MAX_GRID = 1u << 22;
+inline bool grid_fits(int wgs_per_pe) { return wgs_per_pe >= 1 && (uint64_t)H.npes * (uint64_t)wgs_per_pe <= MAX_GRID; }
+
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? SHMEM_OK : SHMEM_ERR_DEVICE; }
 inline int launched() { return hip_rc(hipGetLastError()); }
 
@@ -135,11 +139,6 @@ int max_resident_wgs(K kernel, int threads = WG_THREADS)
     return per_cu * H.num_cus;
 }
 
-// Launch of a kernel whose workgroups wait for one another (in-kernel barriers, signals): the callers
-// have checked that the whole grid fits the device at once (max_resident_wgs), the stream runs one
-// kernel at a time, and every in-kernel wait is bounded.  An ordinary launch is used by default: a
-// cooperative launch gives the same residency as a formal guarantee but measured about 16 us more per
-// launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
 void proxy_stop_and_free(struct shmem_proxy *p);   // defined with the proxy executor below
 
 // End of a BFS level: one launch builds the next frontier's bitmap and degree sum (direction-optimising
@@ -168,6 +167,11 @@ int bfs_level_end(const shmemx::BfsState &s, uint32_t next, bool do_front, bool 
     return SHMEM_OK;
 }
 
+// Launch of a kernel whose workgroups wait for one another (in-kernel barriers, signals): the callers
+// have checked that the whole grid fits the device at once (max_resident_wgs), the stream runs one
+// kernel at a time, and every in-kernel wait is bounded.  An ordinary launch is used by default: a
+// cooperative launch gives the same residency as a formal guarantee but measured about 16 us more per
+// launch here, which is most of a small dispatch.  MI_SHMEM_COOPERATIVE_LAUNCH=1 selects it.
 int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
 {
     if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
@@ -409,7 +413,7 @@ int shmem_stream_sync(uint64_t *first_bad_index)
 int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_per_pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (wgs_per_pe < 1 || (n && !dev_ops) || (uintptr_t)dev_ops % 8) return SHMEM_ERR_INVALID_ARG;
+    if (!grid_fits(wgs_per_pe) || (n && !dev_ops) || (uintptr_t)dev_ops % 8) return SHMEM_ERR_INVALID_ARG;
     if (n == 0) return SHMEM_OK;
     long grid = (long)H.npes * wgs_per_pe;
     // teams of 16 workgroups and more are bandwidth configurations: their large ops stream
@@ -426,7 +430,7 @@ int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, 
                      size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (kind < SHMEM_OP_PUT || kind > SHMEM_OP_IGET || wgs_per_pe < 1 || ops_per_pe < 0 || nslots < 1) return SHMEM_ERR_INVALID_ARG;
+    if (kind < SHMEM_OP_PUT || kind > SHMEM_OP_IGET || !grid_fits(wgs_per_pe) || ops_per_pe < 0 || nslots < 1) return SHMEM_ERR_INVALID_ARG;
     const bool is_strided = kind >= SHMEM_OP_IPUT;
     uint64_t rspan = count, lspan = count;
     if (is_strided) {
@@ -465,7 +469,7 @@ int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe
                     int wgs_per_pe, int aggregate)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (kind < SHMEM_AMO_FETCH_ADD || kind > SHMEM_AMO_MIN_CAS_LOOP || wgs_per_pe < 1 || T == 0) return SHMEM_ERR_INVALID_ARG;
+    if (kind < SHMEM_AMO_FETCH_ADD || kind > SHMEM_AMO_MIN_CAS_LOOP || !grid_fits(wgs_per_pe) || T == 0) return SHMEM_ERR_INVALID_ARG;
     if (T > H.seg / 8) return SHMEM_ERR_OUT_OF_RANGE;
     if ((uintptr_t)ctr_sym % 8) return SHMEM_ERR_ALIGN;
     uint64_t off;
@@ -486,7 +490,7 @@ int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe
 static int hash_common(const uint64_t *table_sym, size_t slots, const uint64_t *keys, size_t n, int wgs, uint64_t *off)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (slots == 0 || wgs < 1 || slots > UINT32_MAX) return SHMEM_ERR_INVALID_ARG;
+    if (slots == 0 || !grid_fits(wgs) || slots > UINT32_MAX) return SHMEM_ERR_INVALID_ARG;
     if (slots > H.seg / 8) return SHMEM_ERR_OUT_OF_RANGE;
     if ((uintptr_t)table_sym % 8) return SHMEM_ERR_ALIGN;
     if (int rc = sym_off(table_sym, (uint64_t)slots * 8, off)) return rc;
@@ -526,7 +530,7 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
                      void **graph_out)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!graph_out || nverts == 0 || !dev_row_off || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if (!graph_out || nverts == 0 || !dev_row_off || !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
     BfsGraph *g = new (std::nothrow) BfsGraph();
     if (!g) return SHMEM_ERR_NOMEM;
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
@@ -564,10 +568,20 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
         return SHMEM_ERR_DEVICE;
     }
     g->nnz = H.pinned[32];
+    if (g->nnz && !dev_nbr) {
+        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
+        delete g;
+        return SHMEM_ERR_INVALID_ARG;
+    }
     s.wgs_per_pe = (uint32_t)wgs_per_pe;     // before any launch that takes the state
     g->wgs_per_pe = wgs_per_pe;
     hipLaunchKernelGGL(shmemx::k_bfs_mark_linked, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
                        ctx(), g->st);
+    if (int rc = launched()) {
+        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
+        delete g;
+        return rc;
+    }
     *graph_out = g;
     return SHMEM_OK;
 }
@@ -716,7 +730,7 @@ int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes,
                         int counter_id, int rounds, int wgs_per_pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!gin || rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if (!gin || rounds < 0 || !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
     GinObj *g = (GinObj *)gin;
     if (signal_id < 0 || (uint32_t)signal_id >= g->st.nsignals || counter_id < 0 ||
         (uint32_t)counter_id >= g->st.ncounters) return SHMEM_ERR_INVALID_ARG;
@@ -760,7 +774,7 @@ int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int i
 int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (rounds < 0 || wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+    if (rounds < 0 || !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
     if ((uintptr_t)slots_sym % 8 || (uintptr_t)dev_errors % 8) return SHMEM_ERR_ALIGN;
     uint64_t off;
     if (int rc = sym_off(slots_sym, 8ull * (uint64_t)H.npes, &off)) return rc;
@@ -835,7 +849,7 @@ int shmem_moe_dispatch(shmem_moe_t m, const void *dev_x, const int32_t *dev_topk
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (!m || !dev_x || !dev_topk || !dev_ntok || !dev_recv_x || !dev_recv_info || !dev_recv_range || !dev_recv_count ||
-        wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+        !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
     if (((uintptr_t)dev_x | (uintptr_t)dev_recv_x | (uintptr_t)dev_recv_info | (uintptr_t)dev_topk) % 16) return SHMEM_ERR_ALIGN;
     long grid = (long)H.npes * wgs_per_pe;
     if (grid > max_resident_wgs(shmemx::k_moe_dispatch, shmemx::MOE_THREADS)) return SHMEM_ERR_INVALID_ARG;
@@ -853,7 +867,7 @@ int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (!m || !dev_expert_out || !dev_recv_info || !dev_recv_range || !dev_topk || !dev_ntok || !dev_combined ||
-        wgs_per_pe < 1) return SHMEM_ERR_INVALID_ARG;
+        !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
     if (((uintptr_t)dev_expert_out | (uintptr_t)dev_combined | (uintptr_t)dev_recv_info) % 16) return SHMEM_ERR_ALIGN;
     long grid = (long)H.npes * wgs_per_pe;
     if (grid > max_resident_wgs(shmemx::k_moe_combine, shmemx::MOE_THREADS)) return SHMEM_ERR_INVALID_ARG;
@@ -1007,7 +1021,10 @@ int shmem_proxy_create(size_t queue_entries, shmem_proxy_t *proxy_out)
     p->q.mask = queue_entries - 1;
     p->head = (uint64_t *)head;
     p->worker = std::thread(proxy_main, p);
-    H.proxies.push_back(p);
+    {
+        std::lock_guard<std::mutex> g(H.mu);
+        H.proxies.push_back(p);
+    }
     *proxy_out = p;
     return SHMEM_OK;
 }
@@ -1061,8 +1078,9 @@ int shmem_proxy_stats(shmem_proxy_t p, uint64_t *submitted, uint64_t *executed, 
 int shmem_proxy_destroy(shmem_proxy_t p)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!p || std::find(H.proxies.begin(), H.proxies.end(), p) == H.proxies.end()) return SHMEM_ERR_INVALID_ARG;
     (void)hipStreamSynchronize(H.stream);            // no producer is still writing into the ring
+    std::lock_guard<std::mutex> g(H.mu);
+    if (!p || std::find(H.proxies.begin(), H.proxies.end(), p) == H.proxies.end()) return SHMEM_ERR_INVALID_ARG;
     proxy_stop_and_free(p);
     return SHMEM_OK;
 }
@@ -1071,7 +1089,7 @@ int shmem_proxy_destroy(shmem_proxy_t p)
 int shmem_transpose(void *out_sym, const void *in_sym, size_t n, size_t elem_bytes, int wgs_per_pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (wgs_per_pe < 1 || (elem_bytes != 4 && elem_bytes != 8)) return SHMEM_ERR_INVALID_ARG;
+    if (!grid_fits(wgs_per_pe) || (elem_bytes != 4 && elem_bytes != 8)) return SHMEM_ERR_INVALID_ARG;
     if (n % (size_t)H.npes) return SHMEM_ERR_INVALID_ARG;
     if (((uintptr_t)out_sym | (uintptr_t)in_sym) % elem_bytes) return SHMEM_ERR_ALIGN;
     const size_t rows = n / (size_t)H.npes;

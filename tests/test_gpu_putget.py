@@ -289,6 +289,8 @@ def test_allocator_matches_oracle_and_host_errors():
             (lambda: sh.op_batch(base, 1, 1, 0), sh.ERR_INVALID_ARG),
             (lambda: sh.op_batch(base, 1, 1, 100000), sh.ERR_INVALID_ARG),   # cannot be co-resident
             (lambda: sh.copy_sweep(0, base, base, 64, 1, 1, 1, 256, 256, 1, 1, 1), sh.ERR_INVALID_ARG),
+            # a team size whose grid would not fit 32 bits (or any sane launch) is refused, not truncated
+            (lambda: sh.copy_sweep(0, base + 4096, base, 64, 1, 1, 1, 256, 256, 1, 1, 2**31 - 1), sh.ERR_INVALID_ARG),
             (lambda: sh.init(2, hb, heap, heap), sh.ERR_ALREADY_INIT),
         ]:
             with pytest.raises(sh.ShmemError) as e:
