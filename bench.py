@@ -316,7 +316,7 @@ def extra_transpose(sh, torch, npes=8, n=16384, wgs=256):
     return {"n": n, "elem_bytes": 4, "npes": npes, "matrix_bytes": n * n * 4, "cells": res}
 
 
-def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=128):
+def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=256):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
     import workgen

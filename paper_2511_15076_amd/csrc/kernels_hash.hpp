@@ -126,4 +126,75 @@ __global__ __launch_bounds__(256) void k_hash_lookup(Ctx c, HashArgs g)
     }
 }
 
+// Lookup for tables whose slot count per PE is a multiple of 8: a probe sequence is read a whole
+// 64-byte sector (8 slots) at a time, the sector that holds the current slot.  The table is far larger
+// than the caches and tens of thousands of probe sequences are in flight per die, so a second 8-byte
+// probe a moment later finds its sector evicted and fetches it from memory again (measured: two sector
+// fetches per key at load 0.5, and a lookup rate that falls with the mean chain length).  One 64-byte
+// read brings everything a sector can contribute; the walk goes on in the next sector only when the
+// chain runs off the end (the table keeps plain linear probing: what is found is unchanged).  Read by
+// one lane as four 16-byte loads this was slower than the 8-byte probes (41 against 50 G lookups/s on
+// single-probe chains): four instructions and four cache look-ups per key.
+constexpr int HASH_SECTOR = 8;   // slots per 64-byte sector
+
+// Four neighbouring lanes (a quad) look one key up: each reads 16 bytes of the sector, so a wave
+// instruction requests 16 whole sectors, one coalesced 64-byte access per key.  Every lane classifies
+// its two slots (2 bits each: 1 = the key, 2 = empty, 0 = another key or before the start), the quad
+// ORs the codes with two DPP quad permutes and the lowest non-zero field decides.
+__device__ __forceinline__ uint32_t quad_or(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false);   // lanes ^ 1
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false);   // lanes ^ 2
+    return v;
+}
+
+template <int KIF>
+__global__ __launch_bounds__(256) void k_hash_lookup_sectors(Ctx c, HashArgs g)
+{
+    const uint32_t pe_self = blockIdx.x / g.wgs_per_pe, wg = blockIdx.x % g.wgs_per_pe;
+    const uint64_t begin = (uint64_t)pe_self * g.per_pe;
+    const uint64_t end = begin + g.per_pe < g.n ? begin + g.per_pe : g.n;
+    const uint32_t q4 = threadIdx.x & 3, quads = blockDim.x >> 2;
+    const uint64_t stride = (uint64_t)g.wgs_per_pe * quads;
+    for (uint64_t i0 = begin + (uint64_t)wg * quads + (threadIdx.x >> 2); i0 < end; i0 += stride * KIF) {
+        uint64_t key[KIF];
+        const u32x4 *table[KIF];           // the owner's table as 16-byte vectors, offset to this lane's quarter
+        uint32_t slot[KIF];
+        u32x4 w[KIF];
+        bool live[KIF];
+#pragma unroll
+        for (int k = 0; k < KIF; ++k) {
+            const uint64_t i = i0 + k * stride;
+            live[k] = i < end;
+            key[k] = live[k] ? __builtin_nontemporal_load(g.keys + i) : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < KIF; ++k) {
+            uint32_t owner;
+            hash_place(c, g.slots, key[k], &owner, &slot[k]);
+            table[k] = (const u32x4 *)ptr(c, g.table_off, owner) + q4;
+            w[k] = live[k] ? table[k][(size_t)(slot[k] / HASH_SECTOR) * 4] : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int k = 0; k < KIF; ++k) {
+            if (!live[k]) continue;                           // the same for all four lanes of a quad
+            const uint32_t klo = (uint32_t)key[k], khi = (uint32_t)(key[k] >> 32);
+            uint32_t sector = slot[k] / HASH_SECTOR, start = slot[k] % HASH_SECTOR;
+            uint32_t found = 0;
+            for (uint32_t probed = 0; probed < g.slots;) {
+                uint32_t code = 0;
+                if (2 * q4 >= start) code |= ((w[k].x == klo && w[k].y == khi) ? 1u : (w[k].x | w[k].y) == 0 ? 2u : 0u) << (4 * q4);
+                if (2 * q4 + 1 >= start) code |= ((w[k].z == klo && w[k].w == khi) ? 1u : (w[k].z | w[k].w) == 0 ? 2u : 0u) << (4 * q4 + 2);
+                code = quad_or(code);
+                if (code) { found = (code >> (__builtin_ctz(code) & ~1)) & 1; break; }
+                probed += HASH_SECTOR - start;
+                start = 0;
+                sector = sector + 1 == g.slots / HASH_SECTOR ? 0 : sector + 1;
+                w[k] = table[k][(size_t)sector * 4];
+            }
+            if (q4 == 0) g.out[i0 + k * stride] = (uint8_t)found;
+        }
+    }
+}
+
 }  // namespace shmemx

@@ -29,6 +29,7 @@ namespace {
 
 constexpr size_t GRAN = 256;       // allocator granularity / minimum alignment
 constexpr int WG_THREADS = 256;    // 4 wavefronts per workgroup
+constexpr int HASH_LOOKUP_KIF = 4;  // keys in flight per lane quad in the sector-wide lookup
 constexpr uint32_t BFS_ALPHA = 30, BFS_BETA = 24;  // default direction thresholds (measured best on R-MAT scale 24)
 
 struct Block { uint64_t off, len; };
@@ -520,8 +521,11 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
     if (!dev_found) return SHMEM_ERR_INVALID_ARG;
     shmemx::HashArgs a{off, (uint32_t)slots_per_pe, dev_keys, n, (n + (size_t)H.npes - 1) / (size_t)H.npes,
                        dev_found, (uint32_t)wgs_per_pe};
-    hipLaunchKernelGGL(shmemx::k_hash_lookup, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
-                       ctx(), a);
+    const dim3 grid((unsigned)(H.npes * wgs_per_pe));
+    if (slots_per_pe % shmemx::HASH_SECTOR == 0 && off % 64 == 0)     // whole, aligned 64-byte sectors
+        hipLaunchKernelGGL(shmemx::k_hash_lookup_sectors<HASH_LOOKUP_KIF>, grid, dim3(WG_THREADS), 0, H.stream, ctx(), a);
+    else
+        hipLaunchKernelGGL(shmemx::k_hash_lookup, grid, dim3(WG_THREADS), 0, H.stream, ctx(), a);
     return launched();
 }
 

@@ -157,7 +157,10 @@ def test_single_amos():
 
 
 # ------------------------------------------------------------------ hash
-@pytest.mark.parametrize("npes,slots,n", [(16, 1 << 12, 30000), (5, 3001, 7000), (16, 64, 1200)])
+# slot counts that are multiples of 8 take the sector-wide lookup, the others the slot-by-slot one; the
+# shapes cover long chains over many sectors (load 0.8), wrap-around inside a single sector, and full tables
+@pytest.mark.parametrize("npes,slots,n", [(16, 1 << 12, 30000), (5, 3001, 7000), (16, 64, 1200), (2, 1 << 12, 5800),
+                                          (3, 8, 40), (4, 24, 60), (3, 8, 12)])
 def test_hash_insert_lookup(npes, slots, n):
     keys = workgen.cfg4_keys(n=n)
     keys = np.concatenate([keys, keys[: n // 8]])        # duplicates; the last shape overfills
@@ -211,6 +214,29 @@ def test_hash_insert_lookup(npes, slots, n):
             while j != s:
                 assert gtab[p, j] != 0
                 j = (j + 1) % slots
+
+
+def test_hash_table_not_sector_aligned():
+    # a table that starts 8 bytes into an allocation: its groups of 8 slots straddle 64-byte sectors,
+    # so the lookup takes the slot-by-slot kernel although the slot count is a multiple of 8
+    npes, slots, n = 3, 512, 700
+    keys = workgen.cfg4_keys(n=n)
+    queries = workgen.cfg4_queries(keys, n=2 * n)
+    hb = 1 << 14
+    w = oracle.World(npes, hb, oracle.SHUFFLED, 0)
+    tab = w.malloc(slots * 8 + 8) + 8
+    ost = w.hash_insert(tab, slots, keys)
+    ofound = w.hash_lookup(tab, slots, queries)
+    with shmem_world(npes, hb) as (heap, base):
+        t = sh.malloc(slots * 8 + 8) + 8
+        assert t - base == tab
+        dst = torch.full((n,), 255, dtype=torch.uint8, device="cuda:0")
+        dfo = torch.full((2 * n,), 255, dtype=torch.uint8, device="cuda:0")
+        sh.hash_insert(t, slots, to_dev(keys), n, dst, 2)
+        sh.hash_lookup(t, slots, to_dev(queries), 2 * n, dfo, 2)
+        sh.stream_sync()
+        assert np.array_equal(as_np(dfo, np.uint8), ofound)
+        assert np.array_equal(np.sort(as_np(dst, np.uint8)), np.sort(ost))
 
 
 # ------------------------------------------------------------------ BFS
