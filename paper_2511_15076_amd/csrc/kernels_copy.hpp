@@ -47,7 +47,8 @@ __device__ __forceinline__ bool desc_valid(const Ctx &c, const shmem_op_desc &d)
         if (d.local_off % eb || d.sym_off % eb) return false;
         if (d.count == 0) return d.local_off <= c.seg && d.sym_off <= c.seg;
         // spans, with overflow guarded by bounding each factor by the segment size
-        if (d.count > c.seg || (uint64_t)d.local_stride > c.seg || (uint64_t)d.sym_stride > c.seg) return false;
+        // (a stride only matters from the second element on; bounding the factors keeps the products in 128 bits)
+        if (d.count > c.seg || (d.count > 1 && ((uint64_t)d.local_stride > c.seg || (uint64_t)d.sym_stride > c.seg))) return false;
         const unsigned __int128 ls = (unsigned __int128)(d.count - 1) * (uint64_t)d.local_stride * eb + eb;
         const unsigned __int128 ss = (unsigned __int128)(d.count - 1) * (uint64_t)d.sym_stride * eb + eb;
         return d.local_off <= c.seg && ls <= c.seg - d.local_off && d.sym_off <= c.seg && ss <= c.seg - d.sym_off;

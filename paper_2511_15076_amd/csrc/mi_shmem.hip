@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "../../include/mi_shmem.h"
+#include "host_logic.hpp"
 #include "shmemx.hpp"
 #include "kernels_copy.hpp"
 #include "kernels_amo.hpp"
@@ -27,12 +28,10 @@
 
 namespace {
 
-constexpr size_t GRAN = 256;       // allocator granularity / minimum alignment
+constexpr size_t GRAN = hostlogic::GRAN;   // allocator granularity / minimum alignment
 constexpr int WG_THREADS = 256;    // 4 wavefronts per workgroup
 constexpr int HASH_LOOKUP_KIF = 4;  // keys in flight per lane quad in the sector-wide lookup
 constexpr uint32_t BFS_ALPHA = 30, BFS_BETA = 24;  // default direction thresholds (measured best on R-MAT scale 24)
-
-struct Block { uint64_t off, len; };
 
 struct Host {
     bool init = false;
@@ -43,8 +42,7 @@ struct Host {
     hipStream_t stream = nullptr;
     int num_cus = 0;
     bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
-    std::vector<Block> free_list;  // address-ordered
-    std::vector<Block> live;
+    hostlogic::SymAllocator alloc; // symmetric offsets (guarded by mu)
     uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
     std::mutex mu;
     std::vector<struct shmem_proxy *> proxies;   // live proxy objects (their threads are stopped at finalize)
@@ -75,16 +73,7 @@ inline int sym_off(const void *sym, uint64_t span, uint64_t *off)
     return SHMEM_OK;
 }
 
-// bytes spanned by nelems elements of eb bytes at a pitch of stride elements; false on overflow
-inline bool strided_span(size_t nelems, ptrdiff_t stride, size_t eb, uint64_t *span)
-{
-    if (nelems == 0) { *span = 0; return true; }
-    unsigned __int128 last = (unsigned __int128)(nelems - 1) * (unsigned __int128)(uint64_t)stride;
-    unsigned __int128 bytes = last * eb + eb;
-    if (bytes > (unsigned __int128)UINT64_MAX) return false;
-    *span = (uint64_t)bytes;
-    return true;
-}
+using hostlogic::strided_span;
 
 // npes * wgs_per_pe workgroups must be a sane grid (the product is formed in 64 bits)
 constexpr uint64_t MAX_GRID = 1u << 22;
@@ -116,19 +105,6 @@ int launch_copy(uint8_t *dst, const uint8_t *src, size_t n)
         hipLaunchKernelGGL(shmemx::k_copy, dim3(wgs_for_bytes(n)), dim3(WG_THREADS), 0, H.stream, dst, src, n);
     }
     return launched();
-}
-
-void free_insert(uint64_t off, uint64_t len)
-{
-    auto it = std::lower_bound(H.free_list.begin(), H.free_list.end(), off,
-                               [](const Block &b, uint64_t o) { return b.off < o; });
-    it = H.free_list.insert(it, Block{off, len});
-    auto nx = it + 1;
-    if (nx != H.free_list.end() && it->off + it->len == nx->off) { it->len += nx->len; it = H.free_list.erase(nx) - 1; }
-    if (it != H.free_list.begin()) {
-        auto pv = it - 1;
-        if (pv->off + pv->len == it->off) { pv->len += it->len; H.free_list.erase(it); }
-    }
 }
 
 // co-residency limit for kernels that contain an in-kernel barrier
@@ -227,8 +203,7 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     H.stream = s; H.num_cus = prop.multiProcessorCount; H.pinned = pinned;
     const char *coop = getenv("MI_SHMEM_COOPERATIVE_LAUNCH");
     H.cooperative = coop && coop[0] == '1';
-    H.free_list.assign(1, Block{0, (uint64_t)heap_bytes_per_pe});
-    H.live.clear();
+    H.alloc.reset((uint64_t)(uintptr_t)dev_heap, (uint64_t)heap_bytes_per_pe);
     H.init = true;
     return SHMEM_OK;
 }
@@ -241,7 +216,7 @@ int shmem_finalize(void)
     while (!H.proxies.empty()) proxy_stop_and_free(H.proxies.back());   // no thread outlives the heap it serves
     if (H.pinned) (void)hipHostFree(H.pinned);
     H.pinned = nullptr; H.init = false; H.npes = 0; H.heap = nullptr; H.scratch = nullptr;
-    H.free_list.clear(); H.live.clear();
+    H.alloc.clear();
     return hip_rc(e);
 }
 
@@ -250,23 +225,9 @@ int shmem_n_pes(void) { return H.init ? H.npes : 0; }
 void *shmem_align(size_t alignment, size_t nbytes)
 {
     std::lock_guard<std::mutex> g(H.mu);
-    if (!H.init || nbytes == 0 || alignment == 0 || (alignment & (alignment - 1))) return nullptr;
-    // the alignment is that of the device address, on every PE's copy
-    if (alignment < GRAN) alignment = GRAN;
-    if (H.seg % alignment || nbytes > H.seg) return nullptr;
-    const uint64_t base = (uint64_t)(uintptr_t)H.heap;
-    uint64_t need = ((uint64_t)nbytes + GRAN - 1) / GRAN * GRAN;
-    for (size_t i = 0; i < H.free_list.size(); ++i) {
-        uint64_t b = H.free_list[i].off, e = b + H.free_list[i].len;
-        uint64_t a = (base + b + alignment - 1) / alignment * alignment - base;
-        if (a < b || a + need > e || a + need < a) continue;
-        H.free_list.erase(H.free_list.begin() + (ptrdiff_t)i);
-        if (a > b) free_insert(b, a - b);
-        if (a + need < e) free_insert(a + need, e - (a + need));
-        H.live.push_back(Block{a, need});
-        return H.heap + a;
-    }
-    return nullptr;
+    if (!H.init) return nullptr;
+    const uint64_t off = H.alloc.align(alignment, nbytes);
+    return off == UINT64_MAX ? nullptr : H.heap + off;
 }
 
 void *shmem_malloc(size_t nbytes) { return shmem_align(GRAN, nbytes); }
@@ -277,15 +238,7 @@ int shmem_free(void *sym)
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     const uint8_t *p = (const uint8_t *)sym;
     if (!p || p < H.heap || p >= H.heap + H.seg) return SHMEM_ERR_BAD_FREE;
-    uint64_t off = (uint64_t)(p - H.heap);
-    for (size_t i = 0; i < H.live.size(); ++i)
-        if (H.live[i].off == off) {
-            uint64_t len = H.live[i].len;
-            H.live[i] = H.live.back(); H.live.pop_back();
-            free_insert(off, len);
-            return SHMEM_OK;
-        }
-    return SHMEM_ERR_BAD_FREE;
+    return H.alloc.release((uint64_t)(p - H.heap)) ? SHMEM_OK : SHMEM_ERR_BAD_FREE;
 }
 
 void *shmem_ptr(const void *sym, int pe)
@@ -913,21 +866,7 @@ namespace {
 
 bool proxy_desc_valid(const shmem_proxy *p, const shmem_op_desc &d)
 {
-    const uint64_t seg = p->seg;
-    if (d.pe >= (uint32_t)p->npes || d.pe_self >= (uint32_t)p->npes) return false;
-    if (d.kind == SHMEM_OP_PUT || d.kind == SHMEM_OP_GET)
-        return d.local_off <= seg && d.count <= seg - d.local_off && d.sym_off <= seg && d.count <= seg - d.sym_off;
-    if (d.kind == SHMEM_OP_IPUT || d.kind == SHMEM_OP_IGET) {
-        const uint32_t eb = d.elem_bytes;
-        if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return false;
-        if (d.local_stride < 1 || d.sym_stride < 1 || d.local_off % eb || d.sym_off % eb) return false;
-        if (d.count == 0) return d.local_off <= seg && d.sym_off <= seg;
-        if (d.count > seg || (uint64_t)d.local_stride > seg || (uint64_t)d.sym_stride > seg) return false;
-        const unsigned __int128 ls = (unsigned __int128)(d.count - 1) * (uint64_t)d.local_stride * eb + eb;
-        const unsigned __int128 ss = (unsigned __int128)(d.count - 1) * (uint64_t)d.sym_stride * eb + eb;
-        return d.local_off <= seg && ls <= seg - d.local_off && d.sym_off <= seg && ss <= seg - d.sym_off;
-    }
-    return false;
+    return hostlogic::desc_valid(d, (uint32_t)p->npes, p->seg);
 }
 
 void proxy_execute(shmem_proxy *p, const shmem_op_desc &d)

@@ -67,8 +67,10 @@ def test_table_window_sizes(batch, nops, wgs):
 def test_table_with_strided_and_large_ops_and_device_fault():
     npes, hb = 3, 1 << 20
     init = seeded_heaps(npes, hb, 555)
-    ops = np.zeros(7, dtype=workgen.OP_DESC)
+    ops = np.zeros(9, dtype=workgen.OP_DESC)
     # disjoint regions by construction
+    ops[7] = (workgen.OP_IGET, 1, 0, 8, 1040000, 1040008, 1, 2**31, 2**62, 0)   # one element: any stride is in range
+    ops[8] = (workgen.OP_IPUT, 2, 1, 4, 1041000, 1041004, 0, 2**40, 1, 0)       # no element at all
     ops[0] = (workgen.OP_PUT, 0, 1, 1, 0, 0, 200000, 1, 1, 0)            # large: whole team
     ops[1] = (workgen.OP_IPUT, 1, 2, 4, 300000, 300000, 5000, 3, 5, 0)   # local stride 3, remote 5
     ops[2] = (workgen.OP_IGET, 2, 0, 8, 500000, 600000, 700, 2, 7, 0)
