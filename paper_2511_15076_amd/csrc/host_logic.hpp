@@ -92,6 +92,38 @@ inline bool strided_span(size_t nelems, ptrdiff_t stride, size_t eb, uint64_t *s
     return true;
 }
 
+// Argument checks of the single-operation entry points, in the order in which their errors are reported
+// (PE, element size, strides, alignment, range).  sym_off = symmetric address - heap address in unsigned
+// arithmetic (an address below the heap becomes a huge offset and is out of range); local_addr is only
+// looked at for its alignment.  A range may end exactly at the end of a segment, an empty one may start there.
+inline bool pe_in(int pe, int npes) { return pe >= 0 && pe < npes; }
+inline bool range_in(uint64_t seg, uint64_t off, uint64_t span) { return off <= seg && span <= seg - off; }
+
+inline int check_contig(int npes, uint64_t seg, int pe_self, int pe, uint64_t sym_off, uint64_t nbytes)
+{
+    if (!pe_in(pe_self, npes) || !pe_in(pe, npes)) return SHMEM_ERR_INVALID_PE;
+    return range_in(seg, sym_off, nbytes) ? SHMEM_OK : SHMEM_ERR_OUT_OF_RANGE;
+}
+
+inline int check_strided(int npes, uint64_t seg, int pe_self, int pe, uint64_t sym_off, ptrdiff_t sym_stride,
+                         uint64_t local_addr, ptrdiff_t local_stride, size_t nelems, size_t eb)
+{
+    if (!pe_in(pe_self, npes) || !pe_in(pe, npes)) return SHMEM_ERR_INVALID_PE;
+    if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return SHMEM_ERR_INVALID_ARG;
+    if (sym_stride < 1 || local_stride < 1) return SHMEM_ERR_INVALID_ARG;
+    if (sym_off % eb || local_addr % eb) return SHMEM_ERR_ALIGN;
+    uint64_t span;
+    if (!strided_span(nelems, sym_stride, eb, &span)) return SHMEM_ERR_OUT_OF_RANGE;
+    return range_in(seg, sym_off, span) ? SHMEM_OK : SHMEM_ERR_OUT_OF_RANGE;
+}
+
+inline int check_amo(int npes, uint64_t seg, int pe_self, int pe, uint64_t sym_off)
+{
+    if (!pe_in(pe_self, npes) || !pe_in(pe, npes)) return SHMEM_ERR_INVALID_PE;
+    if (sym_off % 8) return SHMEM_ERR_ALIGN;
+    return range_in(seg, sym_off, 8) ? SHMEM_OK : SHMEM_ERR_OUT_OF_RANGE;
+}
+
 // A descriptor as the host-side executor accepts it (the device-side executor applies the same rules):
 // known kind, both PEs in range, both ranges inside a segment; strided ops: element size 1/2/4/8,
 // strides >= 1, offsets aligned to the element.

@@ -62,13 +62,18 @@ struct BfsGraph {
 inline shmemx::Ctx ctx() { return shmemx::Ctx{H.heap, (uint64_t)H.seg, H.scratch, H.npes}; }
 inline bool pe_ok(int pe) { return pe >= 0 && pe < H.npes; }
 
+// symmetric address -> offset in unsigned arithmetic: an address below the heap wraps to a huge offset and
+// a null pointer maps to the largest one, so both fail the range checks
+inline uint64_t off_of(const void *sym)
+{
+    return sym ? (uint64_t)((uintptr_t)sym - (uintptr_t)H.heap) : UINT64_MAX;
+}
+
 // symmetric address -> offset; checks [off, off+span) lies inside a segment
 inline int sym_off(const void *sym, uint64_t span, uint64_t *off)
 {
-    const uint8_t *p = (const uint8_t *)sym;
-    if (!p || p < H.heap || p >= H.heap + H.seg) return SHMEM_ERR_OUT_OF_RANGE;
-    uint64_t o = (uint64_t)(p - H.heap);
-    if (span > H.seg - o) return SHMEM_ERR_OUT_OF_RANGE;
+    const uint64_t o = off_of(sym);
+    if (!hostlogic::range_in(H.seg, o, span)) return SHMEM_ERR_OUT_OF_RANGE;
     *off = o;
     return SHMEM_OK;
 }
@@ -253,9 +258,8 @@ void *shmem_ptr(const void *sym, int pe)
 int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, int pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
-    uint64_t off;
-    if (int rc = sym_off(dst_sym, nbytes, &off)) return rc;
+    const uint64_t off = off_of(dst_sym);
+    if (int rc = hostlogic::check_contig(H.npes, H.seg, pe_self, pe, off, nbytes)) return rc;
     if (nbytes == 0) return SHMEM_OK;
     if (!src_local) return SHMEM_ERR_INVALID_ARG;
     uint8_t *dst = H.heap + (size_t)pe * H.seg + off;
@@ -265,9 +269,8 @@ int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, 
 int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, int pe)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
-    uint64_t off;
-    if (int rc = sym_off(src_sym, nbytes, &off)) return rc;
+    const uint64_t off = off_of(src_sym);
+    if (int rc = hostlogic::check_contig(H.npes, H.seg, pe_self, pe, off, nbytes)) return rc;
     if (nbytes == 0) return SHMEM_OK;
     if (!dst_local) return SHMEM_ERR_INVALID_ARG;
     const uint8_t *src = H.heap + (size_t)pe * H.seg + off;
@@ -278,13 +281,9 @@ static int strided_common(int pe_self, const void *sym, const void *local, ptrdi
                           ptrdiff_t local_stride, size_t nelems, size_t eb, int pe, uint64_t *off)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
-    if (eb != 1 && eb != 2 && eb != 4 && eb != 8) return SHMEM_ERR_INVALID_ARG;
-    if (sym_stride < 1 || local_stride < 1) return SHMEM_ERR_INVALID_ARG;
-    if ((uintptr_t)sym % eb || (uintptr_t)local % eb) return SHMEM_ERR_ALIGN;
-    uint64_t span;
-    if (!strided_span(nelems, sym_stride, eb, &span)) return SHMEM_ERR_OUT_OF_RANGE;
-    if (int rc = sym_off(sym, span, off)) return rc;
+    *off = off_of(sym);
+    if (int rc = hostlogic::check_strided(H.npes, H.seg, pe_self, pe, *off, sym_stride, (uint64_t)(uintptr_t)local,
+                                          local_stride, nelems, eb)) return rc;
     if (nelems && !local) return SHMEM_ERR_INVALID_ARG;
     return SHMEM_OK;
 }
@@ -318,10 +317,9 @@ int shmem_iget(int pe_self, void *dst_local, const void *src_sym, ptrdiff_t dst_
 static int amo_single(int kind, int pe_self, uint64_t *sym, uint64_t a, uint64_t b, int pe, uint64_t *dev_result)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
-    if (!pe_ok(pe_self) || !pe_ok(pe)) return SHMEM_ERR_INVALID_PE;
-    if ((uintptr_t)sym % 8 || (uintptr_t)dev_result % 8) return SHMEM_ERR_ALIGN;
-    uint64_t off;
-    if (int rc = sym_off(sym, 8, &off)) return rc;
+    const uint64_t off = off_of(sym);
+    if (int rc = hostlogic::check_amo(H.npes, H.seg, pe_self, pe, off)) return rc;
+    if ((uintptr_t)dev_result % 8) return SHMEM_ERR_ALIGN;
     uint64_t *target = (uint64_t *)(H.heap + (size_t)pe * H.seg + off);
     hipLaunchKernelGGL(shmemx::k_amo_single, dim3(1), dim3(64), 0, H.stream, kind, target, a, b, dev_result);
     return launched();

@@ -95,3 +95,52 @@ def test_descriptor_validation_agrees_with_the_oracle(harness):
     want = ["1" if w.op_batch(ops[i:i + 1], 0) == 0 else "0" for i in range(len(ops))]
     assert got == want
     assert 300 < want.count("1") < len(want) - 300          # both verdicts are well represented
+
+
+def test_single_op_argument_checks_report_what_the_oracle_reports(harness):
+    # put / get, iput / iget and the atomics over edge values of every argument: same status code as the
+    # oracle, in particular the same one when several arguments are wrong at once.  The local side is kept
+    # valid (the library takes any device pointer there and checks only its alignment).
+    npes, seg = 3, 1 << 12
+    rng = np.random.default_rng(23)
+    pick = lambda seq: seq[int(rng.integers(len(seq)))]
+    mostly = lambda sane, odd: pick(sane) if rng.random() < 0.8 else pick(odd)
+    offs = [0, 1, 2, 4, 8, 9, 64, seg // 2, seg - 16, seg - 8, seg - 4, seg - 1, seg]
+    odd_offs = [seg + 1, seg + 8, 2**32, 2**63, 2**64 - 8, 2**64 - 1]
+    counts = [0, 1, 2, 3, 8, 100, seg // 8, seg // 2, seg - 1, seg]
+    odd_counts = [seg + 1, 2**32, 2**63, 2**64 - 1]
+    strides = [1, 1, 2, 3, 17, seg // 8, seg]
+    odd_strides = [0, -1, -2**63, seg + 1, 2**40, 2**63 - 1]
+    pes, odd_pes = [0, 1, 2], [-1, 3, 2**31 - 1, -2**31]
+    w = oracle.World(npes, seg, oracle.EAGER, 0)
+    cmds, want = [], []
+    for _ in range(4000):
+        me, pe = mostly(pes, odd_pes), mostly(pes, odd_pes)
+        so = mostly(offs, odd_offs)
+        kind = int(rng.integers(0, 5))
+        if kind < 2:                                    # put / get of n bytes; local range valid
+            n = mostly(counts, odd_counts)
+            lo = 0
+            cmds.append(f"C {npes} {seg} {me} {pe} {so} {n}")
+            if n > seg:                                 # the oracle also checks the local range: keep that out of the verdict
+                rc = -5 if (0 <= me < npes and 0 <= pe < npes) else -4      # out of range / invalid PE
+            else:
+                rc = w.put(me, so, lo, n, pe) if kind == 0 else w.get(me, lo, so, n, pe)
+            want.append(str(rc))
+        elif kind < 4:                                  # iput / iget; local side: offset 0 or 4, stride 1, fits whenever the count does
+            eb = mostly([1, 2, 4, 8], [0, 3, 16])
+            ss = mostly(strides, odd_strides)
+            n = mostly([0, 1, 2, 5, 60, seg // 8], odd_counts)
+            lo = pick([0, 4, 8])
+            cmds.append(f"S {npes} {seg} {me} {pe} {so} {ss} {lo} 1 {n} {eb}")
+            if eb in (1, 2, 4, 8) and n * eb + lo > seg:
+                cmds.pop()                              # the local span would not fit the oracle's heap: not a case
+                continue
+            rc = w.iput(me, so, lo, ss, 1, n, eb, pe) if kind == 2 else w.iget(me, lo, so, 1, ss, n, eb, pe)
+            want.append(str(rc))
+        else:
+            cmds.append(f"M {npes} {seg} {me} {pe} {so}")
+            want.append(str(w.signal_add(me, so, 1, pe)))     # a remote fetch-add: the atomics' argument checks
+    got = harness(cmds)
+    assert got == want
+    assert {"0", "-3", "-4", "-5", "-6"} <= set(want)   # every class of verdict occurred
