@@ -316,6 +316,29 @@ def extra_transpose(sh, torch, npes=8, n=16384, wgs=256):
     return {"n": n, "elem_bytes": 4, "npes": npes, "matrix_bytes": n * n * 4, "cells": res}
 
 
+def _hash_mean_probes(torch, heap, tab_off, seg, npes, slots):
+    """Measured on the finished table (untimed): mean number of probes that reach a stored key from its
+    home slot = 1 + mean displacement.  Needs the placement rule (SplitMix64 finaliser; owner = h mod npes,
+    home = (h / npes) mod slots), written here in wrapping int64 arithmetic for power-of-two shapes."""
+    if npes & (npes - 1) or slots & (slots - 1):
+        return None
+    lsr = lambda z, k: (z >> k) & ((1 << (64 - k)) - 1)           # logical shift of the uint64 bit pattern
+    as_i64 = lambda c: c - (1 << 64) if c >= 1 << 63 else c
+    total, disp = 0, 0
+    for p in range(npes):
+        t = heap[p * seg + tab_off: p * seg + tab_off + 8 * slots].view(torch.int64)
+        occ = t != 0
+        z = t[occ]
+        z = (z ^ lsr(z, 30)) * as_i64(0xBF58476D1CE4E5B9)
+        z = (z ^ lsr(z, 27)) * as_i64(0x94D049BB133111EB)
+        h = z ^ lsr(z, 31)
+        home = lsr(h, npes.bit_length() - 1) & (slots - 1) if npes > 1 else h & (slots - 1)
+        at = torch.nonzero(occ).squeeze(1)
+        disp += int(((at - home) & (slots - 1)).sum().item())
+        total += int(at.numel())
+    return round(1.0 + disp / max(total, 1), 4)
+
+
 def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=256):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
@@ -339,13 +362,14 @@ def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=256):
         sh.stream_sync()
         found = float(d_fo.float().mean().item())
         inserted = int((d_st == 0).sum().item())
+        mean_probes = _hash_mean_probes(torch, heap, tab - heap.data_ptr(), seg, npes, slots)
     finally:
         sh.finalize()
     # algorithmic bytes: insert = 8 B key + 128 B sector read-modify-write + 1 B status; lookup = 8 + 64 + 1
     return {"keys": n, "npes": npes, "slots_per_pe": slots, "wgs_per_pe": wgs,
             "Minserts_per_s": round(n / ins_ms / 1e3, 1), "Mlookups_per_s": round(n / look_ms / 1e3, 1),
             "insert_eff_GBs": round(n * 137 / ins_ms / 1e6, 1), "lookup_eff_GBs": round(n * 73 / look_ms / 1e6, 1),
-            "inserted": inserted, "found_fraction": round(found, 4)}
+            "inserted": inserted, "found_fraction": round(found, 4), "mean_probes_stored_key": mean_probes}
 
 
 def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
