@@ -296,6 +296,22 @@ int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int i
  * Errors as above. */
 int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors);
 
+/* Message-passing litmus for fence and quiet (Sec. III-A "Ordering semantics":
+ * what is put before the ordering point is visible to whoever sees what is put
+ * after it).  PE 0 and PE 1, one workgroup each.  Round r = 1..rounds: PE 0
+ * puts a block of nbytes (a multiple of 8) filled with r into PE 1's copy of
+ * buf_sym, every wave calls fence (use_quiet = 0) or quiet (use_quiet = 1),
+ * then one lane puts the flag word r and calls quiet; PE 1 polls the flag,
+ * acquires, checks every word of the block and acknowledges.  *dev_errors
+ * (DEVICE uint64, may be NULL) is incremented per word that was not r.
+ * buf_sym spans roundup(nbytes, 256) + 512 bytes; the flag (at roundup(nbytes,
+ * 256)) and the acknowledgement word (256 bytes further) must be 0 on both PEs
+ * before the call and hold `rounds` after it.
+ * Errors: NOT_INIT, INVALID_ARG (fewer than 2 PEs, rounds < 0, nbytes % 8),
+ * ALIGN, OUT_OF_RANGE, DEVICE; a wait that times out surfaces at
+ * shmem_stream_sync(). */
+int shmem_fence_litmus(void *buf_sym, size_t nbytes, int rounds, int use_quiet, uint64_t *dev_errors);
+
 /* -------------------------------------------------------------------------
  * MoE-shaped all-to-all in traffic shape: the low-latency dispatch / combine
  * of Sec. IV-E ("Low-Latency Kernel Integration") with the message sizes of

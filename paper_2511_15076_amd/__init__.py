@@ -79,6 +79,7 @@ _SIG = {
     "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i, _i, _i]),
     "shmem_pingpong": (_i, [_vp, _sz, _vp, _i, _i]),
     "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
+    "shmem_fence_litmus": (_i, [_vp, _sz, _i, _i, _vp]),
     "shmem_moe_create": (_i, [_i, _i, _i, _sz, C.POINTER(_vp)]),
     "shmem_moe_destroy": (_i, [_vp]),
     "shmem_moe_dispatch": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i]),
@@ -285,6 +286,11 @@ def pingpong(buf_sym, nbytes, gin, signal_id, iters):
 def barrier_epochs(slots_sym, rounds, wgs_per_pe, dev_errors=None):
     return _check(_L.shmem_barrier_epochs(_addr(slots_sym), rounds, wgs_per_pe, _addr(dev_errors)),
                   "shmem_barrier_epochs")
+
+
+def fence_litmus(buf_sym, nbytes, rounds, use_quiet=0, dev_errors=None):
+    return _check(_L.shmem_fence_litmus(_addr(buf_sym), nbytes, rounds, use_quiet, _addr(dev_errors)),
+                  "shmem_fence_litmus")
 
 
 def moe_create(num_experts, max_tokens, topk, hidden_bytes):

@@ -59,6 +59,66 @@ __global__ __launch_bounds__(256) void k_pingpong(Ctx c, GinState gs, uint64_t b
     }
 }
 
+// Message-passing litmus for fence / quiet (Sec. III-A "Ordering semantics"; the put -> flag form of the
+// paper's put -> signal rule): PE 0 and PE 1, one workgroup each, on different dies.  Round r: PE 0 fills
+// its copy of the data block with r and puts it to PE 1 (whole workgroup), every wave orders its part with
+// fence() -- or quiet() -- the workgroup meets, and ONE lane puts the 8-byte flag = r and makes it leave
+// with quiet().  PE 1 polls its flag, acquires, and checks that every data word is r; then it puts the
+// acknowledgement r back and PE 0, which waits for it, starts the next round.  A reader that sees the
+// flag but not the data is counted in *errors.  Layout at buf_off: data (nbytes), then the flag and the
+// acknowledgement word on lines of their own.
+__global__ __launch_bounds__(256) void k_fence_litmus(Ctx c, uint64_t buf_off, uint64_t nbytes, uint32_t rounds,
+                                                      int use_quiet, uint64_t *errors)
+{
+    const uint32_t pe = blockIdx.x;  // 0 or 1
+    const uint64_t words = nbytes / 8;
+    const uint64_t flag_off = buf_off + (nbytes + 255) / 256 * 256, ack_off = flag_off + 256;
+    uint64_t *mine = (uint64_t *)ptr(c, buf_off, pe);
+    uint64_t *my_flag = (uint64_t *)ptr(c, flag_off, pe), *my_ack = (uint64_t *)ptr(c, ack_off, pe);
+    uint64_t bad = 0;
+    for (uint32_t r = 1; r <= rounds; ++r) {
+        if (pe == 0) {
+            for (uint64_t i = threadIdx.x; i < words; i += blockDim.x) mine[i] = r;
+            __syncthreads();                                  // the source is complete before anybody copies from it
+            put(c, buf_off, (const uint8_t *)mine, nbytes, 1, threadIdx.x, blockDim.x);
+            if (use_quiet) quiet(); else fence();             // every wave: its puts come before what follows
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                *my_flag = r;                                 // local source word of the flag put
+                put(c, flag_off, (const uint8_t *)my_flag, 8, 1, 0, 1);
+                quiet();                                      // delivery of the flag itself
+                uint32_t spins = 0;
+                while (atomic_fetch(my_ack) < r) {
+                    if (timed_out(c, spins)) break;
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, r); break; }
+                }
+            }
+            __syncthreads();
+        } else {
+            if (threadIdx.x == 0) {
+                uint32_t spins = 0;
+                while (atomic_fetch(my_flag) < r) {
+                    if (timed_out(c, spins)) break;
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, r); break; }
+                }
+                acquire();
+            }
+            wg_acquire();
+            for (uint64_t i = threadIdx.x; i < words; i += blockDim.x)
+                if (*(volatile uint64_t *)(mine + i) != r) ++bad;
+            __syncthreads();                                  // everybody has read before the sender may overwrite
+            if (threadIdx.x == 0) {
+                *my_ack = r;
+                put(c, ack_off, (const uint8_t *)my_ack, 8, 0, 0, 1);
+                quiet();
+            }
+        }
+    }
+    if (bad && errors) atomic_fetch_add(errors, bad);
+}
+
 // Clears the signal and counter arrays of a new Gin object on every PE.
 __global__ void k_gin_zero(Ctx c, GinState gs)
 {

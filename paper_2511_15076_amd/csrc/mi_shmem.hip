@@ -742,6 +742,24 @@ int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64
     return launch_resident((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
+int shmem_fence_litmus(void *buf_sym, size_t nbytes, int rounds, int use_quiet, uint64_t *dev_errors)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (H.npes < 2 || rounds < 0 || nbytes % 8) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)buf_sym % 8 || (uintptr_t)dev_errors % 8) return SHMEM_ERR_ALIGN;
+    if (nbytes > H.seg) return SHMEM_ERR_OUT_OF_RANGE;
+    const uint64_t span = ((uint64_t)nbytes + 255) / 256 * 256 + 512;
+    uint64_t boff;
+    if (int rc = sym_off(buf_sym, span, &boff)) return rc;
+    if (rounds == 0) return SHMEM_OK;
+    if (2 > max_resident_wgs(shmemx::k_fence_litmus)) return SHMEM_ERR_DEVICE;
+    shmemx::Ctx c = ctx();
+    uint64_t nb = nbytes;
+    uint32_t r = (uint32_t)rounds;
+    void *args[] = {&c, &boff, &nb, &r, &use_quiet, &dev_errors};
+    return launch_resident((const void *)shmemx::k_fence_litmus, dim3(2), dim3(WG_THREADS), args);
+}
+
 // ---------------------------------------------------------------------------
 struct shmem_moe {
     shmemx::MoeState st;

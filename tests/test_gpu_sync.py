@@ -116,6 +116,31 @@ def test_barrier_epochs(npes, wgs, rounds):
     assert np.array_equal(got, w.heaps())
 
 
+@pytest.mark.parametrize("use_quiet", [0, 1])
+@pytest.mark.parametrize("nbytes", [8, 4096, 1 << 20])
+def test_fence_and_quiet_order_data_before_the_flag(nbytes, use_quiet):
+    # put data; fence (or quiet); put flag; quiet -- whoever sees the flag sees the data, 300 rounds between
+    # two dies; a stale word would be counted
+    npes, rounds = 3, 300
+    pad = (nbytes + 255) // 256 * 256
+    with shmem_world(npes, pad + 4096) as (heap, base):
+        buf = sh.malloc(pad + 512)
+        errors = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        sh.fence_litmus(buf, nbytes, rounds, use_quiet, errors)
+        sh.stream_sync()
+        assert int(errors.item()) == 0
+        got = heaps_of(heap, npes)
+        off = buf - base
+        assert (got[1, off:off + nbytes].view(np.uint64) == rounds).all()       # the last block arrived whole
+        assert got[1, off + pad:off + pad + 8].view(np.uint64)[0] == rounds     # flag on PE 1
+        assert got[0, off + pad + 256:off + pad + 264].view(np.uint64)[0] == rounds   # acknowledgement on PE 0
+        assert not got[2].any()                                                  # a bystander PE is untouched
+        for call in (lambda: sh.fence_litmus(buf, 12, 1), lambda: sh.fence_litmus(buf, 8, -1),
+                     lambda: sh.fence_litmus(buf + pad, 1 << 20, 1)):
+            with pytest.raises(sh.ShmemError):
+                call()
+
+
 def test_sync_entry_point_errors():
     with shmem_world(4, 1 << 16) as (heap, base):
         gin = sh.gin_create(2, 1)
