@@ -229,6 +229,41 @@ __global__ __launch_bounds__(256) void k_copy_stream(uint8_t *__restrict__ dst, 
     copy_stream(dst, src, n, (uint64_t)blockIdx.x * waves_per_wg + wave, (uint64_t)gridDim.x * waves_per_wg, lane);
 }
 
+// Small messages (up to SMALL_MSG bytes, multiples of 8 or 16): a sub-group of lanes, one vector V per
+// lane, moves one message, so a wave instruction carries 64 / group messages; four such rounds are in
+// flight per wave (all loads before the first store) -- with one round at a time a wave had 512 bytes
+// in flight and the small sizes were latency-bound.
+template <typename V>
+__device__ __forceinline__ void sweep_small(const SweepArgs &a, uint8_t *lbase, uint8_t *rbase, uint64_t my_wave,
+                                            uint64_t team_waves, uint32_t lane)
+{
+    constexpr uint32_t W = sizeof(V);
+    constexpr int U = 8;
+    uint32_t group = 1;
+    while (group * W < a.count) group <<= 1;
+    const uint32_t per_wave = 64 / group, sub = lane / group, j = lane % group;
+    const bool lane_on = (uint64_t)j * W < a.count;
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    for (uint64_t t = my_wave; t * per_wave < a.ops_per_pe; t += team_waves * U) {
+        V v[U];
+        V *dst[U];
+        bool on[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t op = (t + u * team_waves) * per_wave + sub;
+            on[u] = lane_on && op < a.ops_per_pe;
+            const uint64_t slot = op < a.nslots ? op : op % a.nslots;
+            V *l = (V *)(lbase + slot * a.local_slot) + j;
+            V *r = (V *)(rbase + slot * a.remote_slot) + j;
+            dst[u] = is_put ? r : l;
+            if (on[u]) v[u] = __builtin_nontemporal_load(is_put ? l : r);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (on[u]) __builtin_nontemporal_store(v[u], dst[u]);
+    }
+}
+
 __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
 {
     const uint32_t pe = blockIdx.x / a.wgs_per_pe;
@@ -245,21 +280,10 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
     uint8_t *const lbase = ptr(c, a.local_off, pe);
     uint8_t *const rbase = ptr(c, a.remote_off, peer);
     if (contiguous && a.count <= SMALL_MSG && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 7) == 0) {
-        // Small messages: a sub-group of count/8 lanes (rounded up to a power of two)
-        // moves one message, 8 bytes per lane, so a wave issues 64/group messages at once.
-        uint32_t group = 1;
-        while (group * 8 < a.count) group <<= 1;
-        const uint32_t per_wave = 64 / group, sub = lane / group, j = lane % group;
-        for (uint64_t t = my_wave; t * per_wave < a.ops_per_pe; t += team_waves) {
-            const uint64_t op = t * per_wave + sub;
-            if (op < a.ops_per_pe && (uint64_t)j * 8 < a.count) {
-                const uint64_t slot = op % a.nslots;
-                u32x2 *l = (u32x2 *)(lbase + slot * a.local_slot) + j;
-                u32x2 *r = (u32x2 *)(rbase + slot * a.remote_slot) + j;
-                if (a.kind == SHMEM_OP_PUT) __builtin_nontemporal_store(__builtin_nontemporal_load(l), r);
-                else __builtin_nontemporal_store(__builtin_nontemporal_load(r), l);
-            }
-        }
+        if (((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0)
+            sweep_small<u32x4>(a, lbase, rbase, my_wave, team_waves, lane);
+        else
+            sweep_small<u32x2>(a, lbase, rbase, my_wave, team_waves, lane);
         return;
     }
     if (contiguous && a.count >= 1024 && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0) {

@@ -201,6 +201,13 @@ SWEEP_CASES = [
     # kind, count, eb, remote_stride, local_stride, ops_per_pe, nslots, wgs
     (workgen.OP_PUT, 8, 1, 1, 1, 5, 3, 1),
     (workgen.OP_GET, 64, 1, 1, 1, 7, 2, 2),
+    # small messages: 8- and 16-byte vectors, group sizes from 1 to 64 lanes, op counts that leave ragged rounds
+    (workgen.OP_PUT, 16, 1, 1, 1, 301, 301, 1),
+    (workgen.OP_GET, 24, 1, 1, 1, 130, 130, 2),
+    (workgen.OP_PUT, 48, 1, 1, 1, 77, 77, 1),
+    (workgen.OP_GET, 256, 1, 1, 1, 77, 40, 1),
+    (workgen.OP_PUT, 504, 1, 1, 1, 33, 33, 1),
+    (workgen.OP_GET, 512, 1, 1, 1, 131, 131, 3),
     (workgen.OP_PUT, 4096, 1, 1, 1, 9, 4, 3),
     (workgen.OP_PUT, 14352, 1, 1, 1, 6, 3, 2),          # the paper's MoE dispatch message size
     (workgen.OP_GET, 14336, 1, 1, 1, 6, 3, 5),          # ... and its combine message size
