@@ -160,17 +160,25 @@ __device__ __forceinline__ void team_barrier(const Ctx &c, uint32_t pe, uint32_t
     wg_acquire();
 }
 
-// World barrier (barrier_all): quiet by every wave, then two stages so that no
-// word is hammered by more than max(wgs_per_pe, npes) workgroups -- the
-// workgroups of a team meet on the team's words, the last one of each team
+// World barrier (barrier_all): quiet by every wave, then the workgroups meet.  Up to
+// FLAT_BARRIER_WGS workgroups in the launch arrive on the world words directly: arrivals on one
+// address serialise at about 12 ns each, which for a few dozen is less than a second round trip.
+// Larger launches take two stages so that no word is hammered by more than max(wgs_per_pe, npes)
+// workgroups -- the workgroups of a team meet on the team's words, the last one of each team
 // meets the other teams on the world words and then releases its team.
+constexpr uint32_t FLAT_BARRIER_WGS = 256;
+
 __device__ __forceinline__ void barrier_all(const Ctx &c, uint32_t pe, uint32_t wgs_per_pe)
 {
     wg_release();
     if (threadIdx.x == 0) {
         quiet();
+        const uint32_t total = (uint32_t)c.npes * wgs_per_pe;
         uint64_t *t = &c.scratch[W_PE_BASE + pe * W_PE_WORDS + 32], tg, wg_;
-        if (barrier_arrive(c, t, t + 16, wgs_per_pe, &tg)) {
+        if (total <= FLAT_BARRIER_WGS) {
+            if (barrier_arrive(c, &c.scratch[W_BAR_COUNT], &c.scratch[W_BAR_GEN], total, &wg_))
+                barrier_open(&c.scratch[W_BAR_GEN], wg_);
+        } else if (barrier_arrive(c, t, t + 16, wgs_per_pe, &tg)) {
             if (barrier_arrive(c, &c.scratch[W_BAR_COUNT], &c.scratch[W_BAR_GEN], (uint32_t)c.npes, &wg_))
                 barrier_open(&c.scratch[W_BAR_GEN], wg_);
             barrier_open(t + 16, tg);

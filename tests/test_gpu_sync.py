@@ -96,7 +96,8 @@ def test_pingpong(nbytes):
     assert np.array_equal(got[0][pad:pad + nbytes], init[0][:nbytes])   # the payload came back
 
 
-@pytest.mark.parametrize("npes,wgs,rounds", [(16, 2, 10000), (64, 1, 2000), (5, 3, 3000)])
+# launches of up to 256 workgroups meet on one word, larger ones in two stages (team, then world)
+@pytest.mark.parametrize("npes,wgs,rounds", [(16, 2, 10000), (64, 1, 2000), (5, 3, 3000), (16, 24, 500), (3, 100, 500)])
 def test_barrier_epochs(npes, wgs, rounds):
     hb = 4096
     with shmem_world(npes, hb) as (heap, base):
