@@ -105,7 +105,17 @@ __global__ __launch_bounds__(256, 4) void k_op_batch(Ctx c, const shmem_op_desc 
             if (have && d.pe_self >= (uint32_t)c.npes && blockIdx.x == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
             const bool ok = have && d.pe_self == pe && desc_valid(c, d);
             if (have && d.pe_self == pe && !ok && wg == 0 && wave == 0) report(c, DEV_ERR_BAD_OP, i0 + lane);
-            uint64_t todo = ballot(ok);
+            // Which of the PE's ops this wave executes is settled for all 64 descriptors at once: large
+            // ops are everybody's, small op number k of the window (a ballot and a prefix count give k)
+            // belongs to wave k mod team_waves.  The wave then walks only its own ops: walking all of the
+            // PE's ops and skipping the others' cost about 100 instructions each, several microseconds
+            // per window for a wave that has the SIMD to itself.
+            const uint64_t bytes_l = (d.kind <= SHMEM_OP_GET) ? d.count : d.count * d.elem_bytes;
+            const bool big = ok && bytes_l > BIG_OP;
+            const uint64_t small_mask = ballot(ok && !big);
+            const uint32_t ordinal = mine + rank_in(small_mask);
+            uint64_t todo = ballot(big || (ok && !big && ordinal % team_waves == my_wave));
+            mine += (uint32_t)__builtin_popcountll(small_mask);
             while (todo) {
                 const uint32_t j = (uint32_t)__builtin_ctzll(todo);
                 todo &= todo - 1;
@@ -126,8 +136,7 @@ __global__ __launch_bounds__(256, 4) void k_op_batch(Ctx c, const shmem_op_desc 
                         desc_exec(c, u, (size_t)my_wave * 64 + lane, (size_t)team_waves * 64);
                     }
                 } else {
-                    if (mine % team_waves == my_wave) desc_exec(c, u, lane, 64);
-                    ++mine;
+                    desc_exec(c, u, lane, 64);
                 }
             }
         }
