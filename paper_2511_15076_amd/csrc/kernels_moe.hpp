@@ -119,6 +119,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
 {
     __shared__ uint64_t mask[MOE_MAX_EXPERTS][2];   // per expert: which of this PE's tokens go there
     __shared__ uint32_t begin[MOE_MAX_PES + 1];
+    __shared__ int16_t s_topk[MOE_MAX_TOKENS * MOE_MAX_TOPK];   // this PE's routing table (expert ids fit 16 bits)
     const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
     const uint32_t P = (uint32_t)c.npes, E = m.num_experts, T = m.max_tokens, K = m.topk;
     const uint32_t lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -129,11 +130,14 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     const uint32_t hvecs = (uint32_t)(m.hidden / 16);
 
     // ---- routing masks (every workgroup builds its own copy: at most 128 x topk entries) ----
+    // The whole table is read, not just the first ntok rows: its loads then do not wait for the load
+    // of ntok, and the copy kept in LDS saves the send loop a dependent read per message.
     for (uint32_t i = threadIdx.x; i < 2 * E; i += blockDim.x) (&mask[0][0])[i] = 0;
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < ntok * K; i += blockDim.x) {
+    for (uint32_t i = threadIdx.x; i < T * K; i += blockDim.x) {
         const int32_t e = topk[i];
-        if (e < 0) continue;                          // unused entry
+        s_topk[i] = (int16_t)(e >= 0 && (uint32_t)e < E ? e : -1);
+        if (i >= ntok * K || e < 0) continue;         // beyond the batch, or an unused entry
         const uint32_t t = i / K;
         if ((uint32_t)e >= E) { report(c, DEV_ERR_BAD_TARGET, (uint64_t)pe * T * K + i); continue; }
         const uint64_t bit = 1ull << (t & 63);
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
                 const uint32_t t = moe_nth_token(m0, m1, i);
                 uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
                 if (part == 0) {
-                    const uint64_t hit = ballot(lane < K && topk[t * K + min(lane, K - 1)] == (int32_t)e);
+                    const uint64_t hit = ballot(lane < K && s_topk[t * K + min(lane, K - 1)] == (int32_t)e);
                     const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
                     if (lane == 0) {
                         u32x4 meta = {t, pe, j, e};
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     // complete and one release has made them visible, so a count is never seen before its data
     wg_release();
     if (threadIdx.x < 64) {
-        quiet();
+        if (routes) quiet();                                                 // nothing was written: nothing to release
         for (uint32_t e = wg + lane * W; e < E; e += 64 * W) {
             const uint32_t n = (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
             __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)n + 1, __ATOMIC_RELAXED,
