@@ -281,10 +281,19 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
         wg_acquire();
         const u32x4 *slots = (const u32x4 *)ptr(c, m.comb_off + (uint64_t)t * K * m.hidden, pe);
         u32x4 *out = (u32x4 *)(a.combined + ((size_t)pe * T + t) * m.hidden);
+        // every slot of the token is loaded, eight at a time, whether or not its route is in use (an
+        // unused slot holds old bytes that are not added): loads under a condition would go out one
+        // memory round trip after the other
         for (uint32_t v = threadIdx.x; v < hvecs; v += blockDim.x) {
             u32x4 acc = {0, 0, 0, 0};
-            for (uint32_t j = 0; j < K; ++j)
-                if (experts[j] >= 0) acc += __builtin_nontemporal_load(slots + (size_t)j * hvecs + v);
+            for (uint32_t j0 = 0; j0 < K; j0 += 8) {
+                u32x4 w[8];
+#pragma unroll
+                for (uint32_t k = 0; k < 8; ++k) w[k] = __builtin_nontemporal_load(slots + (size_t)min(j0 + k, K - 1) * hvecs + v);
+#pragma unroll
+                for (uint32_t k = 0; k < 8; ++k)
+                    if (j0 + k < K && experts[j0 + k] >= 0) acc += w[k];
+            }
             __builtin_nontemporal_store(acc, out + v);
         }
     }
