@@ -215,9 +215,13 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             uint32_t s = 0;
             while (begin[s + 1] <= i) ++s;
             const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[s])) * m.msg, pe);
-            if (part == 0 && lane == 0) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = *(const u32x4 *)slot;
+            // the metadata is requested before the token and stored after it, so the two reads travel together
+            const bool first = part == 0 && lane == 0;
+            u32x4 info = {0, 0, 0, 0};
+            if (first) info = *(const u32x4 *)slot;
             const uint32_t lo = part * rper, cnt = lo < hvecs ? min(rper, hvecs - lo) : 0;
             wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
+            if (first) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = info;
         }
     }
 }
