@@ -176,52 +176,67 @@ struct Probe {
     uint64_t known[EPL];
 };
 
-// first half: owner, local index and the read of this die's bitmap copy (EPL probes in flight)
+// first half: owner, local index and the read of this die's bitmap copy (EPL probes in flight).
+// Every slot holds a valid vertex (an inactive slot repeats an edge of the batch) and is probed whether
+// or not it is active: with exactly EPL loads per call the compiler can wait for the probes alone
+// later on; loads under a condition make it wait for everything outstanding, the neighbour loads of
+// the next chunk included.
 __device__ __forceinline__ void bfs_probe_issue(const Ctx &c, const BfsState &s, uint32_t xcd, Probe &p,
-                                                const bool (&act)[EPL], const uint32_t (&v)[EPL])
+                                                const uint32_t (&v)[EPL])
 {
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) {
-        p.o[k] = 0; p.l[k] = 0; p.f[k] = nullptr; p.known[k] = ~0ull;
-        if (act[k]) {
-            p.o[k] = bfs_owner(s, v[k]);
-            p.l[k] = v[k] - p.o[k] * s.vpp;
-            p.f[k] = (uint64_t *)ptr(c, s.filter_off, p.o[k]) + (uint64_t)xcd * s.words + (p.l[k] >> 6);
-            p.known[k] = *p.f[k];
-        }
+        p.o[k] = bfs_owner(s, v[k]);
+        p.l[k] = v[k] - p.o[k] * s.vpp;
+        p.f[k] = (uint64_t *)ptr(c, s.filter_off, p.o[k]) + (uint64_t)xcd * s.words + (p.l[k] >> 6);
+        p.known[k] = *p.f[k];
     }
 }
 
-// second half: claim what is not known to be claimed, deliver parent / level, enqueue the winners
-template <bool STAGED>
-__device__ __forceinline__ void bfs_probe_finish(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L,
-                                                 Probe &p, const bool (&act)[EPL], const uint32_t (&v)[EPL],
-                                                 const uint32_t (&u)[EPL])
-{
-    // all claims of the chunk are issued before the first result is used: a fetch_or resolves at the
-    // memory side, so one round trip then covers EPL of them instead of one each
-    bool won[EPL], need[EPL];
+// second half, part one: claim what is not known to be claimed and wait for the outcome.  All claims of
+// the chunk are issued before the first result is used: a fetch_or resolves at the memory side, so one
+// round trip covers EPL of them.  Returns false when no lane of the wave had anything to claim (the
+// common case late in a search).
+struct Claim {
+    bool need[EPL], won[EPL];
     uint64_t old[EPL];
+};
+
+__device__ __forceinline__ bool bfs_claim(const Ctx &c, const BfsState &s, const Probe &p, const bool (&act)[EPL], Claim &cl)
+{
     bool any = false;
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) {
-        need[k] = act[k] && !(p.known[k] & (1ull << (p.l[k] & 63)));
-        any |= need[k];
-        won[k] = false;
-        old[k] = 0;
+        cl.need[k] = act[k] && !(p.known[k] & (1ull << (p.l[k] & 63)));
+        any |= cl.need[k];
+        cl.won[k] = false;
+        cl.old[k] = 0;
     }
-    if (!ballot(any)) return;   // every probe of the chunk hit a vertex known to be claimed (the common case late in a search)
+    if (!ballot(any)) return false;
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k)
-        if (need[k])
-            old[k] = atomic_fetch_or((uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6), 1ull << (p.l[k] & 63));   // the claim
+        if (cl.need[k])
+            cl.old[k] = atomic_fetch_or((uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6), 1ull << (p.l[k] & 63));   // the claim
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) cl.won[k] = cl.need[k] && !(cl.old[k] & (1ull << (p.l[k] & 63)));
+    return true;
+}
+
+// second half, part two: update this die's bitmap copy, deliver parent / level, enqueue the winners.
+// (v, u) are the chunk's vertices; the caller has moved on to the next chunk's registers by now.
+template <bool STAGED>
+__device__ __forceinline__ void bfs_deliver(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L, const Probe &p,
+                                            const Claim &cl, const uint32_t (&v)[EPL], const uint32_t (&u)[EPL])
+{
+    // the queue first: a full staging block waits for its fetch_add on the owner's tail, and that wait
+    // should not have the scattered stores below in front of it
+#pragma unroll
+    for (uint32_t k = 0; k < EPL; ++k) bfs_enqueue<STAGED>(c, s, st, L, cl.won[k], p.o[k], v[k]);
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) {
-        const uint64_t bit = 1ull << (p.l[k] & 63);
-        won[k] = need[k] && !(old[k] & bit);
-        if (need[k]) {
-            *p.f[k] = p.known[k] | old[k] | bit;   // everything the fetch_or showed to be claimed
-            if (won[k]) {
+        if (cl.need[k]) {
+            *p.f[k] = p.known[k] | cl.old[k] | (1ull << (p.l[k] & 63));   // everything the fetch_or showed to be claimed
+            if (cl.won[k]) {
                 // put parent, put level: streaming stores, so the scattered lines do not push the
                 // bitmap copies out of L2
                 __builtin_nontemporal_store(u[k], (uint32_t *)ptr(c, s.parent_off, p.o[k]) + p.l[k]);
@@ -229,8 +244,6 @@ __device__ __forceinline__ void bfs_probe_finish(const Ctx &c, const BfsState &s
             }
         }
     }
-#pragma unroll
-    for (uint32_t k = 0; k < EPL; ++k) bfs_enqueue<STAGED>(c, s, st, L, won[k], p.o[k], v[k]);
 }
 
 // LDS of one workgroup (4 waves)
@@ -293,35 +306,45 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
         pre[lane] = incl - small; su[lane] = u; sr0[lane] = r0;
         __builtin_amdgcn_wave_barrier();
         // edges e0 .. e0 + 64*EPL of the batch: owning row by binary search over the prefix sums
+        // (a slot beyond the batch's last edge repeats that edge, inactive: always EPL loads, all in bounds)
         auto fetch = [&](uint32_t e0, bool (&act)[EPL], uint32_t (&vv)[EPL], uint32_t (&uu)[EPL]) {
 #pragma unroll
             for (uint32_t k = 0; k < EPL; ++k) {
-                const uint32_t e = e0 + k * 64 + lane;
-                act[k] = e < total;
-                vv[k] = 0; uu[k] = 0;
-                if (act[k]) {
-                    uint32_t lo = 0;                 // largest i with pre[i] <= e
+                const uint32_t e_ = e0 + k * 64 + lane;
+                act[k] = e_ < total;
+                const uint32_t e = act[k] ? e_ : total - 1;
+                uint32_t lo = 0;                     // largest i with pre[i] <= e
 #pragma unroll
-                    for (int step = 32; step > 0; step >>= 1)
-                        if (pre[lo + step] <= e) lo += step;
-                    uu[k] = su[lo];
-                    vv[k] = __builtin_nontemporal_load(s.nbr + sr0[lo] + (e - pre[lo]));
-                }
+                for (int step = 32; step > 0; step >>= 1)
+                    if (pre[lo + step] <= e) lo += step;
+                uu[k] = su[lo];
+                vv[k] = __builtin_nontemporal_load(s.nbr + sr0[lo] + (e - pre[lo]));
             }
         };
         bool act[EPL], nact[EPL];
         uint32_t vv[EPL], uu[EPL], nvv[EPL], nuu[EPL];
         fetch(0, act, vv, uu);
+#pragma unroll
+        for (uint32_t k = 0; k < EPL; ++k) asm volatile("" : : "v"(vv[k]));   // arrived before the loop is entered (see below)
         for (uint32_t e0 = 0; e0 < total; e0 += 64 * EPL) {
             Probe pr;
-            bfs_probe_issue(c, s, xcd, pr, act, vv);
+            bfs_probe_issue(c, s, xcd, pr, vv);
             const bool more = e0 + 64 * EPL < total;
-            if (more) fetch(e0 + 64 * EPL, nact, nvv, nuu);   // next neighbours travel while this chunk is probed
-            bfs_probe_finish<STAGED>(c, s, st, L, pr, act, vv, uu);
-            if (more) {
+            fetch(more ? e0 + 64 * EPL : e0, nact, nvv, nuu);  // next neighbours travel while this chunk is probed (the last chunk asks for itself again)
+            // The wait for the claims also sees the next neighbours arrive (they were requested earlier), so
+            // the registers move on to the next chunk HERE, before this chunk's stores and queue traffic
+            // go out: at the top of the loop nothing then has to wait for those to drain.  (The memory
+            // counter is in order: waiting for a load issued before a varying number of stores means
+            // waiting for all of them.)
+            Claim cl;
+            const bool claimed = bfs_claim(c, s, pr, act, cl);
+            uint32_t cv[EPL], cu[EPL];
 #pragma unroll
-                for (uint32_t k = 0; k < EPL; ++k) { act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k]; }
+            for (uint32_t k = 0; k < EPL; ++k) {
+                asm volatile("" : : "v"(nvv[k]));    // the next neighbours are waited for here, not at the top of the loop
+                cv[k] = vv[k]; cu[k] = uu[k]; act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k];
             }
+            if (claimed) bfs_deliver<STAGED>(c, s, st, L, pr, cl, cv, cu);
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -411,22 +434,28 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
                 const uint64_t e = e0 + k * 64 + lane;
                 act[k] = e < deg;
                 uu[k] = u;
-                vv[k] = act[k] ? __builtin_nontemporal_load(s.nbr + r0 + e) : 0;
+                vv[k] = __builtin_nontemporal_load(s.nbr + r0 + (act[k] ? e : deg - 1));   // always a load, always in bounds
             }
         };
         bool act[EPL], nact[EPL];
         uint32_t vv[EPL], uu[EPL], nvv[EPL], nuu[EPL];
         fetch((uint32_t)t0, act, vv, uu);
+#pragma unroll
+        for (uint32_t k = 0; k < EPL; ++k) asm volatile("" : : "v"(vv[k]));   // arrived before the loop is entered
         for (uint32_t t = (uint32_t)t0; t < t1; ++t) {
             Probe pr;
-            bfs_probe_issue(c, s, xcd, pr, act, vv);
+            bfs_probe_issue(c, s, xcd, pr, vv);
             const bool more = t + 1 < t1;
-            if (more) fetch(t + 1, nact, nvv, nuu);          // next segment travels while this one is probed
-            bfs_probe_finish<STAGED>(c, s, st, L, pr, act, vv, uu);
-            if (more) {
+            fetch(more ? t + 1 : t, nact, nvv, nuu);         // next segment travels while this one is probed (the last asks for itself again)
+            Claim cl;
+            const bool claimed = bfs_claim(c, s, pr, act, cl);           // (as in k_bfs_expand)
+            uint32_t cv[EPL], cu[EPL];
 #pragma unroll
-                for (uint32_t k = 0; k < EPL; ++k) { act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k]; }
+            for (uint32_t k = 0; k < EPL; ++k) {
+                asm volatile("" : : "v"(nvv[k]));    // the next neighbours are waited for here, not at the top of the loop
+                cv[k] = vv[k]; cu[k] = uu[k]; act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k];
             }
+            if (claimed) bfs_deliver<STAGED>(c, s, st, L, pr, cl, cv, cu);
         }
     }
     bfs_flush<STAGED>(c, s, st, L);
