@@ -104,41 +104,52 @@ __device__ __forceinline__ void bfs_enqueue(const Ctx &c, const BfsState &s, con
                                             uint32_t o, uint32_t v)
 {
     uint64_t m = ballot(won);
+    if (!m) return;
     const uint32_t lane = lane_id();
-    while (m) {
-        const uint32_t leader = (uint32_t)__builtin_ctzll(m);
-        const uint32_t ol = bcast32(o, leader);
-        const uint64_t grp = ballot(won && o == ol);
-        const uint32_t n = (uint32_t)__builtin_popcountll(grp);
-        uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], ol);
-        uint64_t *tail = bfs_tails(c, s, ol) + T_TAIL0 + (L + 1) % 3;
-        if (STAGED) {
+    if (STAGED) {
+        // Every winner takes its place in its owner's staging buffer with a returning LDS add on the
+        // wave's counter for that owner (lanes with the same owner are served one after the other by
+        // the LDS itself) -- no loop over the owners present in the wave, which with two dozen winners
+        // per chunk on a heavy level was half of a chunk's time.  A counter holds at most
+        // STAGE_BLOCK - 1 between calls and grows by at most 64 here, so it stays below STAGE_CAP.
+        if (won) {
+            const uint32_t pos = __hip_atomic_fetch_add(&st.cnt[o], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            st.buf[o * STAGE_CAP + pos] = v;
+        }
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t cn_l = lane < (uint32_t)c.npes ? st.cnt[lane] : 0;          // npes <= STAGE_PES <= 64
+        uint64_t full = ballot(cn_l >= STAGE_BLOCK);
+        while (full) {                                                             // rare: a block of 64 leaves
+            const uint32_t ol = (uint32_t)__builtin_ctzll(full);
+            full &= full - 1;
+            const uint32_t cn = bcast32(cn_l, ol);
             uint32_t *buf = st.buf + ol * STAGE_CAP;
-            uint32_t cn = st.cnt[ol];
-            if (won && o == ol) buf[cn + rank_in(grp)] = v;
-            cn += n;
+            uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], ol);
+            uint64_t base = 0;
+            if (lane == 0) base = atomic_fetch_add(bfs_tails(c, s, ol) + T_TAIL0 + (L + 1) % 3, (uint64_t)STAGE_BLOCK);
+            base = bcast64(base, 0);
+            if (lane < STAGE_BLOCK) __builtin_nontemporal_store(buf[lane], queue + base + lane);   // put: one full block
+            const uint32_t rest = cn - STAGE_BLOCK;
+            const uint32_t moved = lane < rest ? buf[STAGE_BLOCK + lane] : 0;
             __builtin_amdgcn_wave_barrier();
-            while (cn >= STAGE_BLOCK) {
-                uint64_t base = 0;
-                if (lane == 0) base = atomic_fetch_add(tail, (uint64_t)STAGE_BLOCK);
-                base = bcast64(base, 0);
-                if (lane < STAGE_BLOCK) __builtin_nontemporal_store(buf[lane], queue + base + lane);   // put: one full block
-                const uint32_t rest = cn - STAGE_BLOCK;
-                const uint32_t moved = lane < rest ? buf[STAGE_BLOCK + lane] : 0;
-                __builtin_amdgcn_wave_barrier();
-                if (lane < rest) buf[lane] = moved;
-                __builtin_amdgcn_wave_barrier();
-                cn = rest;
-            }
-            if (lane == 0) st.cnt[ol] = cn;
+            if (lane < rest) buf[lane] = moved;
+            if (lane == 0) st.cnt[ol] = rest;
             __builtin_amdgcn_wave_barrier();
-        } else {
+        }
+    } else {
+        while (m) {
+            const uint32_t leader = (uint32_t)__builtin_ctzll(m);
+            const uint32_t ol = bcast32(o, leader);
+            const uint64_t grp = ballot(won && o == ol);
+            const uint32_t n = (uint32_t)__builtin_popcountll(grp);
+            uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], ol);
+            uint64_t *tail = bfs_tails(c, s, ol) + T_TAIL0 + (L + 1) % 3;
             uint64_t base = 0;
             if (lane == leader) base = atomic_fetch_add(tail, (uint64_t)n);
             base = bcast64(base, leader);
             if (won && o == ol) queue[base + rank_in(grp)] = v;       // put v
+            m &= ~grp;
         }
-        m &= ~grp;
     }
 }
 
