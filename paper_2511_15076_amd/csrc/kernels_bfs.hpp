@@ -37,7 +37,10 @@ struct BfsState {
 
 // words inside the per-PE tails block (uint64 each)
 enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, T_NTASKS = 5,
-                  T_ARRIVE = 6 /* workgroups of this PE that have finished the level-end kernel */ };
+                  T_ARRIVE = 6 /* workgroups of this PE that have finished the level-end kernel */,
+                  // running degree sums, per PE and on a line of their own (adds on one address serialise at
+                  // about 12 ns each: one word for the whole device cost 50 us per launch of 4096 waves)
+                  T_DEG_EXPANDED = 16 /* frontiers expanded top-down */, T_DEG_FOUND = 17 /* frontiers discovered */ };
 
 constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
 constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
@@ -84,9 +87,9 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     if (rank == 0) {
         uint64_t *t = bfs_tails(c, s, pe);
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
-        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
-        if (pe == 0) { c.scratch[W_WORK + 1] = 0; c.scratch[W_WORK + 2] = 0; c.scratch[W_WORK + 4] = 0; }  // degree sums, arrival count
+        if (pe == 0) c.scratch[W_WORK + 4] = 0;   // arrival count of the level-end kernel
     }
 }
 
@@ -362,7 +365,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
     bfs_flush<STAGED>(c, s, st, L);
     // degree sum of this level's frontier -> traversed-edge count
     for (int off = 32; off > 0; off >>= 1) degsum += __shfl_down(degsum, off, 64);
-    if (lane == 0 && degsum) atomic_fetch_add(&c.scratch[W_WORK + 1], degsum);
+    if (lane == 0 && degsum) atomic_fetch_add(tails + T_DEG_EXPANDED, degsum);
 }
 
 // Prefix sum over the long rows' segment counts of each PE (one workgroup per
@@ -579,7 +582,7 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
         }
     }
     for (int off = 32; off > 0; off >>= 1) mf += __shfl_down(mf, off, 64);
-    if (lane == 0 && mf) atomic_fetch_add(&c.scratch[W_WORK + 2], mf);
+    if (lane == 0 && mf) atomic_fetch_add(bfs_tails(c, s, pe) + T_DEG_FOUND, mf);
 }
 
 // Optional post-pass: canonical parents.  parent[v] = the smallest neighbour of v whose level is one
@@ -672,7 +675,7 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
             sum += s.row_off[u + 1] - s.row_off[u];
         }
         for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
-        if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(&c.scratch[W_WORK + 2], sum);
+        if ((threadIdx.x & 63) == 0 && sum) atomic_fetch_add(bfs_tails(c, s, pe) + T_DEG_FOUND, sum);
     }
     // Everything the last workgroup reads below is an atomically updated counter, and those resolve at
     // the memory side: each wave's adds are complete (workgroup-scope release = wait for their
@@ -691,19 +694,25 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
     }
     __syncthreads();
     if (!last || threadIdx.x >= 64) return;
-    uint64_t total = 0;
+    uint64_t total = 0, expanded = 0, found = 0;
     for (uint32_t q = threadIdx.x; q < (uint32_t)c.npes; q += 64) {
         uint64_t *t = bfs_tails(c, s, q);
         total += __hip_atomic_load(&t[T_TAIL0 + next % 3], __ATOMIC_RELAXED, SHMEMX_AGENT);
+        expanded += __hip_atomic_load(&t[T_DEG_EXPANDED], __ATOMIC_RELAXED, SHMEMX_AGENT);
+        found += __hip_atomic_load(&t[T_DEG_FOUND], __ATOMIC_RELAXED, SHMEMX_AGENT);
         t[T_TAIL0 + (next + 1) % 3] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0;
     }
-    for (int off = 32; off > 0; off >>= 1) total += __shfl_down(total, off, 64);
+    for (int off = 32; off > 0; off >>= 1) {
+        total += __shfl_down(total, off, 64);
+        expanded += __shfl_down(expanded, off, 64);
+        found += __shfl_down(found, off, 64);
+    }
     if (threadIdx.x == 0) {
         c.scratch[W_WORK] = total;
         host_counts[0] = total;
-        host_counts[1] = __hip_atomic_load(&c.scratch[W_WORK + 1], __ATOMIC_RELAXED, SHMEMX_AGENT);
-        host_counts[2] = __hip_atomic_load(&c.scratch[W_WORK + 2], __ATOMIC_RELAXED, SHMEMX_AGENT);
+        host_counts[1] = expanded;
+        host_counts[2] = found;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
         __hip_atomic_store(host_counts + 3, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
