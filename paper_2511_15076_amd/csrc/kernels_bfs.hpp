@@ -40,7 +40,8 @@ enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, 
                   T_ARRIVE = 6 /* workgroups of this PE that have finished the level-end kernel */,
                   // running degree sums, per PE and on a line of their own (adds on one address serialise at
                   // about 12 ns each: one word for the whole device cost 50 us per launch of 4096 waves)
-                  T_DEG_EXPANDED = 16 /* frontiers expanded top-down */, T_DEG_FOUND = 17 /* frontiers discovered */ };
+                  T_DEG_EXPANDED = 16 /* frontiers expanded top-down */, T_DEG_FOUND = 17 /* frontiers discovered */,
+                  T_FILL = 18 /* write position of k_bfs_fill_queue */ };
 
 constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
 constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     if (rank == 0) {
         uint64_t *t = bfs_tails(c, s, pe);
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
-        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0; t[T_FILL] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
         if (pe == 0) c.scratch[W_WORK + 4] = 0;   // arrival count of the level-end kernel
     }
@@ -525,9 +526,9 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     const uint64_t *linked = (const uint64_t *)ptr(c, s.linked_off, pe);
     int32_t *lv = (int32_t *)ptr(c, s.level_off, pe);
     uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
-    uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], pe);
     uint64_t *tail = bfs_tails(c, s, pe) + T_TAIL0 + (L + 1) % 3;
     uint64_t mf = 0;
+    uint32_t nfound = 0;   // wave-uniform
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
         const uint64_t visw = vis[w];
         const uint64_t todo = ~visw & linked[w];         // unvisited vertices that have neighbours
@@ -571,18 +572,55 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
         const uint64_t fm = ballot(found);
         if (fm == 0) continue;
         if (lane == 0) vis[w] = visw | fm;               // this wave is the only writer of the word
-        uint64_t base = 0;
-        if (lane == 0) base = atomic_fetch_add(tail, (uint64_t)__builtin_popcountll(fm));
-        base = bcast64(base, 0);
+        nfound += (uint32_t)__builtin_popcountll(fm);
         if (found) {
-            queue[base + rank_in(fm)] = (uint32_t)(first + l);
             lv[l] = (int32_t)(L + 1);
             pr[l] = par;
             mf += deg;
         }
     }
+    // The new frontier is only counted here (one add per wave; an add per bitmap word, thousands on
+    // one address per PE, serialised for tens of microseconds).  Its queue is written by
+    // k_bfs_fill_queue from the frontier bitmap if the next level turns out to run top-down.
+    if (lane == 0 && nfound) atomic_fetch_add(tail, (uint64_t)nfound);
     for (int off = 32; off > 0; off >>= 1) mf += __shfl_down(mf, off, 64);
     if (lane == 0 && mf) atomic_fetch_add(bfs_tails(c, s, pe) + T_DEG_FOUND, mf);
+}
+
+// After a bottom-up level, before a top-down one: the owner's queue for level `next` from its frontier
+// bitmap (the bits set during the last level; k_bfs_level_end has built it).  A wave takes 64 consecutive
+// words, one per lane, reserves room for all their bits with one add and writes the vertices.
+__global__ __launch_bounds__(256) void k_bfs_fill_queue(Ctx c, BfsState s, uint32_t next)
+{
+    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
+    const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
+    const uint64_t *front = (const uint64_t *)ptr(c, s.front_off, pe);
+    uint32_t *queue = (uint32_t *)ptr(c, s.queue_off[next & 1], pe);
+    uint64_t *fill = bfs_tails(c, s, pe) + T_FILL;
+    const uint64_t first = (uint64_t)pe * s.vpp;
+    for (uint64_t w0 = my_wave * 64; w0 < s.words; w0 += team_waves * 64) {
+        const uint64_t w = w0 + lane;
+        uint64_t bits = w < s.words ? front[w] : 0;
+        const uint32_t n = (uint32_t)__builtin_popcountll(bits);
+        uint32_t incl = n;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t t = __shfl_up(incl, d, 64);
+            if (lane >= (uint32_t)d) incl += t;
+        }
+        const uint32_t total = bcast32(incl, 63);
+        if (total == 0) continue;
+        uint64_t base = 0;
+        if (lane == 0) base = atomic_fetch_add(fill, (uint64_t)total);
+        base = bcast64(base, 0) + (incl - n);
+        while (bits) {
+            const uint32_t b = (uint32_t)__builtin_ctzll(bits);
+            bits &= bits - 1;
+            queue[base++] = (uint32_t)(first + w * 64 + b);
+        }
+    }
 }
 
 // Optional post-pass: canonical parents.  parent[v] = the smallest neighbour of v whose level is one
@@ -701,7 +739,7 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
         expanded += __hip_atomic_load(&t[T_DEG_EXPANDED], __ATOMIC_RELAXED, SHMEMX_AGENT);
         found += __hip_atomic_load(&t[T_DEG_FOUND], __ATOMIC_RELAXED, SHMEMX_AGENT);
         t[T_TAIL0 + (next + 1) % 3] = 0;
-        t[T_NBIG] = 0; t[T_NTASKS] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_FILL] = 0;
     }
     for (int off = 32; off > 0; off >>= 1) {
         total += __shfl_down(total, off, 64);

@@ -590,6 +590,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     }
     st.frontier_size[0] = 1;
     bool bottom_up = false;
+    bool queue_written = true;   // the frontier's queue exists (a bottom-up level only counts its finds)
     uint32_t L = 0;
     for (;;) {
         if (g->mode == SHMEM_BFS_BOTTOM_UP) bottom_up = true;
@@ -600,11 +601,16 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             if (!bottom_up) bottom_up = m_f > m_u / g->alpha;
             else if (n_f < s.nverts / g->beta && n_f < n_f_prev) bottom_up = false;
         }
+        if (!bottom_up && !queue_written) {
+            hipLaunchKernelGGL(shmemx::k_bfs_fill_queue, grid, block, 0, H.stream, c, s, L);   // from the frontier bitmap
+            queue_written = true;
+        }
         if (bottom_up) {
             // no LDS and few registers: twice the workgroups per PE fill the CUs' wave slots
             shmemx::BfsState s2 = s;
             s2.wgs_per_pe = s.wgs_per_pe * 2;
             hipLaunchKernelGGL(shmemx::k_bfs_bottomup, dim3(grid.x * 2), block, 0, H.stream, c, s2, L);
+            queue_written = false;
         } else if (staged) {
             hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
             hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
