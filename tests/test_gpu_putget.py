@@ -116,6 +116,58 @@ def test_table_large_ops_take_the_streaming_copy(wgs):
     assert np.array_equal(got, w.heaps())
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3, 4, 5, 6])
+def test_random_mixed_tables_match_oracle(seed):
+    # Random tables of all four kinds with random element sizes, strides, counts (zero included) and byte
+    # alignments, executed by the table executor AND by the proxy executor.  Inside a window every op owns
+    # one local and one remote 4 KiB stripe, so the table is race-free by construction; later windows
+    # reuse stripes, so an op that is dropped, duplicated or misplaced shows in the whole-heap comparison.
+    rng = np.random.default_rng(1000 + seed)
+    npes = int(rng.integers(2, 6))
+    stripes, sb = 48, 4096
+    hb = 2 * stripes * sb
+    window = int(rng.integers(5, stripes // 2))
+    nwin = 12
+    ops = np.zeros(window * nwin, dtype=workgen.OP_DESC)
+    for wdx in range(nwin):
+        # per PE, which local / remote stripes are still free in this window
+        free_l = [list(rng.permutation(stripes)) for _ in range(npes)]
+        free_r = [list(rng.permutation(stripes)) for _ in range(npes)]
+        for k in range(window):
+            me, pe = int(rng.integers(0, npes)), int(rng.integers(0, npes))
+            lo = int(free_l[me].pop()) * sb                       # local stripes: first half of the heap
+            so = (stripes + int(free_r[pe].pop())) * sb           # remote stripes: second half
+            kind = int(rng.integers(0, 4))
+            if kind < 2:
+                n = int(rng.choice([0, 1, 2, 7, 8, 9, 16, 31, 64, 100, 255, 256, 1000, 2048, 3000, sb - 64]))
+                a, b = int(rng.integers(0, 64)), int(rng.integers(0, 64))
+                ops[wdx * window + k] = (kind, me, pe, 1, lo + a, so + b, n, 1, 1, 0)
+            else:
+                eb = int(rng.choice([1, 2, 4, 8]))
+                ls, ss = int(rng.integers(1, 10)), int(rng.integers(1, 10))
+                room = sb // eb
+                cnt = int(rng.integers(0, (room - 8) // max(ls, ss) + 1))
+                a, b = int(rng.integers(0, 4)) * eb, int(rng.integers(0, 4)) * eb
+                ops[wdx * window + k] = (kind, me, pe, eb, lo + a, so + b, cnt, ls, ss, 0)
+    init = seeded_heaps(npes, hb, 300 + seed)
+    w = oracle_world(init)
+    assert w.op_batch(ops, window) == 0
+    want = w.heaps()
+    wgs = int(rng.choice([1, 2, 3, 8]))
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.op_batch(to_dev(ops), len(ops), window, wgs)
+        sh.stream_sync()
+        assert np.array_equal(heaps_of(heap, npes), want), "table executor"
+        # the proxy carries out descriptors one after the other in table order: the same result
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        px = sh.proxy_create(64)
+        sh.proxy_submit(px, to_dev(ops), len(ops), 2)
+        sh.proxy_quiet(px)
+        assert np.array_equal(heaps_of(heap, npes), want), "proxy executor"
+        sh.proxy_destroy(px)
+
+
 def test_single_ops_byte_granular():
     npes, hb = 3, 1 << 18
     init = seeded_heaps(npes, hb, 42)
