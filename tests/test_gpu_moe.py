@@ -102,6 +102,22 @@ CASES = [
 ]
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(7000 + seed)
+    P = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    epp = int(rng.choice([1, 2, 3, 5, 9]))
+    E = P * epp
+    T = int(rng.integers(1, 40))
+    K = int(rng.integers(1, min(E, 8) + 1))
+    Hb = 16 * int(rng.choice([1, 2, 3, 17, 64, 65, 129]))
+    ntok = [int(rng.integers(0, T + 1)) for _ in range(P)]
+    return (P, E, T, K, Hb, ntok, str(rng.choice(["uniform", "zipf"])), float(rng.choice([0.0, 0.0, 0.25])),
+            int(rng.choice([1, 2, 3, 4, 7, 9])))
+
+
+CASES += [_random_case(seed) for seed in range(8)]       # shapes nobody chose: sizes, raggedness and team sizes drawn at random
+
+
 @pytest.mark.parametrize("P,E,T,K,Hb,ntok,dist,drop,wgs", CASES)
 def test_dispatch_and_combine_match_oracle(P, E, T, K, Hb, ntok, dist, drop, wgs):
     topk, ntok = workgen.moe_routing(100 + P + E, P, E, T, K, ntok=ntok, dist=dist, drop=drop)
