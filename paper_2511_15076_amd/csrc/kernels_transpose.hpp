@@ -60,26 +60,32 @@ __global__ __launch_bounds__(256) void k_transpose(Ctx c, TransposeArgs a)
 // The same with 16-byte gets and 16-byte stores (four uint32 or two uint64 per lane): a tile row is then
 // 16 or 32 lanes wide, so one wave instruction covers four or two tile rows.  Needs rows, i.e. n / npes,
 // to be a multiple of the vector length (every vector then lies inside one row block and is 16-byte
-// aligned); the host falls back to the element-wise kernel otherwise.
-template <typename T>
+// aligned); the host falls back to the element-wise kernel otherwise.  TJ source rows make one tile:
+// 64, or 128 for 4-byte elements, which doubles the contiguous run of every output row to 512 bytes
+// (runs of 256 bytes reach about 0.65 of the HBM peak in the put / get sweep as well, 512 bytes 0.67).
+template <typename T, uint32_t TJ>
 __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
 {
     constexpr uint32_t E = 16 / sizeof(T);                 // elements per vector
-    constexpr uint32_t LANES = TR_TILE / E;                // lanes per tile row
-    constexpr uint32_t ROWS = 256 / LANES;                 // tile rows per step of the workgroup
-    constexpr uint32_t STEPS = TR_TILE / ROWS;
+    constexpr uint32_t LANES_IN = TR_TILE / E;             // lanes per source row of the tile (64 elements)
+    constexpr uint32_t ROWS_IN = 256 / LANES_IN;           // source rows per step of the workgroup
+    constexpr uint32_t STEPS_IN = TJ / ROWS_IN;
+    constexpr uint32_t LANES_OUT = TJ / E;                 // lanes per output row of the tile (TJ elements)
+    constexpr uint32_t ROWS_OUT = 256 / LANES_OUT;
+    constexpr uint32_t STEPS_OUT = TR_TILE / ROWS_OUT;
     typedef T vec __attribute__((ext_vector_type(E)));
-    __shared__ T tile[TR_TILE][TR_TILE + 1];
+    __shared__ T tile[TJ][TR_TILE + 1];                    // [source row][local column]; +1: conflict-free column reads
     const uint32_t pe = blockIdx.x / a.wgs_per_pe, wg = blockIdx.x % a.wgs_per_pe;
-    const uint32_t vx = threadIdx.x % LANES, ry = threadIdx.x / LANES;
-    const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TR_TILE - 1) / TR_TILE;
+    const uint32_t vx = threadIdx.x % LANES_IN, ry = threadIdx.x / LANES_IN;
+    const uint32_t ox = threadIdx.x % LANES_OUT, oy = threadIdx.x / LANES_OUT;
+    const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TJ - 1) / TJ;
     T *out = (T *)ptr(c, a.out_off, pe);
     for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
-        const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TR_TILE;
-        vec v[STEPS];
+        const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TJ;
+        vec v[STEPS_IN];
 #pragma unroll
-        for (uint32_t k = 0; k < STEPS; ++k) {
-            const uint64_t j = j0 + ry + k * ROWS, col = i0 + vx * E;      // source row; first local column of the vector
+        for (uint32_t k = 0; k < STEPS_IN; ++k) {
+            const uint64_t j = j0 + ry + k * ROWS_IN, col = i0 + vx * E;   // source row; first local column of the vector
             v[k] = vec(0);
             if (j < a.n && col < a.rows) {                                 // rows % E == 0: a vector is in or out as a whole
                 const uint32_t q = (uint32_t)(j / a.rows);
@@ -88,18 +94,18 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
             }
         }
 #pragma unroll
-        for (uint32_t k = 0; k < STEPS; ++k)
+        for (uint32_t k = 0; k < STEPS_IN; ++k)
 #pragma unroll
-            for (uint32_t e = 0; e < E; ++e) tile[ry + k * ROWS][vx * E + e] = v[k][e];
+            for (uint32_t e = 0; e < E; ++e) tile[ry + k * ROWS_IN][vx * E + e] = v[k][e];
         __syncthreads();
 #pragma unroll
-        for (uint32_t k = 0; k < STEPS; ++k) {
-            const uint32_t r = ry + k * ROWS;                              // tile column = local output row
-            const uint64_t i = i0 + r, j = j0 + vx * E;
+        for (uint32_t k = 0; k < STEPS_OUT; ++k) {
+            const uint32_t r = oy + k * ROWS_OUT;                          // tile column = local output row
+            const uint64_t i = i0 + r, j = j0 + ox * E;
             if (i < a.rows && j < a.n) {                                   // n % E == 0 as well
                 vec o;
 #pragma unroll
-                for (uint32_t e = 0; e < E; ++e) o[e] = tile[vx * E + e][r];
+                for (uint32_t e = 0; e < E; ++e) o[e] = tile[ox * E + e][r];
                 __builtin_nontemporal_store(o, (vec *)(out + i * a.n + j));
             }
         }

@@ -1070,10 +1070,10 @@ int shmem_transpose(void *out_sym, const void *in_sym, size_t n, size_t elem_byt
     const size_t vec_elems = 16 / elem_bytes;
     const bool wide = rows % vec_elems == 0 && ((ooff | ioff) & 15) == 0;   // then n % vec_elems == 0, too
     if (elem_bytes == 4) {
-        if (wide) hipLaunchKernelGGL(shmemx::k_transpose_vec<uint32_t>, grid, block, 0, H.stream, ctx(), a);
+        if (wide) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint32_t, 128>), grid, block, 0, H.stream, ctx(), a);
         else hipLaunchKernelGGL(shmemx::k_transpose<uint32_t>, grid, block, 0, H.stream, ctx(), a);
     } else {
-        if (wide) hipLaunchKernelGGL(shmemx::k_transpose_vec<uint64_t>, grid, block, 0, H.stream, ctx(), a);
+        if (wide) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint64_t, 64>), grid, block, 0, H.stream, ctx(), a);
         else hipLaunchKernelGGL(shmemx::k_transpose<uint64_t>, grid, block, 0, H.stream, ctx(), a);
     }
     return launched();

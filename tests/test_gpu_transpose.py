@@ -16,6 +16,7 @@ from gpu_util import heaps_of, shmem_world  # noqa: E402
 @pytest.mark.parametrize("npes,n,eb,wgs", [
     (1, 5, 4, 1), (2, 64, 4, 2), (4, 128, 8, 3), (3, 195, 4, 2),       # ragged tiles: 65 rows per PE
     (8, 1000, 4, 5), (16, 1024, 8, 4), (5, 70, 8, 1),
+    (4, 320, 4, 3), (2, 392, 4, 2),                                    # 16-byte path with ragged 128-row and 64-column tiles
 ])
 def test_transpose_matches_igets(npes, n, eb, wgs):
     R = n // npes
