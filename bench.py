@@ -253,7 +253,7 @@ def extra_latency(sh, torch):
     return {"pingpong_round_trip_us": pp, "barrier_round_us": bar}
 
 
-def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=36):
+def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=None):
     """MoE-shaped low-latency dispatch / combine (Sec. IV-E, sizes of Sec. V-C): 8 emulated PEs,
     288 experts, top-8 routing, 14,336-byte tokens (14,352-byte dispatch messages), 1-128 tokens
     per PE.  Per launch: microseconds, and payload bytes moved between PEs per second."""
@@ -279,20 +279,22 @@ def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_toke
                                                    ntok=ntok)
             tk, nt = torch.from_numpy(topk_np).to(dev), torch.from_numpy(ntok_np).to(dev)
             routes = int((topk_np >= 0).sum())
-            d_ms = _median_ms(lambda: sh.moe_dispatch(moe, x, tk, nt, recv_x, recv_info, recv_range, recv_count, wgs),
+            # team size: 36 workgroups per PE (one per local expert) while the batch is latency-bound; 32
+            # (one workgroup per CU over the 8 PEs, no CU shared by two) once it is bandwidth-bound
+            w = wgs if wgs else (36 if ntok < 32 else 32)
+            d_ms = _median_ms(lambda: sh.moe_dispatch(moe, x, tk, nt, recv_x, recv_info, recv_range, recv_count, w),
                               lambda: None, reps=20, warm=3)
-            c_ms = _median_ms(lambda: sh.moe_combine(moe, recv_x, recv_info, recv_range, tk, nt, combined, wgs),
+            c_ms = _median_ms(lambda: sh.moe_combine(moe, recv_x, recv_info, recv_range, tk, nt, combined, w),
                               lambda: None, reps=20, warm=3)
             sh.stream_sync()
             assert int(recv_count.sum().item()) == routes
             res[str(ntok)] = {"dispatch_us": round(d_ms * 1e3, 2), "combine_us": round(c_ms * 1e3, 2),
                               "dispatch_GBs": round(routes * (hidden + 16) / d_ms / 1e6, 1),
-                              "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes}
+                              "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes, "wgs_per_pe": w}
         sh.moe_destroy(moe)
     finally:
         sh.finalize()
-    return {"npes": npes, "num_experts": num_experts, "topk": topk, "hidden_bytes": hidden, "wgs_per_pe": wgs,
-            "tokens_per_pe": res}
+    return {"npes": npes, "num_experts": num_experts, "topk": topk, "hidden_bytes": hidden, "tokens_per_pe": res}
 
 
 def extra_transpose(sh, torch, npes=8, n=16384, wgs=256):

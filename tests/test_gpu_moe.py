@@ -191,15 +191,16 @@ def test_argument_checks():
 
 
 def test_full_size_batch_as_benchmarked():
-    # the largest cell bench.py times: 8 PEs, 288 experts, top-8, 128 tokens of 14,336 bytes per PE,
-    # 36 workgroups per PE; the oracle affords the whole batch (8192 messages)
-    P, E, T, K, Hb, wgs = 8, 288, 128, 8, 14336, 36
+    # the largest cell bench.py times: 8 PEs, 288 experts, top-8, 128 tokens of 14,336 bytes per PE, with
+    # the team sizes it uses (36 workgroups per PE for small batches, 32 -- one per CU -- for large ones);
+    # the oracle affords the whole batch (8192 messages)
+    P, E, T, K, Hb = 8, 288, 128, 8, 14336
     topk, ntok = workgen.moe_routing(npes=P, num_experts=E, max_tokens=T, topk=K, ntok=T)
     x = workgen.moe_tokens(npes=P, max_tokens=T, hidden_bytes=Hb)
     want = oracle_run(P, E, T, K, Hb, x, topk, ntok, rounds=1, mutate=bump)
     with shmem_world(P, heap_bytes_for(P, E, T, K, Hb)):
         dm = DevMoe(P, E, T, K, Hb)
-        for _ in range(2):
+        for wgs in (36, 32):
             got = dm.dispatch(x, topk, ntok, wgs)
             check_dispatch(got, want[0][0])
             comb = dm.combine(bump(got[0], got[3]), wgs)
