@@ -142,6 +142,22 @@ def test_fence_and_quiet_order_data_before_the_flag(nbytes, use_quiet):
                 call()
 
 
+def test_cooperative_launch_switch(monkeypatch):
+    # MI_SHMEM_COOPERATIVE_LAUNCH=1 (read at init) launches the kernels with in-kernel waits cooperatively:
+    # same results, the formal residency guarantee instead of the occupancy check alone
+    monkeypatch.setenv("MI_SHMEM_COOPERATIVE_LAUNCH", "1")
+    npes, wgs, rounds = 8, 3, 50
+    with shmem_world(npes, 4096) as (heap, base):
+        slots = sh.malloc(8 * npes)
+        errors = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        sh.barrier_epochs(slots, rounds, wgs, errors)
+        sh.fence_litmus(sh.malloc(1024), 256, 20, 0, errors)
+        sh.stream_sync()
+        assert int(errors.item()) == 0
+        off = slots - base
+        assert (heaps_of(heap, npes)[:, off:off + 8 * npes].view(np.uint64) == rounds).all()
+
+
 def test_sync_entry_point_errors():
     with shmem_world(4, 1 << 16) as (heap, base):
         gin = sh.gin_create(2, 1)
