@@ -220,7 +220,7 @@ class World:
             raise RuntimeError(f"orc_bfs failed: {rc}")
         stats = {"nlevels": st.nlevels, "reached": st.reached,
                  "edges_traversed": st.edges_traversed,
-                 "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}
+                 "frontier_size": [int(st.frontier_size[i]) for i in range(min(st.nlevels, 64))]}
         return level, parent, stats
 
 

@@ -556,8 +556,7 @@ int orc_bfs(orc_world *w, uint32_t nverts, const uint64_t *row_off, const uint32
         uint64_t total = 0;
         for (int p = 0; p < npes; ++p) { uint64_t t; memcpy(&t, w->heap[p] + tl + 8 * cur, 8); total += t; }
         if (total == 0) break;
-        if (L >= 64) { rc = ORC_ERR_OUT_OF_RANGE; goto done; }
-        stats->frontier_size[L] = total;
+        if (L < 64) stats->frontier_size[L] = total;   /* the record holds the first 64 levels; nlevels counts all */
         for (int p = 0; p < npes; ++p) {
             uint64_t cnt; memcpy(&cnt, w->heap[p] + tl + 8 * cur, 8);
             for (uint64_t k = 0; k < cnt; ++k) {

@@ -104,7 +104,7 @@ typedef struct {
     uint32_t nlevels;          /* number of non-empty frontiers (root's counts) */
     uint64_t reached;          /* vertices with level >= 0                      */
     uint64_t edges_traversed;  /* (sum of degrees of reached vertices) / 2      */
-    uint64_t frontier_size[64];/* vertices per level                            */
+    uint64_t frontier_size[64];/* vertices per level, the first 64 levels       */
 } orc_bfs_stats;
 #define ORC_BFS_NONE 0xFFFFFFFFu
 int orc_bfs(orc_world *w, uint32_t nverts, const uint64_t *row_off, const uint32_t *nbr,

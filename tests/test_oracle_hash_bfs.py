@@ -110,7 +110,7 @@ def check_bfs(row, nbr, root, level, parent, stats):
     assert stats["reached"] == int(reached.sum())
     deg = np.diff(row).astype(np.int64)
     assert stats["edges_traversed"] == int(deg[reached].sum()) // 2
-    assert stats["frontier_size"] == [int((level == l).sum()) for l in range(stats["nlevels"])]
+    assert stats["frontier_size"] == [int((level == l).sum()) for l in range(min(stats["nlevels"], 64))]   # the record holds 64 levels
     assert stats["nlevels"] == int(level.max()) + 1
 
 
@@ -137,6 +137,26 @@ def test_bfs_tiny_graphs(npes):
     level, parent, stats = w.bfs(row, nbr, 0)
     assert list(level[:10]) == list(range(10)) and stats["nlevels"] == 10
     assert list(parent[1:10]) == list(range(9))
+
+
+@pytest.mark.parametrize("npes", [1, 4])
+def test_bfs_deep_path_and_cycle(npes):
+    # closed forms far beyond the 64 levels whose sizes the record holds: on a path the level of a vertex is
+    # its distance along the path, on a cycle the shorter way round
+    n = 501
+    row, nbr = workgen.csr_from_edges(n, np.arange(0, n - 1, dtype=np.uint32), np.arange(1, n, dtype=np.uint32))
+    for root in (0, 137, n - 1):
+        level, parent, stats = world_for(n, npes).bfs(row, nbr, root)
+        assert np.array_equal(level, np.abs(np.arange(n) - root))
+        assert stats["nlevels"] == max(root, n - 1 - root) + 1 and stats["reached"] == n and stats["edges_traversed"] == n - 1
+        assert len(stats["frontier_size"]) == 64
+        assert stats["frontier_size"] == [1] + [(1 if k <= root else 0) + (1 if k <= n - 1 - root else 0) for k in range(1, 64)]
+        check_bfs(row, nbr, root, level, parent, stats)
+    row, nbr = workgen.csr_from_edges(n, np.arange(0, n, dtype=np.uint32), (np.arange(0, n, dtype=np.uint32) + 1) % n)
+    level, parent, stats = world_for(n, npes).bfs(row, nbr, 17)
+    d = np.abs(np.arange(n) - 17)
+    assert np.array_equal(level, np.minimum(d, n - d))
+    assert stats["nlevels"] == n // 2 + 1 and stats["frontier_size"] == [1] + [2] * 63
 
 
 @pytest.mark.parametrize("scale,npes", [(8, 4), (12, 16), (11, 5)])
