@@ -71,7 +71,12 @@ size_t shmem_scratch_bytes(int npes);
  * heap_bytes_per_pe a multiple of 256.  dev_scratch: DEVICE,
  * shmem_scratch_bytes(npes) bytes, 256-byte aligned; the library zeroes it.
  * hip_stream: a hipStream_t (NULL = the default stream).
- * Errors: ALREADY_INIT, INVALID_ARG, ALIGN, DEVICE. */
+ * Both buffers must come from the HIP runtime this library is linked to: a
+ * process that holds a second copy of the runtime (a Python wheel that ships
+ * its own) loads that one FIRST, so that the library binds to it, or the
+ * pointers mean nothing here (DEVICE).  If the runtime can name the
+ * allocation behind a buffer and it is shorter than stated: OUT_OF_RANGE.
+ * Errors: ALREADY_INIT, INVALID_ARG, ALIGN, OUT_OF_RANGE, DEVICE. */
 int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scratch, void *hip_stream);
 /* Waits for the stream, forgets everything.  Live allocations are dropped. */
 int shmem_finalize(void);
@@ -216,7 +221,7 @@ typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */
     uint64_t edges_traversed;   /* (sum of degrees of reached vertices) / 2    */
-    uint64_t frontier_size[64]; /* vertices per level                          */
+    uint64_t frontier_size[64]; /* vertices per level, the first 64 levels     */
 } shmem_bfs_stats;
 #define SHMEM_BFS_NONE 0xFFFFFFFFu
 int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_t *dev_nbr,
@@ -242,8 +247,9 @@ int shmem_bfs_configure(void *graph, int mode, int alpha, int beta);
 /* Runs one search; blocks the host (one stream sync per level).  dev_level
  * (int32[nverts], -1 = unreached) and dev_parent (uint32[nverts],
  * SHMEM_BFS_NONE = unreached; parent[root] = root) are DEVICE and may be NULL;
- * stats is HOST and may be NULL.  Errors: INVALID_ARG (root >= nverts, more
- * than 64 levels), DEVICE. */
+ * stats is HOST and may be NULL.  A search may have any number of levels
+ * (nlevels counts them all; a histogram beyond the first 64 follows from
+ * dev_level).  Errors: INVALID_ARG (root >= nverts), DEVICE. */
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
 
 /* ---- the paper's device API shape: signals, counters, put with actions (Sec. III-A, III-B) ---- */

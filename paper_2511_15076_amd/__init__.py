@@ -40,6 +40,15 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
         "This package has no CPU fallback.")
 
+# The library must share ONE HIP runtime with whoever allocates the device memory it is handed.  PyTorch's
+# wheel ships its own copy of the runtime; if the library were loaded first it would bind to the system's copy
+# and torch's pointers would mean nothing to it (shmem_init then fails with ERR_DEVICE).  So where torch is
+# installed it is loaded first, whatever order the caller imports things in.
+try:
+    import torch as _torch  # noqa: F401
+except ImportError:  # callers that bring device memory from elsewhere (plain HIP through ctypes, say)
+    _torch = None
+
 _L = C.CDLL(LIB_PATH)
 _vp, _i, _u64, _sz, _pd = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t, C.c_ssize_t
 _SIG = {
@@ -253,7 +262,7 @@ def bfs(graph, root, dev_level=None, dev_parent=None):
     st = BfsStats()
     _check(_L.shmem_bfs(graph, int(root), _addr(dev_level), _addr(dev_parent), C.byref(st)), "shmem_bfs")
     return {"nlevels": st.nlevels, "reached": st.reached, "edges_traversed": st.edges_traversed,
-            "frontier_size": [int(st.frontier_size[i]) for i in range(st.nlevels)]}
+            "frontier_size": [int(st.frontier_size[i]) for i in range(min(st.nlevels, 64))]}
 
 
 def gin_create(nsignals, ncounters):

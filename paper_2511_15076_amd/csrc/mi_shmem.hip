@@ -189,6 +189,19 @@ size_t shmem_scratch_bytes(int npes)
     return (words * 8 + 255) / 256 * 256;
 }
 
+// False only when the runtime knows the allocation that holds p and it ends before p + bytes.  (A
+// pointer the runtime cannot describe is left to the first runtime call that uses it.)
+static bool device_range_too_small(const void *p, size_t bytes)
+{
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return (uintptr_t)p + bytes > (uintptr_t)base + size;
+}
+
 int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scratch, void *hip_stream)
 {
     std::lock_guard<std::mutex> g(H.mu);
@@ -198,6 +211,9 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (heap_bytes_per_pe > SIZE_MAX / (size_t)npes) return SHMEM_ERR_INVALID_ARG;
+    if (device_range_too_small(dev_heap, (size_t)npes * heap_bytes_per_pe) ||
+        device_range_too_small(dev_scratch, shmem_scratch_bytes(npes))) return SHMEM_ERR_OUT_OF_RANGE;
     hipStream_t s = (hipStream_t)hip_stream;
     if (hipMemsetAsync(dev_scratch, 0, shmem_scratch_bytes(npes), s) != hipSuccess) return SHMEM_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess) return SHMEM_ERR_DEVICE;
@@ -589,6 +605,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
         m_f = cum_mf = counts[2];
     }
     st.frontier_size[0] = 1;
+    st.reached = 1;
     bool bottom_up = false;
     bool queue_written = true;   // the frontier's queue exists (a bottom-up level only counts its finds)
     uint32_t L = 0;
@@ -623,13 +640,13 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
         if (int rc = bfs_level_end(s, L + 1, hybrid, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
         ++L;
         if (counts[0] == 0) break;
-        if (L >= 64) return SHMEM_ERR_INVALID_ARG;
-        st.frontier_size[L] = counts[0];
+        if (L >= (uint32_t)INT32_MAX) return SHMEM_ERR_INVALID_ARG;   // levels are int32
+        if (L < 64) st.frontier_size[L] = counts[0];
+        st.reached += counts[0];
         n_f_prev = n_f; n_f = counts[0];
         if (hybrid) { m_f = counts[2] - cum_mf; cum_mf = counts[2]; }
     }
     st.nlevels = L;
-    for (uint32_t l = 0; l < L; ++l) st.reached += st.frontier_size[l];
     st.edges_traversed = (hybrid ? counts[2] : counts[1]) / 2;
     if (g->canonical) hipLaunchKernelGGL(shmemx::k_bfs_canonical, grid, block, 0, H.stream, c, s);
     if (dev_level || dev_parent) {

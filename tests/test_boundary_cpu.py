@@ -80,3 +80,18 @@ def test_bench_refers_only_to_functions_it_defines():
     local = {n.id for n in ast.walk(tree) if isinstance(n, ast.Name) and isinstance(n.ctx, ast.Store)}
     missing = {c for c in called if c not in defined and c not in local and not hasattr(builtins, c)}
     assert not missing, missing
+
+
+def test_binding_loads_torch_before_the_library():
+    # torch ships its own HIP runtime; the library must bind to that copy whatever the caller imports first
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "assert 'torch' not in sys.modules\n"
+            "import paper_2511_15076_amd\n"
+            "assert 'torch' in sys.modules\n"
+            "maps = open('/proc/self/maps').read()\n"
+            "paths = {l.split()[-1] for l in maps.splitlines() if 'libamdhip64' in l}\n"
+            "assert len(paths) == 1, paths\n") % (ROOT,)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]

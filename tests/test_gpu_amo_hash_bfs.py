@@ -269,6 +269,7 @@ def run_bfs_case(row, nbr, roots, npes, wgs, mode=0):
             level, parent = as_np(dl, np.int32).copy(), as_np(dp, np.uint32).copy()
             olevel, oparent, ostats = w.bfs(row, nbr, int(root))
             assert np.array_equal(level, olevel)          # levels are unique
+            ostats = dict(ostats, frontier_size=ostats["frontier_size"][:64])   # the C struct holds the first 64 levels
             assert stats == ostats                        # sizes per level, reached, traversed edges
             check_tree(row, nbr, int(root), level, parent)
             if mode & sh.BFS_CANONICAL_PARENTS:           # the one tree that can be compared vertex by vertex
@@ -285,6 +286,17 @@ def test_bfs_rmat(scale, npes, wgs, mode):
     row, nbr = workgen.rmat_csr(scale)
     roots = workgen.bfs_roots(row, 3)
     run_bfs_case(row, nbr, roots, npes, wgs, mode)
+
+
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP | sh.BFS_CANONICAL_PARENTS])
+def test_bfs_deep_graphs(mode):
+    # far more levels than the 64 whose sizes the statistics record: a path of 700 vertices with a few chords
+    # and side branches, searched from one end, from the middle and from a leaf
+    n = 900
+    src = np.r_[np.arange(0, 699), [100, 250, 400, 400], np.arange(700, 760)].astype(np.uint32)
+    dst = np.r_[np.arange(1, 700), [103, 252, 700, 760], np.arange(701, 761)].astype(np.uint32)
+    row, nbr = workgen.csr_from_edges(n, src, dst)
+    run_bfs_case(row, nbr, [0, 350, 699, 759], 3, 2, mode)
 
 
 @pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP])

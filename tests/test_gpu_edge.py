@@ -1,6 +1,10 @@
 """Degenerate inputs through the C ABI: every entry point accepts an empty job, enqueues nothing
 that touches the heap, and leaves the library usable (OpenSHMEM: a transfer of zero elements is a
-no-op, not an error)."""
+no-op, not an error).  Also: set-up with buffers that are too short, and the import order."""
+import os
+import subprocess
+import sys
+
 import numpy as np
 import pytest
 import torch
@@ -86,3 +90,47 @@ def test_bfs_on_graphs_without_edges():
                 assert np.array_equal(parent.cpu().numpy().view(np.uint32), want_parent)
                 assert (st["nlevels"], st["reached"], st["edges_traversed"], st["frontier_size"]) == (1, 1, 0, [1])
                 sh.bfs_destroy(g)
+
+
+def test_init_rejects_buffers_shorter_than_stated():
+    # with torch's cache emptied, an allocation of 16 MiB is a block of its own and the runtime knows where it ends
+    def status_of(*args):
+        try:
+            sh.init(*args)
+        except sh.ShmemError as e:
+            return e.status
+        sh.finalize()
+        return sh.OK
+
+    dev = torch.device("cuda:0")
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    heap = torch.zeros(16 << 20, dtype=torch.uint8, device=dev)
+    big = torch.zeros(16 << 20, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(4), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    assert status_of(4, 16 << 20, heap, scratch, stream) == sh.ERR_OUT_OF_RANGE             # four segments claimed, one provided
+    assert status_of(4, 4 << 20, heap.data_ptr() + 256, scratch, stream) == sh.ERR_OUT_OF_RANGE   # the last segment ends 256 bytes late
+    assert status_of(4, 4 << 20, heap, big.data_ptr() + (16 << 20) - 256, stream) == sh.ERR_OUT_OF_RANGE   # scratch words: 256 bytes left
+    assert status_of(4, 4 << 20, heap, scratch, stream) == sh.OK                             # the exact size is fine
+
+
+def test_package_imported_before_torch_shares_its_runtime():
+    # whichever is imported first, the library and torch must end up on one HIP runtime
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2511_15076_amd as sh\n"
+        "import torch\n"
+        "heap = torch.zeros(2 << 16, dtype=torch.uint8, device='cuda:0')\n"
+        "heap[:4096] = 7\n"
+        "scratch = torch.zeros(sh.scratch_bytes(2), dtype=torch.uint8, device='cuda:0')\n"
+        "sh.init(2, 1 << 16, heap, scratch, torch.cuda.current_stream().cuda_stream)\n"
+        "a = sh.malloc(8192)\n"
+        "sh.put(0, a + 4096, sh.ptr(a, 0), 4096, 1)\n"
+        "sh.stream_sync()\n"
+        "assert int(heap[(1 << 16) + 4096:(1 << 16) + 8192].sum()) == 7 * 4096\n"
+        "sh.finalize()\n"
+        "print('ok')\n") % (root,)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stderr[-2000:]
