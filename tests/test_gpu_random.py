@@ -1,0 +1,137 @@
+"""Shapes nobody chose: the parity checks of the other GPU test files on sizes, PE counts, team sizes, table
+loads, graph families and search modes drawn at random inside the documented limits.  A handful of seeds per
+family by default; MI_SHMEM_RANDOM_CASES=<n> widens every family to n seeds (a few thousand take minutes)."""
+import os
+
+import numpy as np
+import pytest
+
+import workgen
+
+pytestmark = pytest.mark.gpu
+
+sh = pytest.importorskip("paper_2511_15076_amd")
+import test_gpu_amo_hash_bfs as t_ahb  # noqa: E402
+import test_gpu_moe as t_moe  # noqa: E402
+import test_gpu_putget as t_pg  # noqa: E402
+import test_gpu_transpose as t_tr  # noqa: E402
+
+SEEDS = range(100, 100 + int(os.environ.get("MI_SHMEM_RANDOM_CASES", "5")))
+MODES = [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP, sh.BFS_TOP_DOWN | sh.BFS_CANONICAL_PARENTS,
+         sh.BFS_DIRECTION_OPTIMIZING | sh.BFS_CANONICAL_PARENTS, sh.BFS_BOTTOM_UP | sh.BFS_CANONICAL_PARENTS]
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_tables(seed):
+    t_pg.test_random_mixed_tables_match_oracle(seed)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_moe_small(seed):
+    t_moe.test_dispatch_and_combine_match_oracle(*t_moe._random_case(seed))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_moe_large(seed):
+    rng = np.random.default_rng(17000 + seed)
+    P = int(rng.choice([2, 4, 8, 16]))
+    epp = int(rng.choice([1, 2, 4, 9, 36]))
+    T = int(rng.integers(1, 129))
+    K = int(rng.integers(1, min(P * epp, 8) + 1))
+    Hb = 16 * int(rng.integers(1, 900))
+    while P * epp * P * T * Hb > (192 << 20):           # the receive buffers of all PEs, kept to what the oracle does in a blink
+        Hb = max(16, Hb // 32 * 16)
+        if Hb == 16:
+            T = max(1, T // 2)
+    ntok = [int(rng.integers(0, T + 1)) for _ in range(P)]
+    wgs = min(256 // P, int(rng.choice([1, 5, 8, 16, 32, 36, 64])))      # the teams of a launch must be co-resident
+    t_moe.test_dispatch_and_combine_match_oracle(P, P * epp, T, K, Hb, ntok, str(rng.choice(["uniform", "zipf"])),
+                                                 float(rng.choice([0.0, 0.0, 0.25])), wgs)
+
+
+def _hash_case(monkeypatch, seed, npes, slots, load, wgs_insert, wgs_lookup):
+    n = max(8, int(npes * slots * load / 1.125))         # the test body adds n / 8 duplicates
+    keys0, queries0, insert0, lookup0 = workgen.cfg4_keys, workgen.cfg4_queries, sh.hash_insert, sh.hash_lookup
+    monkeypatch.setattr(workgen, "cfg4_keys", lambda n: keys0(seed=5000 + seed, n=n))
+    monkeypatch.setattr(workgen, "cfg4_queries", lambda keys, n: queries0(keys, seed=6000 + seed, n=n))
+    monkeypatch.setattr(sh, "hash_insert", lambda t, s, k, m, out, w: insert0(t, s, k, m, out, wgs_insert))
+    monkeypatch.setattr(sh, "hash_lookup", lambda t, s, k, m, out, w: lookup0(t, s, k, m, out, wgs_lookup))
+    t_ahb.test_hash_insert_lookup(npes, slots, n)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_hash_small(monkeypatch, seed):
+    rng = np.random.default_rng(9000 + seed)
+    npes = int(rng.integers(1, 17))
+    slots = int(rng.integers(1, 600)) * 8 if rng.random() < 0.6 else int(rng.integers(1, 5000))
+    load = float(rng.choice([0.05, 0.3, 0.5, 0.8, 0.95, 1.1]))                # the last overfills the table
+    _hash_case(monkeypatch, seed, npes, slots, load, int(rng.integers(1, 5)), int(rng.integers(1, 5)))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_hash_large(monkeypatch, seed):
+    rng = np.random.default_rng(19000 + seed)
+    npes = int(rng.choice([1, 8, 16, 64]))
+    slots = int(rng.integers(1 << 9, 1 << 16)) // 8 * 8 + (0 if rng.random() < 0.7 else int(rng.integers(1, 8)))
+    load = float(rng.choice([0.3, 0.5, 0.8, 0.95]))
+    cap = 64 if npes == 64 else 256
+    _hash_case(monkeypatch, seed, npes, slots, load, min(cap, int(rng.choice([1, 4, 16, 64, 256]))),
+               min(cap, int(rng.choice([1, 4, 16, 64, 256]))))
+
+
+def _graph(rng, seed, large):
+    kind = 0 if large else int(rng.integers(0, 3))
+    if kind == 0:                                        # R-MAT of several skews and densities
+        scale = int(rng.integers(15, 20)) if large else int(rng.integers(6, 16))
+        ef = int(rng.choice([4, 16, 32] if large else [1, 4, 16, 40]))
+        a = float(rng.choice([0.45, 0.57, 0.65] if large else [0.25, 0.45, 0.57, 0.7]))
+        return workgen.rmat_csr(scale, ef, (a, (1 - a) / 3, (1 - a) / 3), seed=777 + seed)
+    if kind == 1:                                        # uniform random, from far below to far above the giant-component threshold
+        n = int(rng.integers(2, 40000))
+        m = int(n * float(rng.choice([0.5, 1.0, 3.0, 10.0])))
+        return workgen.csr_from_edges(n, rng.integers(0, n, m).astype(np.uint32), rng.integers(0, n, m).astype(np.uint32))
+    n = int(rng.integers(3000, 30000))                   # a few rows beyond the long-row threshold, a sparse background, a path
+    src = [rng.integers(0, n, n // 2), np.arange(0, 500)]
+    dst = [rng.integers(0, n, n // 2), np.arange(1, 501)]
+    for h in rng.integers(0, n, int(rng.integers(1, 5))):
+        d = int(rng.integers(900, 6000))
+        src.append(np.full(d, h))
+        dst.append(rng.integers(0, n, d))
+    return workgen.csr_from_edges(n, np.concatenate(src).astype(np.uint32), np.concatenate(dst).astype(np.uint32))
+
+
+def _bfs_case(seed, large):
+    rng = np.random.default_rng((21000 if large else 11000) + seed)
+    npes = int(rng.choice([1, 3, 8, 16])) if large else int(rng.integers(1, 17))
+    wgs = int(rng.choice([8, 16, 32, 64])) if large else int(rng.integers(1, 9))
+    mode = MODES[int(rng.integers(0, len(MODES)))]
+    row, nbr = _graph(rng, seed, large)
+    deg = np.diff(row)
+    if int((deg > 0).sum()) < 3:
+        pytest.skip("a graph with hardly an edge")
+    roots = list(workgen.bfs_roots(row, 2, seed=seed)) + [int(np.argmax(deg))]
+    t_ahb.run_bfs_case(row, nbr, roots, npes, wgs, mode)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_bfs_small(seed):
+    _bfs_case(seed, False)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_bfs_large(seed):
+    _bfs_case(seed, True)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_transpose(seed):
+    rng = np.random.default_rng(13000 + seed)
+    npes = int(rng.integers(1, 9))
+    t_tr.test_transpose_matches_igets(npes, npes * int(rng.integers(1, 200)), int(rng.choice([4, 8])), int(rng.integers(1, 9)))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_fetch_add(seed):
+    rng = np.random.default_rng(15000 + seed)
+    t_ahb.test_fetch_add_batch(int(rng.integers(0, 2)), str(rng.choice(["uniform", "zipf"])),
+                               int(rng.choice([1, 2, 63, 64, 65, 1000, 4096])), int(rng.choice([1, 2, 3, 7, 16, 64])))
