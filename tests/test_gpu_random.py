@@ -135,3 +135,63 @@ def test_fetch_add(seed):
     rng = np.random.default_rng(15000 + seed)
     t_ahb.test_fetch_add_batch(int(rng.integers(0, 2)), str(rng.choice(["uniform", "zipf"])),
                                int(rng.choice([1, 2, 63, 64, 65, 1000, 4096])), int(rng.choice([1, 2, 3, 7, 16, 64])))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_sweep_cell(seed):
+    rng = np.random.default_rng(23000 + seed)
+    kind = int(rng.integers(0, 4))
+    if kind < workgen.OP_IPUT:
+        # every vector width of the small-message path, the chunked path and its tails
+        count = int(rng.choice([int(rng.integers(1, 64)), int(rng.integers(1, 129)) * 8, int(rng.integers(1, 5000)),
+                                (1 << int(rng.integers(10, 21))) + int(rng.integers(0, 9)) * 8, int(rng.integers(1, 1 << 21))]))
+        eb, rs, ls = 1, 1, 1
+    else:
+        count, eb = int(rng.integers(1, 6000)), int(rng.choice([1, 2, 4, 8]))
+        rs, ls = int(rng.choice([1, 1, 2, 3, 16, 70])), int(rng.choice([1, 1, 2, 5, 32]))
+    nops = int(rng.integers(1, 300)) if count * eb * max(rs, ls) < (1 << 16) else int(rng.integers(1, 6))
+    nslots = int(rng.integers(1, nops + 1))
+    t_pg.test_copy_sweep_cell((kind, count, eb, rs, ls, nops, nslots, int(rng.choice([1, 2, 3, 5, 8, 16, 32]))))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_single_put_get_iput_iget(seed):
+    # stand-alone operations, one after the other with a barrier between them (so overlapping ranges are
+    # fine): any size from nothing to megabytes at any byte alignment, any pair of PEs, self included
+    import torch
+    from gpu_util import heaps_of, shmem_world
+    rng = np.random.default_rng(25000 + seed)
+    npes, hb = int(rng.integers(1, 5)), 12 << 20
+    init = t_pg.seeded_heaps(npes, hb, 3000 + seed)
+    w = t_pg.oracle_world(init)
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        for k in range(10):
+            me, pe = int(rng.integers(0, npes)), int(rng.integers(0, npes))
+            if rng.random() < 0.6:
+                n = int(rng.choice([int(rng.integers(0, 300)), int(rng.integers(0, 70000)), int(rng.integers(1 << 20, 5 << 20)),
+                                    (int(rng.integers(1, 5)) << 20) + 16 * int(rng.integers(0, 300))]))
+                al = int(rng.choice([1, 8, 16, 256]))
+                lo = int(rng.integers(0, (hb // 2 - n) // al + 1)) * al              # local range in the low half
+                so = hb // 2 + int(rng.integers(0, (hb // 2 - n) // al + 1)) * al    # remote range in the high half
+                if k % 2:
+                    assert w.put(me, so, lo, n, pe) == 0
+                    sh.put(me, base + so, sh.ptr(base + lo, me), n, pe)
+                else:
+                    assert w.get(me, lo, so, n, pe) == 0
+                    sh.get(me, sh.ptr(base + lo, me), base + so, n, pe)
+            else:
+                eb = int(rng.choice([1, 2, 4, 8]))
+                ds, ss = int(rng.choice([1, 2, 3, 7, 64])), int(rng.choice([1, 2, 5, 9, 33]))
+                n = int(rng.integers(0, min(20000, (hb // 2 - 1024) // (max(ds, ss) * eb))))
+                lo = int(rng.integers(0, 64)) * eb
+                so = hb // 2 + int(rng.integers(0, 64)) * eb
+                if k % 2:
+                    assert w.iput(me, so, lo, ds, ss, n, eb, pe) == 0
+                    sh.iput(me, base + so, sh.ptr(base + lo, me), ds, ss, n, eb, pe)
+                else:
+                    assert w.iget(me, lo, so, ds, ss, n, eb, pe) == 0
+                    sh.iget(me, sh.ptr(base + lo, me), base + so, ds, ss, n, eb, pe)
+            sh.barrier_all()
+            w.barrier_all()
+        assert np.array_equal(heaps_of(heap, npes), w.heaps())
