@@ -14,6 +14,7 @@ sh = pytest.importorskip("paper_2511_15076_amd")
 import test_gpu_amo_hash_bfs as t_ahb  # noqa: E402
 import test_gpu_moe as t_moe  # noqa: E402
 import test_gpu_putget as t_pg  # noqa: E402
+import test_gpu_sync as t_sync  # noqa: E402
 import test_gpu_transpose as t_tr  # noqa: E402
 
 SEEDS = range(100, 100 + int(os.environ.get("MI_SHMEM_RANDOM_CASES", "5")))
@@ -195,3 +196,17 @@ def test_single_put_get_iput_iget(seed):
             sh.barrier_all()
             w.barrier_all()
         assert np.array_equal(heaps_of(heap, npes), w.heaps())
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_ring_pingpong_barrier(seed):
+    # persistent launches: every workgroup must be resident, so PEs x team stays within the 256 CUs
+    rng = np.random.default_rng(27000 + seed)
+    n = int(rng.choice([1, 2, 3, 5, 8, 16, 32]))
+    ds = int(rng.choice([8 * int(rng.integers(1, 40)), 8 * int(rng.integers(1, 9000)), (1 << int(rng.integers(12, 20))) + 8 * int(rng.integers(0, 40))]))
+    ds = min(ds, (128 << 20) // (n * n) // 8 * 8)        # all heaps together stay within 256 MiB
+    t_sync.ring_cases([(n, ds)], int(rng.integers(1, max(1, min(8, 256 // n)) + 1)), int(rng.integers(1, 6)))
+    t_sync.pingpong_case(int(rng.integers(2, 6)), int(rng.choice([8 * int(rng.integers(1, 64)), int(rng.integers(1, 70000))])),
+                         int(rng.integers(1, 60)))
+    npes = int(rng.choice([1, 2, 3, 7, 16, 64]))
+    t_sync.test_barrier_epochs(npes, int(rng.integers(1, max(1, min(40, 256 // npes)) + 1)), int(rng.integers(1, 400)))

@@ -29,7 +29,11 @@ def gin_offsets(hb_payload, nsig, nctr):
 
 @pytest.mark.parametrize("wgs,rounds", [(1, 1), (3, 1), (2, 25)])
 def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
-    for n, ds in golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000), (4, (1 << 20) + 4096 + 32)]:
+    ring_cases(golden_ring_cases(golden_dir) + [(8, 65536 + 24), (16, 1000), (4, (1 << 20) + 4096 + 32)], wgs, rounds)
+
+
+def ring_cases(cases, wgs, rounds):
+    for n, ds in cases:
         span = n * ds
         send, recv = 0, (span + 255) // 256 * 256
         payload = 2 * recv                                    # bytes the test reserves with shmem_malloc
@@ -71,7 +75,10 @@ def test_ring_exchange_matches_listing2(golden_dir, wgs, rounds):
 
 @pytest.mark.parametrize("nbytes", [8, 128, 4096, 14352, 1 << 20])
 def test_pingpong(nbytes):
-    npes, iters = 4, 200
+    pingpong_case(4, nbytes, 200)
+
+
+def pingpong_case(npes, nbytes, iters):
     pad = (nbytes + 255) // 256 * 256
     buf, payload = 0, 2 * pad
     sig_base, ctr_base = gin_offsets(payload, 1, 0)
