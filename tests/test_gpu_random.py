@@ -210,3 +210,9 @@ def test_ring_pingpong_barrier(seed):
                          int(rng.integers(1, 60)))
     npes = int(rng.choice([1, 2, 3, 7, 16, 64]))
     t_sync.test_barrier_epochs(npes, int(rng.integers(1, max(1, min(40, 256 // npes)) + 1)), int(rng.integers(1, 400)))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_compare_swap(seed):
+    rng = np.random.default_rng(29000 + seed)
+    t_ahb.test_compare_swap_claim_batch(str(rng.choice(["uniform", "zipf"])), int(rng.choice([1, 2, 64, 100, 1024, 8192])))
