@@ -34,7 +34,10 @@
  * The library keeps ONE context per process (init ... finalize).  The allocator
  * calls take a lock; everything else expects one calling thread at a time.
  * All entry points are stream-ordered except shmem_bfs, shmem_stream_sync,
- * shmem_init and shmem_finalize, which block the host.
+ * shmem_init and shmem_finalize, which block the host.  The stream-ordered ones
+ * only launch kernels and keep no per-call state on the host, so they may be
+ * captured into a HIP graph and replayed (not: the proxy calls, which involve
+ * a host thread, and the create / destroy calls).
  */
 #ifndef MI_SHMEM_H
 #define MI_SHMEM_H

@@ -42,7 +42,8 @@ struct MoeState {
     uint64_t hidden, msg;    // token bytes (multiple of 16); dispatch message bytes = 16 + hidden
     uint64_t recv_off;       // symmetric: [epp][npes][max_tokens] dispatch messages
     uint64_t comb_off;       // symmetric: [max_tokens][topk] returned tokens
-    GinState gin;            // signals [0, epp*npes): dispatch counts; then num_experts combine flags
+    GinState gin;            // signals [0, epp*npes): dispatch counts; then num_experts combine flags; then two
+                             // words of the PE's own: combines completed, workgroups of the running combine that know it
 };
 
 struct MoeDispatchArgs {
@@ -60,7 +61,6 @@ struct MoeCombineArgs {
     const uint8_t *expert_out;  // [npes][epp][npes*max_tokens][hidden]
     const int32_t *recv_info, *recv_range, *topk, *ntok;
     uint8_t *combined;          // [npes][max_tokens][hidden]
-    uint64_t epoch;             // number of this combine on the object (flags count calls)
     uint32_t wgs_per_pe;
 };
 
@@ -230,6 +230,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
 {
     __shared__ uint32_t begin[MOE_MAX_PES + 1];
     __shared__ int32_t experts[MOE_MAX_TOPK];
+    __shared__ uint64_t epoch;   // number of this combine on the object: the flags count combines and are never reset
     const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
     const uint32_t P = (uint32_t)c.npes, T = m.max_tokens, K = m.topk;
     const uint32_t lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -237,6 +238,12 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
     const Gin gin{c, m.gin, pe, W};
     const uint32_t flag0 = m.epp * P;                                        // first combine flag ID
     const uint32_t hvecs = (uint32_t)(m.hidden / 16);
+    // The count of completed combines lives on the device (a launch replayed from a graph carries no fresh
+    // arguments): ctl[0] on every PE, written by the workgroup of the team that was the LAST to read it --
+    // every workgroup reads ctl[0] first and only then adds itself to ctl[1] -- at its very end.
+    uint64_t *ctl = gin.signal_word(flag0 + m.num_experts, pe);
+    uint64_t completed = 0, arrival = 0;
+    if (threadIdx.x == 0) completed = __hip_atomic_load(ctl, __ATOMIC_RELAXED, SHMEMX_AGENT);   // used after the send phase
 
     // ---- send: the outputs of this workgroup's local experts go back to the tokens' sources ----
     for (uint32_t le = wg; le < m.epp; le += W) {
@@ -271,15 +278,22 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
         }
     }
 
+    if (threadIdx.x == 0) {
+        epoch = completed + 1;
+        uint64_t one = 1;
+        asm volatile("" : "+v"(one) : "v"(completed));   // the arrival is issued only once ctl[0] has been read
+        arrival = __hip_atomic_fetch_add(ctl + 1, one, __ATOMIC_RELAXED, SHMEMX_AGENT);   // looked at when the workgroup ends
+    }
+
     // ---- receive: this workgroup's tokens ----
     const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
     for (uint32_t t = wg; t < ntok; t += W) {
-        __syncthreads();
+        __syncthreads();                                                     // also publishes `epoch`
         if (threadIdx.x < K) {
             const int32_t e = a.topk[((size_t)pe * T + t) * K + threadIdx.x];
             const bool ok = e >= 0 && (uint32_t)e < m.num_experts;
             experts[threadIdx.x] = ok ? e : -1;
-            if (ok) moe_poll(gin, flag0 + (uint32_t)e, a.epoch);             // that expert's outputs for this PE are in
+            if (ok) moe_poll(gin, flag0 + (uint32_t)e, epoch);               // that expert's outputs for this PE are in
         }
         if (threadIdx.x < 64) acquire();
         wg_acquire();
@@ -300,6 +314,10 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
             }
             __builtin_nontemporal_store(acc, out + v);
         }
+    }
+    if (threadIdx.x == 0 && arrival == W - 1) {      // every workgroup of the team has read ctl[0]: this combine is counted
+        __hip_atomic_store(ctl + 1, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        __hip_atomic_store(ctl, completed + 1, __ATOMIC_RELAXED, SHMEMX_AGENT);
     }
 }
 

@@ -786,8 +786,7 @@ int shmem_fence_litmus(void *buf_sym, size_t nbytes, int rounds, int use_quiet, 
 // ---------------------------------------------------------------------------
 struct shmem_moe {
     shmemx::MoeState st;
-    void *recv_alloc, *comb_alloc, *sig_alloc;
-    uint64_t combines;   // combine calls so far (the flags count them)
+    void *recv_alloc, *comb_alloc, *sig_alloc;   // no call counters here: a launch replayed from a graph must find all its state on the device
 };
 
 int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_bytes, shmem_moe_t *moe_out)
@@ -803,7 +802,7 @@ int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_by
     st.num_experts = (uint32_t)num_experts; st.epp = (uint32_t)(num_experts / H.npes);
     st.max_tokens = (uint32_t)max_tokens; st.topk = (uint32_t)topk;
     st.hidden = hidden_bytes; st.msg = hidden_bytes + shmemx::MOE_META_BYTES;
-    const uint32_t nsig = st.epp * (uint32_t)H.npes + st.num_experts;
+    const uint32_t nsig = st.epp * (uint32_t)H.npes + st.num_experts + 2;   // dispatch counts, combine flags, the combine counter and its arrivals
     unsigned __int128 recv_bytes = (unsigned __int128)st.epp * (unsigned)H.npes * (unsigned)max_tokens * st.msg;
     unsigned __int128 comb_bytes = (unsigned __int128)max_tokens * (unsigned)topk * st.hidden;
     if (recv_bytes > H.seg || comb_bytes > H.seg) { delete m; return SHMEM_ERR_NOMEM; }
@@ -821,7 +820,6 @@ int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_by
     st.gin.signals_off = (uint64_t)((uint8_t *)m->sig_alloc - H.heap);
     st.gin.counters_off = st.gin.signals_off;
     st.gin.nsignals = nsig; st.gin.ncounters = 0;
-    m->combines = 0;
     hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), st.gin);
     if (int rc = launched()) { shmem_moe_destroy(m); return rc; }
     *moe_out = m;
@@ -870,11 +868,9 @@ int shmem_moe_combine(shmem_moe_t m, const void *dev_expert_out, const int32_t *
     shmemx::Ctx c = ctx();
     shmemx::MoeState st = m->st;
     shmemx::MoeCombineArgs a{(const uint8_t *)dev_expert_out, dev_recv_info, dev_recv_range, dev_topk, dev_ntok,
-                             (uint8_t *)dev_combined, m->combines + 1, (uint32_t)wgs_per_pe};
+                             (uint8_t *)dev_combined, (uint32_t)wgs_per_pe};
     void *args[] = {&c, &st, &a};
-    int rc = launch_resident((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(shmemx::MOE_THREADS), args);
-    if (rc == SHMEM_OK) m->combines += 1;
-    return rc;
+    return launch_resident((const void *)shmemx::k_moe_combine, dim3((unsigned)grid), dim3(shmemx::MOE_THREADS), args);
 }
 
 // ---------------------------------------------------------------------------
