@@ -256,10 +256,17 @@ def extra_latency(sh, torch):
 def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=None):
     """MoE-shaped low-latency dispatch / combine (Sec. IV-E, sizes of Sec. V-C): 8 emulated PEs,
     288 experts, top-8 routing, 14,336-byte tokens (14,352-byte dispatch messages), 1-128 tokens
-    per PE.  Per launch: microseconds, and payload bytes moved between PEs per second."""
-    import numpy as np
+    per PE.  Per launch: microseconds, and payload bytes moved between PEs per second.  `pair_graph_us`:
+    one dispatch + combine pair when ten pairs are replayed from one HIP graph (a serving loop's way of paying
+    one launch for many), against `dispatch_us + combine_us` launched one by one."""
     import workgen
     dev = torch.device("cuda:0")
+    side = torch.cuda.Stream()              # graphs cannot be captured on the default stream
+    with torch.cuda.stream(side):
+        return _extra_moe_on_current_stream(sh, torch, dev, workgen, npes, num_experts, topk, hidden, max_tokens, wgs)
+
+
+def _extra_moe_on_current_stream(sh, torch, dev, workgen, npes, num_experts, topk, hidden, max_tokens, wgs):
     epp = num_experts // npes
     seg = (epp * npes * max_tokens * (hidden + 16) + max_tokens * topk * hidden + (1 << 20) + 255) // 256 * 256
     heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
@@ -288,7 +295,18 @@ def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_toke
                               lambda: None, reps=20, warm=3)
             sh.stream_sync()
             assert int(recv_count.sum().item()) == routes
+            pairs = 10
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=torch.cuda.current_stream()):
+                for _ in range(pairs):
+                    sh.moe_dispatch(moe, x, tk, nt, recv_x, recv_info, recv_range, recv_count, w)
+                    sh.moe_combine(moe, recv_x, recv_info, recv_range, tk, nt, combined, w)
+            g_ms = _median_ms(graph.replay, lambda: None, reps=10, warm=2)
+            sh.stream_sync()
+            assert int(recv_count.sum().item()) == routes
+            del graph
             res[str(ntok)] = {"dispatch_us": round(d_ms * 1e3, 2), "combine_us": round(c_ms * 1e3, 2),
+                              "pair_graph_us": round(g_ms * 1e3 / pairs, 2),
                               "dispatch_GBs": round(routes * (hidden + 16) / d_ms / 1e6, 1),
                               "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes, "wgs_per_pe": w}
         sh.moe_destroy(moe)
