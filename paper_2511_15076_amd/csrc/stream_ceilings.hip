@@ -50,6 +50,35 @@ __global__ __launch_bounds__(256) void k_copy(const u32x4 *s, u32x4 *d, uint64_t
     }
 }
 
+// Copy with a three-deep software pipeline per wave: each wave owns every (waves)-th 4 KiB task, keeps two
+// tasks' loads in flight while it stores a third.  With one workgroup per CU this is the fastest plain copy
+// found on the box.  The host sizes the copy so that every wave has a whole number of rounds of three.
+__global__ __launch_bounds__(256) void k_copy_pipe(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst, uint64_t tasks)
+{
+    constexpr int D = 3, VPL = 4;
+    constexpr uint64_t TASK = 1024ull * VPL;
+    const uint64_t waves = (uint64_t)gridDim.x * 4, my = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint32_t lo = (threadIdx.x & 63) * 16;
+    const uint64_t mine = tasks / waves;
+    u32x4 v[D][VPL];
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) v[d][j] = __builtin_nontemporal_load((const u32x4 *)(src + (my + d * waves) * TASK + lo) + 64 * j);
+    for (uint64_t r = 0; r < mine; r += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const uint64_t ahead = r + d + D - 1;            // its loads go into the register set stored last
+            if (ahead < mine) {
+#pragma unroll
+                for (int j = 0; j < VPL; ++j)
+                    v[(d + D - 1) % D][j] = __builtin_nontemporal_load((const u32x4 *)(src + (my + ahead * waves) * TASK + lo) + 64 * j);
+            }
+#pragma unroll
+            for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(v[d][j], (u32x4 *)(dst + (my + (r + d) * waves) * TASK + lo) + 64 * j);
+        }
+    }
+}
 
 // counter-based index stream (SplitMix64 finaliser of the global op number)
 __device__ __forceinline__ uint64_t mix(uint64_t z)
@@ -107,8 +136,8 @@ int main()
 {
     const uint64_t bytes = 2ull << 30, nv = bytes / 16;
     uint8_t *buf; uint32_t *flag;
-    CK(hipMalloc(&buf, 2 * bytes)); CK(hipMalloc(&flag, 4));
-    CK(hipMemset(buf, 1, 2 * bytes));
+    CK(hipMalloc(&buf, 3 * bytes)); CK(hipMalloc(&flag, 4));     // the third buffer: room to displace the destination
+    CK(hipMemset(buf, 1, 3 * bytes));
     const u32x4 *s = (const u32x4 *)buf;
     u32x4 *d = (u32x4 *)(buf + bytes);
     printf("{");
@@ -121,6 +150,18 @@ int main()
         printf("\"copy_u4_grid%d_GBs\": %.0f, ", g, 2.0 * bytes / ms / 1e6);
         ms = median_ms([&] { hipLaunchKernelGGL(k_copy<1>, dim3(g), dim3(256), 0, 0, s, d, nv); });
         printf("\"copy_u1_grid%d_GBs\": %.0f, ", g, 2.0 * bytes / ms / 1e6);
+    }
+    // the pipelined copy, one workgroup per CU, and how its rate depends on WHERE the destination lies
+    // relative to the source: destination = source + 2 GiB + one more address bit (the reads and the
+    // writes of a moment then meet, or do not meet, in the same channels and banks)
+    const uint64_t ptasks = bytes / 4096 / (256 * 4 * 3) * (256 * 4 * 3);
+    printf("\"copy_pipelined_grid256_GBs_by_extra_delta_bit\": {");
+    for (int bit = 11; bit <= 30; ++bit) {
+        const uint64_t shift = bit == 11 ? 0 : 1ull << bit;
+        float pms = median_ms([&] { hipLaunchKernelGGL(k_copy_pipe, dim3(256), dim3(256), 0, 0, buf, buf + bytes + shift, ptasks); });
+        char key[16];
+        if (bit == 11) snprintf(key, sizeof key, "none"); else snprintf(key, sizeof key, "%d", bit);
+        printf("\"%s\": %.0f%s", key, 2.0 * ptasks * 4096 / pms / 1e6, bit == 30 ? "}, " : ", ");
     }
     float ms = median_ms([&] { CK(hipMemcpyAsync(d, s, bytes, hipMemcpyDeviceToDevice, 0)); });
     printf("\"hipMemcpyDtoD_GBs\": %.0f, ", 2.0 * bytes / ms / 1e6);
