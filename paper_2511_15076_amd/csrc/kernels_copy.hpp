@@ -175,11 +175,11 @@ constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size a
 // its current one, which keeps reads in flight behind the writes.  (Predicated or conditional loads
 // inside the loop would make the compiler wait for every outstanding access before each store.)
 template <int VPL>
-__device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t body, uint8_t *lbase, uint8_t *rbase,
+__device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t first, uint64_t body, uint8_t *lbase, uint8_t *rbase,
                                                 uint64_t my_wave, uint64_t team_waves, uint32_t lane)
 {
     constexpr uint64_t TASK_VECS = 64 * VPL;
-    const uint64_t chunks = body / (TASK_VECS * 16);   // body: the leading bytes of every message that this path moves
+    const uint64_t chunks = body / (TASK_VECS * 16);   // bytes [first, first + body) of every message are moved here
     const uint64_t tasks = chunks * a.ops_per_pe;
     if (my_wave >= tasks) return;
     // task t = (op, chunk) with slot = op % nslots; the walk t -> t + team_waves needs no division
@@ -188,8 +188,8 @@ __device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t bod
     uint64_t left = (tasks - 1 - my_wave) / team_waves;  // tasks of this wave after its first
     const bool is_put = a.kind == SHMEM_OP_PUT;
     // wave-uniform bases plus one constant per-lane byte offset: the addresses live in scalar registers
-    const uint8_t *const sbase = is_put ? lbase : rbase;
-    uint8_t *const dbase = is_put ? rbase : lbase;
+    const uint8_t *const sbase = (is_put ? lbase : rbase) + first;
+    uint8_t *const dbase = (is_put ? rbase : lbase) + first;
     const uint64_t sslot = is_put ? a.local_slot : a.remote_slot, dslot = is_put ? a.remote_slot : a.local_slot;
     const uint32_t lane_off = lane * 16;
     auto locate = [&](const uint8_t *&src, uint8_t *&dst) {
@@ -296,11 +296,14 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
         return;
     }
     if (contiguous && a.count >= 1024 && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0) {
-        // the leading multiple of 1 KiB of every message goes through the pipelined loop ...
+        // the leading multiple of 1 KiB of every message goes through the pipelined loop: as many 4 KiB
+        // wave tasks as fit (the fastest size), then at most one of 2 KiB and one of 1 KiB per message
+        // (a 14,336-byte token is three of 4 KiB and one of 2 KiB) ...
         const uint64_t body = a.count & ~1023ull, tail_vecs = (a.count - body) / 16;
-        if (body % 4096 == 0) sweep_pipelined<4>(a, body, lbase, rbase, my_wave, team_waves, lane);
-        else if (body % 2048 == 0) sweep_pipelined<2>(a, body, lbase, rbase, my_wave, team_waves, lane);
-        else sweep_pipelined<1>(a, body, lbase, rbase, my_wave, team_waves, lane);
+        const uint64_t body4 = body & ~4095ull;
+        if (body4) sweep_pipelined<4>(a, 0, body4, lbase, rbase, my_wave, team_waves, lane);
+        if (body & 2048) sweep_pipelined<2>(a, body4, 2048, lbase, rbase, my_wave, team_waves, lane);
+        if (body & 1024) sweep_pipelined<1>(a, body4 + (body & 2048), 1024, lbase, rbase, my_wave, team_waves, lane);
         // ... and what is left of each (under 1 KiB, e.g. the 16 metadata bytes of a 14,352-byte MoE
         // message) with one vector per lane
         if (tail_vecs) {
