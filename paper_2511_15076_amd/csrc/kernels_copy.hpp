@@ -230,6 +230,68 @@ __device__ __forceinline__ void sweep_pipelined(const SweepArgs &a, uint64_t fir
     }
 }
 
+// The same pipeline for messages of 4 KiB and more whose length is a multiple of 16 bytes but not of
+// 4 KiB: the last task of every message is short.  Nothing is predicated here either -- a lane whose
+// vector lies beyond the end of the message moves the message's LAST vector again (same bytes to the same
+// place; the lanes of such an instruction share one address, so it is one request) -- which keeps the
+// number of accesses per task fixed and the waits partial.  One pass moves the whole message, including a
+// remainder under 1 KiB such as the 16 metadata bytes of a 14,352-byte MoE message.
+__device__ __forceinline__ void sweep_pipelined_ragged(const SweepArgs &a, uint8_t *lbase, uint8_t *rbase, uint64_t my_wave,
+                                                       uint64_t team_waves, uint32_t lane)
+{
+    constexpr int VPL = 4;
+    constexpr uint64_t TASK_VECS = 64 * VPL, TASK_BYTES = TASK_VECS * 16;
+    const uint64_t chunks = (a.count + TASK_BYTES - 1) / TASK_BYTES;
+    const uint32_t last_vecs = (uint32_t)((a.count - (chunks - 1) * TASK_BYTES) / 16);   // 1 .. TASK_VECS
+    const uint64_t tasks = chunks * a.ops_per_pe;
+    if (my_wave >= tasks) return;
+    const uint64_t step_ch = team_waves % chunks, step_slot = (team_waves / chunks) % a.nslots;
+    uint64_t ch = my_wave % chunks, slot = (my_wave / chunks) % a.nslots;
+    uint64_t left = (tasks - 1 - my_wave) / team_waves;
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    const uint8_t *const sbase = is_put ? lbase : rbase;
+    uint8_t *const dbase = is_put ? rbase : lbase;
+    const uint64_t sslot = is_put ? a.local_slot : a.remote_slot, dslot = is_put ? a.remote_slot : a.local_slot;
+    auto locate = [&](const uint8_t *&src, uint8_t *&dst, uint32_t &nv) {
+        src = sbase + slot * sslot + ch * TASK_BYTES;
+        dst = dbase + slot * dslot + ch * TASK_BYTES;
+        nv = ch == chunks - 1 ? last_vecs : (uint32_t)TASK_VECS;
+    };
+    auto advance = [&]() {
+        ch += step_ch;
+        slot += step_slot;
+        if (ch >= chunks) { ch -= chunks; slot += 1; }
+        if (slot >= a.nslots) slot -= a.nslots;
+    };
+    auto load = [&](u32x4 (&v)[VPL], const uint8_t *src, uint32_t nv) {
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) v[j] = __builtin_nontemporal_load((const u32x4 *)src + min(lane + 64u * j, nv - 1));
+    };
+    auto store = [&](const u32x4 (&v)[VPL], uint8_t *dst, uint32_t nv) {
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) __builtin_nontemporal_store(v[j], (u32x4 *)dst + min(lane + 64u * j, nv - 1));
+    };
+    u32x4 va[VPL], vb[VPL];
+    const uint8_t *src;
+    uint8_t *da, *db;
+    uint32_t na, nb;
+    locate(src, da, na);
+    load(va, src, na);
+    for (;;) {
+        if (left == 0) { store(va, da, na); break; }
+        advance();
+        locate(src, db, nb);
+        load(vb, src, nb);
+        store(va, da, na);
+        if (left == 1) { store(vb, db, nb); break; }
+        advance();
+        locate(src, da, na);
+        load(va, src, na);
+        store(vb, db, nb);
+        left -= 2;
+    }
+}
+
 // One large contiguous put or get with 16-byte aligned ends: the whole grid is the initiator's team.
 __global__ __launch_bounds__(256) void k_copy_stream(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n)
 {
@@ -296,9 +358,13 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
         return;
     }
     if (contiguous && a.count >= 1024 && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0) {
-        // the leading multiple of 1 KiB of every message goes through the pipelined loop: as many 4 KiB
-        // wave tasks as fit (the fastest size), then at most one of 2 KiB and one of 1 KiB per message
-        // (a 14,336-byte token is three of 4 KiB and one of 2 KiB) ...
+        if (a.count > 4096 && a.count % 4096) {
+            sweep_pipelined_ragged(a, lbase, rbase, my_wave, team_waves, lane);
+            return;
+        }
+        // whole multiples of 4 KiB, and messages under 4 KiB: the leading multiple of 1 KiB goes through
+        // the pipelined loop, as 4 KiB wave tasks (the fastest size) or as one task of 2 KiB and / or one
+        // of 1 KiB per message ...
         const uint64_t body = a.count & ~1023ull, tail_vecs = (a.count - body) / 16;
         const uint64_t body4 = body & ~4095ull;
         if (body4) sweep_pipelined<4>(a, 0, body4, lbase, rbase, my_wave, team_waves, lane);
