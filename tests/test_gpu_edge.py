@@ -1,6 +1,7 @@
 """Degenerate inputs through the C ABI: every entry point accepts an empty job, enqueues nothing
 that touches the heap, and leaves the library usable (OpenSHMEM: a transfer of zero elements is a
 no-op, not an error).  Also: set-up with buffers that are too short, and the import order."""
+import gc
 import os
 import subprocess
 import sys
@@ -103,6 +104,7 @@ def test_init_rejects_buffers_shorter_than_stated():
         return sh.OK
 
     dev = torch.device("cuda:0")
+    gc.collect()                                                 # no stale tensor keeps a cached segment alive
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     heap = torch.zeros(16 << 20, dtype=torch.uint8, device=dev)
