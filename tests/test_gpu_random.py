@@ -216,3 +216,47 @@ def test_ring_pingpong_barrier(seed):
 def test_compare_swap(seed):
     rng = np.random.default_rng(29000 + seed)
     t_ahb.test_compare_swap_claim_batch(str(rng.choice(["uniform", "zipf"])), int(rng.choice([1, 2, 64, 100, 1024, 8192])))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_tables_with_large_ops(seed):
+    # tables that mix team-wide operations (above 64 KiB, up to 2 MiB, contiguous and strided, any alignment)
+    # with small ones; every op of a window owns one local and one remote 2 MiB stripe
+    import torch
+    from gpu_util import heaps_of, shmem_world, to_dev
+    rng = np.random.default_rng(31000 + seed)
+    npes, stripes, sb = int(rng.integers(2, 5)), 5, 2 << 20
+    hb = 2 * stripes * sb
+    window = int(rng.integers(1, stripes + 1))
+    nwin = 4
+    ops = np.zeros(window * nwin, dtype=workgen.OP_DESC)
+    for wdx in range(nwin):
+        free_l = [list(rng.permutation(stripes)) for _ in range(npes)]
+        free_r = [list(rng.permutation(stripes)) for _ in range(npes)]
+        for k in range(window):
+            me, pe = int(rng.integers(0, npes)), int(rng.integers(0, npes))
+            lo = int(free_l[me].pop()) * sb
+            so = (stripes + int(free_r[pe].pop())) * sb
+            kind = int(rng.integers(0, 4))
+            if kind < 2:
+                n = int(rng.choice([int(rng.integers(0, 5000)), int(rng.integers(60000, 70000)), 65536, 65536 + 16,
+                                    4096 * int(rng.integers(17, 400)), 16 * int(rng.integers(4097, 120000)),
+                                    int(rng.integers(65537, sb - 8192))]))
+                al = int(rng.choice([1, 8, 16, 4096]))
+                a, b = int(rng.integers(0, 4096 // al)) * al, int(rng.integers(0, 4096 // al)) * al
+                ops[wdx * window + k] = (kind, me, pe, 1, lo + a, so + b, n, 1, 1, 0)
+            else:
+                eb = int(rng.choice([1, 2, 4, 8]))
+                ls, ss = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+                cnt = int(rng.integers(0, (sb // eb - 64) // max(ls, ss) + 1))
+                a, b = int(rng.integers(0, 8)) * eb, int(rng.integers(0, 8)) * eb
+                ops[wdx * window + k] = (kind, me, pe, eb, lo + a, so + b, cnt, ls, ss, 0)
+    init = t_pg.seeded_heaps(npes, hb, 500 + seed)
+    w = t_pg.oracle_world(init)
+    assert w.op_batch(ops, window) == 0
+    want = w.heaps()
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.op_batch(to_dev(ops), len(ops), window, int(rng.choice([1, 4, 16, 33, 64])))
+        sh.stream_sync()
+        assert np.array_equal(heaps_of(heap, npes), want)
