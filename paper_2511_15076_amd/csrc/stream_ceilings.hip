@@ -88,14 +88,15 @@ __device__ __forceinline__ uint64_t mix(uint64_t z)
     return z ^ (z >> 31);
 }
 
-// n random 8-byte reads over `words` uint64 words (a power of two), PER independent reads in flight per lane
-template <int PER>
-__global__ __launch_bounds__(256) void k_randread(const uint64_t *a, uint64_t words, uint64_t n, uint32_t *out)
+// n random reads of one T (8 or 4 bytes) over `words` words of that size (a power of two), PER independent
+// reads in flight per lane
+template <int PER, typename T = uint64_t>
+__global__ __launch_bounds__(256) void k_randread(const T *a, uint64_t words, uint64_t n, uint32_t *out)
 {
-    uint64_t acc = 0;
+    T acc = 0;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride * PER) {
-        uint64_t v[PER];
+        T v[PER];
 #pragma unroll
         for (int k = 0; k < PER; ++k) v[k] = a[mix(i + k * stride) & (words - 1)];
 #pragma unroll
@@ -170,9 +171,14 @@ int main()
     // random 8-byte reads: 2 MiB (one die's L2 holds it), 16 MiB, 1 GiB and 2 GiB footprints
     const uint64_t nops = 1ull << 28;
     for (uint64_t fp : {2ull << 20, 16ull << 20, 1ull << 30, 2ull << 30}) {
-        ms = median_ms([&] { hipLaunchKernelGGL(k_randread<4>, dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, fp / 8, nops, flag); }, 5);
+        ms = median_ms([&] { hipLaunchKernelGGL((k_randread<4, uint64_t>), dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, fp / 8, nops, flag); }, 5);
         printf("\"randread8_%lluMiB_Gops\": %.1f, ", (unsigned long long)(fp >> 20), nops / ms / 1e6);
     }
+    // the L2-resident footprint again: 4-byte reads, and 8 reads in flight per lane
+    ms = median_ms([&] { hipLaunchKernelGGL((k_randread<4, uint32_t>), dim3(4096), dim3(256), 0, 0, (const uint32_t *)buf, (2ull << 20) / 4, nops, flag); }, 5);
+    printf("\"randread4_2MiB_Gops\": %.1f, ", nops / ms / 1e6);
+    ms = median_ms([&] { hipLaunchKernelGGL((k_randread<8, uint64_t>), dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, (2ull << 20) / 8, nops, flag); }, 5);
+    printf("\"randread8_2MiB_8inflight_Gops\": %.1f, ", nops / ms / 1e6);
     // returning atomics: distinct 128-byte lines over 1 GiB, over 8 MiB (64 Ki lines), and one address
     const uint64_t natom = 1ull << 26;
     CK(hipMemset(buf, 0, bytes));
