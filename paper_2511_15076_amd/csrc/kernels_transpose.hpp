@@ -80,9 +80,11 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
     const uint32_t ox = threadIdx.x % LANES_OUT, oy = threadIdx.x / LANES_OUT;
     const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TJ - 1) / TJ;
     T *out = (T *)ptr(c, a.out_off, pe);
-    for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
+    // the gets of a tile: issued one tile ahead, right after the previous tile's vectors have gone into LDS,
+    // so that they travel while the workgroup writes that tile out
+    vec v[STEPS_IN];
+    auto gets = [&](uint64_t t) {
         const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TJ;
-        vec v[STEPS_IN];
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_IN; ++k) {
             const uint64_t j = j0 + ry + k * ROWS_IN, col = i0 + vx * E;   // source row; first local column of the vector
@@ -93,11 +95,17 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
                 v[k] = __builtin_nontemporal_load((const vec *)src);
             }
         }
+    };
+    const uint64_t ntiles = tiles_i * tiles_j;
+    if (wg < ntiles) gets(wg);
+    for (uint64_t t = wg; t < ntiles; t += a.wgs_per_pe) {
+        const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TJ;
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_IN; ++k)
 #pragma unroll
             for (uint32_t e = 0; e < E; ++e) tile[ry + k * ROWS_IN][vx * E + e] = v[k][e];
         __syncthreads();
+        if (t + a.wgs_per_pe < ntiles) gets(t + a.wgs_per_pe);
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_OUT; ++k) {
             const uint32_t r = oy + k * ROWS_OUT;                          // tile column = local output row
