@@ -17,6 +17,7 @@ from gpu_util import heaps_of, shmem_world  # noqa: E402
     (1, 5, 4, 1), (2, 64, 4, 2), (4, 128, 8, 3), (3, 195, 4, 2),       # ragged tiles: 65 rows per PE
     (8, 1000, 4, 5), (16, 1024, 8, 4), (5, 70, 8, 1),
     (4, 320, 4, 3), (2, 392, 4, 2),                                    # 16-byte path with ragged 128-row and 64-column tiles
+    (8, 1000, 4, 128), (4, 1544, 4, 256), (16, 2048, 4, 64), (8, 1024, 8, 128),   # launches of 1024 workgroups and more: 128 x 128 tiles for 4-byte elements, ragged both ways
 ])
 def test_transpose_matches_igets(npes, n, eb, wgs):
     R = n // npes
