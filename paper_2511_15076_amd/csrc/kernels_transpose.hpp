@@ -62,30 +62,27 @@ __global__ __launch_bounds__(256) void k_transpose(Ctx c, TransposeArgs a)
 // to be a multiple of the vector length (every vector then lies inside one row block and is 16-byte
 // aligned); the host falls back to the element-wise kernel otherwise.  TJ source rows make one tile:
 // 64, or 128 for 4-byte elements, which doubles the contiguous run of every output row to 512 bytes
-// (runs of 256 bytes reach about 0.65 of the HBM peak in the put / get sweep as well, 512 bytes 0.67);
-// TI columns: 64, or 128 for 4-byte elements in large launches, which does the same for the gets.
-template <typename T, uint32_t TJ, uint32_t TI = TR_TILE>
+// (runs of 256 bytes reach about 0.65 of the HBM peak in the put / get sweep as well, 512 bytes 0.67).
+template <typename T, uint32_t TJ>
 __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
 {
     constexpr uint32_t E = 16 / sizeof(T);                 // elements per vector
-    constexpr uint32_t LANES_IN = TI / E;                  // lanes per source row of the tile (TI elements)
+    constexpr uint32_t LANES_IN = TR_TILE / E;             // lanes per source row of the tile (64 elements)
     constexpr uint32_t ROWS_IN = 256 / LANES_IN;           // source rows per step of the workgroup
     constexpr uint32_t STEPS_IN = TJ / ROWS_IN;
     constexpr uint32_t LANES_OUT = TJ / E;                 // lanes per output row of the tile (TJ elements)
     constexpr uint32_t ROWS_OUT = 256 / LANES_OUT;
-    constexpr uint32_t STEPS_OUT = TI / ROWS_OUT;
+    constexpr uint32_t STEPS_OUT = TR_TILE / ROWS_OUT;
     typedef T vec __attribute__((ext_vector_type(E)));
-    __shared__ T tile[TJ][TI + 1];                         // [source row][local column]; +1: conflict-free column reads
+    __shared__ T tile[TJ][TR_TILE + 1];                    // [source row][local column]; +1: conflict-free column reads
     const uint32_t pe = blockIdx.x / a.wgs_per_pe, wg = blockIdx.x % a.wgs_per_pe;
     const uint32_t vx = threadIdx.x % LANES_IN, ry = threadIdx.x / LANES_IN;
     const uint32_t ox = threadIdx.x % LANES_OUT, oy = threadIdx.x / LANES_OUT;
-    const uint64_t tiles_i = (a.rows + TI - 1) / TI, tiles_j = (a.n + TJ - 1) / TJ;
+    const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TJ - 1) / TJ;
     T *out = (T *)ptr(c, a.out_off, pe);
-    // the gets of a tile: issued one tile ahead, right after the previous tile's vectors have gone into LDS,
-    // so that they travel while the workgroup writes that tile out
-    vec v[STEPS_IN];
-    auto gets = [&](uint64_t t) {
-        const uint64_t i0 = (t / tiles_j) * TI, j0 = (t % tiles_j) * TJ;
+    for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
+        const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TJ;
+        vec v[STEPS_IN];
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_IN; ++k) {
             const uint64_t j = j0 + ry + k * ROWS_IN, col = i0 + vx * E;   // source row; first local column of the vector
@@ -96,17 +93,11 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
                 v[k] = __builtin_nontemporal_load((const vec *)src);
             }
         }
-    };
-    const uint64_t ntiles = tiles_i * tiles_j;
-    if (wg < ntiles) gets(wg);
-    for (uint64_t t = wg; t < ntiles; t += a.wgs_per_pe) {
-        const uint64_t i0 = (t / tiles_j) * TI, j0 = (t % tiles_j) * TJ;
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_IN; ++k)
 #pragma unroll
             for (uint32_t e = 0; e < E; ++e) tile[ry + k * ROWS_IN][vx * E + e] = v[k][e];
         __syncthreads();
-        if (t + a.wgs_per_pe < ntiles) gets(t + a.wgs_per_pe);
 #pragma unroll
         for (uint32_t k = 0; k < STEPS_OUT; ++k) {
             const uint32_t r = oy + k * ROWS_OUT;                          // tile column = local output row

@@ -1082,12 +1082,8 @@ int shmem_transpose(void *out_sym, const void *in_sym, size_t n, size_t elem_byt
     dim3 grid((unsigned)(H.npes * wgs_per_pe)), block(WG_THREADS);
     const size_t vec_elems = 16 / elem_bytes;
     const bool wide = rows % vec_elems == 0 && ((ooff | ioff) & 15) == 0;   // then n % vec_elems == 0, too
-    // 4-byte elements: tiles of 128 x 128 (512-byte runs on both sides, 66 KB of LDS: two workgroups per CU)
-    // once the launch has four workgroups per CU to draw from, tiles of 128 source rows x 64 columns below that
-    const bool many = (long)H.npes * wgs_per_pe >= 4L * H.num_cus;
     if (elem_bytes == 4) {
-        if (wide && !many) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint32_t, 128, 64>), grid, block, 0, H.stream, ctx(), a);
-        else if (wide) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint32_t, 128, 128>), grid, block, 0, H.stream, ctx(), a);
+        if (wide) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint32_t, 128>), grid, block, 0, H.stream, ctx(), a);
         else hipLaunchKernelGGL(shmemx::k_transpose<uint32_t>, grid, block, 0, H.stream, ctx(), a);
     } else {
         if (wide) hipLaunchKernelGGL((shmemx::k_transpose_vec<uint64_t, 64>), grid, block, 0, H.stream, ctx(), a);
