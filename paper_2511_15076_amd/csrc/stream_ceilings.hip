@@ -90,7 +90,7 @@ __device__ __forceinline__ uint64_t mix(uint64_t z)
 
 // n random reads of one T (8 or 4 bytes) over `words` words of that size (a power of two), PER independent
 // reads in flight per lane
-template <int PER, typename T = uint64_t>
+template <int PER, typename T = uint64_t, bool NT = false>
 __global__ __launch_bounds__(256) void k_randread(const T *a, uint64_t words, uint64_t n, uint32_t *out)
 {
     T acc = 0;
@@ -98,7 +98,10 @@ __global__ __launch_bounds__(256) void k_randread(const T *a, uint64_t words, ui
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride * PER) {
         T v[PER];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) v[k] = a[mix(i + k * stride) & (words - 1)];
+        for (int k = 0; k < PER; ++k) {
+            const T *p = a + (mix(i + k * stride) & (words - 1));
+            v[k] = NT ? __builtin_nontemporal_load(p) : *p;
+        }
 #pragma unroll
         for (int k = 0; k < PER; ++k) acc ^= v[k];
     }
@@ -179,6 +182,9 @@ int main()
     printf("\"randread4_2MiB_Gops\": %.1f, ", nops / ms / 1e6);
     ms = median_ms([&] { hipLaunchKernelGGL((k_randread<8, uint64_t>), dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, (2ull << 20) / 8, nops, flag); }, 5);
     printf("\"randread8_2MiB_8inflight_Gops\": %.1f, ", nops / ms / 1e6);
+    // the HBM-sized footprint with non-temporal loads (does the L2 still fetch whole 128-byte lines?)
+    ms = median_ms([&] { hipLaunchKernelGGL((k_randread<4, uint64_t, true>), dim3(4096), dim3(256), 0, 0, (const uint64_t *)buf, (1ull << 30) / 8, nops, flag); }, 5);
+    printf("\"randread8_1024MiB_nontemporal_Gops\": %.1f, ", nops / ms / 1e6);
     // returning atomics: distinct 128-byte lines over 1 GiB, over 8 MiB (64 Ki lines), and one address
     const uint64_t natom = 1ull << 26;
     CK(hipMemset(buf, 0, bytes));
