@@ -9,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmi_shmem.so")
 CEILINGS_PATH = os.path.join(HERE, "stream_ceilings")
+ROOT = os.path.dirname(HERE)
+CLIENT_PATH = os.path.join(ROOT, "examples", "c_abi_client")
 
 
 def hipcc() -> str:
@@ -30,6 +32,13 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd2), flush=True)
     subprocess.run(cmd2, check=True)
+    # a client of the C ABI without Python (host code only; tests/test_gpu_c_client.py runs it)
+    cmd3 = [hipcc(), "-O2", "-std=c++17", "-Wall", "-I", os.path.join(ROOT, "include"),
+            os.path.join(ROOT, "examples", "c_abi_client.cpp"), "-o", CLIENT_PATH,
+            "-L", HERE, "-lmi_shmem", "-Wl,-rpath,$ORIGIN/../paper_2511_15076_amd"]
+    if verbose:
+        print(" ".join(cmd3), flush=True)
+    subprocess.run(cmd3, check=True)
     return LIB_PATH
 
 
