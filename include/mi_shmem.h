@@ -272,6 +272,27 @@ int shmem_gin_destroy(void *gin);
 void *shmem_gin_signal_sym(void *gin, int id);
 void *shmem_gin_counter_sym(void *gin, int id);
 
+/* For kernels of the caller's own: what a HIP kernel needs to use the device
+ * API of include/mi_shmem_device.hpp (Listing 1: put with actions, putValue,
+ * signal, read/wait/reset of signals and counters, flush, barrier) on the
+ * registered heap.  Both structs are plain values that are passed to a kernel
+ * as arguments; they stay valid until shmem_finalize / shmem_gin_destroy.
+ * The caller launches such kernels on the stream given to shmem_init; a kernel
+ * that waits for another workgroup must have all its workgroups resident.
+ * Errors: NOT_INIT, INVALID_ARG. */
+typedef struct {
+    void *heap;          /* DEVICE: PE 0's segment                     */
+    uint64_t seg;        /* bytes per PE segment                       */
+    uint64_t *scratch;   /* DEVICE: the library's scratch words        */
+    int npes;
+} shmem_device_ctx;
+typedef struct {
+    uint64_t signals_off, counters_off;   /* byte offsets inside every segment */
+    uint32_t nsignals, ncounters;
+} shmem_gin_state;
+int shmem_device_context(shmem_device_ctx *ctx_out /* HOST */);
+int shmem_gin_device_state(void *gin, shmem_gin_state *state_out /* HOST */);
+
 /* The unidirectional ring exchange of Listing 2, `rounds` times in one
  * persistent launch of npes * wgs_per_pe workgroups.  In each round PE r puts
  * bytes [peer*slot_bytes, +slot_bytes) of its send buffer (peer = (r+1) mod

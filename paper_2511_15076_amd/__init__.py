@@ -85,6 +85,8 @@ _SIG = {
     "shmem_gin_destroy": (_i, [_vp]),
     "shmem_gin_signal_sym": (_vp, [_vp, _i]),
     "shmem_gin_counter_sym": (_vp, [_vp, _i]),
+    "shmem_device_context": (_i, [_vp]),
+    "shmem_gin_device_state": (_i, [_vp, _vp]),
     "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i, _i, _i]),
     "shmem_pingpong": (_i, [_vp, _sz, _vp, _i, _i]),
     "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
@@ -281,6 +283,26 @@ def gin_signal_sym(gin, signal_id):
 
 def gin_counter_sym(gin, counter_id):
     return _L.shmem_gin_counter_sym(gin, counter_id)
+
+
+class DeviceCtx(C.Structure):
+    _fields_ = [("heap", C.c_void_p), ("seg", C.c_uint64), ("scratch", C.c_void_p), ("npes", C.c_int)]
+
+
+class GinState(C.Structure):
+    _fields_ = [("signals_off", C.c_uint64), ("counters_off", C.c_uint64), ("nsignals", C.c_uint32), ("ncounters", C.c_uint32)]
+
+
+def device_context():
+    ctx = DeviceCtx()
+    _check(_L.shmem_device_context(C.byref(ctx)), "shmem_device_context")
+    return ctx
+
+
+def gin_device_state(gin):
+    st = GinState()
+    _check(_L.shmem_gin_device_state(gin, C.byref(st)), "shmem_gin_device_state")
+    return st
 
 
 def ring_exchange(recv_sym, send_sym, slot_bytes, gin, signal_id=0, counter_id=0, rounds=1, wgs_per_pe=1):

@@ -39,6 +39,14 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd3), flush=True)
     subprocess.run(cmd3, check=True)
+    # a kernel written outside the library on the device API of include/mi_shmem_device.hpp
+    cmd4 = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"),
+            os.path.join(ROOT, "examples", "device_api_ring.hip"), "-o", os.path.join(ROOT, "examples", "device_api_ring"),
+            "-L", HERE, "-lmi_shmem", "-Wl,-rpath,$ORIGIN/../paper_2511_15076_amd"]
+    if verbose:
+        print(" ".join(cmd4), flush=True)
+    subprocess.run(cmd4, check=True)
     return LIB_PATH
 
 

@@ -704,6 +704,31 @@ void *shmem_gin_counter_sym(void *gin, int id)
     return H.heap + g->st.counters_off + 8ull * (uint32_t)id;
 }
 
+// the two structs of the header are the kernels' own argument structs, field for field
+static_assert(sizeof(shmem_device_ctx) == sizeof(shmemx::Ctx) && offsetof(shmem_device_ctx, heap) == offsetof(shmemx::Ctx, heap) &&
+              offsetof(shmem_device_ctx, seg) == offsetof(shmemx::Ctx, seg) && offsetof(shmem_device_ctx, scratch) == offsetof(shmemx::Ctx, scratch) &&
+              offsetof(shmem_device_ctx, npes) == offsetof(shmemx::Ctx, npes), "shmem_device_ctx must match shmemx::Ctx");
+static_assert(sizeof(shmem_gin_state) == sizeof(shmemx::GinState) && offsetof(shmem_gin_state, counters_off) == offsetof(shmemx::GinState, counters_off) &&
+              offsetof(shmem_gin_state, nsignals) == offsetof(shmemx::GinState, nsignals) &&
+              offsetof(shmem_gin_state, ncounters) == offsetof(shmemx::GinState, ncounters), "shmem_gin_state must match shmemx::GinState");
+
+int shmem_device_context(shmem_device_ctx *ctx_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!ctx_out) return SHMEM_ERR_INVALID_ARG;
+    const shmemx::Ctx c = ctx();
+    memcpy(ctx_out, &c, sizeof c);
+    return SHMEM_OK;
+}
+
+int shmem_gin_device_state(void *gin, shmem_gin_state *state_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!gin || !state_out) return SHMEM_ERR_INVALID_ARG;
+    memcpy(state_out, &((GinObj *)gin)->st, sizeof(shmemx::GinState));
+    return SHMEM_OK;
+}
+
 int shmem_ring_exchange(void *recv_sym, const void *send_sym, size_t slot_bytes, void *gin, int signal_id,
                         int counter_id, int rounds, int wgs_per_pe)
 {
