@@ -70,6 +70,7 @@ def _load():
         "orc_fence": (i, [vp, i]),
         "orc_quiet": (i, [vp, i]),
         "orc_barrier_all": (i, [vp]),
+        "orc_team_sync": (i, [vp, i, i, i]),
         "orc_op_batch": (i, [vp, vp, sz, sz]),
         "orc_amo_batch": (i, [vp, i, u64, vp, vp, vp, vp, vp, sz]),
         "orc_hash_mix64": (u64, [u64]),
@@ -170,6 +171,7 @@ class World:
     def fence(self, pe_self): return self._L.orc_fence(self._w, pe_self)
     def quiet(self, pe_self=-1): return self._L.orc_quiet(self._w, pe_self)
     def barrier_all(self): return self._L.orc_barrier_all(self._w)
+    def team_sync(self, start, stride, size): return self._L.orc_team_sync(self._w, start, stride, size)
 
     def op_batch(self, ops: np.ndarray, quiet_every: int) -> int:
         ops = np.ascontiguousarray(ops)

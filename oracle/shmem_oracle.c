@@ -382,6 +382,18 @@ int orc_quiet(orc_world *w, int pe_self)
  * barrier; Sec. III-B "Barrier synchronization"). */
 int orc_barrier_all(orc_world *w) { return orc_quiet(w, -1); }
 
+/* Barrier over a team of PEs -- the members start, start + stride, ... (size of them), the way the
+ * paper's barrier session takes a team (Listing 1; Sec. III-B "Barrier synchronization") and
+ * OpenSHMEM names an active set: quiet on every MEMBER, then the members are synchronised.  What
+ * the other PEs have issued stays where it is. */
+int orc_team_sync(orc_world *w, int start, int stride, int size)
+{
+    if (start < 0 || stride < 1 || size < 1) return ORC_ERR_INVALID_ARG;
+    if ((long long)start + (long long)(size - 1) * stride >= w->npes) return ORC_ERR_INVALID_PE;
+    for (int i = 0; i < size; ++i) orc_quiet_one(w, start + i * stride);
+    return ORC_OK;
+}
+
 /* ------------------------------------------------------------------ */
 int orc_op_batch(orc_world *w, const orc_op_desc *ops, size_t n, size_t quiet_every)
 {

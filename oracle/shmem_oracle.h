@@ -72,6 +72,8 @@ int orc_signal_add(orc_world *w, int pe_self, uint64_t sig_sym, uint64_t value, 
 int orc_fence(orc_world *w, int pe_self);
 int orc_quiet(orc_world *w, int pe_self);
 int orc_barrier_all(orc_world *w);
+/* barrier over the PEs start, start + stride, ... (size members): quiet on the members only */
+int orc_team_sync(orc_world *w, int start, int stride, int size);
 
 /* 64-byte operation descriptor, same field layout as the generator's table */
 typedef struct {

@@ -275,3 +275,41 @@ def test_transpose_by_igets_is_the_matrix_transpose(npes, n, eb):
         assert np.array_equal(w.heap(p)[:R * n * eb].view(dt).reshape(R, n), A[p * R:(p + 1) * R])
         assert (w.heap(p)[blk + R * n * eb:] == 0xA5).all() and (w.heap(p)[R * n * eb:blk] == 0xA5).all()
 
+
+
+# ------------------------------------------------------------------ barrier over a team of PEs
+@pytest.mark.parametrize("mode", [oracle.AT_QUIET, oracle.SHUFFLED])
+def test_team_sync_completes_the_members_puts_only(mode):
+    # PEs 1, 3, 5 of 6 form a team (start 1, stride 2, size 3).  Every PE has a put in flight; after the
+    # team's barrier exactly the members' puts have landed, whoever their target is, and the others wait
+    # for their own quiet.
+    w = oracle.World(6, HB, mode, 5)
+    fill(w, 21)
+    before = [w.heap(p).copy() for p in range(6)]
+    for p in range(6):
+        assert w.put(p, 4096 + 64 * p, 256, 32, (p + 1) % 6) == 0          # 32 bytes of p's heap into p + 1
+    assert all(w.pending(p) == 1 for p in range(6))
+    assert w.team_sync(1, 2, 3) == 0
+    assert [w.pending(p) for p in range(6)] == [1, 0, 1, 0, 1, 0]
+    for p in range(6):
+        t = (p + 1) % 6
+        landed = np.array_equal(w.heap(t)[4096 + 64 * p: 4096 + 64 * p + 32], before[p][256:288])
+        assert landed == (p in (1, 3, 5)), p
+    w.barrier_all()
+    assert all(w.pending(p) == 0 for p in range(6))
+
+
+def test_team_of_everybody_is_barrier_all_and_bad_teams_are_refused():
+    ws = [oracle.World(4, HB, oracle.SHUFFLED, 9) for _ in range(2)]
+    for w in ws:
+        fill(w, 33)
+        for p in range(4):
+            assert w.put(p, 8192 + 16 * p, 512 + p, 13, (p + 2) % 4) == 0
+    ws[0].barrier_all()
+    assert ws[1].team_sync(0, 1, 4) == 0
+    assert np.array_equal(ws[0].heaps(), ws[1].heaps())
+    w = ws[1]
+    assert w.team_sync(0, 1, 5) != 0          # more members than PEs
+    assert w.team_sync(2, 2, 2) != 0          # 2, 4: PE 4 does not exist
+    assert w.team_sync(-1, 1, 2) != 0 and w.team_sync(0, 0, 2) != 0 and w.team_sync(0, 1, 0) != 0
+    assert w.team_sync(3, 7, 1) == 0          # a team of one PE: its own quiet
