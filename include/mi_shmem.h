@@ -326,6 +326,37 @@ int shmem_pingpong(void *buf_sym, size_t nbytes, void *gin, int signal_id, int i
  * Errors as above. */
 int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64_t *dev_errors);
 
+/* Teams of PEs: the members start, start + stride, ..., `size` of them (the
+ * barrier session of Listing 1 takes a team; OpenSHMEM calls this an active
+ * set).  shmem_team_create takes 256 bytes from the symmetric heap for the
+ * team's arrival and generation words.  shmem_team_sync is the team's barrier
+ * as one launch: quiet on the members, no member leaves before all have
+ * arrived; PEs outside the team take no part (in stream order every earlier
+ * call has completed anyway: the in-kernel form, pe_team_sync in
+ * include/mi_shmem_device.hpp with the state from shmem_team_device_state, is
+ * the one that matters).  shmem_team_epochs runs up to 8 DISJOINT teams side
+ * by side in one persistent launch, team k for rounds[k] rounds: in round e
+ * every member puts the value e into word (its index in the team) of
+ * slots_sym (uint64[npes], symmetric) on every member, the team meets in its
+ * barrier, and every member checks that each word of its own copy is at least
+ * e; *dev_errors (DEVICE uint64, may be NULL) counts violations.  Afterwards
+ * word i < size on every member of team k reads rounds[k]; PEs in no team are
+ * untouched.
+ * Errors: NOT_INIT, INVALID_ARG (also: overlapping teams, more workgroups than
+ * can be co-resident), INVALID_PE (a member beyond npes), NOMEM, ALIGN,
+ * OUT_OF_RANGE, DEVICE. */
+typedef struct shmem_team *shmem_team_t;
+typedef struct {
+    uint32_t start, stride, size, pad;
+    uint64_t words_off;          /* byte offset of the team's words in every segment */
+} shmem_pe_team;
+int shmem_team_create(int start, int stride, int size, shmem_team_t *team_out /* HOST */);
+int shmem_team_destroy(shmem_team_t team);
+int shmem_team_device_state(shmem_team_t team, shmem_pe_team *state_out /* HOST */);
+int shmem_team_sync(shmem_team_t team, int wgs_per_pe);
+int shmem_team_epochs(const shmem_team_t *teams /* HOST */, const int *rounds /* HOST */, int nteams,
+                      uint64_t *slots_sym, int wgs_per_pe, uint64_t *dev_errors);
+
 /* Message-passing litmus for fence and quiet (Sec. III-A "Ordering semantics":
  * what is put before the ordering point is visible to whoever sees what is put
  * after it).  PE 0 and PE 1, one workgroup each.  Round r = 1..rounds: PE 0

@@ -4,7 +4,8 @@
 //   shmemx::Ctx      the heap as a kernel sees it; fill it on the host with shmem_device_context()
 //                    (shmem_device_ctx has the same layout) and pass it to the kernel by value
 //   shmemx::ptr / put / get / strided / atomic_fetch_add / atomic_compare_swap / atomic_fetch_or /
-//   quiet / fence / acquire / team_barrier / barrier_all
+//   quiet / fence / acquire / team_barrier / barrier_all / pe_team_sync (a team of PEs: shmemx::PeTeam from
+//   shmem_team_device_state(), same layout as shmem_pe_team)
 //                    the one-sided operations, team-cooperative: every thread of every workgroup of the
 //                    calling PE's team takes part in a put or get
 //   shmemx::Gin      the interface of Listing 1 of the paper: put with SignalInc / SignalAdd / CounterInc

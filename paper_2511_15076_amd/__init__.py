@@ -87,6 +87,11 @@ _SIG = {
     "shmem_gin_counter_sym": (_vp, [_vp, _i]),
     "shmem_device_context": (_i, [_vp]),
     "shmem_gin_device_state": (_i, [_vp, _vp]),
+    "shmem_team_create": (_i, [_i, _i, _i, _vp]),
+    "shmem_team_destroy": (_i, [_vp]),
+    "shmem_team_device_state": (_i, [_vp, _vp]),
+    "shmem_team_sync": (_i, [_vp, _i]),
+    "shmem_team_epochs": (_i, [_vp, _vp, _i, _vp, _i, _vp]),
     "shmem_ring_exchange": (_i, [_vp, _vp, _sz, _vp, _i, _i, _i, _i]),
     "shmem_pingpong": (_i, [_vp, _sz, _vp, _i, _i]),
     "shmem_barrier_epochs": (_i, [_vp, _i, _i, _vp]),
@@ -283,6 +288,37 @@ def gin_signal_sym(gin, signal_id):
 
 def gin_counter_sym(gin, counter_id):
     return _L.shmem_gin_counter_sym(gin, counter_id)
+
+
+class PeTeam(C.Structure):
+    _fields_ = [("start", C.c_uint32), ("stride", C.c_uint32), ("size", C.c_uint32), ("pad", C.c_uint32), ("words_off", C.c_uint64)]
+
+
+def team_create(start, stride, size):
+    t = _vp(0)
+    _check(_L.shmem_team_create(start, stride, size, C.byref(t)), "shmem_team_create")
+    return t
+
+
+def team_destroy(team):
+    return _check(_L.shmem_team_destroy(team), "shmem_team_destroy")
+
+
+def team_device_state(team):
+    st = PeTeam()
+    _check(_L.shmem_team_device_state(team, C.byref(st)), "shmem_team_device_state")
+    return st
+
+
+def team_sync(team, wgs_per_pe=1):
+    return _check(_L.shmem_team_sync(team, wgs_per_pe), "shmem_team_sync")
+
+
+def team_epochs(teams, rounds, slots_sym, wgs_per_pe=1, dev_errors=None):
+    n = len(teams)
+    arr = (C.c_void_p * max(n, 1))(*[t.value if hasattr(t, "value") else t for t in teams])
+    rr = (C.c_int * max(n, 1))(*rounds)
+    return _check(_L.shmem_team_epochs(arr, rr, n, _addr(slots_sym), wgs_per_pe, _addr(dev_errors)), "shmem_team_epochs")
 
 
 class DeviceCtx(C.Structure):

@@ -149,4 +149,45 @@ __global__ __launch_bounds__(256) void k_barrier_epochs(Ctx c, uint64_t slots_of
     if (bad && errors) atomic_fetch_add(errors, bad);
 }
 
+// One barrier of a team of PEs as a launch of its own (the members' workgroups meet; the others leave at once).
+__global__ __launch_bounds__(256) void k_team_sync(Ctx c, PeTeam t, uint32_t wgs_per_pe)
+{
+    const uint32_t pe = blockIdx.x / wgs_per_pe;
+    if (t.has(pe)) pe_team_sync(c, t, pe, wgs_per_pe);
+}
+
+// Team epochs: several disjoint teams of PEs run side by side in one launch, each for its own number of
+// rounds.  In round e every member puts the value e into word (its index in the team) of the slot array on
+// EVERY member, the team meets in its barrier, and every member checks that each word of its own copy is at
+// least e.  A world barrier could not do this: the teams do not take the same number of rounds.
+constexpr uint32_t TEAM_EPOCHS_MAX = 8;
+struct TeamEpochsArgs {
+    PeTeam team[TEAM_EPOCHS_MAX];
+    uint32_t rounds[TEAM_EPOCHS_MAX];
+    uint32_t nteams, wgs_per_pe;
+    uint64_t slots_off;
+    uint64_t *errors;
+};
+
+__global__ __launch_bounds__(256) void k_team_epochs(Ctx c, TeamEpochsArgs a)
+{
+    const uint32_t pe = blockIdx.x / a.wgs_per_pe, wg = blockIdx.x % a.wgs_per_pe;
+    uint32_t ti = a.nteams;
+    for (uint32_t k = 0; k < a.nteams; ++k)
+        if (a.team[k].has(pe)) ti = k;
+    if (ti == a.nteams) return;                                           // this PE is in none of the teams
+    const PeTeam t = a.team[ti];
+    const uint32_t me = t.index_of(pe);
+    const uint32_t rank = wg * blockDim.x + threadIdx.x, size = a.wgs_per_pe * blockDim.x;
+    uint64_t bad = 0;
+    for (uint32_t e = 1; e <= a.rounds[ti]; ++e) {
+        for (uint32_t q = rank; q < t.size; q += size)                      // putValue to every member
+            *(uint64_t *)ptr(c, a.slots_off + 8ull * me, t.member(q)) = e;
+        pe_team_sync(c, t, pe, a.wgs_per_pe);
+        for (uint32_t q = rank; q < t.size; q += size)
+            if (*(volatile uint64_t *)ptr(c, a.slots_off + 8ull * q, pe) < e) ++bad;
+    }
+    if (bad && a.errors) atomic_fetch_add(a.errors, bad);
+}
+
 }  // namespace shmemx

@@ -790,6 +790,93 @@ int shmem_barrier_epochs(uint64_t *slots_sym, int rounds, int wgs_per_pe, uint64
     return launch_resident((const void *)shmemx::k_barrier_epochs, dim3((unsigned)grid), dim3(WG_THREADS), args);
 }
 
+// ---------------------------------------------------------------------------
+struct shmem_team { shmemx::PeTeam st; void *alloc; };
+
+static_assert(sizeof(shmem_pe_team) == sizeof(shmemx::PeTeam) && offsetof(shmem_pe_team, stride) == offsetof(shmemx::PeTeam, stride) &&
+              offsetof(shmem_pe_team, size) == offsetof(shmemx::PeTeam, size) && offsetof(shmem_pe_team, words_off) == offsetof(shmemx::PeTeam, words_off),
+              "shmem_pe_team must match shmemx::PeTeam");
+
+int shmem_team_create(int start, int stride, int size, shmem_team_t *team_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!team_out || start < 0 || stride < 1 || size < 1) return SHMEM_ERR_INVALID_ARG;
+    if ((long long)start + (long long)(size - 1) * stride >= H.npes) return SHMEM_ERR_INVALID_PE;
+    shmem_team *t = new (std::nothrow) shmem_team();
+    if (!t) return SHMEM_ERR_NOMEM;
+    t->alloc = shmem_malloc(256);
+    if (!t->alloc) { delete t; return SHMEM_ERR_NOMEM; }
+    t->st = shmemx::PeTeam{(uint32_t)start, (uint32_t)stride, (uint32_t)size, 0u, (uint64_t)((uint8_t *)t->alloc - H.heap)};
+    // arrivals and generation start at zero on every PE (only the first member's copy is used)
+    shmemx::GinState z{t->st.words_off, t->st.words_off, 32u, 0u};
+    hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), z);
+    if (int rc = launched()) { shmem_free(t->alloc); delete t; return rc; }
+    *team_out = t;
+    return SHMEM_OK;
+}
+
+int shmem_team_destroy(shmem_team_t t)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!t) return SHMEM_ERR_INVALID_ARG;
+    int rc = shmem_free(t->alloc);
+    delete t;
+    return rc;
+}
+
+int shmem_team_device_state(shmem_team_t t, shmem_pe_team *state_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!t || !state_out) return SHMEM_ERR_INVALID_ARG;
+    memcpy(state_out, &t->st, sizeof t->st);
+    return SHMEM_OK;
+}
+
+int shmem_team_sync(shmem_team_t t, int wgs_per_pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!t || !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_team_sync)) return SHMEM_ERR_INVALID_ARG;
+    shmemx::Ctx c = ctx();
+    shmemx::PeTeam st = t->st;
+    uint32_t w = (uint32_t)wgs_per_pe;
+    void *args[] = {&c, &st, &w};
+    return launch_resident((const void *)shmemx::k_team_sync, dim3((unsigned)grid), dim3(WG_THREADS), args);
+}
+
+int shmem_team_epochs(const shmem_team_t *teams, const int *rounds, int nteams, uint64_t *slots_sym, int wgs_per_pe,
+                      uint64_t *dev_errors)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (nteams < 0 || nteams > (int)shmemx::TEAM_EPOCHS_MAX || (nteams && (!teams || !rounds)) || !grid_fits(wgs_per_pe)) return SHMEM_ERR_INVALID_ARG;
+    if ((uintptr_t)slots_sym % 8 || (uintptr_t)dev_errors % 8) return SHMEM_ERR_ALIGN;
+    uint64_t off;
+    if (int rc = sym_off(slots_sym, 8ull * (uint64_t)H.npes, &off)) return rc;
+    shmemx::TeamEpochsArgs a;
+    memset(&a, 0, sizeof a);
+    std::vector<char> taken((size_t)H.npes, 0);
+    bool work = false;
+    for (int k = 0; k < nteams; ++k) {
+        if (!teams[k] || rounds[k] < 0) return SHMEM_ERR_INVALID_ARG;
+        a.team[k] = teams[k]->st;
+        a.rounds[k] = (uint32_t)rounds[k];
+        work |= rounds[k] > 0;
+        for (uint32_t i = 0; i < a.team[k].size; ++i) {                  // a PE runs the rounds of ONE team
+            char &seen = taken[a.team[k].start + i * a.team[k].stride];
+            if (seen) return SHMEM_ERR_INVALID_ARG;
+            seen = 1;
+        }
+    }
+    if (!work) return SHMEM_OK;
+    long grid = (long)H.npes * wgs_per_pe;
+    if (grid > max_resident_wgs(shmemx::k_team_epochs)) return SHMEM_ERR_INVALID_ARG;
+    a.nteams = (uint32_t)nteams; a.wgs_per_pe = (uint32_t)wgs_per_pe; a.slots_off = off; a.errors = dev_errors;
+    shmemx::Ctx c = ctx();
+    void *args[] = {&c, &a};
+    return launch_resident((const void *)shmemx::k_team_epochs, dim3((unsigned)grid), dim3(WG_THREADS), args);
+}
+
 int shmem_fence_litmus(void *buf_sym, size_t nbytes, int rounds, int use_quiet, uint64_t *dev_errors)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;

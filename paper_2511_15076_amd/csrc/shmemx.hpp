@@ -188,6 +188,39 @@ __device__ __forceinline__ void barrier_all(const Ctx &c, uint32_t pe, uint32_t 
     wg_acquire();
 }
 
+// Barrier over a team of PEs -- the members start, start + stride, ... (size of them; the barrier session
+// of Listing 1 takes a team, OpenSHMEM calls it an active set): quiet by every wave of the members, the
+// workgroups of a member meet on that PE's words, the last one of each member meets the other members on
+// the team's own words (the copy on the team's first PE) and then releases its PE.  Every workgroup of
+// every member must call it; the others are not involved and may be in a barrier of their own team.
+struct PeTeam {
+    uint32_t start, stride, size;
+    uint32_t pad;
+    uint64_t words_off;   // symmetric, 256 bytes: arrivals at +0, generation at +128
+    __device__ __forceinline__ bool has(uint32_t pe) const
+    {
+        return pe >= start && (pe - start) % stride == 0 && (pe - start) / stride < size;
+    }
+    __device__ __forceinline__ uint32_t index_of(uint32_t pe) const { return (pe - start) / stride; }
+    __device__ __forceinline__ uint32_t member(uint32_t i) const { return start + i * stride; }
+};
+
+__device__ __forceinline__ void pe_team_sync(const Ctx &c, const PeTeam &t, uint32_t pe, uint32_t wgs_per_pe)
+{
+    wg_release();
+    if (threadIdx.x == 0) {
+        quiet();
+        uint64_t *mine = &c.scratch[W_PE_BASE + pe * W_PE_WORDS + 32], mg = 0, tg;   // a PE is in one barrier at a time
+        if (wgs_per_pe == 1 || barrier_arrive(c, mine, mine + 16, wgs_per_pe, &mg)) {
+            uint64_t *w = (uint64_t *)ptr(c, t.words_off, t.start);
+            if (t.size > 1 && barrier_arrive(c, w, w + 16, t.size, &tg)) barrier_open(w + 16, tg);
+            if (wgs_per_pe > 1) barrier_open(mine + 16, mg);
+        }
+        acquire();
+    }
+    wg_acquire();
+}
+
 // ---------------------------------------------------------------------------
 // Contiguous copy by `size` cooperating lanes (rank in [0, size)).  Lane r
 // moves 16-byte vectors r, r+size, ... so that a wavefront's access covers

@@ -261,3 +261,23 @@ def test_tables_with_large_ops(seed):
         sh.op_batch(to_dev(ops), len(ops), window, int(rng.choice([1, 4, 16, 33, 64])))
         sh.stream_sync()
         assert np.array_equal(heaps_of(heap, npes), want)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_team_barriers(seed):
+    # disjoint strided teams (one per residue class of the stride) at different paces in one launch
+    import test_gpu_teams as t_teams
+    rng = np.random.default_rng(33000 + seed)
+    npes = int(rng.integers(1, 41))
+    stride = int(rng.integers(1, 5))
+    plan = []
+    for r in range(min(stride, npes)):
+        if rng.random() < 0.75:
+            start = r + stride * int(rng.integers(0, 3))
+            if start >= npes:
+                continue
+            size = int(rng.integers(1, (npes - 1 - start) // stride + 2))
+            plan.append(((start, stride, size), int(rng.choice([0, 1, 2, 17, 150, 400]))))
+    if not plan:
+        plan = [((0, 1, npes), 25)]
+    t_teams.test_team_epochs_match_oracle(npes, int(rng.integers(1, min(4, 256 // npes) + 1)), plan)
