@@ -247,10 +247,20 @@ def extra_latency(sh, torch):
             rounds = 2000
             ms = _median_ms(lambda: sh.barrier_epochs(slots, rounds, wgs, None), lambda: None, reps=3, warm=1)
             bar[f"{npes}x{wgs}_wgs"] = round(ms * 1e3 / rounds, 3)  # us per put-all + barrier_all round
+        # barriers over teams of PEs: two teams of 8 (evens and odds) and four of 4, side by side in one launch
+        tb = {}
+        for name, layout in (("2_teams_of_8", [(0, 2, 8), (1, 2, 8)]), ("4_teams_of_4", [(r, 4, 4) for r in range(4)])):
+            teams = [sh.team_create(*t) for t in layout]
+            rounds = 2000
+            ms = _median_ms(lambda: sh.team_epochs(teams, [rounds] * len(teams), slots, 1, None), lambda: None, reps=3, warm=1)
+            tb[name] = round(ms * 1e3 / rounds, 3)                   # us per put-to-members + team barrier round
+            sh.stream_sync()
+            for t in teams:
+                sh.team_destroy(t)
         sh.stream_sync()
     finally:
         sh.finalize()
-    return {"pingpong_round_trip_us": pp, "barrier_round_us": bar}
+    return {"pingpong_round_trip_us": pp, "barrier_round_us": bar, "team_barrier_round_us": tb}
 
 
 def extra_moe(sh, torch, npes=8, num_experts=288, topk=8, hidden=14336, max_tokens=128, wgs=None):

@@ -114,8 +114,9 @@ struct Gin {
         __hip_atomic_store(counter_word(id), 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
     }
 
-    // barrier session over the world team
+    // barrier session over the world team, or over a team of PEs that the caller is a member of
     __device__ __forceinline__ void barrier_sync() const { barrier_all(c, pe, wgs_per_pe); }
+    __device__ __forceinline__ void barrier_sync(const PeTeam &team) const { pe_team_sync(c, team, pe, wgs_per_pe); }
 };
 
 }  // namespace shmemx
