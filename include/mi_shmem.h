@@ -106,6 +106,14 @@ int shmem_put(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, 
 /* get: copy nbytes from PE pe's copy of src_sym to dst_local (DEVICE); blocking
  * in stream order. */
 int shmem_get(int pe_self, void *dst_local, const void *src_sym, size_t nbytes, int pe);
+/* put with a signal: the put above, then `value` is added to PE pe's copy of
+ * sig_sym (symmetric uint64, 8-byte aligned) and lands only after the data is
+ * visible there -- the paper's put with the SignalAdd{value} action (SignalInc:
+ * value 1; Sec. III-A "Ordering semantics"), OpenSHMEM's put_signal with
+ * SIGNAL_ADD.  nbytes == 0 is the zero-byte put + signal that the paper uses
+ * as a release.  Both halves are checked before either is enqueued. */
+int shmem_put_signal(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, uint64_t *sig_sym,
+                     uint64_t value, int pe);
 /* iput: dest[i * dst_stride] = src[i * src_stride] for i < nelems; strides in
  * elements, >= 1; elem_bytes in {1,2,4,8}; both addresses aligned to it.
  * Bytes between destination elements are not written. */

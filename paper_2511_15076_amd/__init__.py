@@ -63,6 +63,7 @@ _SIG = {
     "shmem_ptr": (_vp, [_vp, _i]),
     "shmem_put": (_i, [_i, _vp, _vp, _sz, _i]),
     "shmem_get": (_i, [_i, _vp, _vp, _sz, _i]),
+    "shmem_put_signal": (_i, [_i, _vp, _vp, _sz, _vp, _u64, _i]),
     "shmem_iput": (_i, [_i, _vp, _vp, _pd, _pd, _sz, _sz, _i]),
     "shmem_iget": (_i, [_i, _vp, _vp, _pd, _pd, _sz, _sz, _i]),
     "shmem_atomic_fetch_add": (_i, [_i, _vp, _u64, _i, _vp]),
@@ -169,6 +170,11 @@ def ptr(sym, pe: int):
 
 def put(pe_self, dst_sym, src_local, nbytes, pe):
     return _check(_L.shmem_put(pe_self, _addr(dst_sym), _addr(src_local), nbytes, pe), "shmem_put")
+
+
+def put_signal(pe_self, dst_sym, src_local, nbytes, sig_sym, value, pe):
+    return _check(_L.shmem_put_signal(pe_self, _addr(dst_sym), _addr(src_local), nbytes, _addr(sig_sym), value, pe),
+                  "shmem_put_signal")
 
 
 def get(pe_self, dst_local, src_sym, nbytes, pe):

@@ -341,6 +341,20 @@ static int amo_single(int kind, int pe_self, uint64_t *sym, uint64_t a, uint64_t
     return launched();
 }
 
+int shmem_put_signal(int pe_self, void *dst_sym, const void *src_local, size_t nbytes, uint64_t *sig_sym, uint64_t value, int pe)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    // both halves are checked before either is enqueued
+    const uint64_t off = off_of(dst_sym), sig_off = off_of(sig_sym);
+    if (int rc = hostlogic::check_contig(H.npes, H.seg, pe_self, pe, off, nbytes)) return rc;
+    if (int rc = hostlogic::check_amo(H.npes, H.seg, pe_self, pe, sig_off)) return rc;
+    if (nbytes && !src_local) return SHMEM_ERR_INVALID_ARG;
+    if (nbytes)
+        if (int rc = launch_copy(H.heap + (size_t)pe * H.seg + off, (const uint8_t *)src_local, nbytes)) return rc;
+    // the add is a launch of its own behind the copy: the kernel boundary makes the data visible first
+    return amo_single(SHMEM_AMO_FETCH_ADD, pe_self, sig_sym, value, 0, pe, nullptr);
+}
+
 int shmem_atomic_fetch_add(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result)
 {
     return amo_single(SHMEM_AMO_FETCH_ADD, pe_self, dst_sym, value, 0, pe, dev_result);

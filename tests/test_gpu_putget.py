@@ -358,3 +358,40 @@ def test_allocator_matches_oracle_and_host_errors():
                 call()
             assert e.value.status == status
         assert sh.ptr(base + hb, 0) is None and sh.ptr(base, 2) is None
+
+
+def test_put_signal_matches_put_then_signal_add():
+    # the paper's put with a SignalAdd action as one stream-ordered call: random sizes (zero included: the
+    # zero-byte put + signal) and values, several initiators adding to the same signal word
+    npes, hb = 4, 1 << 18
+    init = seeded_heaps(npes, hb, 4242)
+    init[:, hb - 256:] = 0                                   # the signal words start at zero
+    w = oracle_world(init)
+    sig = hb - 256
+    rng = np.random.default_rng(8)
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        for k in range(24):
+            me, pe = int(rng.integers(0, npes)), int(rng.integers(0, npes))
+            n = int(rng.choice([0, 1, 8, 100, 3000, 4000]))
+            lo = k * 8192 + int(rng.integers(0, 64))                       # every op works inside its own 8 KiB stripe
+            so = k * 8192 + 4096 + int(rng.integers(0, 64))
+            value, word = int(rng.integers(1, 1000)), sig + 8 * int(rng.integers(0, 3))
+            assert w.put(me, so, lo, n, pe) == 0
+            assert w.signal_add(me, word, value, pe) == 0
+            sh.put_signal(me, base + so, sh.ptr(base + lo, me), n, base + word, value, pe)
+        sh.barrier_all()
+        w.barrier_all()
+        assert np.array_equal(heaps_of(heap, npes), w.heaps())
+        assert heaps_of(heap, npes)[:, sig:sig + 24].view(np.uint64).sum() > 0
+        # host-visible errors enqueue nothing: a bad signal address stops the put as well
+        before = heaps_of(heap, npes).copy()
+        for call, status in [(lambda: sh.put_signal(0, base, sh.ptr(base + 4096, 0), 64, base + sig + 4, 1, 1), sh.ERR_ALIGN),
+                             (lambda: sh.put_signal(0, base, sh.ptr(base + 4096, 0), 64, base + hb, 1, 1), sh.ERR_OUT_OF_RANGE),
+                             (lambda: sh.put_signal(0, base + hb - 8, sh.ptr(base, 0), 64, base + sig, 1, 1), sh.ERR_OUT_OF_RANGE),
+                             (lambda: sh.put_signal(0, base, sh.ptr(base + 4096, 0), 64, base + sig, 1, npes), sh.ERR_INVALID_PE)]:
+            with pytest.raises(sh.ShmemError) as e:
+                call()
+            assert e.value.status == status
+        sh.stream_sync()
+        assert np.array_equal(heaps_of(heap, npes), before)
