@@ -116,6 +116,8 @@ def test_every_stream_ordered_entry_point_replays_to_its_eager_result():
             d_init = torch.from_numpy(init.reshape(-1)).to("cuda:0")
             assert sh.malloc(14 * K) == base               # the regions below
             gin = sh.gin_create(2, 1)
+            teams = [sh.team_create(0, 2, 2), sh.team_create(1, 2, 2)]          # PEs 0, 2 and PEs 1, 3
+            team_words = [sh.team_device_state(t).words_off for t in teams]
             d_keys, d_queries = to_dev(keys), to_dev(queries)
             d_status = torch.zeros(n_keys, dtype=torch.uint8, device="cuda:0")
             d_found = torch.zeros(2 * n_keys, dtype=torch.uint8, device="cuda:0")
@@ -141,6 +143,9 @@ def test_every_stream_ordered_entry_point_replays_to_its_eager_result():
                 sh.transpose(R[10], R[9], n_t, 4, 2)
                 sh.ring_exchange(R[12], R[11], 1000, gin, 1, 0, 3, 2)
                 sh.barrier_epochs(R[13], 50, 3, d_err)
+                sh.put_signal(1, R[1] + 32768, sh.ptr(R[0], 1), 3000, R[3] + 64, 3, 0)
+                sh.team_epochs(teams, [20, 35], R[13] + 1024, 2, d_err)
+                sh.team_sync(teams[1], 2)
                 sh.barrier_all()
 
             def start_over():
@@ -155,6 +160,8 @@ def test_every_stream_ordered_entry_point_replays_to_its_eager_result():
                 h = heaps_of(heap, npes).copy()
                 table = np.sort(h[:, 8 * K: 8 * K + 8 * slots].view(np.uint64), axis=1)   # who won which slot may differ
                 h[:, 8 * K: 9 * K] = 0
+                for off in team_words:                     # the teams' generation words count barriers: the library's own
+                    h[:, off:off + 256] = 0
                 return (h, table, d_old.cpu().numpy().copy(), np.sort(d_status.cpu().numpy()), d_found.cpu().numpy().copy(),
                         int(d_err.item()))
 
@@ -172,4 +179,6 @@ def test_every_stream_ordered_entry_point_replays_to_its_eager_result():
                 for k, (x, y) in enumerate(zip(eager, again)):
                     assert np.array_equal(x, y), (replay, k)
             del graph
+            for t in teams:
+                sh.team_destroy(t)
             sh.gin_destroy(gin)
