@@ -95,3 +95,15 @@ def test_binding_loads_torch_before_the_library():
             "assert len(paths) == 1, paths\n") % (ROOT,)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
+
+
+def test_public_header_is_plain_c_and_cpp(tmp_path):
+    # the boundary is a C ABI: the header must compile as C11 and as C++17, warnings being errors
+    import subprocess
+    (tmp_path / "c.c").write_text('#include "mi_shmem.h"\nint main(void) { return sizeof(shmem_bfs_stats) == 0; }\n')
+    (tmp_path / "cpp.cpp").write_text('#include "mi_shmem.h"\nint main() { shmem_pe_team t = {0, 1, 1, 0, 0}; return (int)t.start; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(tmp_path / "c.c")],
+                ["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(tmp_path / "cpp.cpp")]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
