@@ -97,6 +97,12 @@ int shmem_free(void *sym);             /* BAD_FREE unless sym came from malloc/a
 void *shmem_ptr(const void *sym, int pe);
 
 /* ---- one-sided data movement (Sec. III-A; Table II put / get) ------------- */
+/* Errors of the five calls below: NOT_INIT; INVALID_PE (pe_self or pe);
+ * OUT_OF_RANGE (the symmetric range leaves the segment, or a stride / count
+ * overflows); INVALID_ARG (a NULL local pointer with bytes to move, a stride
+ * < 1, an element size other than 1, 2, 4, 8); ALIGN (iput / iget addresses,
+ * the signal word); DEVICE.  The local side is an ordinary device pointer and
+ * is NOT range-checked: the caller owns it. */
 
 /* put: copy nbytes from src_local (DEVICE) to PE pe's copy of dst_sym.  The
  * source is reusable once the call is stream-complete; delivery is guaranteed
@@ -125,7 +131,9 @@ int shmem_iget(int pe_self, void *dst_local, const void *src_sym, ptrdiff_t dst_
 
 /* ---- atomic memory operations on a 64-bit word (Table II memory atomics) -- */
 /* Each is indivisible with respect to every other AMO on the same word and
- * writes the previous value to *dev_result (DEVICE, may be NULL). */
+ * writes the previous value to *dev_result (DEVICE, may be NULL).  dst_sym:
+ * symmetric, 8-byte aligned.  compare_swap stores `value` if the word equals
+ * `cond`.  Errors: NOT_INIT, INVALID_PE, OUT_OF_RANGE, ALIGN, DEVICE. */
 int shmem_atomic_fetch_add(int pe_self, uint64_t *dst_sym, uint64_t value, int pe, uint64_t *dev_result);
 int shmem_atomic_compare_swap(int pe_self, uint64_t *dst_sym, uint64_t cond, uint64_t value, int pe,
                               uint64_t *dev_result);
