@@ -55,6 +55,16 @@ int main()
     SHMEM_OK_OR_FAIL(shmem_atomic_compare_swap(3, ctr + 1, 0, 99, 2, dev_old + 2));
     SHMEM_OK_OR_FAIL(shmem_atomic_compare_swap(0, ctr + 1, 0, 42, 2, dev_old + 3));   // loses: sees 99
     SHMEM_OK_OR_FAIL(shmem_atomic_fetch_or(2, ctr + 2, 0xF0, 2, dev_old + 4));
+    // put with a signal: 1000 bytes of PE 0's `a` into PE 1's `a` at +6000, then 9 is added to PE 1's fourth counter
+    SHMEM_OK_OR_FAIL(shmem_put_signal(0, a + 6000, shmem_ptr(a, 0), 1000, ctr + 3, 9, 1));
+    // a team of PEs 0 and 2 and one barrier of it (its 256 bytes of the heap are the library's own)
+    shmem_team_t team = nullptr;
+    shmem_pe_team team_state;
+    SHMEM_OK_OR_FAIL(shmem_team_create(0, 2, 2, &team));
+    SHMEM_OK_OR_FAIL(shmem_team_device_state(team, &team_state));
+    CHECK(team_state.start == 0 && team_state.stride == 2 && team_state.size == 2 && team_state.words_off == 12544);
+    SHMEM_OK_OR_FAIL(shmem_team_sync(team, 2));
+    CHECK(shmem_team_create(1, 2, 3, &team) == SHMEM_ERR_INVALID_PE);     // 1, 3, 5: there is no PE 5
     SHMEM_OK_OR_FAIL(shmem_barrier_all());
     uint64_t first_bad = 0;
     SHMEM_OK_OR_FAIL(shmem_stream_sync(&first_bad));
@@ -77,11 +87,19 @@ int main()
     for (int p = 0; p < npes; ++p) memset(&want[p * seg + 12288], 0, 256);
     uint64_t c0 = 12, c1 = 99, c2 = 0xF0;
     memcpy(&want[2 * seg + 12288], &c0, 8); memcpy(&want[2 * seg + 12296], &c1, 8); memcpy(&want[2 * seg + 12304], &c2, 8);
+    memcpy(&want[1 * seg + 6000], &init[0 * seg + 0], 1000);
+    uint64_t c3 = 9;
+    memcpy(&want[1 * seg + 12288 + 24], &c3, 8);
+    for (int p = 0; p < npes; ++p) {                                      // the team's words: not ours to predict
+        memset(&want[p * seg + 12544], 0, 256);
+        memset(&got[p * seg + 12544], 0, 256);
+    }
     size_t bad = 0;
     for (size_t i = 0; i < want.size(); ++i) bad += want[i] != got[i];
     CHECK(bad == 0);
     CHECK(old[0] == 0 && old[1] == 5 && old[2] == 0 && old[3] == 99 && old[4] == 0);   // one stream: the calls ran in order
 
+    SHMEM_OK_OR_FAIL(shmem_team_destroy(team));
     SHMEM_OK_OR_FAIL(shmem_free(b));
     SHMEM_OK_OR_FAIL(shmem_free(a));
     SHMEM_OK_OR_FAIL(shmem_free(ctr));
