@@ -301,37 +301,72 @@ __global__ __launch_bounds__(256) void k_copy_stream(uint8_t *__restrict__ dst, 
 }
 
 // Small messages (up to SMALL_MSG bytes, multiples of 8 or 16): a sub-group of lanes, one vector V per
-// lane, moves one message, so a wave instruction carries 64 / group messages; four such rounds are in
-// flight per wave (all loads before the first store) -- with one round at a time a wave had 512 bytes
-// in flight and the small sizes were latency-bound.
+// lane, moves one message, so a wave instruction carries 64 / group messages; sets of four such rounds
+// alternate between two register sets, the loads of the next set going out before the stores of the
+// current one (with one round at a time a wave had 512 bytes in flight and the small sizes were
+// latency-bound).
 template <typename V>
 __device__ __forceinline__ void sweep_small(const SweepArgs &a, uint8_t *lbase, uint8_t *rbase, uint64_t my_wave,
                                             uint64_t team_waves, uint32_t lane)
 {
     constexpr uint32_t W = sizeof(V);
-    constexpr int U = 8;
+    constexpr int U = 4;                                   // rounds per register set; two sets alternate
     uint32_t group = 1;
     while (group * W < a.count) group <<= 1;
-    const uint32_t per_wave = 64 / group, sub = lane / group, j = lane % group;
-    const bool lane_on = (uint64_t)j * W < a.count;
+    const uint32_t per_wave = 64 / group, sub = lane / group;
+    // Nothing is predicated (a load under a condition makes every later wait a wait for everything in
+    // flight, the stores included): a lane beyond the end of its message moves the message's last vector
+    // again, and a lane beyond the last operation moves the last operation again -- the same bytes to the
+    // same place, harmless whoever does it.  Whole sets of U rounds go through the two-set pipeline; the
+    // up to U - 1 rounds that are left are moved one at a time (repeating rounds to fill a set made the
+    // smallest messages several times slower where a wave has only a round or two).
+    const uint32_t nvec = (uint32_t)(a.count / W);         // the host sends count as a multiple of W, at least W
+    const uint32_t j = min(lane % group, nvec - 1);
+    const uint64_t last_op = a.ops_per_pe - 1;
+    const uint64_t rounds_all = (a.ops_per_pe + per_wave - 1) / per_wave;      // rounds of the whole team
+    if (my_wave >= rounds_all) return;
+    const uint64_t mine = (rounds_all - 1 - my_wave) / team_waves + 1;          // rounds of this wave
+    uint64_t sets = mine / U;
+    const uint32_t rest = (uint32_t)(mine % U);
     const bool is_put = a.kind == SHMEM_OP_PUT;
-    for (uint64_t t = my_wave; t * per_wave < a.ops_per_pe; t += team_waves * U) {
-        V v[U];
-        V *dst[U];
-        bool on[U];
+    const uint8_t *const sbase = is_put ? lbase : rbase;
+    uint8_t *const dbase = is_put ? rbase : lbase;
+    const uint64_t sslot = is_put ? a.local_slot : a.remote_slot, dslot = is_put ? a.remote_slot : a.local_slot;
+    uint64_t t = my_wave;                                  // first round of the next set to load
+    auto load = [&](V (&v)[U], V *(&dst)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint64_t op = (t + u * team_waves) * per_wave + sub;
-            on[u] = lane_on && op < a.ops_per_pe;
+            const uint64_t op_ = (t + (uint64_t)u * team_waves) * per_wave + sub;
+            const uint64_t op = op_ < last_op ? op_ : last_op;
             const uint64_t slot = op < a.nslots ? op : op % a.nslots;
-            V *l = (V *)(lbase + slot * a.local_slot) + j;
-            V *r = (V *)(rbase + slot * a.remote_slot) + j;
-            dst[u] = is_put ? r : l;
-            if (on[u]) v[u] = __builtin_nontemporal_load(is_put ? l : r);
+            dst[u] = (V *)(dbase + slot * dslot) + j;
+            v[u] = __builtin_nontemporal_load((const V *)(sbase + slot * sslot) + j);
         }
+        t += (uint64_t)U * team_waves;
+    };
+    auto store = [&](const V (&v)[U], V *const (&dst)[U]) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (on[u]) __builtin_nontemporal_store(v[u], dst[u]);
+        for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], dst[u]);
+    };
+    if (sets) {
+        V va[U], vb[U];
+        V *da[U], *db[U];
+        load(va, da);
+        for (;;) {
+            if (sets == 1) { store(va, da); break; }
+            load(vb, db);
+            store(va, da);
+            if (sets == 2) { store(vb, db); break; }
+            load(va, da);
+            store(vb, db);
+            sets -= 2;
+        }
+    }
+    for (uint32_t r = 0; r < rest; ++r, t += team_waves) {
+        const uint64_t op_ = t * per_wave + sub;
+        const uint64_t op = op_ < last_op ? op_ : last_op;
+        const uint64_t slot = op < a.nslots ? op : op % a.nslots;
+        __builtin_nontemporal_store(__builtin_nontemporal_load((const V *)(sbase + slot * sslot) + j), (V *)(dbase + slot * dslot) + j);
     }
 }
 
