@@ -64,6 +64,16 @@ struct MoeCombineArgs {
     uint32_t wgs_per_pe;
 };
 
+// Vectors [lo, lo + per) of a row of hvecs vectors that exist: 0 when the part starts at or beyond the end.
+// In 64-bit signed arithmetic on purpose: the 32-bit unsigned form (lo < hvecs ? min(per, hvecs - lo) : 0)
+// was compiled by hipcc 7.2, when an unpredicated variant of the copy below was tried next to it, into code
+// that returned `per` for lo > hvecs (checked in isolation: same source, only this expression differing).
+__device__ __forceinline__ uint32_t moe_part_vecs(uint32_t hvecs, uint32_t lo, uint32_t per)
+{
+    const int64_t rem = (int64_t)hvecs - (int64_t)lo;
+    return rem <= 0 ? 0u : (uint32_t)(rem < (int64_t)per ? rem : (int64_t)per);
+}
+
 // One wave copies nv 16-byte vectors, eight loads per lane in flight.
 __device__ __forceinline__ void wave_copy16(u32x4 *__restrict__ d, const u32x4 *__restrict__ s, uint32_t nv, uint32_t lane)
 {
@@ -168,7 +178,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
                         __builtin_nontemporal_store(meta, (u32x4 *)slot);
                     }
                 }
-                const uint32_t lo = part * sper, cnt = lo < hvecs ? min(sper, hvecs - lo) : 0;
+                const uint32_t lo = part * sper, cnt = moe_part_vecs(hvecs, lo, sper);
                 wave_copy16((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo,
                             cnt, lane);
             }
@@ -219,7 +229,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             const bool first = part == 0 && lane == 0;
             u32x4 info = {0, 0, 0, 0};
             if (first) info = *(const u32x4 *)slot;
-            const uint32_t lo = part * rper, cnt = lo < hvecs ? min(rper, hvecs - lo) : 0;
+            const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
             wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
             if (first) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = info;
         }
@@ -265,7 +275,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
             const u32x4 info = *(const u32x4 *)(a.recv_info + (row0 + i) * 4);   // token, source PE, position, expert
             const uint32_t t = info.x, s = info.y, j = info.z;
             if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row0 + i); continue; }
-            const uint32_t lo = part * cper, cnt = lo < hvecs ? min(cper, hvecs - lo) : 0;
+            const uint32_t lo = part * cper, cnt = moe_part_vecs(hvecs, lo, cper);
             wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
                         (const u32x4 *)(a.expert_out + (row0 + i) * m.hidden) + lo, cnt, lane);
         }
