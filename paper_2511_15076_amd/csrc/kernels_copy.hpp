@@ -166,7 +166,8 @@ struct SweepArgs {
 
 constexpr uint64_t CHUNK_BYTES = 4096;  // per wave-task, contiguous ops
 constexpr uint64_t CHUNK_ELEMS = 2048;  // per wave-task, strided ops
-constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size are packed into sub-wave groups
+constexpr uint64_t SMALL_MSG = 512;     // contiguous messages up to this size (twice that with 16-byte alignment: what one
+                                        // wave instruction covers) are packed into sub-wave groups
 
 // Contiguous 16-byte aligned messages of at least 1 KiB (the bandwidth cells), their leading multiple of
 // 1 KiB: every
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(256) void k_copy_stream(uint8_t *__restrict__ dst, 
     copy_stream(dst, src, n, (uint64_t)blockIdx.x * waves_per_wg + wave, (uint64_t)gridDim.x * waves_per_wg, lane);
 }
 
-// Small messages (up to SMALL_MSG bytes, multiples of 8 or 16): a sub-group of lanes, one vector V per
+// Small messages (up to 64 vectors of 8 or 16 bytes): a sub-group of lanes, one vector V per
 // lane, moves one message, so a wave instruction carries 64 / group messages; sets of four such rounds
 // alternate between two register sets, the loads of the next set going out before the stores of the
 // current one (with one round at a time a wave had 512 bytes in flight and the small sizes were
@@ -385,14 +386,17 @@ __global__ __launch_bounds__(256) void k_copy_sweep(Ctx c, SweepArgs a)
     const uint64_t tasks = chunks * a.ops_per_pe;
     uint8_t *const lbase = ptr(c, a.local_off, pe);
     uint8_t *const rbase = ptr(c, a.remote_off, peer);
-    if (contiguous && a.count <= SMALL_MSG && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 7) == 0) {
-        if (((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0)
-            sweep_small<u32x4>(a, lbase, rbase, my_wave, team_waves, lane);
-        else
-            sweep_small<u32x2>(a, lbase, rbase, my_wave, team_waves, lane);
+    // a message that one wave instruction covers (64 lanes x 16 bytes, or x 8 where only that alignment holds)
+    const uint64_t align_bits = a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off;
+    if (contiguous && (align_bits & 15) == 0 && a.count <= 2 * SMALL_MSG) {
+        sweep_small<u32x4>(a, lbase, rbase, my_wave, team_waves, lane);
         return;
     }
-    if (contiguous && a.count >= 1024 && ((a.count | a.local_slot | a.remote_slot | a.local_off | a.remote_off) & 15) == 0) {
+    if (contiguous && (align_bits & 7) == 0 && a.count <= SMALL_MSG) {
+        sweep_small<u32x2>(a, lbase, rbase, my_wave, team_waves, lane);
+        return;
+    }
+    if (contiguous && a.count > 2 * SMALL_MSG && (align_bits & 15) == 0) {
         if (a.count > 4096 && a.count % 4096) {
             sweep_pipelined_ragged(a, lbase, rbase, my_wave, team_waves, lane);
             return;
