@@ -187,17 +187,29 @@ enum { SHMEM_OP_PUT = 0, SHMEM_OP_GET = 1, SHMEM_OP_IPUT = 2, SHMEM_OP_IGET = 3 
 int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_per_pe);
 
 /* Bandwidth sweep cell.  Every PE p, as initiator, issues ops_per_pe operations
- * of `kind` towards PE (p+1) mod npes, back to back in one launch of
+ * of `kind` towards PE (p+1) mod npes, back to back in one launch of at most
  * npes * wgs_per_pe workgroups.  Op k works on slot k mod nslots: the local
  * buffer at local_sym + slot * local_slot_bytes in p's own segment and the
  * remote buffer at remote_sym + slot * remote_slot_bytes in the peer's segment.
  * PUT/GET move `count` bytes; IPUT/IGET move `count` elements of elem_bytes
- * with the given strides (local_stride applies to the local side).  Completion
- * is the kernel boundary.  Errors as for the single ops, checked for the last
+ * with the given strides (local_stride applies to the local side).  The ops of
+ * a cell are independent and unordered; completion is the kernel boundary.
+ * Bandwidth cells -- PUT/GET of whole multiples of 4 KiB with 16-byte aligned
+ * placement, asked for with at least one workgroup per compute unit -- run on
+ * one larger workgroup per compute unit (compute units / npes per PE) that
+ * streams through LDS at a paced rate; shmem_copy_sweep_geometry tells which
+ * launch a cell gets.  Errors as for the single ops, checked for the last
  * slot too. */
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
                      ptrdiff_t remote_stride, ptrdiff_t local_stride, size_t remote_slot_bytes,
                      size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe);
+/* HOST: the launch that shmem_copy_sweep makes for a contiguous or strided
+ * cell with these arguments: *workgroups_out workgroups of *threads_out
+ * threads (either may be NULL).  Enqueues nothing.
+ * Errors: NOT_INIT, INVALID_ARG. */
+int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_t count, size_t remote_slot_bytes,
+                              size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe,
+                              int *workgroups_out /* HOST */, int *threads_out /* HOST */);
 
 /* n AMOs on the symmetric counter array ctr_sym (uint64[T] on every PE).
  * Op i targets word dev_idx[i] of PE dev_pe[i] and is issued by PE

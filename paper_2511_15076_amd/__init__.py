@@ -75,6 +75,7 @@ _SIG = {
     "shmem_stream_sync": (_i, [C.POINTER(C.c_uint64)]),
     "shmem_op_batch": (_i, [_vp, _sz, _sz, _i]),
     "shmem_copy_sweep": (_i, [_i, _vp, _vp, _sz, _sz, _pd, _pd, _sz, _sz, _sz, _i, _i]),
+    "shmem_copy_sweep_geometry": (_i, [_i, _vp, _vp, _sz, _sz, _sz, _sz, _i, _i, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "shmem_amo_batch": (_i, [_i, _vp, _sz, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i]),
     "shmem_hash_insert": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
     "shmem_hash_lookup": (_i, [_vp, _sz, _vp, _sz, _vp, _i]),
@@ -238,6 +239,16 @@ def copy_sweep(kind, remote_sym, local_sym, count, elem_bytes=1, remote_stride=1
     return _check(_L.shmem_copy_sweep(kind, _addr(remote_sym), _addr(local_sym), count, elem_bytes,
                                       remote_stride, local_stride, remote_slot_bytes, local_slot_bytes,
                                       nslots, ops_per_pe, wgs_per_pe), "shmem_copy_sweep")
+
+
+def copy_sweep_geometry(kind, remote_sym, local_sym, count, remote_slot_bytes, local_slot_bytes, nslots, ops_per_pe,
+                        wgs_per_pe):
+    """(workgroups, threads per workgroup) of the launch copy_sweep makes for this cell."""
+    wgs, thr = C.c_int(0), C.c_int(0)
+    _check(_L.shmem_copy_sweep_geometry(kind, _addr(remote_sym), _addr(local_sym), count, remote_slot_bytes,
+                                        local_slot_bytes, nslots, ops_per_pe, wgs_per_pe, C.byref(wgs), C.byref(thr)),
+           "shmem_copy_sweep_geometry")
+    return wgs.value, thr.value
 
 
 def amo_batch(kind, ctr_sym, T, dev_pe, dev_idx, dev_a, dev_b, dev_old, n, wgs_per_pe, aggregate=0):

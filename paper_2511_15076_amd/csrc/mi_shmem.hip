@@ -18,6 +18,7 @@
 #include "host_logic.hpp"
 #include "shmemx.hpp"
 #include "kernels_copy.hpp"
+#include "kernels_stream.hpp"
 #include "kernels_amo.hpp"
 #include "kernels_hash.hpp"
 #include "kernels_bfs.hpp"
@@ -41,6 +42,8 @@ struct Host {
     uint64_t *scratch = nullptr;
     hipStream_t stream = nullptr;
     int num_cus = 0;
+    int wall_khz = 100000;         // rate of the constant-rate clock the streaming copy paces itself by
+    double stream_pace_ns = 0;     // pacing of the streaming copy: ns per 4 KiB task and workgroup when 256 workgroups stream
     bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
     hostlogic::SymAllocator alloc; // symmetric offsets (guarded by mu)
     uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
@@ -100,9 +103,33 @@ inline int wgs_for_bytes(size_t n)
     return (int)std::max<size_t>(1, std::min(w, cap));
 }
 
+// Pacing of the streaming copy (kernels_stream.hpp) for a launch of nwg workgroups, in 1/256 ticks of the
+// constant-rate clock per task and workgroup.  The target is a chip-wide task rate: 256 workgroups issue one
+// 4 KiB task each per STREAM_PACE_NS, i.e. 3.33 TB/s of reads and as much of writes, a few per cent under
+// what the memory system sustains for a copy (about 6.8 TB/s of traffic; beyond that it congests and
+// delivers 5.5).  Fewer workgroups get proportionally shorter periods (a single compute unit cannot
+// reach them, so small launches run unpaced in effect).
+constexpr double STREAM_PACE_NS = 315.0;
+uint32_t stream_period(unsigned nwg)
+{
+    const double ns = H.stream_pace_ns * (double)nwg / 256.0;
+    const double ticks = ns * (double)H.wall_khz / 1e6;
+    return (uint32_t)(ticks * 256.0 + 0.5);
+}
+
 int launch_copy(uint8_t *dst, const uint8_t *src, size_t n)
 {
-    if (n >= (1u << 20) && (((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
+    const bool aligned = (((uintptr_t)dst | (uintptr_t)src) & 15) == 0;
+    if (n >= (32u << 20) && aligned && n / shmemx::ST_CHUNK < UINT32_MAX) {
+        // whole 4 KiB tasks through the wave-specialised streaming copy, one workgroup per compute unit;
+        // what is left (under 4 KiB) through the generic copy
+        const uint32_t chunks = (uint32_t)(n / shmemx::ST_CHUNK);
+        const unsigned grid = (unsigned)std::max(1, H.num_cus);
+        hipLaunchKernelGGL(shmemx::k_copy_stream_lds, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, dst, src, chunks,
+                           stream_period(grid));
+        const size_t done = (size_t)chunks * shmemx::ST_CHUNK;
+        if (n > done) hipLaunchKernelGGL(shmemx::k_copy, dim3(1), dim3(WG_THREADS), 0, H.stream, dst + done, src + done, n - done);
+    } else if (n >= (1u << 20) && aligned) {
         const size_t want = (n + 16383) / 16384;
         const size_t grid = std::min<size_t>(want, (size_t)std::max(1, H.num_cus) * 2);
         hipLaunchKernelGGL(shmemx::k_copy_stream, dim3((unsigned)grid), dim3(WG_THREADS), 0, H.stream, dst, src, n);
@@ -158,6 +185,22 @@ int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
 {
     if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
     return hip_rc(hipLaunchKernel(kernel, grid, block, args, 0, H.stream));
+}
+
+// Bandwidth cells -- contiguous messages of whole 4 KiB tasks with 16-byte aligned placement, asked for with at
+// least one workgroup per compute unit and enough tasks to fill the rings -- go through the streaming copy: one
+// wave-specialised workgroup per compute unit, team = compute units / PEs.  Returns that team size, or 0 for
+// the cells that stay on the register-pipelined kernel.
+uint32_t sweep_stream_team(bool is_strided, uint64_t count, uint64_t remote_slot, uint64_t local_slot, uint64_t roff,
+                           uint64_t loff, uint64_t nslots, int ops_per_pe, int wgs_per_pe)
+{
+    if (is_strided || count == 0 || count % shmemx::ST_CHUNK) return 0;
+    if ((count | remote_slot | local_slot | roff | loff) & 15) return 0;
+    const uint32_t team = (uint32_t)(H.num_cus / H.npes);
+    const uint64_t ntasks = (count / shmemx::ST_CHUNK) * (uint64_t)ops_per_pe;
+    if (team < 1 || (uint64_t)H.npes * (uint64_t)wgs_per_pe < (uint64_t)H.num_cus) return 0;
+    if (ntasks >= UINT32_MAX || ntasks < (uint64_t)team * shmemx::ST_RING || nslots > UINT32_MAX) return 0;
+    return team;
 }
 
 }  // namespace
@@ -224,6 +267,12 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     H.stream = s; H.num_cus = prop.multiProcessorCount; H.pinned = pinned;
     const char *coop = getenv("MI_SHMEM_COOPERATIVE_LAUNCH");
     H.cooperative = coop && coop[0] == '1';
+    int khz = 0;
+    H.wall_khz = (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0) ? khz : 100000;
+    (void)hipGetLastError();
+    const char *pace = getenv("MI_SHMEM_STREAM_PACE_NS");     // measurement aid: 0 = unpaced
+    H.stream_pace_ns = pace ? atof(pace) : STREAM_PACE_NS;
+    if (!(H.stream_pace_ns >= 0.0 && H.stream_pace_ns < 1e6)) H.stream_pace_ns = STREAM_PACE_NS;
     H.alloc.reset((uint64_t)(uintptr_t)dev_heap, (uint64_t)heap_bytes_per_pe);
     H.init = true;
     return SHMEM_OK;
@@ -441,9 +490,33 @@ int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, 
     a.remote_stride = remote_stride; a.local_stride = local_stride; a.remote_slot = remote_slot_bytes;
     a.local_slot = local_slot_bytes; a.nslots = nslots; a.ops_per_pe = (uint32_t)ops_per_pe;
     a.wgs_per_pe = (uint32_t)wgs_per_pe;
+    if (const uint32_t team = sweep_stream_team(is_strided, count, remote_slot_bytes, local_slot_bytes, roff, loff, nslots,
+                                                ops_per_pe, wgs_per_pe)) {
+        shmemx::StreamSweepArgs sa;
+        sa.kind = kind; sa.remote_off = roff; sa.local_off = loff; sa.count = count;
+        sa.remote_slot = remote_slot_bytes; sa.local_slot = local_slot_bytes; sa.nslots = (uint32_t)nslots;
+        sa.ops_per_pe = (uint32_t)ops_per_pe; sa.team = team;
+        const unsigned grid = (unsigned)H.npes * team;
+        sa.period = stream_period(grid);
+        hipLaunchKernelGGL(shmemx::k_copy_sweep_stream, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, ctx(), sa);
+        return launched();
+    }
     hipLaunchKernelGGL(shmemx::k_copy_sweep, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
                        ctx(), a);
     return launched();
+}
+
+int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_t count, size_t remote_slot_bytes,
+                              size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe, int *workgroups_out,
+                              int *threads_out)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (kind < SHMEM_OP_PUT || kind > SHMEM_OP_IGET || !grid_fits(wgs_per_pe) || ops_per_pe < 0 || nslots < 1) return SHMEM_ERR_INVALID_ARG;
+    const uint32_t team = sweep_stream_team(kind >= SHMEM_OP_IPUT, count, remote_slot_bytes, local_slot_bytes, off_of(remote_sym),
+                                            off_of(local_sym), nslots, ops_per_pe, wgs_per_pe);
+    if (workgroups_out) *workgroups_out = team ? H.npes * (int)team : H.npes * wgs_per_pe;
+    if (threads_out) *threads_out = team ? (int)shmemx::ST_THREADS : WG_THREADS;
+    return SHMEM_OK;
 }
 
 int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe, const uint32_t *dev_idx,

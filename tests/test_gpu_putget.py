@@ -315,6 +315,83 @@ def test_copy_sweep_cell(case):
     assert not np.array_equal(got, init)
 
 
+# Bandwidth cells: whole 4 KiB tasks, at least one workgroup per compute unit -> the streaming copy (wave-specialised
+# workgroups, LDS ring, every PE's task list rotated).  Team sizes that are not powers of two, slots used several times
+# over, unequal slot pitches, a PE that is its own peer, and task counts that leave some workgroups one task short.
+STREAM_CASES = [
+    # npes, kind, count, ops_per_pe, nslots, wgs_per_pe
+    (8, workgen.OP_PUT, 4096, 600, 600, 32),
+    (8, workgen.OP_GET, 8192, 300, 77, 256),
+    (8, workgen.OP_PUT, 20480, 131, 131, 64),
+    (3, workgen.OP_GET, 12288, 500, 500, 86),
+    (5, workgen.OP_PUT, 4096, 1001, 333, 52),
+    (7, workgen.OP_PUT, 1 << 20, 3, 3, 40),
+    (16, workgen.OP_GET, 4096, 300, 300, 16),
+    (1, workgen.OP_PUT, 1 << 16, 300, 300, 256),
+    (2, workgen.OP_GET, 4096, 2048, 5, 128),             # exactly one ring's worth of tasks per workgroup
+]
+
+
+@pytest.mark.parametrize("case", STREAM_CASES)
+def test_copy_sweep_streaming_cell(case):
+    npes, kind, count, nops, nslots, wgs = case
+    rslot = count + 4096 + 256
+    lslot = count + 16
+    hb = ((rslot + lslot) * nslots + 8192 + 255) // 256 * 256
+    init = seeded_heaps(npes, hb, 1300 + npes + count % 89)
+    w = oracle_world(init)
+    local_off, remote_off = 16, (lslot * nslots + 16 + 255) // 256 * 256 + 32
+    for p in range(npes):
+        peer = (p + 1) % npes
+        for k in range(nops):
+            s = k % nslots
+            lo, ro = local_off + s * lslot, remote_off + s * rslot
+            rc = w.put(p, ro, lo, count, peer) if kind == workgen.OP_PUT else w.get(p, lo, ro, count, peer)
+            assert rc == 0
+    w.barrier_all()
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        wgs_launched, threads = sh.copy_sweep_geometry(kind, base + remote_off, base + local_off, count, rslot, lslot, nslots,
+                                                       nops, wgs)
+        assert threads == 384 and wgs_launched == npes * (256 // npes), "this cell was meant for the streaming copy"
+        sh.copy_sweep(kind, base + remote_off, base + local_off, count, 1, 1, 1, rslot, lslot, nslots, nops, wgs)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+    assert not np.array_equal(got, init)
+
+
+def test_copy_sweep_geometry_keeps_small_cells_on_the_register_path():
+    with shmem_world(8, 1 << 22) as (heap, base):
+        half = 1 << 21
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 64, 16) == (128, 256)     # under one workgroup per CU
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 64, 32) == (256, 256)     # too few tasks
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4112, 4352, 4352, 64, 640, 32) == (256, 256)    # not whole tasks
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 640, 32) == (256, 384)
+        assert sh.copy_sweep_geometry(workgen.OP_IPUT, base + half, base, 4096, 4096 * 8, 4096 * 8, 4, 640, 32) == (256, 256)
+
+
+@pytest.mark.parametrize("nbytes", [32 << 20, (32 << 20) + 4096 + 48, (40 << 20) + 8])
+def test_large_standalone_put_and_get_stream(nbytes):
+    """Stand-alone copies of 32 MiB and more: whole 4 KiB tasks through the streaming copy, the rest generic."""
+    npes = 2
+    hb = ((2 * nbytes + 8192) + 255) // 256 * 256
+    init = seeded_heaps(npes, hb, 77 + nbytes % 13)
+    w = oracle_world(init)
+    src_off, dst_off = 16, (nbytes + 16 + 255) // 256 * 256 + 16
+    assert w.put(0, dst_off, src_off, nbytes, 1) == 0
+    w.barrier_all()
+    assert w.get(1, src_off, dst_off, nbytes, 0) == 0
+    w.barrier_all()
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.put(0, base + dst_off, base + src_off, nbytes, 1)
+        sh.get(1, base + hb + src_off, base + dst_off, nbytes, 0)
+        sh.stream_sync()
+        got = heaps_of(heap, npes)
+    assert np.array_equal(got, w.heaps())
+
+
 def test_allocator_matches_oracle_and_host_errors():
     npes, hb = 2, 64 * 256
     w = oracle.World(npes, hb, oracle.EAGER, 0)
