@@ -186,6 +186,28 @@ enum { SHMEM_OP_PUT = 0, SHMEM_OP_GET = 1, SHMEM_OP_IPUT = 2, SHMEM_OP_IGET = 3 
  * co-resident), DEVICE. */
 int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_per_pe);
 
+/* The executor above for callers that cannot allocate or register anything:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It needs no shmem_init and no scratch buffer from the caller: the
+ * barrier and fault words it uses are a fixed array inside the library's code
+ * object (33,280 bytes, held by every GPU that loads the library until the
+ * process ends), which limits it to npes <= 64 (OUT_OF_RANGE beyond).  The
+ * call allocates and frees nothing; it launches kernels on hip_stream only (a
+ * fill of the words it uses, the executor, and -- if dev_fault is given -- a
+ * copy of the fault words) and is asynchronous.
+ * dev_heap: DEVICE, npes * heap_bytes_per_pe bytes, 256-byte aligned, segment
+ * size a multiple of 256; dev_ops: DEVICE table of n descriptors whose offsets
+ * refer to that heap; dev_fault: DEVICE uint64[2] (may be NULL) that receives
+ * the device error word and the index of the first rejected descriptor (0, 0 =
+ * none) once the stream has reached that point.  Same table semantics, same
+ * heap contents afterwards as shmem_op_batch.  All calls on one GPU share the
+ * one array: calls that overlap in time on a GPU (two streams, two threads)
+ * race on the barrier words and must be serialised by the caller.
+ * Errors: INVALID_ARG (also: more workgroups than can be co-resident),
+ * OUT_OF_RANGE (npes > 64), ALIGN, DEVICE. */
+int shmem_op_batch_noalloc(int npes, size_t heap_bytes_per_pe, void *dev_heap, const void *dev_ops, size_t n,
+                           size_t quiet_every, int wgs_per_pe, uint64_t *dev_fault, void *hip_stream);
+
 /* Bandwidth sweep cell.  Every PE p, as initiator, issues ops_per_pe operations
  * of `kind` towards PE (p+1) mod npes, back to back in one launch of at most
  * npes * wgs_per_pe workgroups.  Op k works on slot k mod nslots: the local

@@ -74,6 +74,7 @@ _SIG = {
     "shmem_barrier_all": (_i, []),
     "shmem_stream_sync": (_i, [C.POINTER(C.c_uint64)]),
     "shmem_op_batch": (_i, [_vp, _sz, _sz, _i]),
+    "shmem_op_batch_noalloc": (_i, [_i, _sz, _vp, _vp, _sz, _sz, _i, _vp, _vp]),
     "shmem_copy_sweep": (_i, [_i, _vp, _vp, _sz, _sz, _pd, _pd, _sz, _sz, _sz, _i, _i]),
     "shmem_copy_sweep_geometry": (_i, [_i, _vp, _vp, _sz, _sz, _sz, _sz, _i, _i, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "shmem_amo_batch": (_i, [_i, _vp, _sz, _vp, _vp, _vp, _vp, _vp, _sz, _i, _i]),
@@ -232,6 +233,11 @@ def stream_sync():
 
 def op_batch(dev_ops, n, quiet_every, wgs_per_pe):
     return _check(_L.shmem_op_batch(_addr(dev_ops), n, quiet_every, wgs_per_pe), "shmem_op_batch")
+
+
+def op_batch_noalloc(npes, heap_bytes_per_pe, dev_heap, dev_ops, n, quiet_every, wgs_per_pe, dev_fault, hip_stream):
+    return _check(_L.shmem_op_batch_noalloc(npes, heap_bytes_per_pe, _addr(dev_heap), _addr(dev_ops), n, quiet_every,
+                                            wgs_per_pe, _addr(dev_fault), hip_stream), "shmem_op_batch_noalloc")
 
 
 def copy_sweep(kind, remote_sym, local_sym, count, elem_bytes=1, remote_stride=1, local_stride=1,

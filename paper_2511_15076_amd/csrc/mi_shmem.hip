@@ -187,6 +187,58 @@ int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
     return hip_rc(hipLaunchKernel(kernel, grid, block, args, 0, H.stream));
 }
 
+// ---------------------------------------------------------------------------
+// Scratch words that live in the code object, for shmem_op_batch_noalloc: callers that cannot allocate (code
+// under graph capture, serving loops, harnesses that forbid it) get the executor's barrier and fault words from
+// here instead of from a buffer of their own.  Each GPU that loads the library holds its own copy of the array
+// until the process ends.  In host code the array's name is only a stand-in: the device address is looked up
+// once per device (with that device current) and kept; kernels, fills and copies get that pointer.
+constexpr int NOALLOC_MAX_PES = 64;
+constexpr size_t NOALLOC_WORDS = shmemx::W_PE_BASE + (size_t)NOALLOC_MAX_PES * shmemx::W_PE_WORDS;   // 4160 words = 33,280 bytes
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static __device__ __align__(256) uint64_t scratch[NOALLOC_WORDS];
+
+struct NoallocDevice {
+    uint64_t *ptr = nullptr;       // device address of this device's copy of `scratch`
+    int num_cus = 0;
+    int resident_small = 0, resident_stream = 0;   // co-residency limits of the two executor instances
+    bool ready = false;
+};
+NoallocDevice noalloc_dev[NOALLOC_MAX_DEVICES];
+std::mutex noalloc_mu;
+
+__global__ void k_fill_zero(uint64_t *p, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+__global__ void k_fault_out(const uint64_t *words, uint64_t *out)
+{
+    if (threadIdx.x < 2) out[threadIdx.x] = __hip_atomic_load(&words[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Set-up for the current device, on the first call there.
+int noalloc_setup(NoallocDevice **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return SHMEM_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(noalloc_mu);
+    NoallocDevice &d = noalloc_dev[dev];
+    if (!d.ready) {
+        uint64_t *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SHMEM_ERR_DEVICE;
+        int cus = 0, per_cu_small = 0, per_cu_stream = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return SHMEM_ERR_DEVICE;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_small, shmemx::k_op_batch<false>, WG_THREADS, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_stream, shmemx::k_op_batch<true>, WG_THREADS, 0) != hipSuccess)
+            return SHMEM_ERR_DEVICE;
+        d.ptr = ptr; d.num_cus = cus; d.resident_small = per_cu_small * cus; d.resident_stream = per_cu_stream * cus;
+        d.ready = true;
+    }
+    *out = &d;
+    return SHMEM_OK;
+}
+
 // Bandwidth cells -- contiguous messages of whole 4 KiB tasks with 16-byte aligned placement, asked for with at
 // least one workgroup per compute unit and enough tasks to fill the rings -- go through the streaming copy: one
 // wave-specialised workgroup per compute unit, team = compute units / PEs.  Returns that team size, or 0 for
@@ -454,6 +506,39 @@ int shmem_op_batch(const void *dev_ops, size_t n, size_t quiet_every, int wgs_pe
     const shmem_op_desc *ops = (const shmem_op_desc *)dev_ops;
     void *args[] = {&c, &ops, &n, &quiet_every, &wgs_per_pe};
     return launch_resident((const void *)kernel, dim3((unsigned)grid), dim3(WG_THREADS), args);
+}
+
+int shmem_op_batch_noalloc(int npes, size_t heap_bytes_per_pe, void *dev_heap, const void *dev_ops, size_t n,
+                           size_t quiet_every, int wgs_per_pe, uint64_t *dev_fault, void *hip_stream)
+{
+    if (npes < 1 || heap_bytes_per_pe == 0 || !dev_heap || (n && !dev_ops) || wgs_per_pe < 1 || (uintptr_t)dev_ops % 8 ||
+        (uintptr_t)dev_fault % 8) return SHMEM_ERR_INVALID_ARG;
+    if (npes > NOALLOC_MAX_PES) return SHMEM_ERR_OUT_OF_RANGE;       // beyond what the built-in scratch words cover
+    if (heap_bytes_per_pe % GRAN || (uintptr_t)dev_heap % GRAN) return SHMEM_ERR_ALIGN;
+    if (heap_bytes_per_pe > SIZE_MAX / (size_t)npes) return SHMEM_ERR_INVALID_ARG;
+    NoallocDevice *d = nullptr;
+    if (int rc = noalloc_setup(&d)) return rc;
+    const long grid = (long)npes * wgs_per_pe;
+    const bool stream_inst = wgs_per_pe >= 16;
+    if (grid > (stream_inst ? d->resident_stream : d->resident_small)) return SHMEM_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // every call on a GPU shares that GPU's words and finds what the last call left: clear the ones this
+    // launch uses (a fill kernel, not a memset node, so that the sequence can be captured into a graph)
+    const uint32_t words = (uint32_t)(shmemx::W_PE_BASE + (size_t)npes * shmemx::W_PE_WORDS);
+    hipLaunchKernelGGL(k_fill_zero, dim3((words + 255) / 256), dim3(256), 0, st, d->ptr, words);
+    if (int rc = launched()) return rc;
+    if (n) {
+        shmemx::Ctx c{(uint8_t *)dev_heap, (uint64_t)heap_bytes_per_pe, d->ptr, npes};
+        const shmem_op_desc *ops = (const shmem_op_desc *)dev_ops;
+        void *args[] = {&c, &ops, &n, &quiet_every, &wgs_per_pe};
+        const void *kernel = stream_inst ? (const void *)shmemx::k_op_batch<true> : (const void *)shmemx::k_op_batch<false>;
+        if (hipLaunchKernel(kernel, dim3((unsigned)grid), dim3(WG_THREADS), args, 0, st) != hipSuccess) return SHMEM_ERR_DEVICE;
+    }
+    if (dev_fault) {
+        hipLaunchKernelGGL(k_fault_out, dim3(1), dim3(64), 0, st, (const uint64_t *)d->ptr, dev_fault);
+        if (int rc = launched()) return rc;
+    }
+    return SHMEM_OK;
 }
 
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
