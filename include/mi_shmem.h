@@ -152,7 +152,13 @@ int shmem_quiet(int pe_self);
 int shmem_barrier_all(void);
 /* HOST waits for the stream.  DEVICE_FAULT if the device error word is set
  * (the word is then cleared); *first_bad_index (HOST, may be NULL) receives
- * the index of the first rejected op. */
+ * the index of the first rejected op.  If the fault was a bounded wait that
+ * gave up (a barrier or signal wait that timed out: some workgroup never
+ * arrived), arrival counts and generations are left half-advanced, so the
+ * call also starts all synchronisation state afresh before it returns: the
+ * scratch words, and the signals, counters and barrier words of every live
+ * Gin, team and MoE object read 0 again.  The library is usable as after
+ * shmem_init; data in the heap is as the failed launch left it. */
 int shmem_stream_sync(uint64_t *first_bad_index);
 
 /* ---- batched entry points: inputs device-resident, one launch each -------- */
@@ -240,8 +246,10 @@ int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_
  * word is 0 or larger, through a compare-swap retry loop.  dev_old[i]
  * (DEVICE, may be NULL) receives the fetched value.  All arrays DEVICE.
  * `aggregate` != 0 lets a workgroup combine its ops on the same word before
- * they reach memory (FETCH_ADD, FETCH_OR, MIN_CAS_LOOP); results are
- * indistinguishable from some serial order either way. */
+ * they reach memory (FETCH_ADD, FETCH_OR, MIN_CAS_LOOP); results -- final
+ * words and fetched values -- are indistinguishable from some serial order
+ * either way (for MIN_CAS_LOOP the fetched value is what the word held just
+ * before the op in that order). */
 enum { SHMEM_AMO_FETCH_ADD = 0, SHMEM_AMO_COMPARE_SWAP = 1, SHMEM_AMO_FETCH_OR = 2, SHMEM_AMO_MIN_CAS_LOOP = 3 };
 int shmem_amo_batch(int kind, uint64_t *ctr_sym, size_t T, const int32_t *dev_pe, const uint32_t *dev_idx,
                     const uint64_t *dev_a, const uint64_t *dev_b, uint64_t *dev_old, size_t n,
@@ -495,8 +503,8 @@ int shmem_moe_combine(shmem_moe_t moe, const void *dev_expert_out, const int32_t
  * It is the second backend of the same descriptor format and a debugging twin
  * of shmem_op_batch: same table, same heap contents afterwards.
  *
- * shmem_proxy_create: queue_entries is a power of two in [2, 2^20]; starts the
- * thread.  shmem_proxy_submit: asynchronous; launches `workgroups` workgroups
+ * shmem_proxy_create: queue_entries is a power of two in [2, 2^20] (a ring may
+ * be much shorter than one submission, or than a wavefront); starts the thread.  shmem_proxy_submit: asynchronous; launches `workgroups` workgroups
  * (all must be co-resident) on the library's stream that enqueue dev_ops[0..n)
  * (DEVICE table, 16-byte aligned); descriptor i takes ticket (descriptors
  * submitted before) + i, so the ring order is the table order; producers wait

@@ -124,8 +124,15 @@ __global__ __launch_bounds__(256) void k_amo_batch_agg(Ctx c, AmoArgs g)
             const uint64_t i = p0 + (uint64_t)j * blockDim.x + threadIdx.x;
             if (slot[j] == AGG_EMPTY || !g.old) continue;
             const unsigned long long base = s_base[slot[j]];
-            g.old[i] = g.kind == SHMEM_AMO_FETCH_ADD ? base + pos[j]
-                     : g.kind == SHMEM_AMO_FETCH_OR ? (base | pos[j]) : base;
+            // what the word held just before this op, the group's ops taken in the order in which they reached
+            // the LDS slot: the base plus / or-ed with / lowered by what the earlier ones brought (pos is the
+            // slot's value before this op; for the minimum it starts at all ones = nothing yet, and a word of 0
+            // counts as empty)
+            unsigned long long seen;
+            if (g.kind == SHMEM_AMO_FETCH_ADD) seen = base + pos[j];
+            else if (g.kind == SHMEM_AMO_FETCH_OR) seen = base | pos[j];
+            else seen = pos[j] == ~0ull ? base : (base == 0 || pos[j] < base ? pos[j] : base);
+            g.old[i] = seen;
         }
         __syncthreads();
     }

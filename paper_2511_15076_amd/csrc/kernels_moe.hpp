@@ -68,6 +68,9 @@ struct MoeCombineArgs {
 // In 64-bit signed arithmetic on purpose: the 32-bit unsigned form (lo < hvecs ? min(per, hvecs - lo) : 0)
 // was compiled by hipcc 7.2, when an unpredicated variant of the copy below was tried next to it, into code
 // that returned `per` for lo > hvecs (checked in isolation: same source, only this expression differing).
+// A second hazard of that variant, whatever the compiler does: a copy that lets the lanes beyond the end
+// repeat the LAST vector indexes vector count - 1, so it must never be entered with a count of 0 -- and parts
+// with a count of 0 are exactly what messages split over more waves than they have vectors produce.
 __device__ __forceinline__ uint32_t moe_part_vecs(uint32_t hvecs, uint32_t lo, uint32_t per)
 {
     const int64_t rem = (int64_t)hvecs - (int64_t)lo;

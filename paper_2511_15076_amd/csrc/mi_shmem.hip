@@ -49,6 +49,9 @@ struct Host {
     uint64_t *pinned = nullptr;    // small host staging area (error word, BFS counts)
     std::mutex mu;
     std::vector<struct shmem_proxy *> proxies;   // live proxy objects (their threads are stopped at finalize)
+    // live objects that own synchronisation words in the heap (signal arrays, team barrier words): after a
+    // barrier time-out their words are half-advanced and are cleared together with the scratch words
+    std::vector<shmemx::GinState> sync_words;
 } H;
 
 struct BfsGraph {
@@ -185,6 +188,21 @@ int launch_resident(const void *kernel, dim3 grid, dim3 block, void **args)
 {
     if (H.cooperative) return hip_rc(hipLaunchCooperativeKernel(kernel, grid, block, args, 0, H.stream));
     return hip_rc(hipLaunchKernel(kernel, grid, block, args, 0, H.stream));
+}
+
+void sync_words_add(const shmemx::GinState &g)
+{
+    std::lock_guard<std::mutex> lk(H.mu);
+    H.sync_words.push_back(g);
+}
+void sync_words_remove(const shmemx::GinState &g)
+{
+    std::lock_guard<std::mutex> lk(H.mu);
+    for (size_t i = 0; i < H.sync_words.size(); ++i)
+        if (H.sync_words[i].signals_off == g.signals_off && H.sync_words[i].counters_off == g.counters_off) {
+            H.sync_words.erase(H.sync_words.begin() + (long)i);
+            return;
+        }
 }
 
 // ---------------------------------------------------------------------------
@@ -339,6 +357,7 @@ int shmem_finalize(void)
     if (H.pinned) (void)hipHostFree(H.pinned);
     H.pinned = nullptr; H.init = false; H.npes = 0; H.heap = nullptr; H.scratch = nullptr;
     H.alloc.clear();
+    H.sync_words.clear();
     return hip_rc(e);
 }
 
@@ -488,7 +507,23 @@ int shmem_stream_sync(uint64_t *first_bad_index)
     if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
     if (H.pinned[0] == 0) return SHMEM_OK;
     if (first_bad_index) *first_bad_index = H.pinned[1];
-    if (hipMemsetAsync(H.scratch, 0, 16, H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    if (H.pinned[0] == shmemx::DEV_ERR_BARRIER_TIMEOUT) {
+        // A bounded wait gave up: arrival counts and generations of whatever barrier or signal wait was under
+        // way are half-advanced, and every later barrier on them would miscount.  Nothing runs on the stream
+        // now, so all synchronisation state starts again from zero: the scratch words, and the signal, counter
+        // and barrier words of every live Gin, team and MoE object.
+        if (hipMemsetAsync(H.scratch, 0, shmem_scratch_bytes(H.npes), H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+        std::vector<shmemx::GinState> words;
+        {
+            std::lock_guard<std::mutex> lk(H.mu);
+            words = H.sync_words;
+        }
+        for (const shmemx::GinState &g : words)
+            hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), g);
+        if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
+    } else if (hipMemsetAsync(H.scratch, 0, 16, H.stream) != hipSuccess) {
+        return SHMEM_ERR_DEVICE;
+    }
     return SHMEM_ERR_DEVICE_FAULT;
 }
 
@@ -846,6 +881,7 @@ int shmem_gin_create(int nsignals, int ncounters, void **gin_out)
     g->st.nsignals = (uint32_t)nsignals; g->st.ncounters = (uint32_t)ncounters;
     hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), g->st);
     if (int rc = launched()) { shmem_free(g->alloc); delete g; return rc; }
+    sync_words_add(g->st);
     *gin_out = g;
     return SHMEM_OK;
 }
@@ -855,6 +891,7 @@ int shmem_gin_destroy(void *gin)
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (!gin) return SHMEM_ERR_INVALID_ARG;
     GinObj *g = (GinObj *)gin;
+    sync_words_remove(g->st);
     int rc = shmem_free(g->alloc);
     delete g;
     return rc;
@@ -983,6 +1020,7 @@ int shmem_team_create(int start, int stride, int size, shmem_team_t *team_out)
     shmemx::GinState z{t->st.words_off, t->st.words_off, 32u, 0u};
     hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), z);
     if (int rc = launched()) { shmem_free(t->alloc); delete t; return rc; }
+    sync_words_add(z);
     *team_out = t;
     return SHMEM_OK;
 }
@@ -991,6 +1029,7 @@ int shmem_team_destroy(shmem_team_t t)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (!t) return SHMEM_ERR_INVALID_ARG;
+    sync_words_remove(shmemx::GinState{t->st.words_off, t->st.words_off, 32u, 0u});
     int rc = shmem_free(t->alloc);
     delete t;
     return rc;
@@ -1106,6 +1145,7 @@ int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_by
     st.gin.nsignals = nsig; st.gin.ncounters = 0;
     hipLaunchKernelGGL(shmemx::k_gin_zero, dim3((unsigned)std::min(H.npes, 1024)), dim3(256), 0, H.stream, ctx(), st.gin);
     if (int rc = launched()) { shmem_moe_destroy(m); return rc; }
+    sync_words_add(st.gin);
     *moe_out = m;
     return SHMEM_OK;
 }
@@ -1114,6 +1154,7 @@ int shmem_moe_destroy(shmem_moe_t m)
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (!m) return SHMEM_ERR_INVALID_ARG;
+    sync_words_remove(m->st.gin);
     int rc = shmem_free(m->sig_alloc);
     int rc2 = shmem_free(m->comb_alloc);
     int rc3 = shmem_free(m->recv_alloc);

@@ -23,23 +23,35 @@ __global__ __launch_bounds__(256) void k_proxy_submit(Ctx c, ProxyQueue q, const
                                                       uint64_t base)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-        const uint64_t ticket = base + i, slot = ticket & q.mask;
-        // flow control: the slot still holds descriptor ticket - entries until the host has taken it out
-        uint32_t spins = 0;
-        bool ok = true;
-        while (ticket > __hip_atomic_load(q.head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) + q.mask) {
-            if (timed_out(c)) { ok = false; break; }
-            __builtin_amdgcn_s_sleep(8);
-            if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, i); ok = false; break; }
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool live = i < n;
+    uint32_t spins = 0;
+    // The lanes of a wave hold consecutive tickets, and with a ring shorter than a wave the higher lanes'
+    // slots only become free after the host has taken out what the LOWER lanes of the same wave publish.
+    // So no lane may wait inside a loop of its own: every pass of this wave-wide loop lets each lane look
+    // at its slot once, and a lane publishes (descriptor, release, flag) in the pass in which it finds its
+    // slot free, while the others go round again.
+    while (ballot(live)) {
+        if (live) {
+            const uint64_t ticket = base + i, slot = ticket & q.mask;
+            // flow control: the slot still holds descriptor ticket - entries until the host has taken it out
+            if (ticket <= __hip_atomic_load(q.head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) + q.mask) {
+                const u32x4 *s = (const u32x4 *)(ops + i);
+                u32x4 *d = (u32x4 *)(q.ring + slot);
+                const u32x4 a = s[0], b = s[1], e = s[2], f = s[3];
+                d[0] = a; d[1] = b; d[2] = e; d[3] = f;                         // fire and forget: nothing is read back
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");                   // system scope: the descriptor before its flag
+                __hip_atomic_store(q.flags + slot, ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                i += stride;
+                live = i < n;
+                spins = 0;
+            } else if (timed_out(c)) {
+                live = false;
+            } else {
+                __builtin_amdgcn_s_sleep(8);
+                if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, i); live = false; }
+            }
         }
-        if (!ok) break;
-        const u32x4 *s = (const u32x4 *)(ops + i);
-        u32x4 *d = (u32x4 *)(q.ring + slot);
-        const u32x4 a = s[0], b = s[1], e = s[2], f = s[3];
-        d[0] = a; d[1] = b; d[2] = e; d[3] = f;                         // fire and forget: nothing is read back
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");                   // system scope: the descriptor before its flag
-        __hip_atomic_store(q.flags + slot, ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 

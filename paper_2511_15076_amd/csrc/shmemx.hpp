@@ -120,7 +120,13 @@ __device__ __forceinline__ bool barrier_arrive(const Ctx &c, uint64_t *count, ui
 {
     // All atomics here are relaxed: the caller's quiet() before and acquire() after are the
     // fences.  (An acquire on every poll would invalidate the die's L2 once per poll.)
-    const uint64_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    // The generation must be read BEFORE the arrival is counted (counted first, the last arriver could open the
+    // barrier before this read, which would then see the new generation and wait for a release that has
+    // already happened).  The two are relaxed atomics on different addresses, which neither the compiler nor
+    // the memory system keeps in order by themselves: the empty asm consumes the loaded value, so the wave has
+    // the generation in a register (the load has returned) before the add can be issued.
+    uint64_t g = __hip_atomic_load(gen, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    asm volatile("" : "+v"(g) : : "memory");
     *my_gen = g;
     const uint64_t a = __hip_atomic_fetch_add(count, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
     if (a == n - 1) {

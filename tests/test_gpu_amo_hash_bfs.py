@@ -89,6 +89,49 @@ def test_fetch_or_and_min_loop_batch(agg):
     assert np.array_equal(final, np.stack([w2.heap(p)[off:off + 8 * T].view(np.uint64) for p in range(npes)]))
 
 
+def _min_loop_values_fit_a_serial_order(a, old):
+    """The ops on ONE word (operands a, fetched values old, word initially 0): is there an order in which every
+    op fetched what the word held just before it?  The word only changes when an op lowers it (or fills it while
+    it is 0), so the order is forced: at value v, first every op that fetched v and leaves it alone, then the one
+    op that fetched v and changes it."""
+    left = list(zip(a.tolist(), old.tolist()))
+    v = 0
+    while left:
+        here = [(x, o) for x, o in left if o == v]
+        if not here:
+            return False
+        movers = [x for x, o in here if v == 0 or x < v]
+        if len(movers) > 1:
+            return False
+        left = [(x, o) for x, o in left if o != v]
+        if movers:
+            v = movers[0]
+        elif left:
+            return False           # nobody moves the word on, yet ops remain that fetched something else
+    return True
+
+
+@pytest.mark.parametrize("agg", [0, 1])
+def test_min_loop_fetched_values_fit_a_serial_order(agg):
+    # few words, many ops per word, operands with repeats: the combining kernel merges dozens of ops per word
+    npes, T, n, hb = 4, 3, 6000, 1 << 12
+    rng = np.random.default_rng(17)
+    pe = rng.integers(0, npes, n).astype(np.int32)
+    idx = rng.integers(0, T, n).astype(np.uint32)
+    a = rng.integers(1, 400, n).astype(np.uint64)
+    final, old, _ = run_amo(sh.AMO_MIN_CAS_LOOP, npes, T, pe, idx, a, None, 2, agg, hb)
+    for p in range(npes):
+        for t in range(T):
+            m = (pe == p) & (idx == t)
+            assert final[p, t] == a[m].min()
+            assert _min_loop_values_fit_a_serial_order(a[m], old[m]), (p, t)
+    # the checker itself: a dropped dependency must not pass
+    assert _min_loop_values_fit_a_serial_order(np.array([5, 3, 7]), np.array([0, 5, 3]))
+    assert not _min_loop_values_fit_a_serial_order(np.array([5, 3]), np.array([0, 0]))
+    assert not _min_loop_values_fit_a_serial_order(np.array([5, 3, 7]), np.array([0, 5, 7]))
+    assert not _min_loop_values_fit_a_serial_order(np.array([5, 3, 2]), np.array([0, 5, 5]))
+
+
 @pytest.mark.parametrize("dist,T", [("uniform", 1), ("zipf", 1024)])
 def test_compare_swap_claim_batch(dist, T):
     npes, n, hb = 64, 120000, 1 << 16

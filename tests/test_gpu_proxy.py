@@ -54,6 +54,26 @@ def test_proxy_matches_oracle_and_device_path(entries, wgs):
         assert np.array_equal(heaps_of(heap, npes), got_proxy)
 
 
+@pytest.mark.parametrize("entries,nops,wgs", [(2, 700, 1), (4, 900, 2), (8, 1000, 1), (32, 3000, 3)])
+def test_proxy_ring_shorter_than_a_wavefront(entries, nops, wgs):
+    # one submission of far more descriptors than the ring holds, and a ring shorter than the 64 lanes of a
+    # wave: the higher lanes' slots only come free after the host has taken out what the lower lanes of the
+    # SAME wave publish, so no lane may spin on its slot while the others wait for it
+    npes, hb = 4, 1 << 18
+    ops = workgen.cfg1_op_table(seed=4242 + entries, npes=npes, heap_bytes=hb, nops=nops)
+    init = seeded_heaps(npes, hb, 300 + entries)
+    want = oracle_heaps(init, ops, 100)
+    with shmem_world(npes, hb) as (heap, base):
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        px = sh.proxy_create(entries)
+        sh.proxy_submit(px, to_dev(ops), len(ops), wgs)
+        sh.proxy_quiet(px)
+        assert sh.proxy_stats(px) == {"submitted": nops, "executed": nops, "rejected": 0}
+        assert np.array_equal(heaps_of(heap, npes), want)
+        sh.proxy_destroy(px)
+        sh.stream_sync()                                   # no producer gave up
+
+
 def test_proxy_strided_and_several_submissions():
     npes, hb = 3, 1 << 16
     init = seeded_heaps(npes, hb, 50)

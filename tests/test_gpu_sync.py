@@ -186,3 +186,51 @@ def test_sync_entry_point_errors():
             assert e.value.status == status
         sh.gin_destroy(gin)
         sh.stream_sync()
+
+
+def test_a_timed_out_wait_leaves_the_library_usable():
+    """After a bounded wait has given up, arrival counts and generations are half-advanced.  The state is planted
+    from the host (no kernel is made to hang): a time-out code in the fault word, stale arrivals on the world
+    barrier, on a PE's team words, on a team object's words and on a Gin signal.  shmem_stream_sync reports the
+    fault once and starts all of it afresh; barriers and signal waits then work as after shmem_init."""
+    npes, hb = 8, 1 << 16
+    dev = torch.device("cuda:0")
+    heap = torch.zeros(npes * hb, dtype=torch.uint8, device=dev)
+    scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
+    sh.init(npes, hb, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    try:
+        base = heap.data_ptr()
+        slots = sh.malloc(8 * npes)
+        gin = sh.gin_create(2, 1)
+        team = sh.team_create(0, 2, 4)
+        sig_off = sh.gin_signal_sym(gin, 0) - base
+        team_off = int(sh.team_device_state(team).words_off)
+        words = scratch.view(torch.int64)
+        hv = heap.view(npes, hb)
+        words[0] = 2                      # DEV_ERR_BARRIER_TIMEOUT
+        words[1] = 5                      # the workgroup that gave up
+        words[16] = 3                     # three stale arrivals on the world barrier
+        words[32] = 41                    # ... and a generation somewhere in the middle
+        words[64 + 64 * 2] = 1            # PE 2's team barrier: one stale arrival
+        words[64 + 64 * 2 + 32] = 1       # and its stage of the world barrier
+        hv[0, team_off:team_off + 8].view(torch.int64)[0] = 2          # the team object: two of four arrived
+        hv[1, sig_off:sig_off + 8].view(torch.int64)[0] = 9            # a signal that was never reset
+        torch.cuda.synchronize()
+        with pytest.raises(sh.ShmemError) as ei:
+            sh.stream_sync()
+        assert ei.value.status == sh.ERR_DEVICE_FAULT and ei.value.first_bad_index == 5
+        torch.cuda.synchronize()
+        assert int(words.abs().sum().item()) == 0
+        assert int(hv[0, team_off:team_off + 256].sum().item()) == 0 and int(hv[1, sig_off:sig_off + 8].sum().item()) == 0
+        sh.stream_sync()                  # reported once
+        errors = torch.zeros(1, dtype=torch.int64, device=dev)
+        sh.barrier_epochs(slots, 200, 4, errors)
+        sh.team_epochs([team], [150], slots, 2, errors)
+        recv, send = sh.malloc(8 * 256), sh.malloc(8 * 256)
+        sh.ring_exchange(recv, send, 256, gin, 0, 0, 20, 2)
+        sh.stream_sync()
+        assert int(errors.item()) == 0
+        sh.team_destroy(team)
+        sh.gin_destroy(gin)
+    finally:
+        sh.finalize()
