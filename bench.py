@@ -645,7 +645,7 @@ def main():
         out["extras"] = extras
     if args.ceilings:
         import subprocess
-        exe = os.path.join(ROOT, "paper_2511_15076_amd", "stream_ceilings")
+        exe = os.path.join(ROOT, "bench_ceilings")
         res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
         out["stream_ceilings"] = json.loads(res.stdout) if res.returncode == 0 else {"error": res.stdout[-200:]}
     if not args.no_cpu_baseline:

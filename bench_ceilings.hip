@@ -3,9 +3,15 @@
 // These are the sanity ceilings the put/get kernels are held against.  Also the
 // random-access ceilings the AMO, hash and BFS kernels are held against: random
 // 8-byte reads over footprints from L2-resident to HBM-sized, returning 64-bit
-// atomics to distinct lines (R_indep) and to one address (R_same).  This
+// atomics to distinct lines (R_indep) and to one address (R_same).  Also the
+// mixed read / write ceilings of a copy: wave-specialised workgroups (reader
+// waves filling an LDS ring with global-load-to-LDS, writer waves draining it)
+// over a sweep of reader waves, writer waves, stage size and ring depth, all
+// unpaced, and the library's own streaming copy at a sweep of paces.  This
 // program is a measurement aid, not part of the library.
 #include <hip/hip_runtime.h>
+
+#include "paper_2511_15076_amd/csrc/kernels_stream.hpp"   // the library's streaming copy, measured here at several paces
 
 #include <algorithm>
 #include <cstdint>
@@ -119,6 +125,61 @@ __global__ __launch_bounds__(256) void k_atomics(uint64_t *a, uint64_t lines, ui
     if (acc == 0x12345u) out[0] = 1;
 }
 
+// ---------------------------------------------------------------------------
+// Mixed ceiling: one workgroup per compute unit, `nr` reader waves that load `lps` KiB each per stage
+// straight into an LDS ring of `S` stages, `nwr` writer waves that store a stage from the ring; one
+// s_barrier per stage, nothing paced (every load goes out as soon as a ring slot is free).  Workgroup b
+// takes stages b, b + grid, ...
+struct MixedParams { const uint8_t *src; uint8_t *dst; uint32_t nr, nwr, lps, S, steps; };
+
+__device__ __forceinline__ void wait_vm(uint32_t n)      // s_waitcnt vmcnt(n), n a run-time value
+{
+    switch (n) {
+#define C1(n) case n: ST_WAIT_VM(n); break;
+#define C8(b) C1(b) C1(b + 1) C1(b + 2) C1(b + 3) C1(b + 4) C1(b + 5) C1(b + 6) C1(b + 7)
+        C8(0) C8(8) C8(16) C8(24) C8(32) C8(40) C8(48)
+        C1(56) C1(57) C1(58) C1(59) C1(60) C1(61) C1(62)
+    default: ST_WAIT_VM(63); break;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_mixed(MixedParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t mixed_ring[];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t stage_bytes = p.nr * p.lps * 1024, T = p.steps, S = p.S;
+    if (wave < p.nr) {
+        const uint32_t my = wave * p.lps * 1024;
+        auto issue = [&](uint32_t t) {
+            const uint8_t *g = p.src + ((uint64_t)t * gridDim.x + blockIdx.x) * stage_bytes + my + lane * 16;
+            uint8_t *l = mixed_ring + (t % S) * stage_bytes + my;
+            for (uint32_t i = 0; i < p.lps; ++i)
+                __builtin_amdgcn_global_load_lds((shmemx::glb_ptr_t)(g + i * 1024), (shmemx::lds_ptr_t)(l + i * 1024), 16, 0, 2);
+        };
+        const uint32_t pro = S - 1 < T ? S - 1 : T;
+        for (uint32_t t = 0; t < pro; ++t) issue(t);
+        for (uint32_t t = 0; t < T; ++t) {
+            const uint32_t later = S - 2 < T - 1 - t ? S - 2 : T - 1 - t;
+            wait_vm(later * p.lps);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (t + S - 1 < T) issue(t + S - 1);
+        }
+    } else {
+        const uint32_t w = wave - p.nr, per = stage_bytes / p.nwr, n = per / 1024;
+        for (uint32_t t = 0; t < T; ++t) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const u32x4 *l = (const u32x4 *)(mixed_ring + (t % S) * stage_bytes + w * per) + lane;
+            u32x4 *g = (u32x4 *)(p.dst + ((uint64_t)t * gridDim.x + blockIdx.x) * stage_bytes + w * per) + lane;
+            for (uint32_t j = 0; j < n; ++j) __builtin_nontemporal_store(l[j * 64], g + j * 64);
+        }
+    }
+}
+
 template <typename F>
 static float median_ms(F f, int reps = 9)
 {
@@ -166,6 +227,54 @@ int main()
         char key[16];
         if (bit == 11) snprintf(key, sizeof key, "none"); else snprintf(key, sizeof key, "%d", bit);
         printf("\"%s\": %.0f%s", key, 2.0 * ptasks * 4096 / pms / 1e6, bit == 30 ? "}, " : ", ");
+    }
+    // mixed read + write ceilings, unpaced: (reader waves, writer waves, KiB per reader per stage, ring stages)
+    CK(hipFuncSetAttribute((const void *)k_mixed, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    printf("\"copy_wave_specialised_unpaced_GBs\": {");
+    {
+        bool first = true;
+        float best = 0;
+        for (uint32_t nr : {2u, 4u, 8u, 12u})
+            for (uint32_t nwr : {1u, 2u, 4u})
+                for (uint32_t lps : {1u, 2u, 4u, 8u})
+                    for (uint32_t S : {4u, 8u, 16u}) {
+                        const uint32_t stage = nr * lps * 1024;
+                        if (stage * S > 160 * 1024 || (nr * lps) % nwr || (S - 2) * lps > 63 || stage * (S - 1) < 16 * 1024) continue;
+                        MixedParams mp{buf, buf + bytes, nr, nwr, lps, S, (uint32_t)(bytes / stage / 256)};
+                        float mms = median_ms([&] { hipLaunchKernelGGL(k_mixed, dim3(256), dim3((nr + nwr) * 64), stage * S, 0, mp); }, 5);
+                        const float gbs = 2.0 * mp.steps * 256.0 * stage / mms / 1e6;
+                        best = std::max(best, gbs);
+                        printf("%s\"r%u_w%u_stage%uKiB_ring%u\": %.0f", first ? "" : ", ", nr, nwr, stage >> 10, S, gbs);
+                        first = false;
+                    }
+        printf(", \"best\": %.0f}, ", best);
+    }
+    // the library's streaming copy (4 reader waves, 2 writer waves, 4 KiB tasks, ring of 16) on one 2 GiB stream,
+    // by pace: ns per task and workgroup with 256 workgroups (0 = unpaced); median and worst of 15 launches
+    {
+        int khz = 100000;
+        (void)hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, 0);
+        printf("\"copy_streaming_one_stream_GBs_by_pace_ns\": {");
+        bool first = true;
+        for (double pace : {0.0, 290.0, 300.0, 308.0, 315.0, 322.0, 330.0, 340.0, 360.0}) {
+            const uint32_t period = (uint32_t)(pace * khz / 1e6 * 256.0 + 0.5);
+            const uint32_t chunks = (uint32_t)(bytes / shmemx::ST_CHUNK);
+            std::vector<float> v;
+            hipEvent_t a, b;
+            CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
+            for (int r = 0; r < 17; ++r) {
+                CK(hipEventRecord(a));
+                hipLaunchKernelGGL(shmemx::k_copy_stream_lds, dim3(256), dim3(shmemx::ST_THREADS), 0, 0, buf + bytes, buf, chunks, period);
+                CK(hipEventRecord(b)); CK(hipEventSynchronize(b));
+                float m; CK(hipEventElapsedTime(&m, a, b));
+                if (r >= 2) v.push_back(m);
+            }
+            std::sort(v.begin(), v.end());
+            printf("%s\"%.0f\": {\"median\": %.0f, \"worst\": %.0f}", first ? "" : ", ", pace, 2.0 * bytes / v[v.size() / 2] / 1e6, 2.0 * bytes / v.back() / 1e6);
+            first = false;
+            CK(hipEventDestroy(a)); CK(hipEventDestroy(b));
+        }
+        printf("}, ");
     }
     float ms = median_ms([&] { CK(hipMemcpyAsync(d, s, bytes, hipMemcpyDeviceToDevice, 0)); });
     printf("\"hipMemcpyDtoD_GBs\": %.0f, ", 2.0 * bytes / ms / 1e6);

@@ -277,7 +277,8 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * neighbours uint32[nnz]; PE p reads only its own rows) and allocates the
  * per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
  * long-row list and its scan, per-die bitmap copies, frontier and previous-level
- * bitmaps, counters: about 25.4 bytes per owned vertex).  Errors: NOMEM, INVALID_ARG. */
+ * bitmaps, counters: about 25.4 bytes per owned vertex; parent and level of a
+ * vertex are one 8-byte record there, delivered with one put).  Errors: NOMEM, INVALID_ARG. */
 typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */
@@ -312,6 +313,14 @@ int shmem_bfs_configure(void *graph, int mode, int alpha, int beta);
  * (nlevels counts them all; a histogram beyond the first 64 follows from
  * dev_level).  Errors: INVALID_ARG (root >= nverts), DEVICE. */
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
+
+/* HOST: how the last shmem_bfs on this graph spent its time, level by level:
+ * us_out[i] (HOST, may be NULL) = microseconds of host clock around level i's
+ * launches and its hand-over to the host, bottom_up_out[i] (HOST, may be
+ * NULL) = 1 if that level ran bottom-up; the first min(levels, 64, max_levels)
+ * levels, their number in *nlevels_out.  A measurement aid: no device work.
+ * Errors: NOT_INIT, INVALID_ARG. */
+int shmem_bfs_level_times(void *graph, uint32_t *nlevels_out, float *us_out, uint8_t *bottom_up_out, uint32_t max_levels);
 
 /* ---- the paper's device API shape: signals, counters, put with actions (Sec. III-A, III-B) ---- */
 

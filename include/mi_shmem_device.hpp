@@ -17,4 +17,5 @@
 // PE = blockIdx.x / wgs_per_pe; a kernel that waits for a signal, a counter or a barrier needs all its
 // workgroups resident at once.  examples/device_api_ring.hip is a complete program.
 #pragma once
-#include "../paper_2511_15076_amd/csrc/gin.hpp"
+#include "mi_shmemx.hpp"      // the one-sided primitives (the library's own kernels are built on this same file)
+#include "mi_shmem_gin.hpp"   // signals, counters, put with actions

@@ -5,7 +5,7 @@
 // the symmetric heap itself, addressed by byte offset; a signal / counter ID is
 // an index into two small symmetric uint64 arrays owned by the Gin object.
 #pragma once
-#include "shmemx.hpp"
+#include "mi_shmemx.hpp"
 
 namespace shmemx {
 

@@ -84,6 +84,7 @@ _SIG = {
     "shmem_bfs_destroy": (_i, [_vp]),
     "shmem_bfs_configure": (_i, [_vp, _i, _i, _i]),
     "shmem_bfs": (_i, [_vp, C.c_uint32, _vp, _vp, C.POINTER(BfsStats)]),
+    "shmem_bfs_level_times": (_i, [_vp, C.POINTER(C.c_uint32), C.POINTER(C.c_float), C.POINTER(C.c_uint8), C.c_uint32]),
     "shmem_gin_create": (_i, [_i, _i, C.POINTER(_vp)]),
     "shmem_gin_destroy": (_i, [_vp]),
     "shmem_gin_signal_sym": (_vp, [_vp, _i]),
@@ -293,6 +294,15 @@ def bfs(graph, root, dev_level=None, dev_parent=None):
     _check(_L.shmem_bfs(graph, int(root), _addr(dev_level), _addr(dev_parent), C.byref(st)), "shmem_bfs")
     return {"nlevels": st.nlevels, "reached": st.reached, "edges_traversed": st.edges_traversed,
             "frontier_size": [int(st.frontier_size[i]) for i in range(min(st.nlevels, 64))]}
+
+
+def bfs_level_times(graph):
+    """[(microseconds, ran bottom-up)] per level of the last search on this graph (the first 64 levels)."""
+    n = C.c_uint32(0)
+    us = (C.c_float * 64)()
+    bu = (C.c_uint8 * 64)()
+    _check(_L.shmem_bfs_level_times(graph, C.byref(n), us, bu, 64), "shmem_bfs_level_times")
+    return [(float(us[i]), bool(bu[i])) for i in range(n.value)]
 
 
 def gin_create(nsignals, ncounters):

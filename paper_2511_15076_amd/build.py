@@ -8,8 +8,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmi_shmem.so")
-CEILINGS_PATH = os.path.join(HERE, "stream_ceilings")
 ROOT = os.path.dirname(HERE)
+CEILINGS_PATH = os.path.join(ROOT, "bench_ceilings")
 CLIENT_PATH = os.path.join(ROOT, "examples", "c_abi_client")
 
 
@@ -27,8 +27,8 @@ def build(verbose: bool = False) -> str:
     subprocess.run(cmd, check=True)
     # measurement aid: plain read / write / copy ceilings of the box (bench.py --ceilings)
     cmd2 = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
-            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-            os.path.join(CSRC, "stream_ceilings.hip"), "-o", CEILINGS_PATH]
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I", ROOT,
+            os.path.join(ROOT, "bench_ceilings.hip"), "-o", CEILINGS_PATH]
     if verbose:
         print(" ".join(cmd2), flush=True)
     subprocess.run(cmd2, check=True)

@@ -2,7 +2,7 @@
 // (direct, and with workgroup-level combining in LDS).
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

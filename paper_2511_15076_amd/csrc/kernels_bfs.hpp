@@ -17,7 +17,7 @@
 //                  totals the next frontier, resets counters and hands the counts to the host.
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 
@@ -28,7 +28,7 @@ struct BfsState {
     const uint64_t *row_off;     // CSR row offsets (PE p reads rows of its own vertices)
     const uint32_t *nbr;         // CSR neighbours
     // symmetric offsets of the per-PE state
-    uint64_t bitmap_off, level_off, parent_off, queue_off[2], big_off, bigscan_off, tails_off;
+    uint64_t bitmap_off, pl_off, queue_off[2], big_off, bigscan_off, tails_off;   // pl: (parent, level) pairs, 8 bytes per vertex
     uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
     uint64_t front_off, prev_off; // frontier bitmap and the bitmap as of the previous level (bottom-up levels)
     uint64_t linked_off;          // bit set = the vertex has at least one neighbour (never changes)
@@ -65,6 +65,19 @@ __device__ __forceinline__ uint64_t *bfs_tails(const Ctx &c, const BfsState &s, 
     return (uint64_t *)ptr(c, s.tails_off, pe);
 }
 
+// Parent and level of a vertex are ONE 8-byte record in its owner's segment (parent in the low word, level in
+// the high one): whoever claims a vertex delivers both with a single put instead of two scattered 4-byte ones
+// -- half the partial-sector writes of a level.  The caller's separate level / parent arrays are filled from
+// the records when the search is over.
+__device__ __forceinline__ uint64_t bfs_pl(uint32_t parent, int32_t level)
+{
+    return ((uint64_t)(uint32_t)level << 32) | parent;
+}
+__device__ __forceinline__ uint64_t *bfs_pl_of(const Ctx &c, const BfsState &s, uint32_t pe)
+{
+    return (uint64_t *)ptr(c, s.pl_off, pe);
+}
+
 // Every owner clears its slice; the root's owner seeds the search.
 __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t root)
 {
@@ -72,8 +85,7 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
     const uint32_t ro = bfs_owner(s, root), rl = root - ro * s.vpp;
     uint64_t *bm = (uint64_t *)ptr(c, s.bitmap_off, pe);
-    int32_t *lv = (int32_t *)ptr(c, s.level_off, pe);
-    uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
+    uint64_t *pl = bfs_pl_of(c, s, pe);
     for (uint64_t w = rank; w < s.words; w += size)
         bm[w] = (pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
     uint64_t *flt = (uint64_t *)ptr(c, s.filter_off, pe);
@@ -82,8 +94,7 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     for (uint64_t w = rank; w < s.words; w += size) prev[w] = 0;
     for (uint64_t l = rank; l < s.vpp; l += size) {
         const bool is_root = pe == ro && l == rl;
-        lv[l] = is_root ? 0 : -1;
-        pr[l] = is_root ? root : SHMEM_BFS_NONE;
+        pl[l] = is_root ? bfs_pl(root, 0) : bfs_pl(SHMEM_BFS_NONE, -1);
     }
     if (rank == 0) {
         uint64_t *t = bfs_tails(c, s, pe);
@@ -252,10 +263,9 @@ __device__ __forceinline__ void bfs_deliver(const Ctx &c, const BfsState &s, con
         if (cl.need[k]) {
             *p.f[k] = p.known[k] | cl.old[k] | (1ull << (p.l[k] & 63));   // everything the fetch_or showed to be claimed
             if (cl.won[k]) {
-                // put parent, put level: streaming stores, so the scattered lines do not push the
+                // put (parent, level): one streaming 8-byte store, so the scattered lines do not push the
                 // bitmap copies out of L2
-                __builtin_nontemporal_store(u[k], (uint32_t *)ptr(c, s.parent_off, p.o[k]) + p.l[k]);
-                __builtin_nontemporal_store((int32_t)(L + 1), (int32_t *)ptr(c, s.level_off, p.o[k]) + p.l[k]);
+                __builtin_nontemporal_store(bfs_pl(u[k], (int32_t)(L + 1)), bfs_pl_of(c, s, p.o[k]) + p.l[k]);
             }
         }
     }
@@ -524,8 +534,7 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
     uint64_t *vis = (uint64_t *)ptr(c, s.bitmap_off, pe);
     const uint64_t *linked = (const uint64_t *)ptr(c, s.linked_off, pe);
-    int32_t *lv = (int32_t *)ptr(c, s.level_off, pe);
-    uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
+    uint64_t *pl = bfs_pl_of(c, s, pe);
     uint64_t *tail = bfs_tails(c, s, pe) + T_TAIL0 + (L + 1) % 3;
     uint64_t mf = 0;
     uint32_t nfound = 0;   // wave-uniform
@@ -574,8 +583,7 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
         if (lane == 0) vis[w] = visw | fm;               // this wave is the only writer of the word
         nfound += (uint32_t)__builtin_popcountll(fm);
         if (found) {
-            lv[l] = (int32_t)(L + 1);
-            pr[l] = par;
+            pl[l] = bfs_pl(par, (int32_t)(L + 1));
             mf += deg;
         }
     }
@@ -631,7 +639,7 @@ constexpr uint32_t CANON_LANE_EDGES = 32;   // rows up to this long are scanned 
 __device__ __forceinline__ int32_t bfs_level_of(const Ctx &c, const BfsState &s, uint32_t u)
 {
     const uint32_t o = bfs_owner(s, u);
-    return ((const int32_t *)ptr(c, s.level_off, o))[u - o * s.vpp];
+    return ((const int32_t *)ptr(c, s.pl_off, o))[2 * (uint64_t)(u - o * s.vpp) + 1];    // the high word of the record
 }
 
 __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
@@ -643,11 +651,10 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
     const uint64_t first = (uint64_t)pe * s.vpp;
     if (first >= s.nverts) return;
     const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
-    const int32_t *lv = (const int32_t *)ptr(c, s.level_off, pe);
-    uint32_t *pr = (uint32_t *)ptr(c, s.parent_off, pe);
+    uint64_t *pl = bfs_pl_of(c, s, pe);
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
         const uint64_t l = w * 64 + lane;
-        const int32_t lvl = l < count ? lv[l] : -1;
+        const int32_t lvl = l < count ? (int32_t)(pl[l] >> 32) : -1;
         const bool need = lvl > 0;                       // reached and not the root
         uint32_t best = SHMEM_BFS_NONE, deg = 0;
         uint64_t r0 = 0;
@@ -677,7 +684,7 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
             for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off, 64));
             if (lane == j) best = mn;
         }
-        if (need) pr[l] = best;
+        if (need) ((uint32_t *)(pl + l))[0] = best;      // the low word of the record
     }
 }
 
@@ -756,7 +763,7 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
     }
 }
 
-// Every owner copies its level / parent slice into the caller's flat arrays.
+// Every owner splits its (parent, level) records into the caller's flat level / parent arrays.
 __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, int32_t *level, uint32_t *parent)
 {
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
@@ -764,8 +771,12 @@ __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, int32_t *
     const uint64_t first = (uint64_t)pe * s.vpp;
     if (first >= s.nverts) return;
     const uint64_t cnt = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
-    if (level) copy((uint8_t *)(level + first), ptr(c, s.level_off, pe), cnt * 4, rank, size);
-    if (parent) copy((uint8_t *)(parent + first), ptr(c, s.parent_off, pe), cnt * 4, rank, size);
+    const uint64_t *pl = bfs_pl_of(c, s, pe);
+    for (uint64_t l = rank; l < cnt; l += size) {
+        const uint64_t rec = __builtin_nontemporal_load(pl + l);
+        if (level) __builtin_nontemporal_store((int32_t)(rec >> 32), level + first + l);
+        if (parent) __builtin_nontemporal_store((uint32_t)rec, parent + first + l);
+    }
 }
 
 }  // namespace shmemx

@@ -2,7 +2,7 @@
 // executor and the bandwidth-sweep cell.
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

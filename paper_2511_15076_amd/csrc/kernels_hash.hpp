@@ -1,7 +1,7 @@
 // Distributed open-addressing hash table: insert by compare-swap, lookup by get.
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

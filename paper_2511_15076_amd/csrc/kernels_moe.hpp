@@ -25,8 +25,8 @@
 // against the occupancy limit) and every workgroup finishes sending before it
 // starts to wait, so the waits end; they are bounded besides.
 #pragma once
-#include "gin.hpp"
-#include "shmemx.hpp"
+#include "../../include/mi_shmem_gin.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

@@ -1,11 +1,11 @@
 // Kernels that exercise in-kernel ordering through the GIN-shaped device API
-// (gin.hpp): put with a signal action, waitSignal, counters, the barrier
+// (include/mi_shmem_gin.hpp): put with a signal action, waitSignal, counters, the barrier
 // session, and barrier epochs.  They are the device forms of the paper's ring
 // exchange (Listing 2) and put-with-signal ping-pong (Sec. V-A).
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "gin.hpp"
-#include "shmemx.hpp"
+#include "../../include/mi_shmem_gin.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

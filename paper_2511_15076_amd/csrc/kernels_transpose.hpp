@@ -7,7 +7,7 @@
 // 64 elements from the row's owner, and the transposed tile leaves as 64
 // contiguous local stores, so both sides move whole lines.
 #pragma once
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

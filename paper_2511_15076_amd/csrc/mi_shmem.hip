@@ -1,6 +1,6 @@
 // mi_shmem: host side of the C ABI declared in include/mi_shmem.h plus the
 // gfx950 kernels it launches.  One translation unit; the kernels live in the
-// headers included below and are built from the primitives in shmemx.hpp.
+// headers included below and are built from the primitives in include/mi_shmemx.hpp.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -16,7 +16,7 @@
 
 #include "../../include/mi_shmem.h"
 #include "host_logic.hpp"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 #include "kernels_copy.hpp"
 #include "kernels_stream.hpp"
 #include "kernels_amo.hpp"
@@ -63,6 +63,10 @@ struct BfsGraph {
     uint64_t nnz;      // CSR entries (sum of all row lengths)
     void *allocs[12];
     int nallocs;
+    // the last search, level by level (host clock around each level's launches and its hand-over; the first 64)
+    uint32_t last_levels;
+    float last_level_us[64];
+    uint8_t last_level_bottom_up[64];
 };
 
 inline shmemx::Ctx ctx() { return shmemx::Ctx{H.heap, (uint64_t)H.seg, H.scratch, H.npes}; }
@@ -713,14 +717,14 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     if (!g) return SHMEM_ERR_NOMEM;
     const uint32_t vpp = (uint32_t)(((uint64_t)nverts + (uint64_t)H.npes - 1) / (uint64_t)H.npes);
     const uint64_t words = ((uint64_t)vpp + 63) / 64;
-    // bitmap, level, parent, two queues, long-row list, its segment scan, counters, per-die bitmap copies,
-    // frontier bitmap, previous-level bitmap, has-neighbours bitmap
-    const size_t sizes[12] = {words * 8, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4, (size_t)vpp * 4,
+    // bitmap, (parent, level) records, two queues, long-row list, its segment scan, counters, per-die bitmap
+    // copies, frontier bitmap, previous-level bitmap, has-neighbours bitmap
+    const size_t sizes[11] = {words * 8, (size_t)vpp * 8, (size_t)vpp * 4, (size_t)vpp * 4,
                               (size_t)vpp * 4, ((size_t)vpp + 1) * 4, 256, words * 8 * shmemx::NXCD, words * 8,
                               words * 8, words * 8};
-    uint64_t offs[12];
+    uint64_t offs[11];
     g->nallocs = 0;
-    for (int i = 0; i < 12; ++i) {
+    for (int i = 0; i < 11; ++i) {
         void *p = shmem_malloc(sizes[i]);
         if (!p) {
             for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
@@ -734,9 +738,9 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     s.nverts = nverts; s.vpp = vpp; s.words = words;
     s.shift = (vpp & (vpp - 1)) == 0 ? (int)__builtin_ctz(vpp) : -1;
     s.row_off = dev_row_off; s.nbr = dev_nbr;
-    s.bitmap_off = offs[0]; s.level_off = offs[1]; s.parent_off = offs[2];
-    s.queue_off[0] = offs[3]; s.queue_off[1] = offs[4]; s.big_off = offs[5]; s.bigscan_off = offs[6];
-    s.tails_off = offs[7]; s.filter_off = offs[8]; s.front_off = offs[9]; s.prev_off = offs[10]; s.linked_off = offs[11];
+    s.bitmap_off = offs[0]; s.pl_off = offs[1];
+    s.queue_off[0] = offs[2]; s.queue_off[1] = offs[3]; s.big_off = offs[4]; s.bigscan_off = offs[5];
+    s.tails_off = offs[6]; s.filter_off = offs[7]; s.front_off = offs[8]; s.prev_off = offs[9]; s.linked_off = offs[10];
     g->mode = SHMEM_BFS_TOP_DOWN; g->canonical = false; g->alpha = BFS_ALPHA; g->beta = BFS_BETA;
     g->nnz = 0;
     if (hipMemcpyAsync(H.pinned + 32, dev_row_off + nverts, 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
@@ -796,6 +800,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     BfsGraph *g = (BfsGraph *)graph;
     const shmemx::BfsState &s = g->st;
     if (root >= s.nverts) return SHMEM_ERR_INVALID_ARG;
+    g->last_levels = 0;
     shmemx::Ctx c = ctx();
     dim3 grid((unsigned)(H.npes * g->wgs_per_pe)), block(WG_THREADS);
     shmem_bfs_stats st;
@@ -816,6 +821,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     bool bottom_up = false;
     bool queue_written = true;   // the frontier's queue exists (a bottom-up level only counts its finds)
     uint32_t L = 0;
+    auto t_level = std::chrono::steady_clock::now();
     for (;;) {
         if (g->mode == SHMEM_BFS_BOTTOM_UP) bottom_up = true;
         else if (g->mode == SHMEM_BFS_DIRECTION_OPTIMIZING) {
@@ -845,6 +851,12 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
         }
         if (int rc = bfs_level_end(s, L + 1, hybrid, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
+        if (L < 64) {
+            const auto t_now = std::chrono::steady_clock::now();
+            g->last_level_us[L] = std::chrono::duration<float, std::micro>(t_now - t_level).count();
+            g->last_level_bottom_up[L] = bottom_up ? 1 : 0;
+            t_level = t_now;
+        }
         ++L;
         if (counts[0] == 0) break;
         if (L >= (uint32_t)INT32_MAX) return SHMEM_ERR_INVALID_ARG;   // levels are int32
@@ -854,6 +866,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
         if (hybrid) { m_f = counts[2] - cum_mf; cum_mf = counts[2]; }
     }
     st.nlevels = L;
+    g->last_levels = L < 64 ? L : 64;
     st.edges_traversed = (hybrid ? counts[2] : counts[1]) / 2;
     if (g->canonical) hipLaunchKernelGGL(shmemx::k_bfs_canonical, grid, block, 0, H.stream, c, s);
     if (dev_level || dev_parent) {
@@ -862,6 +875,20 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     }
     if (stats) *stats = st;
     return launched();
+}
+
+int shmem_bfs_level_times(void *graph, uint32_t *nlevels_out, float *us_out, uint8_t *bottom_up_out, uint32_t max_levels)
+{
+    if (!H.init) return SHMEM_ERR_NOT_INIT;
+    if (!graph || !nlevels_out) return SHMEM_ERR_INVALID_ARG;
+    const BfsGraph *g = (const BfsGraph *)graph;
+    const uint32_t n = std::min(g->last_levels, max_levels);
+    *nlevels_out = n;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (us_out) us_out[i] = g->last_level_us[i];
+        if (bottom_up_out) bottom_up_out[i] = g->last_level_bottom_up[i];
+    }
+    return SHMEM_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -8,7 +8,7 @@
 // system-scope release) and reusable when the host's `head` has passed it.
 #pragma once
 #include "../../include/mi_shmem.h"
-#include "shmemx.hpp"
+#include "../../include/mi_shmemx.hpp"
 
 namespace shmemx {
 

@@ -107,3 +107,19 @@ def test_public_header_is_plain_c_and_cpp(tmp_path):
                 ["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(tmp_path / "cpp.cpp")]):
         r = subprocess.run(cmd, capture_output=True, text=True)
         assert r.returncode == 0, r.stderr[-2000:]
+
+
+def test_public_headers_stand_alone():
+    """include/ is what a user of the library installs: no header there may reach outside it, and the device API
+    header must hold real code (the library's own kernels are built on the same files)."""
+    import re
+    inc = os.path.join(ROOT, "include")
+    for name in sorted(os.listdir(inc)):
+        text = open(os.path.join(inc, name)).read()
+        for target in re.findall(r'#include\s+"([^"]+)"', text):
+            assert "/" not in target and os.path.exists(os.path.join(inc, target)), f"{name} includes {target}"
+    dev = open(os.path.join(inc, "mi_shmemx.hpp")).read()
+    assert "__device__" in dev and "barrier_all" in dev and "copy(" in dev
+    # and the library's sources take those primitives from include/, not from a private copy
+    csrc = os.path.join(ROOT, "paper_2511_15076_amd", "csrc")
+    assert not os.path.exists(os.path.join(csrc, "shmemx.hpp")) and not os.path.exists(os.path.join(csrc, "gin.hpp"))
