@@ -140,8 +140,21 @@ def _median_ms(fn, reset, reps=5, warm=2):
     return out[len(out) // 2]
 
 
-def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
-    """Configuration 3: 2^24 AMOs on 64 PEs, T in {1, 1024, 2^20}, uniform / Zipf(1.0)."""
+def _agg_hw_atomics(torch, d_pe, d_idx, T, n, npes, wgs, pass_ops=1024):
+    """Hardware atomics the combining kernel issues for this batch: one per distinct word per pass of 1024 ops
+    of a workgroup (a PE's block of ops is cut into consecutive passes) -- counted here from the op arrays."""
+    per_pe = (n + npes - 1) // npes
+    i = torch.arange(n, device=d_pe.device, dtype=torch.int64)
+    within = i - (i // per_pe) * per_pe
+    window = (i // per_pe) * ((per_pe + pass_ops - 1) // pass_ops) + within // pass_ops
+    key = window * (npes * T) + d_pe.to(torch.int64) * T + d_idx.to(torch.int64)
+    return int(torch.unique(key).numel())
+
+
+def extra_amo(sh, torch, ceilings=None, n=1 << 24, npes=64, wgs=32):
+    """Configuration 3: 2^24 AMOs on 64 PEs, T in {1, 1024, 2^20}, uniform / Zipf(1.0).  Every cell is held
+    against the atomic ceiling of the same run that matches its footprint: 64 x the one-address rate for
+    T = 1, the distinct-line rate over 8 MiB for T = 1024 (512 KiB of counters), over 1 GiB for T = 2^20."""
     import numpy as np
     import workgen
     dev = torch.device("cuda:0")
@@ -150,6 +163,10 @@ def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
     scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
     sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
     res = {}
+    c = ceilings or {}
+    ceil_of = {1: ("64 x atomic_same_address_Gops", 64e3 * c["atomic_same_address_Gops"] if "atomic_same_address_Gops" in c else None),
+               1024: ("atomic_indep_8MiB_Gops", 1e3 * c["atomic_indep_8MiB_Gops"] if "atomic_indep_8MiB_Gops" in c else None),
+               1 << 20: ("atomic_indep_1GiB_Gops", 1e3 * c["atomic_indep_1GiB_Gops"] if "atomic_indep_1GiB_Gops" in c else None)}
     try:
         d_old = torch.empty(n, dtype=torch.int64, device=dev)
         d_zero = torch.zeros(n, dtype=torch.int64, device=dev)
@@ -164,6 +181,7 @@ def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
                 d_pe, d_idx, d_a16 = up(pe), up(idx), up(a16)
                 d_one = torch.ones(n, dtype=torch.int64, device=dev)
                 reset = lambda: view.zero_()
+                agg_atomics = _agg_hw_atomics(torch, d_pe.view(torch.int32), d_idx.view(torch.int32), T, n, npes, wgs)
                 cell = {}
                 for name, kind, a, b, agg in (("fadd1", sh.AMO_FETCH_ADD, d_one, None, 0),
                                               ("fadd1_agg", sh.AMO_FETCH_ADD, d_one, None, 1),
@@ -174,14 +192,29 @@ def extra_amo(sh, torch, n=1 << 24, npes=64, wgs=32):
                                               ("cas_min_agg", sh.AMO_MIN_CAS_LOOP, d_tag, None, 1)):
                     ms = _median_ms(lambda: sh.amo_batch(kind, ctr, T, d_pe, d_idx, a, b, d_old, n, wgs, agg),
                                     reset, reps=3, warm=1)
-                    cell[name] = round(n / ms / 1e3, 1)       # Mops/s
+                    mops = n / ms / 1e3
+                    entry = {"Mops_per_s": round(mops, 1)}
+                    if agg:
+                        entry["ops_per_hw_atomic"] = round(n / agg_atomics, 2)
+                    elif name != "cas_min":
+                        entry["ops_per_hw_atomic"] = 1.0      # cas_min retries: more than one atomic per op, not counted here
+                    cname, cval = ceil_of[T]
+                    if cval:
+                        # a combining kernel is priced by the hardware atomics it still issues
+                        hw_rate = mops / entry["ops_per_hw_atomic"] if "ops_per_hw_atomic" in entry else mops
+                        entry["roofline"] = {"bound": "atomic", "ceiling": round(cval, 1), "unit": "M hardware atomics/s",
+                                             "ceiling_source": f"same run: {cname}", "achieved": round(hw_rate, 1),
+                                             "frac": round(hw_rate / cval, 4)}
+                    cell[name] = entry
                 res[f"T{T}_{dist}"] = cell
                 del d_pe, d_idx, d_a16
             sh.free(ctr)
         sh.stream_sync()
     finally:
         sh.finalize()
-    return {"unit": "Mops/s", "ops": n, "npes": npes, "wgs_per_pe": wgs, "cells": res}
+    return {"unit": "Mops/s", "ops": n, "npes": npes, "wgs_per_pe": wgs,
+            "hbm_random_bound_Mops": 62000.0, "note": "T = 2^20 also against the 62 Gop/s HBM random-access bound (128 B of line traffic per op at 8 TB/s)",
+            "cells": res}
 
 
 def extra_config1(sh, torch, wgs=2):
@@ -318,7 +351,12 @@ def _extra_moe_on_current_stream(sh, torch, dev, workgen, npes, num_experts, top
             res[str(ntok)] = {"dispatch_us": round(d_ms * 1e3, 2), "combine_us": round(c_ms * 1e3, 2),
                               "pair_graph_us": round(g_ms * 1e3 / pairs, 2),
                               "dispatch_GBs": round(routes * (hidden + 16) / d_ms / 1e6, 1),
-                              "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes, "wgs_per_pe": w}
+                              "combine_GBs": round(routes * hidden / c_ms / 1e6, 1), "routes": routes, "wgs_per_pe": w,
+                              # HBM traffic per route: dispatch writes the remote slot and the packed row and reads both
+                              # sources (4 x message); combine moves a row there, reads it in the sum (3 x) and writes the
+                              # token once per top-k routes
+                              "dispatch_hbm_frac": round(routes * 4 * (hidden + 16) / d_ms / 1e6 / HBM_PEAK_GBS, 4),
+                              "combine_hbm_frac": round((routes * 3 * hidden + npes * ntok * hidden) / c_ms / 1e6 / HBM_PEAK_GBS, 4)}
         sh.moe_destroy(moe)
     finally:
         sh.finalize()
@@ -346,30 +384,7 @@ def extra_transpose(sh, torch, npes=8, n=16384, wgs=256):
     return {"n": n, "elem_bytes": 4, "npes": npes, "matrix_bytes": n * n * 4, "cells": res}
 
 
-def _hash_mean_probes(torch, heap, tab_off, seg, npes, slots):
-    """Measured on the finished table (untimed): mean number of probes that reach a stored key from its
-    home slot = 1 + mean displacement.  Needs the placement rule (SplitMix64 finaliser; owner = h mod npes,
-    home = (h / npes) mod slots), written here in wrapping int64 arithmetic for power-of-two shapes."""
-    if npes & (npes - 1) or slots & (slots - 1):
-        return None
-    lsr = lambda z, k: (z >> k) & ((1 << (64 - k)) - 1)           # logical shift of the uint64 bit pattern
-    as_i64 = lambda c: c - (1 << 64) if c >= 1 << 63 else c
-    total, disp = 0, 0
-    for p in range(npes):
-        t = heap[p * seg + tab_off: p * seg + tab_off + 8 * slots].view(torch.int64)
-        occ = t != 0
-        z = t[occ]
-        z = (z ^ lsr(z, 30)) * as_i64(0xBF58476D1CE4E5B9)
-        z = (z ^ lsr(z, 27)) * as_i64(0x94D049BB133111EB)
-        h = z ^ lsr(z, 31)
-        home = lsr(h, npes.bit_length() - 1) & (slots - 1) if npes > 1 else h & (slots - 1)
-        at = torch.nonzero(occ).squeeze(1)
-        disp += int(((at - home) & (slots - 1)).sum().item())
-        total += int(at.numel())
-    return round(1.0 + disp / max(total, 1), 4)
-
-
-def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=256):
+def extra_hash(sh, torch, ceilings=None, n=1 << 26, npes=16, wgs=256):
     """Configuration 4: 2^26 inserts at load factor 0.5, then 2^26 lookups (50 % present)."""
     import numpy as np
     import workgen
@@ -392,17 +407,32 @@ def extra_hash(sh, torch, n=1 << 26, npes=16, wgs=256):
         sh.stream_sync()
         found = float(d_fo.float().mean().item())
         inserted = int((d_st == 0).sum().item())
-        mean_probes = _hash_mean_probes(torch, heap, tab - heap.data_ptr(), seg, npes, slots)
     finally:
         sh.finalize()
+    c = ceilings or {}
     # algorithmic bytes: insert = 8 B key + 128 B sector read-modify-write + 1 B status; lookup = 8 + 64 + 1
-    return {"keys": n, "npes": npes, "slots_per_pe": slots, "wgs_per_pe": wgs,
-            "Minserts_per_s": round(n / ins_ms / 1e3, 1), "Mlookups_per_s": round(n / look_ms / 1e3, 1),
-            "insert_eff_GBs": round(n * 137 / ins_ms / 1e6, 1), "lookup_eff_GBs": round(n * 73 / look_ms / 1e6, 1),
-            "inserted": inserted, "found_fraction": round(found, 4), "mean_probes_stored_key": mean_probes}
+    ins_gbs, look_gbs = n * 137 / ins_ms / 1e6, n * 73 / look_ms / 1e6
+    out = {"keys": n, "npes": npes, "slots_per_pe": slots, "wgs_per_pe": wgs,
+           "Minserts_per_s": round(n / ins_ms / 1e3, 1), "Mlookups_per_s": round(n / look_ms / 1e3, 1),
+           "inserted": inserted, "found_fraction": round(found, 4),
+           "roofline_insert": {"bound": "hbm", "algorithmic_bytes_per_key": 137, "achieved": round(ins_gbs, 1), "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": round(ins_gbs / HBM_PEAK_GBS, 4),
+                               "note": "the memory moves whole 128-byte lines: counters show 1.7x the algorithmic bytes per insert"},
+           "roofline_lookup": {"bound": "hbm", "algorithmic_bytes_per_key": 73, "achieved": round(look_gbs, 1), "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": round(look_gbs / HBM_PEAK_GBS, 4),
+                               "note": "64-byte sectors are algorithmic, 128-byte lines are fetched: 2.0x"}}
+    if "atomic_indep_1GiB_Gops" in c:
+        out["roofline_insert_ops"] = {"bound": "atomic", "ceiling": 1e3 * c["atomic_indep_1GiB_Gops"], "unit": "M ops/s",
+                                      "ceiling_source": "same run: atomic_indep_1GiB_Gops (one compare-swap per key)",
+                                      "achieved": round(n / ins_ms / 1e3, 1), "frac": round(n / ins_ms / 1e3 / (1e3 * c["atomic_indep_1GiB_Gops"]), 4)}
+    if "randread8_1024MiB_Gops" in c:
+        out["roofline_lookup_lines"] = {"bound": "hbm random lines", "ceiling": 1e3 * c["randread8_1024MiB_Gops"], "unit": "M lines/s",
+                                        "ceiling_source": "same run: randread8_1024MiB_Gops (random 8-byte reads over 1 GiB)",
+                                        "achieved": round(n / look_ms / 1e3, 1), "frac": round(n / look_ms / 1e3 / (1e3 * c["randread8_1024MiB_Gops"]), 4)}
+    return out
 
 
-def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
+def extra_bfs(sh, torch, ceilings=None, scale=24, npes=16, wgs=64, nroots=64):
     """Configuration 5: level-synchronous BFS on an R-MAT graph, 64 seeded roots."""
     import numpy as np
     import workgen
@@ -415,6 +445,10 @@ def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
     heap = torch.zeros(npes * seg, dtype=torch.uint8, device=dev)
     scratch = torch.zeros(sh.scratch_bytes(npes), dtype=torch.uint8, device=dev)
     sh.init(npes, seg, heap, scratch, torch.cuda.current_stream().cuda_stream)
+    c = ceilings or {}
+    # per search the path streams the adjacency of the reached vertices (4 B per CSR entry), their row offsets,
+    # and the (parent, level) records, queue entries and bitmaps: about 2.5 GB at scale 24
+    stream_bytes = len(nbr) * 4 + n * 8 + n * (8 + 4 + 4)
     try:
         d_row = torch.from_numpy(row.view(np.int64)).to(dev)
         d_nbr = torch.from_numpy(nbr.view(np.int32)).to(dev)
@@ -423,7 +457,8 @@ def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
         for name, mode in (("top_down", sh.BFS_TOP_DOWN), ("direction_optimizing", sh.BFS_DIRECTION_OPTIMIZING)):
             sh.bfs_configure(g, mode)
             sh.bfs(g, int(roots[0]))                               # warm-up
-            teps, times, levels = [], [], []
+            teps, times, levels, probes = [], [], [], []
+            level_rows = None
             for r in roots:
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
@@ -432,11 +467,27 @@ def extra_bfs(sh, torch, scale=24, npes=16, wgs=64, nroots=64):
                 teps.append(st["edges_traversed"] / dt / 1e9)
                 times.append(dt * 1e3)
                 levels.append(st["nlevels"])
+                probes.append(2 * st["edges_traversed"] / dt / 1e9)     # one bitmap probe per CSR entry of a reached vertex (top-down)
+                if level_rows is None:
+                    level_rows = [{"level": i, "ms": round(us / 1e3, 4), "bottom_up": bu, "frontier": st["frontier_size"][i]}
+                                  for i, (us, bu) in enumerate(sh.bfs_level_times(g))]
             teps = np.array(teps)
-            results[name] = {"GTEPS_harmonic_mean": round(float(len(teps) / (1.0 / teps).sum()), 3),
-                             "GTEPS_min": round(float(teps.min()), 3), "GTEPS_median": round(float(np.median(teps)), 3),
-                             "GTEPS_max": round(float(teps.max()), 3), "ms_median": round(float(np.median(times)), 3),
-                             "levels_median": int(np.median(levels))}
+            hm = float(len(teps) / (1.0 / teps).sum())
+            med_ms = float(np.median(times))
+            res = {"GTEPS_harmonic_mean": round(hm, 3),
+                   "GTEPS_min": round(float(teps.min()), 3), "GTEPS_median": round(float(np.median(teps)), 3),
+                   "GTEPS_max": round(float(teps.max()), 3), "ms_median": round(med_ms, 3),
+                   "levels_median": int(np.median(levels)), "levels_of_first_root": level_rows,
+                   "roofline_stream": {"bound": "hbm", "algorithmic_bytes_per_search": stream_bytes,
+                                       "achieved": round(stream_bytes / med_ms / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": round(stream_bytes / med_ms / 1e6 / HBM_PEAK_GBS, 4),
+                                       "GTEPS_at_peak": round(hm / (stream_bytes / med_ms / 1e6 / HBM_PEAK_GBS), 1)}}
+            if name == "top_down" and "randread8_2MiB_Gops" in c:
+                pr = float(np.median(probes))
+                res["roofline_probes"] = {"bound": "L2 random-probe rate", "ceiling": c["randread8_2MiB_Gops"], "unit": "G probes/s",
+                                          "ceiling_source": "same run: randread8_2MiB_Gops (random 8-byte reads of an L2-resident 2 MiB)",
+                                          "achieved": round(pr, 1), "frac": round(pr / c["randread8_2MiB_Gops"], 4)}
+            results[name] = res
         sh.bfs_destroy(g)
         sh.stream_sync()
     finally:
@@ -482,21 +533,34 @@ def run_sweep(path):
                                   "traffic_GBs": round(2 * payload / ms / 1e6, 2),
                                   "hbm_frac": round(2 * payload / ms / 1e6 / HBM_PEAK_GBS, 4),
                                   "us_per_op": round(ms * 1e3 / ops, 4)})
-    # strided: uint32 elements, stride on the local side (gather for iput), the remote side (scatter) or both
-    for payload_bytes in (4096, 1 << 20, 1 << 22):
+    # strided: uint32 elements, stride on the local side (gather for iput), the remote side (scatter) or both;
+    # payloads from 4 KiB in steps of 4x up to the largest whose spans fit the 512 MiB windows, team sizes 1..256.
+    # Traffic is counted in the memory's granularity as the counters show it (profiles/): a strided read side costs
+    # min(pitch, 128) bytes per element, a strided written side min(pitch, 32), a unit-stride side 4.
+    skipped = []
+    for payload_bytes in [4096 << (2 * k) for k in range(9)]:         # 4 KiB .. 256 MiB
         nelems = payload_bytes // 4
         for stride in (2, 4, 8, 16, 32, 64):
             for mode, ls, rs in (("local", stride, 1), ("remote", 1, stride), ("both", stride, stride)):
                 lspan, rspan = ((nelems - 1) * ls + 1) * 4, ((nelems - 1) * rs + 1) * 4
                 lslot, rslot = (lspan + 255) // 256 * 256, (rspan + 255) // 256 * 256
+                if max(lslot, rslot) > window:
+                    skipped.append({"bytes": payload_bytes, "stride_mode": mode, "stride": stride,
+                                    "reason": f"span {max(lspan, rspan)} B exceeds the {window} B window"})
+                    continue
                 nslots = max(1, min(window // max(lslot, rslot), (1 << 26) // payload_bytes))
                 ops = max(1, (1 << 26) // payload_bytes)
-                for wgs in (16, 64, 256):
+                for wgs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
                     for kind, name in ((sh.OP_IPUT, "iput"), (sh.OP_IGET, "iget")):
-                        ms = time_cell(kind, nelems, 4, rs, ls, rslot, lslot, nslots, ops, wgs)
+                        fn = lambda: sh.copy_sweep(kind, remote_sym, local_sym, nelems, 4, rs, ls, rslot, lslot, nslots, ops, wgs)
+                        ms = _median_ms(fn, lambda: None, reps=2 if wgs < 8 else 3, warm=1)
                         payload = NPES * ops * payload_bytes
-                        sect = lambda st_: min(st_ * 4, 64) if st_ > 1 else 4   # bytes of memory sectors per element
-                        traffic = NPES * ops * nelems * (sect(ls) + sect(rs))
+                        # bytes the memory moves per element (profiles/k_copy_sweep_strided_cells_counters.md): reads come
+                        # in whole 128-byte lines, writes in 32-byte pieces; a unit-stride side costs its 4 bytes
+                        rd = lambda st_: min(st_ * 4, 128) if st_ > 1 else 4
+                        wr = lambda st_: min(st_ * 4, 32) if st_ > 1 else 4
+                        read_stride, write_stride = (ls, rs) if kind == sh.OP_IPUT else (rs, ls)
+                        traffic = NPES * ops * nelems * (rd(read_stride) + wr(write_stride))
                         cells_out.append({"op": name, "bytes": payload_bytes, "stride_mode": mode, "stride": stride,
                                           "wgs_per_pe": wgs, "ops_per_pe": ops, "ms": round(ms, 4),
                                           "payload_GBs": round(payload / ms / 1e6, 2),
@@ -505,9 +569,73 @@ def run_sweep(path):
     sh.stream_sync()
     sh.finalize()
     with open(path, "w") as f:
-        json.dump({"npes": NPES, "heap_bytes_per_pe": SEG, "cells": cells_out}, f)
+        json.dump({"npes": NPES, "heap_bytes_per_pe": SEG, "cells": cells_out, "skipped": skipped}, f)
     best = max((c for c in cells_out if c["op"] in ("put", "get") and c["bytes"] >= 1 << 20), key=lambda c: c["hbm_frac"])
-    print(json.dumps({"sweep_cells": len(cells_out), "file": path, "best_contiguous_ge_1MiB": best}), flush=True)
+    print(json.dumps({"sweep_cells": len(cells_out), "skipped_cells": len(skipped), "file": path, "best_contiguous_ge_1MiB": best}), flush=True)
+
+
+def run_ceilings():
+    """The plain-stream, random-access, atomic and mixed read / write ceilings of THIS box (bench_ceilings, a few seconds)."""
+    import subprocess
+    exe = os.path.join(ROOT, "bench_ceilings")
+    try:
+        res = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+        return json.loads(res.stdout) if res.returncode == 0 else {"error": (res.stdout + res.stderr)[-300:]}
+    except Exception as ex:  # noqa: BLE001
+        return {"error": f"{type(ex).__name__}: {ex}"}
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of the dominant kernel from rocprofv3 counters: a small tracked file that the profiling
+    command writes (bench_profile.py), with the commit it was taken at.  None if there is no such file."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_traffic.json")
+    try:
+        with open(path) as f:
+            d = json.load(f)
+        return d["traffic_bytes_per_launch"], {"file": os.path.relpath(path, ROOT), "commit": d.get("commit"),
+                                              "fetch_bytes": d.get("fetch_bytes_per_launch"), "write_bytes": d.get("write_bytes_per_launch")}
+    except (OSError, KeyError, ValueError):
+        return None, None
+
+
+def profile_cells(which):
+    """A few launches of one family of kernels and nothing else, for rocprofv3 (--kernel-trace --stats, --pmc):
+    strided  six iput cells of configuration 2 (4 MiB payload, 256 workgroups per PE): gather and scatter at stride 2, 16, 64
+    hash     configuration 4 once (2^26 inserts, 2^26 lookups)
+    bfs      configuration 5, one root, top-down, then the same root direction-optimising
+    Every mode also runs one plain 1 GiB tensor copy, the reference dispatch for scaling FETCH_SIZE / WRITE_SIZE."""
+    import numpy as np
+    import torch
+    import paper_2511_15076_amd as sh
+    import workgen
+    dev = torch.device("cuda:0")
+    cal = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    cal[1 << 30:].copy_(cal[:1 << 30])                      # plain copy: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del cal
+    torch.cuda.empty_cache()
+    if which == "strided":
+        heap = torch.empty(NPES * SEG, dtype=torch.uint8, device=dev)
+        heap.view(torch.int64).random_()
+        scratch = torch.zeros(sh.scratch_bytes(NPES), dtype=torch.uint8, device=dev)
+        sh.init(NPES, SEG, heap, scratch, torch.cuda.current_stream().cuda_stream)
+        base = heap.data_ptr()
+        nelems, ops = (4 << 20) // 4, 16
+        for stride in (2, 16, 64):
+            for ls, rs in ((stride, 1), (1, stride)):           # iput: local side strided = gather, remote side strided = scatter
+                lslot, rslot = (((nelems - 1) * ls + 1) * 4 + 255) // 256 * 256, (((nelems - 1) * rs + 1) * 4 + 255) // 256 * 256
+                nslots = max(1, min((SEG // 2) // max(lslot, rslot), ops))
+                sh.copy_sweep(sh.OP_IPUT, base + SEG // 2, base, nelems, 4, rs, ls, rslot, lslot, nslots, ops, 256)
+                sh.stream_sync()
+        sh.finalize()
+        print(json.dumps({"profile_cells": "strided", "launch_order": ["gather s2", "scatter s2", "gather s16", "scatter s16", "gather s64", "scatter s64"],
+                          "elements_per_launch": NPES * ops * nelems}), flush=True)
+    elif which == "hash":
+        print(json.dumps({"profile_cells": "hash", "result": extra_hash(sh, torch)}), flush=True)
+    elif which == "bfs":
+        print(json.dumps({"profile_cells": "bfs", "result": extra_bfs(sh, torch, nroots=1)}), flush=True)
+    else:
+        raise SystemExit(f"unknown --profile-cells {which}")
 
 
 def main():
@@ -522,11 +650,14 @@ def main():
     ap.add_argument("--bfs-scale", type=int, default=24)
     ap.add_argument("--sweep", metavar="FILE", default=None,
                     help="run the whole configuration-2 sweep instead of the headline and write its cells to FILE")
-    ap.add_argument("--ceilings", action="store_true",
-                    help="also run the plain read / write / copy stream kernels (sanity ceilings of the box)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the plain read / write / copy, random-access, atomic and mixed ceilings of the box "
+                         "(they are what the extras' fractions are taken against)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB tensor copy (a reference dispatch for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--profile-cells", metavar="FAMILY", default=None,
+                    help="run only a few launches of one kernel family (strided, hash, bfs) for rocprofv3")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (PEs are emulated as workgroup teams on one "
@@ -539,6 +670,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.sweep:
         run_sweep(args.sweep)
+        return
+    if args.profile_cells:
+        profile_cells(args.profile_cells)
         return
     dev = torch.device("cuda:0")
     heap = torch.empty(NPES * SEG, dtype=torch.uint8, device=dev)
@@ -554,6 +688,9 @@ def main():
         sh.copy_sweep(c["kind"], remote_sym, local_sym, c["nbytes"], 1, 1, 1, c["nbytes"], c["nbytes"],
                       c["nslots"], c["ops"], c["wgs"])
 
+    geometry = sh.copy_sweep_geometry(0, remote_sym, local_sym, SIZES[0], SIZES[0], SIZES[0], plan[0]["nslots"], plan[0]["ops"],
+                                      args.wgs_per_pe)
+    kernel = "k_copy_sweep_stream" if geometry[1] == 384 else "k_copy_sweep"
     for _ in range(args.warmup):
         for c in plan:
             launch(c)
@@ -594,7 +731,9 @@ def main():
         med = v[len(v) // 2]
         detail[f"{'put' if kind == 0 else 'get'}_{nbytes >> 20}MiB"] = {
             "payload_GBs": round(payload_per_launch / (med * 1e-3) / 1e9, 1),
-            "hbm_frac": round(2.0 * payload_per_launch / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            "hbm_frac": round(2.0 * payload_per_launch / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "hbm_frac_slowest_launch": round(2.0 * payload_per_launch / (v[-1] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    traffic, traffic_source = measured_traffic(kernel)
 
     out = {
         "metric": "put/get payload bandwidth, messages >= 1 MiB (config 2 sweep, 8 emulated PEs)",
@@ -604,19 +743,33 @@ def main():
         "config": {"workload": "configs[1]: 8 emulated PEs in a ring, contiguous put and get, message sizes "
                                "1/4/16/64 MiB, 256 MiB payload per PE per launch",
                    "npes": NPES, "heap_bytes_per_pe": SEG, "wgs_per_pe": args.wgs_per_pe,
-                   "launches_per_step": len(plan)},
+                   "launches_per_step": len(plan), "launch_geometry": {"workgroups": geometry[0], "threads": geometry[1]}},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled by a plain 1 GiB copy
-                     # (profiles/k_copy_sweep_config2_put_get_1-64MiB.md)
-                     "traffic": 4295.11e6,
-                     "kernel": "k_copy_sweep", "avg_launch_ms": round(avg_launch_ms, 4),
-                     "algorithmic_bytes_per_launch": 2 * payload_per_launch},
+                     # rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, each scaled by what a plain 1 GiB copy reads
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": kernel, "avg_launch_ms": round(avg_launch_ms, 4),
+                     "algorithmic_bytes_per_launch": 2 * payload_per_launch,
+                     "target": "north_star: >= 0.80 of HBM peak for messages >= 1 MiB"},
         "cells": detail,
     }
     sh.finalize()
     del heap
     torch.cuda.empty_cache()
+    ceilings = {} if args.no_ceilings else run_ceilings()
+    if ceilings and "error" not in ceilings:
+        paced = ceilings.get("copy_streaming_one_stream_GBs_by_pace_ns", {})
+        out["roofline"]["box_copy_ceilings_GBs"] = {
+            "read_only_best": max(ceilings.get(f"read_grid{g}_GBs", 0) for g in (256, 1024, 2048, 4096)),
+            "write_only_best": max(ceilings.get(f"write_grid{g}_GBs", 0) for g in (256, 1024, 2048, 4096)),
+            "plain_copy_best": max([ceilings.get(f"copy_u{u}_grid{g}_GBs", 0) for g in (256, 1024, 2048, 4096) for u in (1, 4)]
+                                   + list(ceilings.get("copy_pipelined_grid256_GBs_by_extra_delta_bit", {}).values())),
+            "wave_specialised_unpaced_best": ceilings.get("copy_wave_specialised_unpaced_GBs", {}).get("best"),
+            "streaming_copy_one_stream_by_pace_ns": paced,
+            "source": "same run (bench_ceilings)"}
+        best_paced = max([v["median"] for v in paced.values()] or [0])
+        if best_paced:
+            out["roofline"]["frac_of_box_best_copy"] = round(achieved / best_paced, 4)
     want = [] if args.extras == "none" else args.extras.split(",")
     extras = {}
 
@@ -634,20 +787,18 @@ def main():
                 pass
         torch.cuda.empty_cache()
 
+    ceil_ok = ceilings if ceilings and "error" not in ceilings else None
     run_extra("cfg1", "config1_optable", extra_config1)
     run_extra("latency", "latency", extra_latency)
     run_extra("moe", "moe_low_latency", extra_moe)
     run_extra("transpose", "transpose_by_gets", extra_transpose)
-    run_extra("amo", "config3_amo", extra_amo)
-    run_extra("hash", "config4_hash", extra_hash)
-    run_extra("bfs", "config5_bfs", extra_bfs, scale=args.bfs_scale)
+    run_extra("amo", "config3_amo", extra_amo, ceilings=ceil_ok)
+    run_extra("hash", "config4_hash", extra_hash, ceilings=ceil_ok)
+    run_extra("bfs", "config5_bfs", extra_bfs, ceilings=ceil_ok, scale=args.bfs_scale)
     if extras:
         out["extras"] = extras
-    if args.ceilings:
-        import subprocess
-        exe = os.path.join(ROOT, "bench_ceilings")
-        res = subprocess.run([exe], capture_output=True, text=True, timeout=120)
-        out["stream_ceilings"] = json.loads(res.stdout) if res.returncode == 0 else {"error": res.stdout[-200:]}
+    if ceilings:
+        out["stream_ceilings"] = ceilings
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
         if extras:
