@@ -27,7 +27,7 @@ def oracle_world(init, seed=3):
     return w
 
 
-@pytest.mark.parametrize("wgs", [1, 3])
+@pytest.mark.parametrize("wgs", [1, 2, 3, 8])       # 1, 2 and 8 are the team sizes bench.py times
 def test_config1_full_table(wgs):
     npes, hb = 4, 1 << 20
     ops = workgen.cfg1_op_table()                       # 10,000 ops, batches of 100
