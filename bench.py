@@ -520,6 +520,7 @@ def run_sweep(path):
 
     sizes = sorted([1 << k for k in range(3, 27)] + [14336, 14352])
     for nbytes in sizes:
+        print(f"sweep: contiguous {nbytes} B", file=sys.stderr, flush=True)      # progress, so that a long run is seen to be alive
         slot = (nbytes + 255) // 256 * 256
         nslots = max(1, min(window // slot, (1 << 28) // slot))
         ops = max(1, min((1 << 28) // nbytes, 1 << 16))
@@ -541,6 +542,7 @@ def run_sweep(path):
     for payload_bytes in [4096 << (2 * k) for k in range(9)]:         # 4 KiB .. 256 MiB
         nelems = payload_bytes // 4
         for stride in (2, 4, 8, 16, 32, 64):
+            print(f"sweep: strided payload {payload_bytes} B stride {stride}", file=sys.stderr, flush=True)
             for mode, ls, rs in (("local", stride, 1), ("remote", 1, stride), ("both", stride, stride)):
                 lspan, rspan = ((nelems - 1) * ls + 1) * 4, ((nelems - 1) * rs + 1) * 4
                 lslot, rslot = (lspan + 255) // 256 * 256, (rspan + 255) // 256 * 256
