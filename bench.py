@@ -692,7 +692,7 @@ def main():
 
     geometry = sh.copy_sweep_geometry(0, remote_sym, local_sym, SIZES[0], SIZES[0], SIZES[0], plan[0]["nslots"], plan[0]["ops"],
                                       args.wgs_per_pe)
-    kernel = "k_copy_sweep_stream" if geometry[1] == 384 else "k_copy_sweep"
+    kernel = {384: "k_copy_sweep_stream", 448: "k_copy_sweep_stream_dyn"}.get(geometry[1], "k_copy_sweep")
     for _ in range(args.warmup):
         for c in plan:
             launch(c)

@@ -225,9 +225,13 @@ int shmem_op_batch_noalloc(int npes, size_t heap_bytes_per_pe, void *dev_heap, c
  * Bandwidth cells -- PUT/GET of whole multiples of 4 KiB with 16-byte aligned
  * placement, asked for with at least one workgroup per compute unit -- run on
  * one larger workgroup per compute unit (compute units / npes per PE) that
- * streams through LDS at a paced rate; shmem_copy_sweep_geometry tells which
- * launch a cell gets.  Errors as for the single ops, checked for the last
- * slot too. */
+ * streams through LDS at a paced rate; where a PE's operations make at least
+ * 32 tasks of 4 KiB per workgroup (and a whole number of blocks of four) the
+ * workgroups claim their tasks block by block from a per-PE counter in the
+ * scratch words instead of walking fixed shares (the counters are zero between
+ * launches; MI_SHMEM_STREAM_DYNAMIC=0 in the environment of shmem_init
+ * switches that off).  shmem_copy_sweep_geometry tells which launch a cell
+ * gets.  Errors as for the single ops, checked for the last slot too. */
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
                      ptrdiff_t remote_stride, ptrdiff_t local_stride, size_t remote_slot_bytes,
                      size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe);

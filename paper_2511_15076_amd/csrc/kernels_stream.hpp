@@ -149,6 +149,193 @@ __device__ __forceinline__ void stream_copy(const StreamPlan &p, uint8_t *ring)
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The same copy with the team's task list handed out DYNAMICALLY: a workgroup claims blocks of ST_BLOCK
+// consecutive tasks from a per-team counter (one returning atomic add per block, issued two blocks ahead of
+// its use by a seventh wave that also does the pacing).  A workgroup that the memory system serves more
+// slowly then simply takes fewer blocks: the launch ends when the work is done instead of when the slowest
+// workgroup has walked its fixed share, and the tasks in flight stay a compact window however far the
+// workgroups' rates drift apart.
+//
+// The first ST_STATIC blocks of a workgroup are fixed (rank, rank + team, ...), so loading starts without
+// waiting for a claim; the counter hands out blocks from ST_STATIC * team on.  Block numbers travel to the
+// reader and writer waves through a small queue in LDS; the end (the first claim beyond the last block) is
+// published at least ST_RING steps before the last task, so every wave runs the same number of barriers.
+constexpr uint32_t ST_BLOCK = 4;
+constexpr uint32_t ST_STATIC = 4;        // ST_STATIC * ST_BLOCK >= ST_RING: the prologue needs no claim
+constexpr uint32_t ST_QUEUE = 16;        // block numbers kept in LDS (a power of two)
+constexpr uint32_t ST_DYN_THREADS = ST_THREADS + 64;
+// s_waitcnt lgkmcnt(0) alone
+#define ST_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14))
+
+// tasks of one block, in order: (chunk, slot) advanced by one
+struct BlockWalker {
+    uint32_t ch, slot, tau, left, j;
+    __device__ __forceinline__ void start(const StreamPlan &p, uint32_t block)
+    {
+        uint32_t t = block * ST_BLOCK + p.rot;                // below 2^32: ntasks < 2^31
+        if (t >= p.ntasks) t -= p.ntasks;
+        tau = ST_UNIFORM(t);
+        const uint32_t op = tau / p.cpo;
+        ch = ST_UNIFORM(tau - op * p.cpo);
+        slot = ST_UNIFORM(op % p.nslots);
+        left = ST_BLOCK;
+    }
+    __device__ __forceinline__ void next(const StreamPlan &p)
+    {
+        --left; ++tau; ++ch;
+        if (ch == p.cpo) { ch = 0; ++slot; if (slot == p.nslots) slot = 0; }
+        if (tau == p.ntasks) { tau = 0; ch = 0; slot = 0; }
+    }
+};
+
+typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
+typedef __attribute__((address_space(1))) uint64_t glb_u64_t;
+
+// Two LDS words read by a wave that has global-load-to-LDS instructions in flight.  Written as one asm
+// statement with its own wait: an LDS read the compiler can see makes it wait for every outstanding
+// load-to-LDS first (they might alias), which would serialise the ring.
+__device__ __forceinline__ void lds_read_pair(uint32_t addr_a, uint32_t addr_b, uint32_t &a, uint32_t &b)
+{
+    asm volatile("ds_read_b32 %0, %2\n\tds_read_b32 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a), "=&v"(b) : "v"(addr_a), "v"(addr_b) : "memory");
+}
+
+// `claim`: the team's counter, `done`: one word for the whole launch; both zero at launch and zero again at
+// its end (`claim0`, `nteams`, `claim_stride`: all the launch's counters, for the workgroup that finishes last).
+// `ring`: ST_RING * ST_CHUNK bytes of LDS, `q`: ST_QUEUE block numbers and one word for the end, in LDS.
+__device__ __forceinline__ void stream_copy_dyn(const StreamPlan &p, uint64_t *claim, uint64_t *done, uint64_t *claim0,
+                                                uint32_t nteams, uint32_t claim_stride, uint8_t *ring, uint32_t *q_generic)
+{
+    constexpr uint32_t S = ST_RING, B = ST_BLOCK, Q = ST_QUEUE;
+    static_assert(ST_STATIC * B >= S && (Q & (Q - 1)) == 0 && Q >= ST_STATIC + S / B + 4, "queue and static prefix cover the read-ahead");
+    volatile lds_u32_t *const q = (volatile lds_u32_t *)q_generic;
+    const uint32_t lane16 = (threadIdx.x & 63) * 16;
+    const uint32_t wave = ST_UNIFORM(threadIdx.x >> 6);
+    const uint32_t nblocks = p.ntasks / B;                            // host: ntasks % B == 0, nblocks >= 2 * ST_STATIC * team
+    if (threadIdx.x < ST_STATIC) q[threadIdx.x] = p.rank + threadIdx.x * p.team;
+    if (threadIdx.x == 0) q[Q] = 0xffffffffu;
+    __syncthreads();
+    uint32_t T = 0xffffffffu;                                         // tasks of this workgroup, once its end is known
+    if (wave < ST_READERS) {
+        const uint32_t row_off = wave * 1024;
+        const uint32_t qaddr = (uint32_t)(uintptr_t)q;
+        BlockWalker w;
+        w.left = 0; w.j = 0;
+        uint32_t issued = 0;
+        auto issue = [&]() {
+            if (w.left == 0) {
+                uint32_t blk, te;
+                lds_read_pair(qaddr + 4 * (w.j & (Q - 1)), qaddr + 4 * Q, blk, te);
+                T = ST_UNIFORM(te);
+                if (issued >= T) return;                              // the workgroup's last block has been issued
+                w.start(p, ST_UNIFORM(blk));
+                ++w.j;
+            }
+            const uint8_t *g = p.src + (uint64_t)w.slot * p.spitch + (uint64_t)w.ch * ST_CHUNK + row_off + lane16;
+            uint8_t *l = ring + (issued & (S - 1)) * ST_CHUNK + row_off;
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 2 /* nt */);
+            w.next(p);
+            ++issued;
+        };
+        for (uint32_t t = 0; t < S - 1; ++t) issue();
+        for (uint32_t t = 0; t < T; ++t) {
+            // task t has landed once at most the S - 2 loads issued after it are outstanding
+            if (issued - t - 1 >= S - 2) ST_WAIT_VM(S - 2); else ST_WAIT_VM(0);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue();
+        }
+    } else if (wave < ST_READERS + ST_WRITERS) {
+        constexpr uint32_t PER = ST_READERS / ST_WRITERS;
+        const uint32_t wr = wave - ST_READERS;
+        BlockWalker w;
+        w.left = 0; w.j = 0;
+        for (uint32_t t = 0; t < T; ++t) {
+            if (w.left == 0) {
+                T = ST_UNIFORM(q[Q]);                                 // published at least ST_RING steps before it matters
+                w.start(p, ST_UNIFORM(q[w.j & (Q - 1)]));
+                ++w.j;
+            }
+            uint8_t *d = p.dst + (uint64_t)w.slot * p.dpitch + (uint64_t)w.ch * ST_CHUNK + lane16;
+            w.next(p);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const uint8_t *l = ring + (t & (S - 1)) * ST_CHUNK + lane16;
+            u32x4 v[PER];
+#pragma unroll
+            for (uint32_t j = 0; j < PER; ++j) v[j] = *(const u32x4 *)(l + (wr + j * ST_WRITERS) * 1024);
+#pragma unroll
+            for (uint32_t j = 0; j < PER; ++j) __builtin_nontemporal_store(v[j], (u32x4 *)(d + (wr + j * ST_WRITERS) * 1024));
+        }
+    } else {
+        // The scheduler wave: claims blocks two ahead of their use, publishes them, and paces the barrier.
+        const bool lead = (threadIdx.x & 63) == 0;
+        // The counter's address goes through a vector register the compiler cannot see through: an atomic on
+        // an address it knows to be uniform is rewritten into a wave-wide reduction whose result is read at
+        // once, which would make every claim a full round trip in this wave.
+        uint64_t craw = (uint64_t)claim;
+        asm volatile("" : "+v"(craw));
+        glb_u64_t *const cp = (glb_u64_t *)craw;
+        const uint64_t phase = ((uint64_t)p.period * ((blockIdx.x * 167u) & 255u)) >> 8;
+        uint64_t next_issue = 0, cA = 0, cB = 0;
+        if (lead) {
+            cA = __hip_atomic_fetch_add(cp, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            cB = __hip_atomic_fetch_add(cp, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        }
+        uint32_t j = ST_STATIC, t = 0;
+        bool ended = false;
+        // B paced barriers
+        auto steps = [&]() {
+            for (uint32_t i = 0; i < B && t < T; ++i, ++t) {
+                if (p.period && t + (S - 1) < T) {
+                    uint64_t now = __builtin_amdgcn_s_memrealtime() << 8;
+                    if (t == 0) next_issue = now + phase;
+                    while (now < next_issue) { __builtin_amdgcn_s_sleep(1); now = __builtin_amdgcn_s_memrealtime() << 8; }
+                    if (now > next_issue + p.period) next_issue = now + phase;
+                    next_issue += p.period;
+                }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+            }
+        };
+        // One block: publish block j = ST_STATIC + t / B of this workgroup from the claim `c` made two turns ago
+        // (the readers look for it after barrier t + 1), make the next claim into `c`, run the block's barriers.
+        // Called for cA and cB in turn, so that each claim has its own register and nothing waits for the newest.
+        auto turn = [&](uint64_t &c) {
+            if (!ended) {
+                const uint64_t b = (uint64_t)ST_UNIFORM((uint32_t)c) + (uint64_t)ST_STATIC * p.team;   // counts stay below 2^31
+                if (b >= nblocks) {
+                    ended = true;
+                    T = j * B;
+                    if (lead) q[Q] = T;
+                } else {
+                    if (lead) q[j & (Q - 1)] = (uint32_t)b;
+                    ++j;
+                }
+                ST_WAIT_LGKM0();
+                if (!ended && lead) c = __hip_atomic_fetch_add(cp, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            }
+            steps();
+        };
+        while (t < T) { turn(cA); turn(cB); }
+        if (lead) {
+            // every claim of this workgroup has returned (both values are read) before it counts itself done;
+            // the last workgroup of the launch puts the counters back to zero for the next launch
+            const uint64_t seen = cA + cB;
+            asm volatile("" :: "v"(seen) : "memory");
+            const uint64_t d = __hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            if (d + 1 == gridDim.x) {
+                for (uint32_t i = 0; i < nteams; ++i) __hip_atomic_store(claim0 + (uint64_t)i * claim_stride, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+                __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            }
+        }
+    }
+}
+
 // Bandwidth-sweep cell through the streaming copy: contiguous messages that are whole multiples of
 // ST_CHUNK with 16-byte aligned placement.  PE team p = workgroups [p * team, (p + 1) * team).
 struct StreamSweepArgs {
@@ -176,6 +363,32 @@ __global__ __launch_bounds__(ST_THREADS) void k_copy_sweep_stream(Ctx c, StreamS
     p.rot = (uint32_t)(((uint64_t)ST_ROT * pe) % p.ntasks);
     p.period = a.period;
     stream_copy(p, ring);
+}
+
+// The same cell with dynamic task claiming (ntasks a multiple of ST_BLOCK, at least 2 * ST_STATIC blocks per
+// workgroup, fewer than 2^31 tasks).  The claim counter of PE p is word 8 of the PE's first scratch line (no
+// barrier runs in this kernel), the launch's done count a general-purpose scratch word.
+__global__ __launch_bounds__(ST_DYN_THREADS) void k_copy_sweep_stream_dyn(Ctx c, StreamSweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t ring[ST_RING * ST_CHUNK];
+    __shared__ uint32_t q[ST_QUEUE + 1];
+    const uint32_t pe = blockIdx.x / a.team, peer = (pe + 1) % (uint32_t)c.npes;
+    uint8_t *const lbase = ptr(c, a.local_off, pe);
+    uint8_t *const rbase = ptr(c, a.remote_off, peer);
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    StreamPlan p;
+    p.src = is_put ? lbase : rbase;
+    p.dst = is_put ? rbase : lbase;
+    p.spitch = is_put ? a.local_slot : a.remote_slot;
+    p.dpitch = is_put ? a.remote_slot : a.local_slot;
+    p.cpo = (uint32_t)(a.count / ST_CHUNK);
+    p.nslots = a.nslots;
+    p.ntasks = p.cpo * a.ops_per_pe;
+    p.team = a.team; p.rank = blockIdx.x % a.team;
+    p.rot = (uint32_t)(((uint64_t)ST_ROT * pe) % p.ntasks);
+    p.period = a.period;
+    uint64_t *const claim0 = &c.scratch[W_PE_BASE + 8];
+    stream_copy_dyn(p, claim0 + (uint64_t)pe * W_PE_WORDS, &c.scratch[W_WORK + 8], claim0, (uint32_t)c.npes, W_PE_WORDS, ring, q);
 }
 
 // One contiguous copy of `chunks` whole chunks: the grid is one team.

@@ -43,6 +43,7 @@ struct Host {
     hipStream_t stream = nullptr;
     int num_cus = 0;
     int wall_khz = 100000;         // rate of the constant-rate clock the streaming copy paces itself by
+    bool stream_dynamic = true;    // bandwidth cells claim their tasks dynamically (kernels_stream.hpp)
     double stream_pace_ns = 0;     // pacing of the streaming copy: ns per 4 KiB task and workgroup when 256 workgroups stream
     bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
     hostlogic::SymAllocator alloc; // symmetric offsets (guarded by mu)
@@ -277,6 +278,15 @@ uint32_t sweep_stream_team(bool is_strided, uint64_t count, uint64_t remote_slot
     return team;
 }
 
+// Whether a streaming cell hands its tasks out dynamically (blocks of ST_BLOCK tasks claimed from a per-team
+// counter): whole blocks, enough of them that the fixed first blocks of every workgroup are a small part.
+bool sweep_stream_dynamic(uint32_t team, uint64_t count, int ops_per_pe)
+{
+    const uint64_t ntasks = (count / shmemx::ST_CHUNK) * (uint64_t)ops_per_pe;
+    return H.stream_dynamic && team > 1 && ntasks % shmemx::ST_BLOCK == 0 && ntasks < (1ull << 31) &&
+           ntasks / shmemx::ST_BLOCK >= 2ull * shmemx::ST_STATIC * team;
+}
+
 }  // namespace
 
 extern "C" {
@@ -347,6 +357,8 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     const char *pace = getenv("MI_SHMEM_STREAM_PACE_NS");     // measurement aid: 0 = unpaced
     H.stream_pace_ns = pace ? atof(pace) : STREAM_PACE_NS;
     if (!(H.stream_pace_ns >= 0.0 && H.stream_pace_ns < 1e6)) H.stream_pace_ns = STREAM_PACE_NS;
+    const char *dyn = getenv("MI_SHMEM_STREAM_DYNAMIC");
+    H.stream_dynamic = !dyn || atoi(dyn) != 0;
     H.alloc.reset((uint64_t)(uintptr_t)dev_heap, (uint64_t)heap_bytes_per_pe);
     H.init = true;
     return SHMEM_OK;
@@ -622,7 +634,10 @@ int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, 
         sa.ops_per_pe = (uint32_t)ops_per_pe; sa.team = team;
         const unsigned grid = (unsigned)H.npes * team;
         sa.period = stream_period(grid);
-        hipLaunchKernelGGL(shmemx::k_copy_sweep_stream, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, ctx(), sa);
+        if (sweep_stream_dynamic(team, count, ops_per_pe))
+            hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_dyn, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
+        else
+            hipLaunchKernelGGL(shmemx::k_copy_sweep_stream, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, ctx(), sa);
         return launched();
     }
     hipLaunchKernelGGL(shmemx::k_copy_sweep, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
@@ -639,7 +654,7 @@ int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_
     const uint32_t team = sweep_stream_team(kind >= SHMEM_OP_IPUT, count, remote_slot_bytes, local_slot_bytes, off_of(remote_sym),
                                             off_of(local_sym), nslots, ops_per_pe, wgs_per_pe);
     if (workgroups_out) *workgroups_out = team ? H.npes * (int)team : H.npes * wgs_per_pe;
-    if (threads_out) *threads_out = team ? (int)shmemx::ST_THREADS : WG_THREADS;
+    if (threads_out) *threads_out = !team ? WG_THREADS : sweep_stream_dynamic(team, count, ops_per_pe) ? (int)shmemx::ST_DYN_THREADS : (int)shmemx::ST_THREADS;
     return SHMEM_OK;
 }
 

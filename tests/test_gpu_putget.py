@@ -329,12 +329,29 @@ STREAM_CASES = [
     (16, workgen.OP_GET, 4096, 300, 300, 16),
     (1, workgen.OP_PUT, 1 << 16, 300, 300, 256),
     (2, workgen.OP_GET, 4096, 2048, 5, 128),             # exactly one ring's worth of tasks per workgroup
+    (8, workgen.OP_PUT, 4096, 4096, 64, 32),             # from here on: enough blocks of four tasks per workgroup
+    (8, workgen.OP_GET, 16384, 1024, 1024, 64),          # for the task list to be handed out dynamically
+    (4, workgen.OP_PUT, 12288, 2048, 100, 64),           # three tasks per message: blocks straddle messages and slots
+    (8, workgen.OP_GET, 1 << 20, 8, 8, 256),
+    (2, workgen.OP_PUT, 8192, 4100, 4100, 128),          # 8200 tasks, 128 workgroups per team
 ]
 
 
+def _stream_threads(npes, count, nops, dynamic=True):
+    """Workgroup size the library is expected to choose for a streaming cell: 448 (a seventh wave that claims
+    blocks of four tasks) when the task list is whole blocks, at least eight per workgroup; else 384."""
+    team, ntasks = 256 // npes, count // 4096 * nops
+    return 448 if dynamic and team > 1 and ntasks % 4 == 0 and ntasks // 4 >= 8 * team else 384
+
+
+@pytest.mark.parametrize("dynamic", [True, False])
 @pytest.mark.parametrize("case", STREAM_CASES)
-def test_copy_sweep_streaming_cell(case):
+def test_copy_sweep_streaming_cell(case, dynamic, monkeypatch):
     npes, kind, count, nops, nslots, wgs = case
+    if not dynamic:
+        if _stream_threads(npes, count, nops) == 384:
+            pytest.skip("this cell has a fixed task assignment anyway")
+        monkeypatch.setenv("MI_SHMEM_STREAM_DYNAMIC", "0")        # read by shmem_init
     rslot = count + 4096 + 256
     lslot = count + 16
     hb = ((rslot + lslot) * nslots + 8192 + 255) // 256 * 256
@@ -353,12 +370,18 @@ def test_copy_sweep_streaming_cell(case):
         heap.copy_(torch.from_numpy(init.reshape(-1)))
         wgs_launched, threads = sh.copy_sweep_geometry(kind, base + remote_off, base + local_off, count, rslot, lslot, nslots,
                                                        nops, wgs)
-        assert threads == 384 and wgs_launched == npes * (256 // npes), "this cell was meant for the streaming copy"
+        assert wgs_launched == npes * (256 // npes), "this cell was meant for the streaming copy"
+        assert threads == _stream_threads(npes, count, nops, dynamic)
         sh.copy_sweep(kind, base + remote_off, base + local_off, count, 1, 1, 1, rslot, lslot, nslots, nops, wgs)
         sh.stream_sync()
         got = heaps_of(heap, npes)
-    assert np.array_equal(got, w.heaps())
-    assert not np.array_equal(got, init)
+        assert np.array_equal(got, w.heaps())
+        assert not np.array_equal(got, init)
+        # the claim counters are back at zero: the same cell again, from the same start, gives the same heap
+        heap.copy_(torch.from_numpy(init.reshape(-1)))
+        sh.copy_sweep(kind, base + remote_off, base + local_off, count, 1, 1, 1, rslot, lslot, nslots, nops, wgs)
+        sh.stream_sync()
+        assert np.array_equal(heaps_of(heap, npes), w.heaps())
 
 
 def test_copy_sweep_geometry_keeps_small_cells_on_the_register_path():
@@ -367,7 +390,8 @@ def test_copy_sweep_geometry_keeps_small_cells_on_the_register_path():
         assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 64, 16) == (128, 256)     # under one workgroup per CU
         assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 64, 32) == (256, 256)     # too few tasks
         assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4112, 4352, 4352, 64, 640, 32) == (256, 256)    # not whole tasks
-        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 640, 32) == (256, 384)
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 640, 32) == (256, 384)     # 20 tasks per workgroup: fixed shares
+        assert sh.copy_sweep_geometry(workgen.OP_PUT, base + half, base, 4096, 4096, 4096, 64, 1024, 32) == (256, 448)    # 32 per workgroup: claimed in blocks
         assert sh.copy_sweep_geometry(workgen.OP_IPUT, base + half, base, 4096, 4096 * 8, 4096 * 8, 4, 640, 32) == (256, 256)
 
 
