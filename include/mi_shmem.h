@@ -457,8 +457,9 @@ int shmem_fence_litmus(void *buf_sym, size_t nbytes, int rounds, int use_quiet, 
  *
  * shmem_moe_create allocates, in the symmetric heap, the dispatch receive slots
  * ((num_experts/npes) * npes * max_tokens messages per PE), the combine slots
- * (max_tokens * topk tokens per PE) and the signals (one per (local expert,
- * sender) pair for the counts, one per expert for the combine flags), and
+ * (max_tokens * topk tokens per PE) and 2 * num_experts + 8 64-bit words of
+ * signals per PE (one per (local expert, sender) pair for the counts, one per
+ * expert for the combine flags, eight for the library's own bookkeeping), and
  * clears the signals.  Limits: num_experts a multiple of npes and <= 1024,
  * max_tokens <= 128, topk <= 64, npes <= 256, hidden_bytes a positive
  * multiple of 16.  *moe_out is owned by the library until shmem_moe_destroy.

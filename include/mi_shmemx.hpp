@@ -67,6 +67,17 @@ __device__ __forceinline__ uint64_t atomic_fetch_add(uint64_t *p, uint64_t v)
 {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, SHMEMX_AGENT);
 }
+// A returning fetch-add whose result is looked at LATER (a claim of work made ahead of its use).  The address
+// goes through a vector register the compiler cannot see through: an atomic on an address it knows to be
+// wave-uniform is rewritten into a wave-wide reduction whose result is read at once, which turns the claim
+// into a synchronous round trip.
+__device__ __forceinline__ uint64_t atomic_fetch_add_deferred(uint64_t *p, uint64_t v)
+{
+    typedef __attribute__((address_space(1))) uint64_t global_u64;
+    uint64_t raw = (uint64_t)p;
+    asm volatile("" : "+v"(raw));
+    return __hip_atomic_fetch_add((global_u64 *)raw, v, __ATOMIC_RELAXED, SHMEMX_AGENT);
+}
 __device__ __forceinline__ uint64_t atomic_fetch_or(uint64_t *p, uint64_t v)
 {
     return __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, SHMEMX_AGENT);

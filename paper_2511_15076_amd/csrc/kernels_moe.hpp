@@ -18,9 +18,13 @@
 // data; the destination waits for the flags of a token's experts and sums the
 // copies.
 //
-// Work split: workgroup w of a PE's team owns the experts e = w (mod team size)
-// when sending and the local experts / tokens with the same residue when
-// receiving, so one workgroup-level release covers all messages of a pair.
+// Work split, batches under 32 tokens per PE (latency-bound): workgroup w of a
+// PE's team owns the experts e = w (mod team size) when sending and the local
+// experts / tokens with the same residue when receiving, so one workgroup-level
+// release covers all messages of a pair.  Larger batches (bandwidth-bound):
+// messages are shared out half in fixed ranges, half in blocks claimed from a
+// counter of the PE (moe_share), inside a workgroup piece by piece; a pair's
+// count is then the sum of what several workgroups add after their releases.
 // All workgroups of a launch are resident at once (the host checks the grid
 // against the occupancy limit) and every workgroup finishes sending before it
 // starts to wait, so the waits end; they are bounded besides.
@@ -30,12 +34,25 @@
 
 namespace shmemx {
 
+
 constexpr uint32_t MOE_MAX_EXPERTS = 1024;  // per-expert token masks live in LDS
 constexpr uint32_t MOE_MAX_TOKENS = 128;    // two 64-bit mask words per expert
 constexpr uint32_t MOE_MAX_TOPK = 64;       // one lane per top-k position
 constexpr uint32_t MOE_MAX_PES = 256;
 constexpr uint32_t MOE_META_BYTES = 16;
 constexpr int MOE_THREADS = 512;              // eight waves per workgroup: more copies in flight per team
+constexpr uint32_t MOE_BULK_TOKENS = 32;      // batches from this size on are balanced dynamically
+constexpr uint32_t MOE_SEND_WAVES = 7;        // large batches: waves 0..6 move messages, the eighth claims work for them
+constexpr uint32_t MOE_BLOCK = 4;             // messages per claim
+constexpr uint32_t MOE_PARTS = 2;             // large batches: pieces of a message, each moved by one wave
+// Measured at 128 tokens per PE: blocks of 2, 4 or 8 messages in 2 pieces are alike, 4 pieces per message cost 10 %.
+// Whole messages as pieces (MOE_PARTS = 1) are excluded: the one measurement run with them produced no output for
+// two minutes and was ended by its time limit, and reading the code has not shown why.
+static_assert(MOE_PARTS >= 2, "see above");
+constexpr uint32_t MOE_RANGES = 512;          // ranges of routes one workgroup can take in a dispatch
+// per-PE control words, after the combine flags in the signal array
+enum : uint32_t { MOE_CTL_COMBINES = 0, MOE_CTL_ARRIVALS = 1, MOE_CTL_SEND_CLAIM = 2, MOE_CTL_SEND_DONE = 3,
+                  MOE_CTL_RECV_CLAIM = 4, MOE_CTL_RECV_DONE = 5, MOE_CTL_COMB_CLAIM = 6, MOE_CTL_COMB_DONE = 7, MOE_CTL_WORDS = 8 };
 
 struct MoeState {
     uint32_t num_experts, epp, max_tokens, topk;
@@ -128,11 +145,125 @@ __device__ __forceinline__ uint64_t moe_poll(const Gin &gin, uint32_t id, uint64
     return v;
 }
 
+// Row g of a PE's flattened list of received rows (local experts in order, within an expert the senders in
+// ascending order): which local expert it belongs to, given the experts' first rows ebase[0..epp].
+__device__ __forceinline__ uint32_t moe_expert_of_row(const uint32_t *ebase, uint32_t epp, uint32_t g)
+{
+    uint32_t lo = 0, hi = epp;                  // ebase[lo] <= g < ebase[hi]
+    while (hi - lo > 1) {                       // ends: the interval halves
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ebase[mid] <= g) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// A dispatch count signal carries two numbers: the high half is count + 1, announced once per pair (so that "no
+// tokens" differs from "not announced"); the low half grows by the number of messages that have become visible
+// -- in one addition for a small batch, in one addition per contributing workgroup for a large one.  The pair
+// is complete when the low half has reached the announced count.  Returns the count (0 after a time-out).
+__device__ __forceinline__ uint32_t moe_poll_count(const Gin &gin, uint32_t id, bool patient = false)
+{
+    uint32_t spins = 0;
+    for (;;) {
+        const uint64_t v = gin.read_signal(id);
+        const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+        if (hi && lo + 1 == hi) return lo;
+        if (timed_out(gin.c, spins)) return 0;
+        if (patient) __builtin_amdgcn_s_sleep(100); else
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > SPIN_LIMIT) { report(gin.c, DEV_ERR_BARRIER_TIMEOUT, gin.pe); return 0; }
+    }
+}
+
+// Sharing N units of work (routes, rows: one message each) among the W workgroups of a PE when the batch is
+// large.  The first half goes out in equal fixed ranges, the second in blocks of MOE_BLOCK units that the
+// workgroups CLAIM from a counter of the PE -- so a workgroup that the memory serves slowly ends up with fewer
+// units and all of them finish within a block or two of each other, while nothing waits for a claim at the
+// start.  The eighth wave claims (never more than one range ahead of the range being worked on: a claim ahead
+// of need is work nobody else can take over at the end) and publishes ranges through LDS.  Inside the
+// workgroup the same idea once more: a message is MOE_PARTS pieces, and waves 0..6 take the workgroup's pieces
+// one at a time off a counter in LDS, so that a wave whose pieces come back slowly takes fewer of them.
+// work(unit, part) moves one piece.
+struct MoeRanges {
+    uint32_t rq[MOE_RANGES][2];     // the ranges this workgroup has taken, in order
+    uint32_t pub, next;             // ranges published (bit 31: no more will come); pieces handed to waves so far
+};
+
+template <class F>
+__device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
+                                          uint32_t wave, uint32_t lane, F &&work)
+{
+    constexpr uint32_t B = MOE_BLOCK, BP = MOE_BLOCK * MOE_PARTS;            // units, pieces per claimed block
+    const uint32_t S = N / (2 * W) / B * B, Ns = S * W;                      // fixed units per workgroup, and in all
+    const uint32_t NB = (N - Ns + B - 1) / B;                                // blocks to claim
+    const uint32_t k0 = S ? 1u : 0u, p0 = S * MOE_PARTS;                     // ranges, pieces of the fixed part
+    if (threadIdx.x == 0) {
+        q.rq[0][0] = wg * S; q.rq[0][1] = wg * S + S;
+        q.pub = k0; q.next = 0;
+    }
+    __syncthreads();
+    if (wave == MOE_SEND_WAVES) {
+        uint32_t k = k0;                                                     // ranges published
+        for (;;) {                                                           // ends: the counter only grows
+            // wait until the waves have started on the last range published
+            for (uint32_t spins = 0; spins < SPIN_LIMIT; ++spins) {
+                const uint32_t nx = *(volatile uint32_t *)&q.next;
+                const uint32_t at = nx < p0 ? 0u : k0 + (nx - p0) / BP;      // the range piece `nx` belongs to
+                if (k <= at + 1) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            uint64_t cv = 0;
+            if (lane == 0) cv = atomic_fetch_add(claim, 1);
+            const uint32_t blk = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)min(cv, (uint64_t)0xffffffffu));
+            if (blk >= NB || k >= MOE_RANGES) {                              // (a full list: the other workgroups take the rest)
+                if (lane == 0) *(volatile uint32_t *)&q.pub = k | 0x80000000u;
+                break;
+            }
+            if (lane == 0) {
+                *(volatile uint32_t *)&q.rq[k][0] = Ns + blk * B;
+                *(volatile uint32_t *)&q.rq[k][1] = min(N, Ns + blk * B + B);
+                *(volatile uint32_t *)&q.pub = k + 1;                        // LDS stores of one lane stay in order
+            }
+            ++k;
+        }
+    } else if (wave < MOE_SEND_WAVES) {
+        for (;;) {
+            uint32_t p = 0;
+            if (lane == 0) p = __hip_atomic_fetch_add(&q.next, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            p = (uint32_t)__builtin_amdgcn_readfirstlane((int)p);
+            const uint32_t k = p < p0 ? 0u : k0 + (p - p0) / BP, within = p < p0 ? p : (p - p0) % BP;
+            uint32_t pub, spins = 0;
+            while (((pub = *(volatile uint32_t *)&q.pub) & 0x7fffffffu) <= k && !(pub >> 31)) {
+                __builtin_amdgcn_s_sleep(1);
+                if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); pub = 0x80000000u; break; }
+            }
+            if ((pub & 0x7fffffffu) <= k) break;                             // the list has ended
+            const uint32_t unit = *(volatile uint32_t *)&q.rq[k][0] + within / MOE_PARTS;
+            if (unit < *(volatile uint32_t *)&q.rq[k][1]) work(unit, within % MOE_PARTS);   // (the last block may be short)
+        }
+    }
+    __syncthreads();
+}
+
+// After moe_share: the workgroup of the PE that is the last to get here puts the claim counter back to zero
+// for the next launch (thread 0 only; `done` counts the workgroups).
+__device__ __forceinline__ bool moe_share_done(uint64_t *claim, uint64_t *done, uint32_t W)
+{
+    if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT) != W - 1) return false;
+    __hip_atomic_store(claim, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+    return true;
+}
+
 __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
 {
     __shared__ uint64_t mask[MOE_MAX_EXPERTS][2];   // per expert: which of this PE's tokens go there
-    __shared__ uint32_t begin[MOE_MAX_PES + 1];
+    __shared__ uint32_t begin[MOE_MAX_EXPERTS + 1]; // small batches: one expert's senders; large: first row of (expert, sender)
+    __shared__ uint32_t ebase[MOE_MAX_EXPERTS + 1]; // large batches: first row of every local expert
     __shared__ int16_t s_topk[MOE_MAX_TOKENS * MOE_MAX_TOPK];   // this PE's routing table (expert ids fit 16 bits)
+    __shared__ uint32_t rbase[MOE_MAX_EXPERTS + 1]; // large batches: first route of every expert in the PE's flattened list
+    __shared__ MoeRanges rq;                        // large batches: the ranges of routes / rows this workgroup takes
+    __shared__ uint32_t s_last;
     const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
     const uint32_t P = (uint32_t)c.npes, E = m.num_experts, T = m.max_tokens, K = m.topk;
     const uint32_t lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
@@ -141,6 +272,10 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
     const int32_t *topk = a.topk + (size_t)pe * T * K;
     const uint32_t hvecs = (uint32_t)(m.hidden / 16);
+    const uint32_t ctl0 = m.epp * P + E;                                     // first control word after the combine flags
+    // Large batches are bandwidth-bound and are balanced dynamically; small ones are latency-bound and keep the
+    // fixed split, which needs no claim before the first message.  Every workgroup of a PE decides alike.
+    const bool bulk = ntok >= MOE_BULK_TOKENS && nwaves > MOE_SEND_WAVES;
 
     // ---- routing masks (every workgroup builds its own copy: at most 128 x topk entries) ----
     // The whole table is read, not just the first ntok rows: its loads then do not wait for the load
@@ -159,89 +294,193 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     }
     __syncthreads();
 
-    // ---- send: the routes of this workgroup's experts, dealt round-robin to its waves ----
-    uint32_t routes = 0;
-    for (uint32_t e = wg; e < E; e += W) routes += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
-    const uint32_t sparts = moe_parts(nwaves, routes), sper = (hvecs + sparts - 1) / sparts;
-    uint32_t q = 0;                                                          // running piece number (same in every wave)
-    for (uint32_t e = wg; e < E; e += W) {
+    // one piece of one message: token number i of expert e (in ascending token order), vectors [part * per, ...)
+    auto send_piece = [&](uint32_t e, uint64_t m0, uint64_t m1, uint32_t i, uint32_t part, uint32_t per) {
         const uint32_t owner = e / m.epp, le = e % m.epp;
-        const uint64_t m0 = mask[e][0], m1 = mask[e][1];
-        const uint32_t n = (uint32_t)(__popcll(m0) + __popcll(m1));
-        for (uint32_t i = 0; i < n; ++i) {                                   // slot i = i-th token in ascending order
-            for (uint32_t part = 0; part < sparts; ++part, ++q) {
-                if (q % nwaves != wave) continue;
-                const uint32_t t = moe_nth_token(m0, m1, i);
-                uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
-                if (part == 0) {
-                    const uint64_t hit = ballot(lane < K && s_topk[t * K + min(lane, K - 1)] == (int32_t)e);
-                    const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
-                    if (lane == 0) {
-                        u32x4 meta = {t, pe, j, e};
-                        __builtin_nontemporal_store(meta, (u32x4 *)slot);
-                    }
-                }
-                const uint32_t lo = part * sper, cnt = moe_part_vecs(hvecs, lo, sper);
-                wave_copy16((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo,
-                            cnt, lane);
+        const uint32_t t = moe_nth_token(m0, m1, i);
+        uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
+        if (part == 0) {
+            const uint64_t hit = ballot(lane < K && s_topk[t * K + min(lane, K - 1)] == (int32_t)e);
+            const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
+            if (lane == 0) {
+                u32x4 meta = {t, pe, j, e};
+                __builtin_nontemporal_store(meta, (u32x4 *)slot);
             }
         }
+        const uint32_t lo = part * per, cnt = moe_part_vecs(hvecs, lo, per);
+        wave_copy16((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo, cnt, lane);
+    };
+
+    uint32_t routes = 0;
+    if (!bulk) {
+        // ---- send: the routes of this workgroup's experts (e = wg mod W), dealt round-robin to its waves ----
+        for (uint32_t e = wg; e < E; e += W) routes += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+        const uint32_t sparts = moe_parts(nwaves, routes), sper = (hvecs + sparts - 1) / sparts;
+        uint32_t q = 0;                                                      // running piece number (same in every wave)
+        for (uint32_t e = wg; e < E; e += W) {
+            const uint64_t m0 = mask[e][0], m1 = mask[e][1];
+            const uint32_t n = (uint32_t)(__popcll(m0) + __popcll(m1));
+            for (uint32_t i = 0; i < n; ++i)                                 // slot i = i-th token in ascending order
+                for (uint32_t part = 0; part < sparts; ++part, ++q)
+                    if (q % nwaves == wave) send_piece(e, m0, m1, i, part, sper);
+        }
+    } else {
+        // ---- send, large batch: the PE's routes, flattened in expert order (route r = token number r - rbase[e]
+        // of expert e), shared out by moe_share.
+        if (threadIdx.x < 64) {
+            const uint32_t per = (E + 63) / 64, e0 = min(lane * per, E), e1 = min(e0 + per, E);
+            uint32_t sum = 0;
+            for (uint32_t e = e0; e < e1; ++e) sum += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+            uint32_t incl = sum;
+            for (uint32_t d = 1; d < 64; d <<= 1) {                          // inclusive scan over the lanes
+                const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
+                if (lane >= d) incl += up;
+            }
+            uint32_t run = incl - sum;
+            for (uint32_t e = e0; e < e1; ++e) { rbase[e] = run; run += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1])); }
+            if (lane == 63) rbase[E] = incl;
+        }
+        __syncthreads();
+        // the announcements (count + 1 in the high half) can go at once: they say nothing about the data
+        if (threadIdx.x < 64)
+            for (uint32_t e = wg + lane * W; e < E; e += 64 * W)
+                __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(rbase[e + 1] - rbase[e] + 1) << 32,
+                                       __ATOMIC_RELAXED, SHMEMX_AGENT);
+        const uint32_t sper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
+        routes = rbase[E];
+        moe_share(c, rq, routes, W, wg, gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), wave, lane, [&](uint32_t r, uint32_t part) {
+            const uint32_t e = moe_expert_of_row(rbase, E, r);
+            send_piece(e, mask[e][0], mask[e][1], r - rbase[e], part, sper);
+        });
     }
     // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
     // complete and one release has made them visible, so a count is never seen before its data
     wg_release();
     if (threadIdx.x < 64) {
         if (routes) quiet();                                                 // nothing was written: nothing to release
-        for (uint32_t e = wg + lane * W; e < E; e += 64 * W) {
-            const uint32_t n = (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
-            __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)n + 1, __ATOMIC_RELAXED,
-                                   SHMEMX_AGENT);
+        if (!bulk) {
+            for (uint32_t e = wg + lane * W; e < E; e += 64 * W) {
+                const uint64_t n = (uint64_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+                __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (n + 1) << 32 | n, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            }
+        } else {
+            // what this workgroup sent, pair by pair (a range may span experts, an expert may be split among workgroups)
+            const uint32_t mine = rq.pub & 0x7fffffffu;
+            for (uint32_t k = lane; k < mine; k += 64) {
+                uint32_t lo = rq.rq[k][0];
+                const uint32_t hi = rq.rq[k][1];
+                for (uint32_t e = moe_expert_of_row(rbase, E, lo); lo < hi && e < E; ++e) {
+                    const uint32_t up = min(hi, rbase[e + 1]);
+                    if (up <= lo) continue;                                  // an expert without routes
+                    __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(up - lo), __ATOMIC_RELAXED,
+                                           SHMEMX_AGENT);
+                    lo = up;
+                }
+            }
+            if (lane == 0)
+                moe_share_done(gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), gin.signal_word(ctl0 + MOE_CTL_SEND_DONE, pe), W);
         }
     }
 
-    // ---- receive: this workgroup's local experts ----
-    for (uint32_t le = wg; le < m.epp; le += W) {
-        __syncthreads();                                                     // begin[] of the previous expert is done with
-        for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
-            const uint64_t v = moe_poll(gin, le * P + s, 1);
-            begin[s + 1] = v ? (uint32_t)min(v - 1, (uint64_t)T) : 0;        // 0 only after a time-out
-            gin.reset_signal(le * P + s);                                    // nobody else reads it; next dispatch starts clean
+    if (!bulk) {
+        // ---- receive: this workgroup's local experts ----
+        for (uint32_t le = wg; le < m.epp; le += W) {
+            __syncthreads();                                                 // begin[] of the previous expert is done with
+            for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+                begin[s + 1] = min(moe_poll_count(gin, le * P + s), T);
+                gin.reset_signal(le * P + s);                                // nobody else reads it; next dispatch starts clean
+            }
+            __syncthreads();
+            if (le == wg)            if (threadIdx.x < 64) acquire();                                 // what the signals released is now readable
+            wg_acquire();
+            if (threadIdx.x == 0) {
+                begin[0] = 0;
+                for (uint32_t s = 0; s < P; ++s) begin[s + 1] += begin[s];
+            }
+            __syncthreads();
+            const uint32_t total = begin[P];
+            const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
+            for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)begin[s];
+                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(begin[s + 1] - begin[s]);
+            }
+            if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
+            const uint32_t rparts = moe_parts(nwaves, total), rper = (hvecs + rparts - 1) / rparts;
+            for (uint32_t u = wave; u < total * rparts; u += nwaves) {
+                const uint32_t i = u / rparts, part = u % rparts;
+                uint32_t s = 0;
+                while (begin[s + 1] <= i) ++s;
+                const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[s])) * m.msg, pe);
+                // the metadata is requested before the token and stored after it, so the two reads travel together
+                const bool first = part == 0 && lane == 0;
+                u32x4 info = {0, 0, 0, 0};
+                if (first) info = *(const u32x4 *)slot;
+                const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
+                wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
+                if (first) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = info;
+            }
         }
+    } else {
+        // ---- receive, large batch: every workgroup of the PE reads ALL the PE's counts, and the rows of all local
+        // experts, flattened, are shared out by moe_share (36 experts on 32 workgroups would otherwise leave four
+        // workgroups with twice the work).  The signals are put
+        // back to zero by the workgroup of the PE that finishes last.
+        const uint32_t npairs = m.epp * P;
+        for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) begin[i] = min(moe_poll_count(gin, i, true), T);
         __syncthreads();
-        if (threadIdx.x < 64) acquire();                                     // what the signals released is now readable
+        if (threadIdx.x < 64) acquire();
         wg_acquire();
-        if (threadIdx.x == 0) {
-            begin[0] = 0;
-            for (uint32_t s = 0; s < P; ++s) begin[s + 1] += begin[s];
+        for (uint32_t le = threadIdx.x; le < m.epp; le += blockDim.x) {      // counts -> first rows within the expert
+            uint32_t run = 0;
+            for (uint32_t s = 0; s < P; ++s) {
+                const uint32_t n = begin[le * P + s];
+                begin[le * P + s] = run;
+                run += n;
+            }
+            ebase[le + 1] = run;
         }
         __syncthreads();
-        const uint32_t total = begin[P];
-        const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
-        for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
-            a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)begin[s];
-            a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(begin[s + 1] - begin[s]);
+        if (threadIdx.x == 0) {
+            ebase[0] = 0;
+            for (uint32_t le = 0; le < m.epp; ++le) ebase[le + 1] += ebase[le];
         }
-        if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
-        const uint32_t rparts = moe_parts(nwaves, total), rper = (hvecs + rparts - 1) / rparts;
-        for (uint32_t u = wave; u < total * rparts; u += nwaves) {
-            const uint32_t i = u / rparts, part = u % rparts;
+        __syncthreads();
+        for (uint32_t le = wg; le < m.epp; le += W) {                        // the bookkeeping of an expert: one workgroup
+            const uint32_t total = ebase[le + 1] - ebase[le];
+            for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+                const uint32_t b = begin[le * P + s], nx = s + 1 < P ? begin[le * P + s + 1] : total;
+                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)b;
+                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(nx - b);
+            }
+            if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
+        }
+        const uint32_t rper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
+        moe_share(c, rq, ebase[m.epp], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
+            const uint32_t le = moe_expert_of_row(ebase, m.epp, g), i = g - ebase[le];
             uint32_t s = 0;
-            while (begin[s + 1] <= i) ++s;
-            const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[s])) * m.msg, pe);
-            // the metadata is requested before the token and stored after it, so the two reads travel together
+            while (s + 1 < P && begin[le * P + s + 1] <= i) ++s;            // the last sender whose first row is <= i (empty senders share a first row)
+            const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[le * P + s])) * m.msg, pe);
+            const size_t row = ((size_t)pe * m.epp + le) * ((size_t)P * T) + i;
             const bool first = part == 0 && lane == 0;
             u32x4 info = {0, 0, 0, 0};
             if (first) info = *(const u32x4 *)slot;
             const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
-            wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
-            if (first) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = info;
-        }
+            wave_copy16((u32x4 *)(a.recv_x + row * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
+            if (first) *(u32x4 *)(a.recv_info + row * 4) = info;
+        });
+        if (threadIdx.x == 0)
+            s_last = moe_share_done(gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), gin.signal_word(ctl0 + MOE_CTL_RECV_DONE, pe), W);
+        __syncthreads();
+        if (s_last)                                                          // every workgroup of the PE has read the counts
+            for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) gin.reset_signal(i);
     }
 }
 
 __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, MoeCombineArgs a)
 {
     __shared__ uint32_t begin[MOE_MAX_PES + 1];
+    __shared__ uint32_t ebase[MOE_MAX_EXPERTS + 1]; // large batches: first row of every local expert
+    __shared__ MoeRanges rq;                        // large batches: the ranges of rows this workgroup returns
     __shared__ int32_t experts[MOE_MAX_TOPK];
     __shared__ uint64_t epoch;   // number of this combine on the object: the flags count combines and are never reset
     const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
@@ -254,40 +493,82 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
     // The count of completed combines lives on the device (a launch replayed from a graph carries no fresh
     // arguments): ctl[0] on every PE, written by the workgroup of the team that was the LAST to read it --
     // every workgroup reads ctl[0] first and only then adds itself to ctl[1] -- at its very end.
-    uint64_t *ctl = gin.signal_word(flag0 + m.num_experts, pe);
+    uint64_t *ctl = gin.signal_word(flag0 + m.num_experts + MOE_CTL_COMBINES, pe);
     uint64_t completed = 0, arrival = 0;
     if (threadIdx.x == 0) completed = __hip_atomic_load(ctl, __ATOMIC_RELAXED, SHMEMX_AGENT);   // used after the send phase
 
-    // ---- send: the outputs of this workgroup's local experts go back to the tokens' sources ----
-    for (uint32_t le = wg; le < m.epp; le += W) {
-        __syncthreads();
-        const size_t pair0 = ((size_t)pe * m.epp + le) * P;
-        if (threadIdx.x == 0) {
-            begin[0] = 0;
-            for (uint32_t s = 0; s < P; ++s) {
-                const int32_t n = a.recv_range[(pair0 + s) * 2 + 1];
-                begin[s + 1] = begin[s] + (uint32_t)min(max(n, 0), (int32_t)T);
+    // the row counts of the first expert are requested before the batch size is looked at (two dependent round
+    // trips to memory would otherwise open every small combine)
+    int32_t n_first = 0;
+    if (wg < m.epp && threadIdx.x < P) n_first = a.recv_range[((((size_t)pe * m.epp + wg) * P) + threadIdx.x) * 2 + 1];
+    const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
+    const uint32_t ctl0 = flag0 + m.num_experts;
+    const bool bulk = ntok >= MOE_BULK_TOKENS && nwaves > MOE_SEND_WAVES;    // as in the dispatch: large batches are balanced dynamically
+    // one piece of one row back to its token's source
+    auto return_piece = [&](size_t row, uint32_t part, uint32_t parts, uint32_t per) {
+        const u32x4 info = *(const u32x4 *)(a.recv_info + row * 4);          // token, source PE, position, expert
+        const uint32_t t = info.x, s = info.y, j = info.z;
+        if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row); return; }
+        const uint32_t lo = part * per, cnt = moe_part_vecs(hvecs, lo, per);
+        wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
+                    (const u32x4 *)(a.expert_out + row * m.hidden) + lo, cnt, lane);
+    };
+    if (!bulk) {
+        // ---- send: the outputs of this workgroup's local experts go back to the tokens' sources ----
+        for (uint32_t le = wg; le < m.epp; le += W) {
+            __syncthreads();
+            const size_t pair0 = ((size_t)pe * m.epp + le) * P;
+            if (threadIdx.x < P) {
+                const int32_t n = le == wg ? n_first : a.recv_range[(pair0 + threadIdx.x) * 2 + 1];
+                begin[threadIdx.x + 1] = (uint32_t)min(max(n, 0), (int32_t)T);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                begin[0] = 0;
+                for (uint32_t s = 0; s < P; ++s) begin[s + 1] += begin[s];
+            }
+            __syncthreads();
+            const uint32_t total = begin[P];
+            const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
+            const uint32_t cparts = moe_parts(nwaves, total), cper = (hvecs + cparts - 1) / cparts;
+            for (uint32_t u = wave; u < total * cparts; u += nwaves) return_piece(row0 + u / cparts, u % cparts, cparts, cper);
+            // flags: zero-byte put + SignalAdd to every destination, after one release for the whole expert
+            wg_release();
+            if (threadIdx.x < 64) {
+                quiet();
+                for (uint32_t s = lane; s < P; s += 64)
+                    __hip_atomic_fetch_add(gin.signal_word(flag0 + pe * m.epp + le, s), 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
             }
         }
-        __syncthreads();
-        const uint32_t total = begin[P];
-        const size_t row0 = ((size_t)pe * m.epp + le) * ((size_t)P * T);
-        const uint32_t cparts = moe_parts(nwaves, total), cper = (hvecs + cparts - 1) / cparts;
-        for (uint32_t u = wave; u < total * cparts; u += nwaves) {
-            const uint32_t i = u / cparts, part = u % cparts;
-            const u32x4 info = *(const u32x4 *)(a.recv_info + (row0 + i) * 4);   // token, source PE, position, expert
-            const uint32_t t = info.x, s = info.y, j = info.z;
-            if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row0 + i); continue; }
-            const uint32_t lo = part * cper, cnt = moe_part_vecs(hvecs, lo, cper);
-            wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
-                        (const u32x4 *)(a.expert_out + (row0 + i) * m.hidden) + lo, cnt, lane);
+    } else {
+        // ---- send, large batch: the rows of all local experts, flattened, are shared out by moe_share.  An
+        // expert's rows then leave from several workgroups, so its flags can only go once all of them have
+        // released: every workgroup counts itself done on a word of the PE after its release, and the last one
+        // raises the flags of all the PE's experts (the workgroups finish together: that is what the sharing is for).
+        for (uint32_t le = threadIdx.x; le < m.epp; le += blockDim.x) {
+            uint32_t run = 0;
+            for (uint32_t s = 0; s < P; ++s) run += (uint32_t)min(max(a.recv_range[((((size_t)pe * m.epp + le) * P) + s) * 2 + 1], 0), (int32_t)T);
+            ebase[le + 1] = run;
         }
-        // flags: zero-byte put + SignalAdd to every destination, after one release for the whole expert
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            ebase[0] = 0;
+            for (uint32_t le = 0; le < m.epp; ++le) ebase[le + 1] += ebase[le];
+        }
+        __syncthreads();
+        const uint32_t cper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
+        moe_share(c, rq, ebase[m.epp], W, wg, gin.signal_word(ctl0 + MOE_CTL_COMB_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
+            const uint32_t le = moe_expert_of_row(ebase, m.epp, g);
+            return_piece(((size_t)pe * m.epp + le) * ((size_t)P * T) + (g - ebase[le]), part, MOE_PARTS, cper);
+        });
         wg_release();
         if (threadIdx.x < 64) {
             quiet();
-            for (uint32_t s = lane; s < P; s += 64)
-                __hip_atomic_fetch_add(gin.signal_word(flag0 + pe * m.epp + le, s), 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            uint32_t last = 0;
+            if (lane == 0) last = moe_share_done(gin.signal_word(ctl0 + MOE_CTL_COMB_CLAIM, pe), gin.signal_word(ctl0 + MOE_CTL_COMB_DONE, pe), W);
+            if (__builtin_amdgcn_readfirstlane((int)last))
+                for (uint32_t i = lane; i < m.epp * P; i += 64)
+                    __hip_atomic_fetch_add(gin.signal_word(flag0 + pe * m.epp + i / P, i % P), 1ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
         }
     }
 
@@ -299,7 +580,6 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
     }
 
     // ---- receive: this workgroup's tokens ----
-    const uint32_t ntok = min((uint32_t)max(a.ntok[pe], 0), T);
     for (uint32_t t = wg; t < ntok; t += W) {
         __syncthreads();                                                     // also publishes `epoch`
         if (threadIdx.x < K) {

@@ -1167,7 +1167,7 @@ int shmem_moe_create(int num_experts, int max_tokens, int topk, size_t hidden_by
     st.num_experts = (uint32_t)num_experts; st.epp = (uint32_t)(num_experts / H.npes);
     st.max_tokens = (uint32_t)max_tokens; st.topk = (uint32_t)topk;
     st.hidden = hidden_bytes; st.msg = hidden_bytes + shmemx::MOE_META_BYTES;
-    const uint32_t nsig = st.epp * (uint32_t)H.npes + st.num_experts + 2;   // dispatch counts, combine flags, the combine counter and its arrivals
+    const uint32_t nsig = st.epp * (uint32_t)H.npes + st.num_experts + shmemx::MOE_CTL_WORDS;   // dispatch counts, combine flags, the PE's control words
     unsigned __int128 recv_bytes = (unsigned __int128)st.epp * (unsigned)H.npes * (unsigned)max_tokens * st.msg;
     unsigned __int128 comb_bytes = (unsigned __int128)max_tokens * (unsigned)topk * st.hidden;
     if (recv_bytes > H.seg || comb_bytes > H.seg) { delete m; return SHMEM_ERR_NOMEM; }

@@ -33,7 +33,7 @@ def oracle_run(P, E, T, K, Hb, x, topk, ntok, rounds=1, mutate=None):
 def heap_bytes_for(P, E, T, K, Hb):
     epp = E // P
     up = lambda v: (v + 255) // 256 * 256
-    return up(epp * P * T * (Hb + 16)) + up(T * K * Hb) + up(8 * (epp * P + E)) + 4096
+    return up(epp * P * T * (Hb + 16)) + up(T * K * Hb) + up(8 * (2 * E + 8)) + 4096
 
 
 class DevMoe:
@@ -99,6 +99,11 @@ CASES = [
     (1, 4, 9, 2, 16, None, "uniform", 0.0, 2),                 # a single PE talks to itself; smallest token
     (4, 64, 128, 64, 32, [128, 1, 77, 128], "uniform", 0.3, 5),  # widest top-k, every expert, ragged batches
     (2, 1024, 16, 8, 64, None, "zipf", 0.0, 7),                # the largest expert count
+    # batches of 32 tokens and more per PE are shared out dynamically (fixed ranges + claimed blocks):
+    (4, 8, 64, 2, 48, [64, 31, 32, 0], "uniform", 0.0, 1),      # both kinds of PE in one exchange, one workgroup per PE
+    (2, 6, 40, 3, 80, None, "zipf", 1.0, 3),                   # every entry dropped: large batches with nothing to send
+    (8, 16, 32, 1, 16, None, "uniform", 0.0, 64),              # more workgroups than messages: nothing fixed, every block claimed
+    (3, 12, 100, 4, 14352, None, "zipf", 0.1, 11),             # long messages of an odd length, odd team size
 ]
 
 
