@@ -41,7 +41,9 @@ enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, 
                   // running degree sums, per PE and on a line of their own (adds on one address serialise at
                   // about 12 ns each: one word for the whole device cost 50 us per launch of 4096 waves)
                   T_DEG_EXPANDED = 16 /* frontiers expanded top-down */, T_DEG_FOUND = 17 /* frontiers discovered */,
-                  T_FILL = 18 /* write position of k_bfs_fill_queue */ };
+                  T_FILL = 18 /* write position of k_bfs_fill_queue */,
+                  // work handed out to the waves of the two top-down kernels of a level (reset with the level)
+                  T_CLAIM_EXPAND = 24 /* batches of frontier vertices */, T_CLAIM_BIG = 25 /* runs of long-row segments */ };
 
 constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
 constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
@@ -100,6 +102,7 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
         uint64_t *t = bfs_tails(c, s, pe);
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0; t[T_FILL] = 0;
+        t[T_CLAIM_EXPAND] = 0; t[T_CLAIM_BIG] = 0;
         if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
         if (pe == 0) c.scratch[W_WORK + 4] = 0;   // arrival count of the level-end kernel
     }
@@ -280,6 +283,14 @@ struct BfsLds {
     uint64_t r0[4][64];
 };
 
+// How the top-down kernels of a level share their work inside a PE: it is CLAIMED, not dealt.  A wave takes its
+// first batch (run) by its number and every further one from a counter of the PE when it has finished the one
+// before (nothing is held in reserve: what a wave holds nobody else can take over at the end), so that the slow
+// waves of a PE take less and its fast ones more.  Per-wave timestamps showed why: the chip places the workgroups
+// of a launch in order, four to a compute unit, and the waves run at very different speeds (with equal shares
+// the waves of a heavy level finished between 0.15 and 1.63 ms).  The PE of a workgroup stays b / wgs_per_pe:
+// dealing the workgroups of every vintage and die to every PE evened the PEs out but made every level slower.
+//
 // Expand level L: short rows packed, long rows set aside.
 template <bool STAGED>
 __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t L)
@@ -300,8 +311,20 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
     const uint32_t *queue = (const uint32_t *)ptr(c, s.queue_off[L & 1], pe);
     uint32_t *big = (uint32_t *)ptr(c, s.big_off, pe);
     uint64_t degsum = 0;
-    for (uint64_t base = my_wave * 64; base < cnt; base += team_waves * 64) {
-        const bool valid = base + lane < cnt;
+    // a batch is 64 frontier vertices, or 16 while the frontier is short (a short frontier is the hubs: 64 of
+    // them are a millisecond of edges, and a PE's waves would have one batch each, or two)
+    const uint32_t bs = cnt >= team_waves * 64 * 4 ? 64u : 16u;
+    const uint64_t nbatch = (cnt + bs - 1) / bs;
+    uint64_t batch = my_wave;                        // the first one by number, the others claimed (a round trip of a
+    for (bool first = true;; first = false) {        // microsecond or two per batch of a hundred)
+        if (!first) {
+            uint64_t got = 0;
+            if (lane == 0) got = atomic_fetch_add(tails + T_CLAIM_EXPAND, 1);
+            batch = team_waves + bcast64(got, 0);
+        }
+        if (batch >= nbatch) break;
+        const uint64_t base = batch * bs;
+        const bool valid = lane < bs && base + lane < cnt;
         uint32_t u = 0, deg = 0;
         uint64_t r0 = 0;
         if (valid) {
@@ -417,33 +440,59 @@ __global__ __launch_bounds__(1024) void k_bfs_bigscan(Ctx c, BfsState s)
     if (threadIdx.x == 0) { scan[nbig] = carry_s; tails[T_NTASKS] = carry_s; }
 }
 
-// Long rows of level L: every wave of the owner's team takes an equal run of
-// consecutive 256-edge segments.
+// Long rows of level L, as 256-edge segments numbered through all the PE's long rows: a wave takes runs of
+// up to BIG_RUN consecutive segments, the first by its number, the others claimed from a counter of the PE (see above
+// k_bfs_expand).  Finding the row a run starts in is a search in the segment scan; its upper levels are a
+// sample of the scan that every workgroup keeps in LDS, so a search costs two or three dependent reads of
+// global memory instead of a dozen.
+constexpr uint32_t BIG_RUN = 16;
+constexpr uint32_t BIG_SAMPLES = 128;     // (with 512 the workgroup no longer fitted a compute unit four times)
 template <bool STAGED>
 __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
 {
     __shared__ BfsLds lds;
+    __shared__ uint32_t sample[BIG_SAMPLES];
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t team_waves = (uint64_t)s.wgs_per_pe * wpw, my_wave = (uint64_t)wg * wpw + wave;
-    const uint64_t *tails = bfs_tails(c, s, pe);
+    uint64_t *tails = bfs_tails(c, s, pe);
     const uint32_t nbig = (uint32_t)tails[T_NBIG], ntasks = (uint32_t)tails[T_NTASKS];
-    if (ntasks == 0) return;
+    if (ntasks == 0) return;                         // the whole workgroup
     const uint32_t xcd = xcd_id();
     const Stage st{lds.cnt[wave], lds.buf[wave]};
     if (STAGED && lane < STAGE_PES) st.cnt[lane] = 0;
-    __builtin_amdgcn_wave_barrier();
     const uint32_t *big = (const uint32_t *)ptr(c, s.big_off, pe);
     const uint32_t *scan = (const uint32_t *)ptr(c, s.bigscan_off, pe);
-    const uint32_t per = (uint32_t)((ntasks + team_waves - 1) / team_waves);
-    const uint64_t t0 = my_wave * per;
-    const uint32_t t1 = (uint32_t)(t0 + per < ntasks ? t0 + per : ntasks);
-    if (t0 < ntasks) {
-        uint32_t i = 0;                              // long row that holds segment t0
-        for (uint32_t hi = nbig; hi - i > 1;) {
-            const uint32_t mid = i + (hi - i) / 2;
-            if (scan[mid] <= (uint32_t)t0) i = mid; else hi = mid;
+    // sample[j] = scan[j * stride]: first segment of every stride-th long row
+    const uint32_t stride = (nbig + BIG_SAMPLES - 1) / BIG_SAMPLES, nsamples = (nbig + stride - 1) / stride;
+    for (uint32_t j = threadIdx.x; j < nsamples; j += blockDim.x) sample[j] = scan[j * stride];
+    __syncthreads();
+    // runs of BIG_RUN segments; a level with few segments (a handful of hubs) is one equal run per wave, as claims
+    // and searches would cost more than they even out
+    const uint32_t R = ntasks >= team_waves * 4 * BIG_RUN ? BIG_RUN : (uint32_t)((ntasks + team_waves - 1) / team_waves);
+    const uint64_t nruns = ((uint64_t)ntasks + R - 1) / R;
+    uint64_t run = my_wave;
+    for (bool first_run = true;; first_run = false) {
+        if (!first_run) {
+            uint64_t got = 0;
+            if (lane == 0) got = atomic_fetch_add(tails + T_CLAIM_BIG, 1);
+            run = team_waves + bcast64(got, 0);
+        }
+        if (run >= nruns) break;
+        const uint32_t t0 = (uint32_t)(run * R), t1 = min(t0 + R, ntasks);
+        uint32_t i;                                  // long row that holds segment t0: the last with scan[i] <= t0
+        {
+            uint32_t lo = 0, hi = nsamples;          // sample[lo] <= t0 < sample[hi] (sample[nsamples] = infinity)
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (sample[mid] <= t0) lo = mid; else hi = mid;
+            }
+            i = lo * stride;
+            for (uint32_t up = min(i + stride, nbig); up - i > 1;) {
+                const uint32_t mid = i + (up - i) / 2;
+                if (scan[mid] <= t0) i = mid; else up = mid;
+            }
         }
         uint32_t first = scan[i], next = scan[i + 1], u = big[i];
         uint64_t r0 = s.row_off[u], deg = s.row_off[u + 1] - r0;
@@ -464,10 +513,10 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
         };
         bool act[EPL], nact[EPL];
         uint32_t vv[EPL], uu[EPL], nvv[EPL], nuu[EPL];
-        fetch((uint32_t)t0, act, vv, uu);
+        fetch(t0, act, vv, uu);
 #pragma unroll
         for (uint32_t k = 0; k < EPL; ++k) asm volatile("" : : "v"(vv[k]));   // arrived before the loop is entered
-        for (uint32_t t = (uint32_t)t0; t < t1; ++t) {
+        for (uint32_t t = t0; t < t1; ++t) {
             Probe pr;
             bfs_probe_issue(c, s, xcd, pr, vv);
             const bool more = t + 1 < t1;
@@ -746,7 +795,7 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
         expanded += __hip_atomic_load(&t[T_DEG_EXPANDED], __ATOMIC_RELAXED, SHMEMX_AGENT);
         found += __hip_atomic_load(&t[T_DEG_FOUND], __ATOMIC_RELAXED, SHMEMX_AGENT);
         t[T_TAIL0 + (next + 1) % 3] = 0;
-        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_FILL] = 0;
+        t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_FILL] = 0; t[T_CLAIM_EXPAND] = 0; t[T_CLAIM_BIG] = 0;
     }
     for (int off = 32; off > 0; off >>= 1) {
         total += __shfl_down(total, off, 64);
