@@ -80,7 +80,16 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
     const uint32_t ox = threadIdx.x % LANES_OUT, oy = threadIdx.x / LANES_OUT;
     const uint64_t tiles_i = (a.rows + TR_TILE - 1) / TR_TILE, tiles_j = (a.n + TJ - 1) / TJ;
     T *out = (T *)ptr(c, a.out_off, pe);
-    for (uint64_t t = wg; t < tiles_i * tiles_j; t += a.wgs_per_pe) {
+    // Tiles are CLAIMED from a counter of the PE, not dealt (the workgroups of a launch run at unequal speeds, and
+    // with equal shares the launch lasts as long as the slowest needs): the first tile of a workgroup is its
+    // number, the claim for the next is made when a tile is started and read when it is finished.  The last
+    // workgroup of the launch to finish puts the counters back to zero.
+    __shared__ uint64_t next_tile;
+    uint64_t *const claim = &c.scratch[W_PE_BASE + (uint64_t)pe * W_PE_WORDS + 9];
+    const uint64_t ntiles = tiles_i * tiles_j;
+    uint64_t got = 0;
+    for (uint64_t t = wg; t < ntiles;) {
+        if (threadIdx.x == 0) got = atomic_fetch_add_deferred(claim, 1);
         const uint64_t i0 = (t / tiles_j) * TR_TILE, j0 = (t % tiles_j) * TJ;
         vec v[STEPS_IN];
 #pragma unroll
@@ -109,7 +118,18 @@ __global__ __launch_bounds__(256) void k_transpose_vec(Ctx c, TransposeArgs a)
                 __builtin_nontemporal_store(o, (vec *)(out + i * a.n + j));
             }
         }
+        if (threadIdx.x == 0) next_tile = (uint64_t)a.wgs_per_pe + got;
         __syncthreads();
+        t = next_tile;
+    }
+    if (threadIdx.x == 0) {
+        // (a workgroup that never entered the loop has made no claim; every other one has read its last)
+        uint64_t *const done = &c.scratch[W_WORK + 9];
+        if (atomic_fetch_add(done, 1) == (uint64_t)gridDim.x - 1) {
+            for (uint32_t p = 0; p < (uint32_t)c.npes; ++p)
+                __hip_atomic_store(&c.scratch[W_PE_BASE + (uint64_t)p * W_PE_WORDS + 9], 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+            __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, SHMEMX_AGENT);
+        }
     }
 }
 
