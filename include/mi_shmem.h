@@ -222,16 +222,19 @@ int shmem_op_batch_noalloc(int npes, size_t heap_bytes_per_pe, void *dev_heap, c
  * PUT/GET move `count` bytes; IPUT/IGET move `count` elements of elem_bytes
  * with the given strides (local_stride applies to the local side).  The ops of
  * a cell are independent and unordered; completion is the kernel boundary.
- * Bandwidth cells -- PUT/GET of whole multiples of 4 KiB with 16-byte aligned
+ * Bandwidth cells -- PUT/GET of 1 KiB and more with 16-byte aligned sizes and
  * placement, asked for with at least one workgroup per compute unit -- run on
  * one larger workgroup per compute unit (compute units / npes per PE) that
- * streams through LDS at a paced rate; where a PE's operations make at least
- * 32 tasks of 4 KiB per workgroup (and a whole number of blocks of four) the
- * workgroups claim their tasks block by block from a per-PE counter in the
- * scratch words instead of walking fixed shares (the counters are zero between
- * launches; MI_SHMEM_STREAM_DYNAMIC=0 in the environment of shmem_init
- * switches that off).  shmem_copy_sweep_geometry tells which launch a cell
- * gets.  Errors as for the single ops, checked for the last slot too. */
+ * streams through LDS at a paced rate.  Where a PE's operations make enough
+ * work (whole multiples of 4 KiB: at least 32 tasks of 4 KiB per workgroup in
+ * whole blocks of four; other sizes: messages that fill at least nine tenths
+ * of their 1 KiB rows, at least 128 rows per workgroup) the workgroups claim
+ * it block by block from a per-PE counter in the scratch words (the counters
+ * are zero between launches; MI_SHMEM_STREAM_DYNAMIC=0 in the environment of
+ * shmem_init switches that off); else whole multiples of 4 KiB walk fixed
+ * shares, and everything else takes the register path.
+ * shmem_copy_sweep_geometry tells which launch a cell gets.  Errors as for the
+ * single ops, checked for the last slot too. */
 int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, size_t elem_bytes,
                      ptrdiff_t remote_stride, ptrdiff_t local_stride, size_t remote_slot_bytes,
                      size_t local_slot_bytes, size_t nslots, int ops_per_pe, int wgs_per_pe);

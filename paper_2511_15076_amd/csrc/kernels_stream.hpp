@@ -189,6 +189,61 @@ struct BlockWalker {
     }
 };
 
+// For messages that are not whole multiples of 4 KiB the dynamic copy works on ROWS of 1 KiB (one wave
+// instruction; the last row of a message may be short), so that messages of any length pack into full tasks: the
+// team's list is the rows of all its operations in order, a task is four consecutive rows (one per reader wave,
+// two per writer wave), a block ST_BLOCK tasks.  Whole multiples of 4 KiB keep the task walk above: the row walk
+// costs them a few per cent (it sits closer to the edge of the congested regime at the same pace).
+struct StreamRows {
+    const uint8_t *src;
+    uint8_t *dst;
+    uint64_t spitch, dpitch;    // slot pitches in bytes
+    uint32_t rpo;               // rows per operation, the last of which may be short:
+    uint32_t tail;              // its bytes (a multiple of 16, at most 1024)
+    uint32_t step_r, step_s;    // four rows on: 4 % rpo rows and 4 / rpo operations (kept so that a step needs no loop)
+    uint32_t nslots;
+    uint32_t nrows;             // rpo * operations, below 2^31; the last block may be short
+    uint32_t team, rank;
+    uint32_t rot;               // the team starts rot rows into its list (below nrows)
+    uint32_t period;            // pacing per task, as in StreamPlan
+};
+
+// Every fourth row of a block, from row `w` of its first task on: (row in its operation, slot) advanced by four
+// rows.  Position u of the list (block * 16 + ...) is row (u + rot) mod nrows; a position from nrows on, in the
+// last block, stands for position 0 once more: that row is then moved a second time, the same bytes to the same
+// place, and every wave keeps exactly one load or two stores per step.
+struct RowWalker {
+    uint32_t r, slot, rho, u, left, j;
+    __device__ __forceinline__ void seek(const StreamRows &p, uint32_t at)
+    {
+        rho = ST_UNIFORM(at);
+        const uint32_t op = rho / p.rpo;
+        r = ST_UNIFORM(rho - op * p.rpo);
+        slot = ST_UNIFORM(op % p.nslots);
+    }
+    __device__ __forceinline__ void start(const StreamRows &p, uint32_t block, uint32_t w)
+    {
+        u = ST_UNIFORM(block * (4 * ST_BLOCK) + w);
+        uint32_t at = (u < p.nrows ? u : 0) + p.rot;          // below 2^32: nrows < 2^31
+        if (at >= p.nrows) at -= p.nrows;
+        seek(p, at);
+        left = ST_BLOCK;
+    }
+    __device__ __forceinline__ void next(const StreamRows &p)
+    {
+        --left; u += 4; rho += 4;
+        if (__builtin_expect(u >= p.nrows, 0)) { seek(p, p.rot); return; }               // beyond the list
+        if (__builtin_expect(rho >= p.nrows, 0)) { seek(p, rho - p.nrows); return; }     // the rotation wraps once
+        r += p.step_r; slot += p.step_s;
+        if (r >= p.rpo) { r -= p.rpo; ++slot; }
+        if (slot >= p.nslots) { slot -= p.nslots; if (slot >= p.nslots) slot %= p.nslots; }   // (fewer than five slots)
+    }
+};
+
+template <class Plan> struct StreamWalk;
+template <> struct StreamWalk<StreamPlan> { typedef BlockWalker type; };
+template <> struct StreamWalk<StreamRows> { typedef RowWalker type; };
+
 typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
 typedef __attribute__((address_space(1))) uint64_t glb_u64_t;
 
@@ -204,15 +259,19 @@ __device__ __forceinline__ void lds_read_pair(uint32_t addr_a, uint32_t addr_b, 
 // `claim`: the team's counter, `done`: one word for the whole launch; both zero at launch and zero again at
 // its end (`claim0`, `nteams`, `claim_stride`: all the launch's counters, for the workgroup that finishes last).
 // `ring`: ST_RING * ST_CHUNK bytes of LDS, `q`: ST_QUEUE block numbers and one word for the end, in LDS.
-__device__ __forceinline__ void stream_copy_dyn(const StreamPlan &p, uint64_t *claim, uint64_t *done, uint64_t *claim0,
+// Plan = StreamPlan: whole 4 KiB tasks (ntasks a multiple of ST_BLOCK); Plan = StreamRows: rows, as above.
+template <class Plan>
+__device__ __forceinline__ void stream_copy_dyn(const Plan &p, uint64_t *claim, uint64_t *done, uint64_t *claim0,
                                                 uint32_t nteams, uint32_t claim_stride, uint8_t *ring, uint32_t *q_generic)
 {
     constexpr uint32_t S = ST_RING, B = ST_BLOCK, Q = ST_QUEUE;
+    constexpr bool ROWS = __is_same(Plan, StreamRows);
     static_assert(ST_STATIC * B >= S && (Q & (Q - 1)) == 0 && Q >= ST_STATIC + S / B + 4, "queue and static prefix cover the read-ahead");
     volatile lds_u32_t *const q = (volatile lds_u32_t *)q_generic;
     const uint32_t lane16 = (threadIdx.x & 63) * 16;
     const uint32_t wave = ST_UNIFORM(threadIdx.x >> 6);
-    const uint32_t nblocks = p.ntasks / B;                            // host: ntasks % B == 0, nblocks >= 2 * ST_STATIC * team
+    uint32_t nblocks;                                                 // host: nblocks >= 2 * ST_STATIC * team
+    if constexpr (ROWS) nblocks = (p.nrows + 4 * B - 1) / (4 * B); else nblocks = p.ntasks / B;   // (tasks: whole blocks)
     if (threadIdx.x < ST_STATIC) q[threadIdx.x] = p.rank + threadIdx.x * p.team;
     if (threadIdx.x == 0) q[Q] = 0xffffffffu;
     __syncthreads();
@@ -220,7 +279,7 @@ __device__ __forceinline__ void stream_copy_dyn(const StreamPlan &p, uint64_t *c
     if (wave < ST_READERS) {
         const uint32_t row_off = wave * 1024;
         const uint32_t qaddr = (uint32_t)(uintptr_t)q;
-        BlockWalker w;
+        typename StreamWalk<Plan>::type w;
         w.left = 0; w.j = 0;
         uint32_t issued = 0;
         auto issue = [&]() {
@@ -229,10 +288,18 @@ __device__ __forceinline__ void stream_copy_dyn(const StreamPlan &p, uint64_t *c
                 lds_read_pair(qaddr + 4 * (w.j & (Q - 1)), qaddr + 4 * Q, blk, te);
                 T = ST_UNIFORM(te);
                 if (issued >= T) return;                              // the workgroup's last block has been issued
-                w.start(p, ST_UNIFORM(blk));
+                if constexpr (ROWS) w.start(p, ST_UNIFORM(blk), wave); else w.start(p, ST_UNIFORM(blk));
                 ++w.j;
             }
-            const uint8_t *g = p.src + (uint64_t)w.slot * p.spitch + (uint64_t)w.ch * ST_CHUNK + row_off + lane16;
+            const uint8_t *g;
+            if constexpr (ROWS) {
+                // (the lanes beyond a short last row fetch its last vector once more: nothing is predicated, and the
+                // writers, which do the same, put the same bytes in the same place)
+                const uint32_t at = min(lane16, (w.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                g = p.src + (uint64_t)w.slot * p.spitch + (uint64_t)w.r * 1024 + at;
+            } else {
+                g = p.src + (uint64_t)w.slot * p.spitch + (uint64_t)w.ch * ST_CHUNK + row_off + lane16;
+            }
             uint8_t *l = ring + (issued & (S - 1)) * ST_CHUNK + row_off;
             __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 2 /* nt */);
             w.next(p);
@@ -250,25 +317,50 @@ __device__ __forceinline__ void stream_copy_dyn(const StreamPlan &p, uint64_t *c
     } else if (wave < ST_READERS + ST_WRITERS) {
         constexpr uint32_t PER = ST_READERS / ST_WRITERS;
         const uint32_t wr = wave - ST_READERS;
-        BlockWalker w;
-        w.left = 0; w.j = 0;
-        for (uint32_t t = 0; t < T; ++t) {
-            if (w.left == 0) {
-                T = ST_UNIFORM(q[Q]);                                 // published at least ST_RING steps before it matters
-                w.start(p, ST_UNIFORM(q[w.j & (Q - 1)]));
-                ++w.j;
+        if constexpr (ROWS) {
+            static_assert(PER == 2, "a writer wave walks two rows of every task");
+            RowWalker wa, wb;                                         // rows wr and wr + ST_WRITERS of every task
+            wa.left = 0; wa.j = 0;
+            for (uint32_t t = 0; t < T; ++t) {
+                if (wa.left == 0) {
+                    T = ST_UNIFORM(q[Q]);                             // published at least ST_RING steps before it matters
+                    const uint32_t blk = ST_UNIFORM(q[wa.j & (Q - 1)]);
+                    wa.start(p, blk, wr);
+                    wb.start(p, blk, wr + ST_WRITERS);
+                    ++wa.j;
+                }
+                uint8_t *da = p.dst + (uint64_t)wa.slot * p.dpitch + (uint64_t)wa.r * 1024 + min(lane16, (wa.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                uint8_t *db = p.dst + (uint64_t)wb.slot * p.dpitch + (uint64_t)wb.r * 1024 + min(lane16, (wb.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                wa.next(p); wb.next(p);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                const uint8_t *l = ring + (t & (S - 1)) * ST_CHUNK + lane16;
+                const u32x4 va = *(const u32x4 *)(l + wr * 1024), vb = *(const u32x4 *)(l + (wr + ST_WRITERS) * 1024);
+                __builtin_nontemporal_store(va, (u32x4 *)da);
+                __builtin_nontemporal_store(vb, (u32x4 *)db);
             }
-            uint8_t *d = p.dst + (uint64_t)w.slot * p.dpitch + (uint64_t)w.ch * ST_CHUNK + lane16;
-            w.next(p);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            const uint8_t *l = ring + (t & (S - 1)) * ST_CHUNK + lane16;
-            u32x4 v[PER];
+        } else {
+            BlockWalker w;
+            w.left = 0; w.j = 0;
+            for (uint32_t t = 0; t < T; ++t) {
+                if (w.left == 0) {
+                    T = ST_UNIFORM(q[Q]);                             // published at least ST_RING steps before it matters
+                    w.start(p, ST_UNIFORM(q[w.j & (Q - 1)]));
+                    ++w.j;
+                }
+                uint8_t *d = p.dst + (uint64_t)w.slot * p.dpitch + (uint64_t)w.ch * ST_CHUNK + lane16;
+                w.next(p);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                const uint8_t *l = ring + (t & (S - 1)) * ST_CHUNK + lane16;
+                u32x4 v[PER];
 #pragma unroll
-            for (uint32_t j = 0; j < PER; ++j) v[j] = *(const u32x4 *)(l + (wr + j * ST_WRITERS) * 1024);
+                for (uint32_t j = 0; j < PER; ++j) v[j] = *(const u32x4 *)(l + (wr + j * ST_WRITERS) * 1024);
 #pragma unroll
-            for (uint32_t j = 0; j < PER; ++j) __builtin_nontemporal_store(v[j], (u32x4 *)(d + (wr + j * ST_WRITERS) * 1024));
+                for (uint32_t j = 0; j < PER; ++j) __builtin_nontemporal_store(v[j], (u32x4 *)(d + (wr + j * ST_WRITERS) * 1024));
+            }
         }
     } else {
         // The scheduler wave: claims blocks two ahead of their use, publishes them, and paces the barrier.
@@ -386,6 +478,33 @@ __global__ __launch_bounds__(ST_DYN_THREADS) void k_copy_sweep_stream_dyn(Ctx c,
     p.ntasks = p.cpo * a.ops_per_pe;
     p.team = a.team; p.rank = blockIdx.x % a.team;
     p.rot = (uint32_t)(((uint64_t)ST_ROT * pe) % p.ntasks);
+    p.period = a.period;
+    uint64_t *const claim0 = &c.scratch[W_PE_BASE + 8];
+    stream_copy_dyn(p, claim0 + (uint64_t)pe * W_PE_WORDS, &c.scratch[W_WORK + 8], claim0, (uint32_t)c.npes, W_PE_WORDS, ring, q);
+}
+
+// Dynamic claiming for messages of 1 KiB rows of which the last may be short (any 16-byte multiple from 1 KiB
+// up): at least 2 * ST_STATIC blocks of rows per workgroup, fewer than 2^31 rows.  Same counters.
+__global__ __launch_bounds__(ST_DYN_THREADS) void k_copy_sweep_stream_rows(Ctx c, StreamSweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t ring[ST_RING * ST_CHUNK];
+    __shared__ uint32_t q[ST_QUEUE + 1];
+    const uint32_t pe = blockIdx.x / a.team, peer = (pe + 1) % (uint32_t)c.npes;
+    uint8_t *const lbase = ptr(c, a.local_off, pe);
+    uint8_t *const rbase = ptr(c, a.remote_off, peer);
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    StreamRows p;
+    p.src = is_put ? lbase : rbase;
+    p.dst = is_put ? rbase : lbase;
+    p.spitch = is_put ? a.local_slot : a.remote_slot;
+    p.dpitch = is_put ? a.remote_slot : a.local_slot;
+    p.rpo = (uint32_t)((a.count + 1023) / 1024);
+    p.tail = (uint32_t)(a.count - (uint64_t)(p.rpo - 1) * 1024);
+    p.step_r = 4 % p.rpo; p.step_s = 4 / p.rpo;
+    p.nslots = a.nslots;
+    p.nrows = p.rpo * a.ops_per_pe;
+    p.team = a.team; p.rank = blockIdx.x % a.team;
+    p.rot = (uint32_t)(((uint64_t)ST_ROT * 4 * pe) % p.nrows);
     p.period = a.period;
     uint64_t *const claim0 = &c.scratch[W_PE_BASE + 8];
     stream_copy_dyn(p, claim0 + (uint64_t)pe * W_PE_WORDS, &c.scratch[W_WORK + 8], claim0, (uint32_t)c.npes, W_PE_WORDS, ring, q);

@@ -266,25 +266,31 @@ int noalloc_setup(NoallocDevice **out)
 // least one workgroup per compute unit and enough tasks to fill the rings -- go through the streaming copy: one
 // wave-specialised workgroup per compute unit, team = compute units / PEs.  Returns that team size, or 0 for
 // the cells that stay on the register-pipelined kernel.
-uint32_t sweep_stream_team(bool is_strided, uint64_t count, uint64_t remote_slot, uint64_t local_slot, uint64_t roff,
-                           uint64_t loff, uint64_t nslots, int ops_per_pe, int wgs_per_pe)
+// How a sweep cell is launched.  1: streaming copy with dynamic claiming of 4 KiB tasks (whole multiples of 4 KiB,
+// whole blocks of tasks, enough blocks that the fixed first blocks of every workgroup are a small part);
+// 3: streaming copy with dynamic claiming of 1 KiB rows (any 16-byte multiple from 1 KiB up whose last row wastes
+// less than a tenth of the message's turns); 2: streaming copy with fixed shares (whole 4 KiB tasks, at least a
+// ring's worth per workgroup); 0: the register-pipelined kernel.  All streaming launches need 16-byte aligned
+// placement and at least one workgroup per compute unit asked for.  *team_out: workgroups per PE of the streaming
+// launch (compute units / PEs).
+int sweep_stream_kind(bool is_strided, uint64_t count, uint64_t remote_slot, uint64_t local_slot, uint64_t roff,
+                      uint64_t loff, uint64_t nslots, int ops_per_pe, int wgs_per_pe, uint32_t *team_out)
 {
-    if (is_strided || count == 0 || count % shmemx::ST_CHUNK) return 0;
+    if (is_strided || count == 0) return 0;
     if ((count | remote_slot | local_slot | roff | loff) & 15) return 0;
     const uint32_t team = (uint32_t)(H.num_cus / H.npes);
+    if (team < 1 || (uint64_t)H.npes * (uint64_t)wgs_per_pe < (uint64_t)H.num_cus || nslots > UINT32_MAX) return 0;
+    *team_out = team;
+    const bool whole = count % shmemx::ST_CHUNK == 0;
     const uint64_t ntasks = (count / shmemx::ST_CHUNK) * (uint64_t)ops_per_pe;
-    if (team < 1 || (uint64_t)H.npes * (uint64_t)wgs_per_pe < (uint64_t)H.num_cus) return 0;
-    if (ntasks >= UINT32_MAX || ntasks < (uint64_t)team * shmemx::ST_RING || nslots > UINT32_MAX) return 0;
-    return team;
-}
-
-// Whether a streaming cell hands its tasks out dynamically (blocks of ST_BLOCK tasks claimed from a per-team
-// counter): whole blocks, enough of them that the fixed first blocks of every workgroup are a small part.
-bool sweep_stream_dynamic(uint32_t team, uint64_t count, int ops_per_pe)
-{
-    const uint64_t ntasks = (count / shmemx::ST_CHUNK) * (uint64_t)ops_per_pe;
-    return H.stream_dynamic && team > 1 && ntasks % shmemx::ST_BLOCK == 0 && ntasks < (1ull << 31) &&
-           ntasks / shmemx::ST_BLOCK >= 2ull * shmemx::ST_STATIC * team;
+    const bool dynamic = H.stream_dynamic && team > 1;
+    if (whole && dynamic && ntasks % shmemx::ST_BLOCK == 0 && ntasks < (1ull << 31) &&
+        ntasks / shmemx::ST_BLOCK >= 2ull * shmemx::ST_STATIC * team) return 1;
+    const uint64_t rpo = (count + 1023) / 1024, nrows = rpo * (uint64_t)ops_per_pe, rows_per_block = 4 * shmemx::ST_BLOCK;
+    if (dynamic && count * 10 >= rpo * 1024 * 9 && nrows < (1ull << 31) &&
+        nrows / rows_per_block >= 2ull * shmemx::ST_STATIC * team) return 3;
+    if (!whole || ntasks >= UINT32_MAX || ntasks < (uint64_t)team * shmemx::ST_RING) return 0;
+    return 2;
 }
 
 }  // namespace
@@ -626,16 +632,19 @@ int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, 
     a.remote_stride = remote_stride; a.local_stride = local_stride; a.remote_slot = remote_slot_bytes;
     a.local_slot = local_slot_bytes; a.nslots = nslots; a.ops_per_pe = (uint32_t)ops_per_pe;
     a.wgs_per_pe = (uint32_t)wgs_per_pe;
-    if (const uint32_t team = sweep_stream_team(is_strided, count, remote_slot_bytes, local_slot_bytes, roff, loff, nslots,
-                                                ops_per_pe, wgs_per_pe)) {
+    uint32_t team = 0;
+    if (const int how = sweep_stream_kind(is_strided, count, remote_slot_bytes, local_slot_bytes, roff, loff, nslots, ops_per_pe,
+                                          wgs_per_pe, &team)) {
         shmemx::StreamSweepArgs sa;
         sa.kind = kind; sa.remote_off = roff; sa.local_off = loff; sa.count = count;
         sa.remote_slot = remote_slot_bytes; sa.local_slot = local_slot_bytes; sa.nslots = (uint32_t)nslots;
         sa.ops_per_pe = (uint32_t)ops_per_pe; sa.team = team;
         const unsigned grid = (unsigned)H.npes * team;
         sa.period = stream_period(grid);
-        if (sweep_stream_dynamic(team, count, ops_per_pe))
+        if (how == 1)
             hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_dyn, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
+        else if (how == 3)
+            hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_rows, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
         else
             hipLaunchKernelGGL(shmemx::k_copy_sweep_stream, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, ctx(), sa);
         return launched();
@@ -651,10 +660,11 @@ int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_
 {
     if (!H.init) return SHMEM_ERR_NOT_INIT;
     if (kind < SHMEM_OP_PUT || kind > SHMEM_OP_IGET || !grid_fits(wgs_per_pe) || ops_per_pe < 0 || nslots < 1) return SHMEM_ERR_INVALID_ARG;
-    const uint32_t team = sweep_stream_team(kind >= SHMEM_OP_IPUT, count, remote_slot_bytes, local_slot_bytes, off_of(remote_sym),
-                                            off_of(local_sym), nslots, ops_per_pe, wgs_per_pe);
-    if (workgroups_out) *workgroups_out = team ? H.npes * (int)team : H.npes * wgs_per_pe;
-    if (threads_out) *threads_out = !team ? WG_THREADS : sweep_stream_dynamic(team, count, ops_per_pe) ? (int)shmemx::ST_DYN_THREADS : (int)shmemx::ST_THREADS;
+    uint32_t team = 0;
+    const int how = sweep_stream_kind(kind >= SHMEM_OP_IPUT, count, remote_slot_bytes, local_slot_bytes, off_of(remote_sym),
+                                      off_of(local_sym), nslots, ops_per_pe, wgs_per_pe, &team);
+    if (workgroups_out) *workgroups_out = how ? H.npes * (int)team : H.npes * wgs_per_pe;
+    if (threads_out) *threads_out = how == 1 || how == 3 ? (int)shmemx::ST_DYN_THREADS : how == 2 ? (int)shmemx::ST_THREADS : WG_THREADS;
     return SHMEM_OK;
 }
 

@@ -334,14 +334,38 @@ STREAM_CASES = [
     (4, workgen.OP_PUT, 12288, 2048, 100, 64),           # three tasks per message: blocks straddle messages and slots
     (8, workgen.OP_GET, 1 << 20, 8, 8, 256),
     (2, workgen.OP_PUT, 8192, 4100, 4100, 128),          # 8200 tasks, 128 workgroups per team
+    (8, workgen.OP_PUT, 1024, 8192, 500, 32),            # from here on: whole 1 KiB rows that are not whole 4 KiB tasks
+    (8, workgen.OP_GET, 3072, 4096, 4096, 64),           # three rows per message: a task straddles messages
+    (8, workgen.OP_PUT, 14336, 1024, 300, 256),          # the 14,336-byte token: fourteen rows
+    (4, workgen.OP_GET, 5120, 2048, 77, 64),
+    (8, workgen.OP_PUT, 2048, 8190, 8190, 32),           # rows not a multiple of sixteen: the last block is short
+    (8, workgen.OP_GET, 14336, 301, 301, 64),            # 4214 rows: six rows in the last block; two of the last task's rows are none
+    (4, workgen.OP_PUT, 1024, 8195, 1000, 64),           # an odd number of rows
+    (8, workgen.OP_PUT, 2048, 1000, 1000, 32),           # too few rows to claim, and no whole 4 KiB tasks: not streamed
+    (8, workgen.OP_PUT, 14352, 600, 600, 64),            # the 14,352-byte dispatch message: fourteen rows and 16 bytes
+    (8, workgen.OP_GET, 4080, 4100, 999, 32),            # a last row 16 bytes short
+    (4, workgen.OP_GET, 1952, 9000, 9000, 64),           # two rows, the second 928 bytes
+    (4, workgen.OP_PUT, 1040, 9000, 9000, 64),           # 16 bytes into a second row: too wasteful to stream
+    (8, workgen.OP_PUT, 4096, 4099, 4099, 32),           # whole tasks, but not whole blocks of four: claimed as rows
 ]
 
 
 def _stream_threads(npes, count, nops, dynamic=True):
-    """Workgroup size the library is expected to choose for a streaming cell: 448 (a seventh wave that claims
-    blocks of four tasks) when the task list is whole blocks, at least eight per workgroup; else 384."""
-    team, ntasks = 256 // npes, count // 4096 * nops
-    return 448 if dynamic and team > 1 and ntasks % 4 == 0 and ntasks // 4 >= 8 * team else 384
+    """Workgroup size the library is expected to choose for a streaming cell: 448 (a seventh wave that claims the
+    work) either for whole 4 KiB tasks in whole blocks of four, at least eight blocks per workgroup, or for 1 KiB
+    rows when the messages fill at least nine tenths of their rows and the PE's rows make at least eight blocks of
+    sixteen per workgroup; else 384 (fixed shares of 4 KiB tasks, at least sixteen per workgroup); 256 for cells
+    that do not stream."""
+    if count % 16:
+        return 256
+    team, rpo, whole, ntasks = 256 // npes, (count + 1023) // 1024, count % 4096 == 0, count // 4096 * nops
+    rows = rpo * nops
+    claiming = dynamic and team > 1
+    if whole and claiming and ntasks % 4 == 0 and ntasks // 4 >= 8 * team:
+        return 448
+    if claiming and count * 10 >= rpo * 1024 * 9 and rows // 16 >= 8 * team:
+        return 448
+    return 384 if whole and ntasks >= 16 * team else 256
 
 
 @pytest.mark.parametrize("dynamic", [True, False])
@@ -349,7 +373,7 @@ def _stream_threads(npes, count, nops, dynamic=True):
 def test_copy_sweep_streaming_cell(case, dynamic, monkeypatch):
     npes, kind, count, nops, nslots, wgs = case
     if not dynamic:
-        if _stream_threads(npes, count, nops) == 384:
+        if _stream_threads(npes, count, nops) != 448:
             pytest.skip("this cell has a fixed task assignment anyway")
         monkeypatch.setenv("MI_SHMEM_STREAM_DYNAMIC", "0")        # read by shmem_init
     rslot = count + 4096 + 256
@@ -370,8 +394,8 @@ def test_copy_sweep_streaming_cell(case, dynamic, monkeypatch):
         heap.copy_(torch.from_numpy(init.reshape(-1)))
         wgs_launched, threads = sh.copy_sweep_geometry(kind, base + remote_off, base + local_off, count, rslot, lslot, nslots,
                                                        nops, wgs)
-        assert wgs_launched == npes * (256 // npes), "this cell was meant for the streaming copy"
         assert threads == _stream_threads(npes, count, nops, dynamic)
+        assert wgs_launched == (npes * (256 // npes) if threads != 256 else npes * wgs)
         sh.copy_sweep(kind, base + remote_off, base + local_off, count, 1, 1, 1, rslot, lslot, nslots, nops, wgs)
         sh.stream_sync()
         got = heaps_of(heap, npes)
