@@ -81,7 +81,9 @@ __device__ __forceinline__ uint64_t *bfs_pl_of(const Ctx &c, const BfsState &s, 
 }
 
 // Every owner clears its slice; the root's owner seeds the search.
-__global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t root)
+// `prev_has_root`: the snapshot of the bitmap "as of the previous level" starts with the root in it (searches
+// that derive a level's frontier bitmap from the first level on without a level-end pass for level 0).
+__global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t root, int prev_has_root)
 {
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
@@ -93,7 +95,8 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     uint64_t *flt = (uint64_t *)ptr(c, s.filter_off, pe);
     for (uint64_t w = rank; w < s.words * NXCD; w += size) flt[w] = 0;
     uint64_t *prev = (uint64_t *)ptr(c, s.prev_off, pe);
-    for (uint64_t w = rank; w < s.words; w += size) prev[w] = 0;
+    for (uint64_t w = rank; w < s.words; w += size)
+        prev[w] = (prev_has_root && pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
     for (uint64_t l = rank; l < s.vpp; l += size) {
         const bool is_root = pe == ro && l == rl;
         pl[l] = is_root ? bfs_pl(root, 0) : bfs_pl(SHMEM_BFS_NONE, -1);
@@ -644,9 +647,12 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     if (lane == 0 && mf) atomic_fetch_add(bfs_tails(c, s, pe) + T_DEG_FOUND, mf);
 }
 
-// After a bottom-up level, before a top-down one: the owner's queue for level `next` from its frontier
-// bitmap (the bits set during the last level; k_bfs_level_end has built it).  A wave takes 64 consecutive
-// words, one per lane, reserves room for all their bits with one add and writes the vertices.
+// The owner's queue for level `next` written from its frontier bitmap (the bits set during the last level;
+// k_bfs_level_end has built it): after a bottom-up level, which only counts its finds, before a top-down one;
+// and before the top-down expansion of a LARGE frontier, whose queue then lists the vertices in ascending runs
+// instead of in the order the claims arrived -- a batch of 64 frontier vertices reads neighbouring rows of the
+// adjacency, which share their 128-byte lines, and its row offsets in a few coalesced requests.  A wave takes
+// 64 consecutive words, one per lane, reserves room for all their bits with one add and writes the vertices.
 __global__ __launch_bounds__(256) void k_bfs_fill_queue(Ctx c, BfsState s, uint32_t next)
 {
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;

@@ -33,6 +33,7 @@ constexpr size_t GRAN = hostlogic::GRAN;   // allocator granularity / minimum al
 constexpr int WG_THREADS = 256;    // 4 wavefronts per workgroup
 constexpr int HASH_LOOKUP_KIF = 4;  // keys in flight per lane quad in the sector-wide lookup
 constexpr uint32_t BFS_ALPHA = 30, BFS_BETA = 24;  // default direction thresholds (measured best on R-MAT scale 24)
+constexpr uint32_t BFS_SORT_DIV = 64;              // frontiers from nverts / 64 vertices on are expanded in vertex order
 
 struct Host {
     bool init = false;
@@ -44,6 +45,7 @@ struct Host {
     int num_cus = 0;
     int wall_khz = 100000;         // rate of the constant-rate clock the streaming copy paces itself by
     bool stream_dynamic = true;    // bandwidth cells claim their tasks dynamically (kernels_stream.hpp)
+    uint32_t bfs_sort_div = 0;     // BFS: frontiers of nverts / this many vertices and more are expanded in vertex order (0: never)
     double stream_pace_ns = 0;     // pacing of the streaming copy: ns per 4 KiB task and workgroup when 256 workgroups stream
     bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
     hostlogic::SymAllocator alloc; // symmetric offsets (guarded by mu)
@@ -168,7 +170,8 @@ int bfs_level_end(const shmemx::BfsState &s, uint32_t next, bool do_front, bool 
 {
     static uint64_t seq = 0;
     ++seq;
-    const unsigned grid = (unsigned)H.npes * (unsigned)((do_front || do_degree) ? wgs_per_pe : 1);
+    // the frontier bitmap alone is a pass over 1/8 byte per vertex: a few workgroups per PE (fewer arrivals to count)
+    const unsigned grid = (unsigned)H.npes * (unsigned)(do_degree ? wgs_per_pe : do_front ? std::min(wgs_per_pe, 8) : 1);
     hipLaunchKernelGGL(shmemx::k_bfs_level_end, dim3(grid), dim3(WG_THREADS), 0, H.stream, ctx(), s, next,
                        (int)do_front, (int)do_degree, counts, seq);
     if (int rc = launched()) return rc;
@@ -363,6 +366,8 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     const char *pace = getenv("MI_SHMEM_STREAM_PACE_NS");     // measurement aid: 0 = unpaced
     H.stream_pace_ns = pace ? atof(pace) : STREAM_PACE_NS;
     if (!(H.stream_pace_ns >= 0.0 && H.stream_pace_ns < 1e6)) H.stream_pace_ns = STREAM_PACE_NS;
+    const char *sortdiv = getenv("MI_SHMEM_BFS_SORT_DIV");    // measurement aid: 0 = frontiers are never put in vertex order
+    H.bfs_sort_div = sortdiv ? (uint32_t)strtoul(sortdiv, nullptr, 10) : BFS_SORT_DIV;
     const char *dyn = getenv("MI_SHMEM_STREAM_DYNAMIC");
     H.stream_dynamic = !dyn || atoi(dyn) != 0;
     H.alloc.reset((uint64_t)(uintptr_t)dev_heap, (uint64_t)heap_bytes_per_pe);
@@ -835,7 +840,11 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     // [0] size of the next frontier, [1] degree sum of the expanded frontiers (top-down only mode),
     // [2] running degree sum of every frontier discovered so far (direction-optimising modes)
     uint64_t *counts = H.pinned + 16;
-    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root);
+    // Frontiers of at least nverts / sort_div vertices are expanded from a queue in vertex order (rewritten from
+    // the level's new bits); the frontier bitmap is then kept level by level in top-down searches as well.
+    const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(s.nverts / H.bfs_sort_div, 4096) : UINT64_MAX;
+    const bool fronts = hybrid || H.bfs_sort_div != 0;
+    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root, (int)(fronts && !hybrid));
     uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;
     if (hybrid) {
         if (int rc = bfs_level_end(s, 0u, true, true, g->wgs_per_pe, counts)) return rc;
@@ -859,6 +868,8 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
         if (!bottom_up && !queue_written) {
             hipLaunchKernelGGL(shmemx::k_bfs_fill_queue, grid, block, 0, H.stream, c, s, L);   // from the frontier bitmap
             queue_written = true;
+        } else if (!bottom_up && L > 0 && n_f >= sort_from) {
+            hipLaunchKernelGGL(shmemx::k_bfs_fill_queue, grid, block, 0, H.stream, c, s, L);   // the same entries, in vertex order
         }
         if (bottom_up) {
             // no LDS and few registers: twice the workgroups per PE fill the CUs' wave slots
@@ -875,7 +886,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
             hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
         }
-        if (int rc = bfs_level_end(s, L + 1, hybrid, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
+        if (int rc = bfs_level_end(s, L + 1, fronts, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
         if (L < 64) {
             const auto t_now = std::chrono::steady_clock::now();
             g->last_level_us[L] = std::chrono::duration<float, std::micro>(t_now - t_level).count();
