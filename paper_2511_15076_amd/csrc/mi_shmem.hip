@@ -842,7 +842,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     uint64_t *counts = H.pinned + 16;
     // Frontiers of at least nverts / sort_div vertices are expanded from a queue in vertex order (rewritten from
     // the level's new bits); the frontier bitmap is then kept level by level in top-down searches as well.
-    const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(s.nverts / H.bfs_sort_div, 4096) : UINT64_MAX;
+    const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(s.nverts / H.bfs_sort_div, 1024) : UINT64_MAX;
     const bool fronts = hybrid || H.bfs_sort_div != 0;
     hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root, (int)(fronts && !hybrid));
     uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;

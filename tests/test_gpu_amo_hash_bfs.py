@@ -331,6 +331,18 @@ def test_bfs_rmat(scale, npes, wgs, mode):
     run_bfs_case(row, nbr, roots, npes, wgs, mode)
 
 
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_TOP_DOWN | sh.BFS_CANONICAL_PARENTS, sh.BFS_DIRECTION_OPTIMIZING])
+@pytest.mark.parametrize("sort_div", ["0", "4000000000"])
+def test_bfs_frontier_order(sort_div, mode, monkeypatch):
+    # large frontiers are expanded from a queue rewritten in vertex order: never (0), or from 1024 vertices on
+    # (a divisor beyond the vertex count leaves the floor); levels, statistics and the canonical tree do not
+    # depend on the order
+    monkeypatch.setenv("MI_SHMEM_BFS_SORT_DIV", sort_div)          # read by shmem_init
+    for scale, npes, wgs in ((14, 16, 4), (16, 5, 8)):
+        row, nbr = workgen.rmat_csr(scale)
+        run_bfs_case(row, nbr, workgen.bfs_roots(row, 2), npes, wgs, mode)
+
+
 @pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP | sh.BFS_CANONICAL_PARENTS])
 def test_bfs_deep_graphs(mode):
     # far more levels than the 64 whose sizes the statistics record: a path of 700 vertices with a few chords
