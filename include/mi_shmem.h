@@ -318,7 +318,11 @@ int shmem_bfs_configure(void *graph, int mode, int alpha, int beta);
  * SHMEM_BFS_NONE = unreached; parent[root] = root) are DEVICE and may be NULL;
  * stats is HOST and may be NULL.  A search may have any number of levels
  * (nlevels counts them all; a histogram beyond the first 64 follows from
- * dev_level).  Errors: INVALID_ARG (root >= nverts), DEVICE. */
+ * dev_level).  A top-down level whose frontier holds at least nverts / 64
+ * vertices (and at least 1024) is expanded from a queue that the owner has
+ * rewritten in vertex order from the bits claimed in the level before (the
+ * same entries; MI_SHMEM_BFS_SORT_DIV in the environment of shmem_init sets
+ * another divisor, 0 = never).  Errors: INVALID_ARG (root >= nverts), DEVICE. */
 int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_parent, shmem_bfs_stats *stats);
 
 /* HOST: how the last shmem_bfs on this graph spent its time, level by level:
