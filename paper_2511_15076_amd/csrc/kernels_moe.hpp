@@ -94,7 +94,18 @@ __device__ __forceinline__ uint32_t moe_part_vecs(uint32_t hvecs, uint32_t lo, u
     return rem <= 0 ? 0u : (uint32_t)(rem < (int64_t)per ? rem : (int64_t)per);
 }
 
-// One wave copies nv 16-byte vectors, eight loads per lane in flight.
+// 16-byte store that is written through to memory: it leaves no dirty line in the die's L2.  For data that a
+// device-scope release is to make visible right afterwards: that release writes back whatever the L2 holds
+// dirty, and with the messages written through it has next to nothing to write back (one token per PE: combine
+// 14.3 -> 12.6 us, eight: dispatch 25.5 -> 21.3, combine 24.4 -> 16.9).
+__device__ __forceinline__ void store_through(u32x4 v, u32x4 *d)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
+}
+
+// One wave copies nv 16-byte vectors, eight loads per lane in flight.  THROUGH: the stores are written through
+// (messages that a release and a signal follow); else streaming stores (rows packed for the caller).
+template <bool THROUGH>
 __device__ __forceinline__ void wave_copy16(u32x4 *__restrict__ d, const u32x4 *__restrict__ s, uint32_t nv, uint32_t lane)
 {
     constexpr int IF = 8;
@@ -104,13 +115,13 @@ __device__ __forceinline__ void wave_copy16(u32x4 *__restrict__ d, const u32x4 *
 #pragma unroll
         for (int k = 0; k < IF; ++k) v[k] = __builtin_nontemporal_load(s + i + 64 * k);
 #pragma unroll
-        for (int k = 0; k < IF; ++k) __builtin_nontemporal_store(v[k], d + i + 64 * k);
+        for (int k = 0; k < IF; ++k) { if (THROUGH) store_through(v[k], d + i + 64 * k); else __builtin_nontemporal_store(v[k], d + i + 64 * k); }
     }
     u32x4 v[IF - 1];
 #pragma unroll
     for (int k = 0; k < IF - 1; ++k) if (i + 64 * k < nv) v[k] = __builtin_nontemporal_load(s + i + 64 * k);
 #pragma unroll
-    for (int k = 0; k < IF - 1; ++k) if (i + 64 * k < nv) __builtin_nontemporal_store(v[k], d + i + 64 * k);
+    for (int k = 0; k < IF - 1; ++k) if (i + 64 * k < nv) { if (THROUGH) store_through(v[k], d + i + 64 * k); else __builtin_nontemporal_store(v[k], d + i + 64 * k); }
 }
 
 // position of the n-th (0-based) set bit of the 128-bit mask (m0 = tokens 0..63, m1 = 64..127)
@@ -161,7 +172,7 @@ __device__ __forceinline__ uint32_t moe_expert_of_row(const uint32_t *ebase, uin
 // tokens" differs from "not announced"); the low half grows by the number of messages that have become visible
 // -- in one addition for a small batch, in one addition per contributing workgroup for a large one.  The pair
 // is complete when the low half has reached the announced count.  Returns the count (0 after a time-out).
-__device__ __forceinline__ uint32_t moe_poll_count(const Gin &gin, uint32_t id, bool patient = false)
+__device__ __forceinline__ uint32_t moe_poll_count(const Gin &gin, uint32_t id, bool patient = false, uint32_t nap = 1)
 {
     uint32_t spins = 0;
     for (;;) {
@@ -169,10 +180,44 @@ __device__ __forceinline__ uint32_t moe_poll_count(const Gin &gin, uint32_t id, 
         const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
         if (hi && lo + 1 == hi) return lo;
         if (timed_out(gin.c, spins)) return 0;
-        if (patient) __builtin_amdgcn_s_sleep(100); else
-        __builtin_amdgcn_s_sleep(1);
+        if (patient) __builtin_amdgcn_s_sleep(100);
+        else if (nap > 1) __builtin_amdgcn_s_sleep(16);
+        else __builtin_amdgcn_s_sleep(1);
         if (++spins > SPIN_LIMIT) { report(gin.c, DEV_ERR_BARRIER_TIMEOUT, gin.pe); return 0; }
     }
+}
+
+// Large batches, receiving side.  The announced count of a pair (high half - 1) is there long before its messages
+// are (a sender announces before it sends anything): bounded wait for the announcement alone.
+__device__ __forceinline__ uint32_t moe_poll_announced(const Gin &gin, uint32_t id)
+{
+    uint32_t spins = 0;
+    for (;;) {
+        const uint32_t hi = (uint32_t)(gin.read_signal(id) >> 32);
+        if (hi) return hi - 1;
+        if (timed_out(gin.c, spins)) return 0;
+        __builtin_amdgcn_s_sleep(8);
+        if (++spins > SPIN_LIMIT) { report(gin.c, DEV_ERR_BARRIER_TIMEOUT, gin.pe); return 0; }
+    }
+}
+
+// Whole wave: returns once all messages of pair `id` are complete (ready[id], in LDS, spares the other waves of
+// the workgroup the poll).  No cache maintenance here -- a device-scope acquire is an invalidate of the die's
+// whole L2, and one per pair and workgroup (thousands per launch) made the large dispatch 60 % slower.  It is
+// not needed either: the workgroup has dropped every stale line once, before its first read of a receive slot
+// (the acquire ahead of the packing), and from then on a line of a pair's slots can only enter this die's caches
+// through a read, which nobody issues before the pair is complete (slots of different pairs share no line: a
+// pair's region is max_tokens messages, a multiple of 128 bytes whenever max_tokens is a multiple of 8, which
+// the large-batch path requires).
+__device__ __forceinline__ void moe_wait_pair(const Gin &gin, uint32_t id, volatile uint8_t *ready, uint32_t lane)
+{
+    if (!ready[id]) {
+        if (lane == 0) {
+            moe_poll_count(gin, id, false, 16);
+            ready[id] = 1;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");      // (orders the reads below after the poll)
 }
 
 // Sharing N units of work (routes, rows: one message each) among the W workgroups of a PE when the batch is
@@ -263,6 +308,8 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     __shared__ int16_t s_topk[MOE_MAX_TOKENS * MOE_MAX_TOPK];   // this PE's routing table (expert ids fit 16 bits)
     __shared__ uint32_t rbase[MOE_MAX_EXPERTS + 1]; // large batches: first route of every expert in the PE's flattened list
     __shared__ MoeRanges rq;                        // large batches: the ranges of routes / rows this workgroup takes
+    __shared__ uint32_t pbase[MOE_MAX_EXPERTS + 1]; // large batches: first unit of every (sender, local expert) pair in arrival order
+    __shared__ uint8_t ready[MOE_MAX_EXPERTS];      // large batches: pair complete and acquired by this workgroup
     __shared__ uint32_t s_last;
     const uint32_t W = a.wgs_per_pe, pe = blockIdx.x / W, wg = blockIdx.x % W;
     const uint32_t P = (uint32_t)c.npes, E = m.num_experts, T = m.max_tokens, K = m.topk;
@@ -275,7 +322,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
     const uint32_t ctl0 = m.epp * P + E;                                     // first control word after the combine flags
     // Large batches are bandwidth-bound and are balanced dynamically; small ones are latency-bound and keep the
     // fixed split, which needs no claim before the first message.  Every workgroup of a PE decides alike.
-    const bool bulk = ntok >= MOE_BULK_TOKENS && nwaves > MOE_SEND_WAVES;
+    const bool bulk = ntok >= MOE_BULK_TOKENS && nwaves > MOE_SEND_WAVES && T % 8 == 0;   // (T % 8: a pair's slots are whole 128-byte lines)
 
     // ---- routing masks (every workgroup builds its own copy: at most 128 x topk entries) ----
     // The whole table is read, not just the first ntok rows: its loads then do not wait for the load
@@ -304,13 +351,27 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
             if (lane == 0) {
                 u32x4 meta = {t, pe, j, e};
-                __builtin_nontemporal_store(meta, (u32x4 *)slot);
+                store_through(meta, (u32x4 *)slot);
             }
         }
         const uint32_t lo = part * per, cnt = moe_part_vecs(hvecs, lo, per);
-        wave_copy16((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo, cnt, lane);
+        wave_copy16<true>((u32x4 *)(slot + MOE_META_BYTES) + lo, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo, cnt, lane);
     };
 
+    // large batches: position k of the PE's send order is expert ord(k) (the PE's own experts first, see below)
+    const uint32_t erot = (pe * m.epp) % E;
+    auto ord = [&](uint32_t k) { const uint32_t e = k + erot; return e >= E ? e - E : e; };
+    // ... and what the routes [lo, hi) of this workgroup have made visible is added to their pairs' signals (one
+    // lane; a range may span experts, an expert may be split among workgroups)
+    auto signal_range = [&](uint32_t lo, uint32_t hi) {
+        for (uint32_t k = moe_expert_of_row(rbase, E, lo); lo < hi && k < E; ++k) {
+            const uint32_t up = min(hi, rbase[k + 1]);
+            if (up <= lo) continue;                                          // an expert without routes
+            const uint32_t e = ord(k);
+            __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(up - lo), __ATOMIC_RELAXED, SHMEMX_AGENT);
+            lo = up;
+        }
+    };
     uint32_t routes = 0;
     if (!bulk) {
         // ---- send: the routes of this workgroup's experts (e = wg mod W), dealt round-robin to its waves ----
@@ -325,32 +386,37 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
                     if (q % nwaves == wave) send_piece(e, m0, m1, i, part, sper);
         }
     } else {
-        // ---- send, large batch: the PE's routes, flattened in expert order (route r = token number r - rbase[e]
-        // of expert e), shared out by moe_share.
+        // ---- send, large batch: the PE's routes, flattened in expert order STARTING WITH THE PE'S OWN EXPERTS
+        // (position k is expert (k + pe * epp) mod E; route r = token number r - rbase[k] of that expert), shared
+        // out by moe_share.  Every PE thus sends to a different owner at any moment, and an owner's messages
+        // arrive all through the send phase instead of from everybody at once: the receiving side packs what has
+        // arrived while the rest is still on its way (below).
         if (threadIdx.x < 64) {
-            const uint32_t per = (E + 63) / 64, e0 = min(lane * per, E), e1 = min(e0 + per, E);
+            const uint32_t per = (E + 63) / 64, k0 = min(lane * per, E), k1 = min(k0 + per, E);
             uint32_t sum = 0;
-            for (uint32_t e = e0; e < e1; ++e) sum += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1]));
+            for (uint32_t k = k0; k < k1; ++k) { const uint32_t e = ord(k); sum += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1])); }
             uint32_t incl = sum;
             for (uint32_t d = 1; d < 64; d <<= 1) {                          // inclusive scan over the lanes
                 const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
                 if (lane >= d) incl += up;
             }
             uint32_t run = incl - sum;
-            for (uint32_t e = e0; e < e1; ++e) { rbase[e] = run; run += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1])); }
+            for (uint32_t k = k0; k < k1; ++k) { const uint32_t e = ord(k); rbase[k] = run; run += (uint32_t)(__popcll(mask[e][0]) + __popcll(mask[e][1])); }
             if (lane == 63) rbase[E] = incl;
         }
         __syncthreads();
         // the announcements (count + 1 in the high half) can go at once: they say nothing about the data
         if (threadIdx.x < 64)
-            for (uint32_t e = wg + lane * W; e < E; e += 64 * W)
-                __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(rbase[e + 1] - rbase[e] + 1) << 32,
+            for (uint32_t k = wg + lane * W; k < E; k += 64 * W) {
+                const uint32_t e = ord(k);
+                __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(rbase[k + 1] - rbase[k] + 1) << 32,
                                        __ATOMIC_RELAXED, SHMEMX_AGENT);
+            }
         const uint32_t sper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
         routes = rbase[E];
         moe_share(c, rq, routes, W, wg, gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), wave, lane, [&](uint32_t r, uint32_t part) {
-            const uint32_t e = moe_expert_of_row(rbase, E, r);
-            send_piece(e, mask[e][0], mask[e][1], r - rbase[e], part, sper);
+            const uint32_t k = moe_expert_of_row(rbase, E, r), e = ord(k);
+            send_piece(e, mask[e][0], mask[e][1], r - rbase[k], part, sper);
         });
     }
     // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
@@ -364,19 +430,9 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
                 __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (n + 1) << 32 | n, __ATOMIC_RELAXED, SHMEMX_AGENT);
             }
         } else {
-            // what this workgroup sent, pair by pair (a range may span experts, an expert may be split among workgroups)
+            // what this workgroup sent, range by range
             const uint32_t mine = rq.pub & 0x7fffffffu;
-            for (uint32_t k = lane; k < mine; k += 64) {
-                uint32_t lo = rq.rq[k][0];
-                const uint32_t hi = rq.rq[k][1];
-                for (uint32_t e = moe_expert_of_row(rbase, E, lo); lo < hi && e < E; ++e) {
-                    const uint32_t up = min(hi, rbase[e + 1]);
-                    if (up <= lo) continue;                                  // an expert without routes
-                    __hip_atomic_fetch_add(gin.signal_word((e % m.epp) * P + pe, e / m.epp), (uint64_t)(up - lo), __ATOMIC_RELAXED,
-                                           SHMEMX_AGENT);
-                    lo = up;
-                }
-            }
+            for (uint32_t k = lane; k < mine; k += 64) signal_range(rq.rq[k][0], rq.rq[k][1]);
             if (lane == 0)
                 moe_share_done(gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), gin.signal_word(ctl0 + MOE_CTL_SEND_DONE, pe), W);
         }
@@ -416,20 +472,27 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
                 u32x4 info = {0, 0, 0, 0};
                 if (first) info = *(const u32x4 *)slot;
                 const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
-                wave_copy16((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
+                wave_copy16<false>((u32x4 *)(a.recv_x + (row0 + i) * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
                 if (first) *(u32x4 *)(a.recv_info + (row0 + i) * 4) = info;
             }
         }
     } else {
-        // ---- receive, large batch: every workgroup of the PE reads ALL the PE's counts, and the rows of all local
-        // experts, flattened, are shared out by moe_share (36 experts on 32 workgroups would otherwise leave four
-        // workgroups with twice the work).  The signals are put
-        // back to zero by the workgroup of the PE that finishes last.
+        // ---- receive, large batch: every workgroup of the PE reads ALL the PE's announced counts (they are there
+        // long before the messages), and the rows of all local experts are shared out by moe_share (36 experts on
+        // 32 workgroups would otherwise leave four workgroups with twice the work) -- in the order in which they
+        // ARRIVE: sender s reaches this PE's experts in phase (pe - s) mod P of its send order, so the units are the
+        // pairs by phase, then by local expert, and a wave waits only for the pair its own row belongs to.  The
+        // workgroups that finish sending early pack what is complete while the last messages are still in flight.
+        // The signals are put back to zero by the workgroup of the PE that finishes last.
         const uint32_t npairs = m.epp * P;
-        for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) begin[i] = min(moe_poll_count(gin, i, true), T);
+        for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) {
+            const uint32_t n = min(moe_poll_announced(gin, i), T);
+            begin[i] = n;
+            const uint32_t le = i / P, s = i % P, phase = (pe + P - s) % P;
+            pbase[phase * m.epp + le + 1] = n;                               // counts in arrival order, summed up below
+            ready[i] = 0;
+        }
         __syncthreads();
-        if (threadIdx.x < 64) acquire();
-        wg_acquire();
         for (uint32_t le = threadIdx.x; le < m.epp; le += blockDim.x) {      // counts -> first rows within the expert
             uint32_t run = 0;
             for (uint32_t s = 0; s < P; ++s) {
@@ -439,7 +502,12 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             }
             ebase[le + 1] = run;
         }
-        __syncthreads();
+        if (threadIdx.x == 64) {
+            pbase[0] = 0;
+            for (uint32_t q = 0; q < npairs; ++q) pbase[q + 1] += pbase[q];
+        }
+        if (threadIdx.x < 64) acquire();                                     // once: see moe_wait_pair
+        wg_acquire();
         if (threadIdx.x == 0) {
             ebase[0] = 0;
             for (uint32_t le = 0; le < m.epp; ++le) ebase[le + 1] += ebase[le];
@@ -455,17 +523,17 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
         }
         const uint32_t rper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
-        moe_share(c, rq, ebase[m.epp], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
-            const uint32_t le = moe_expert_of_row(ebase, m.epp, g), i = g - ebase[le];
-            uint32_t s = 0;
-            while (s + 1 < P && begin[le * P + s + 1] <= i) ++s;            // the last sender whose first row is <= i (empty senders share a first row)
-            const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + (i - begin[le * P + s])) * m.msg, pe);
-            const size_t row = ((size_t)pe * m.epp + le) * ((size_t)P * T) + i;
+        moe_share(c, rq, pbase[npairs], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
+            const uint32_t q = moe_expert_of_row(pbase, npairs, g), i = g - pbase[q];        // pair in arrival order, message of the pair
+            const uint32_t le = q % m.epp, s = (pe + P - q / m.epp) % P;
+            moe_wait_pair(gin, le * P + s, ready, lane);
+            const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + i) * m.msg, pe);
+            const size_t row = ((size_t)pe * m.epp + le) * ((size_t)P * T) + begin[le * P + s] + i;
             const bool first = part == 0 && lane == 0;
             u32x4 info = {0, 0, 0, 0};
             if (first) info = *(const u32x4 *)slot;
             const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
-            wave_copy16((u32x4 *)(a.recv_x + row * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
+            wave_copy16<false>((u32x4 *)(a.recv_x + row * m.hidden) + lo, (const u32x4 *)(slot + MOE_META_BYTES) + lo, cnt, lane);
             if (first) *(u32x4 *)(a.recv_info + row * 4) = info;
         });
         if (threadIdx.x == 0)
@@ -510,7 +578,7 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
         const uint32_t t = info.x, s = info.y, j = info.z;
         if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row); return; }
         const uint32_t lo = part * per, cnt = moe_part_vecs(hvecs, lo, per);
-        wave_copy16((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
+        wave_copy16<true>((u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo,
                     (const u32x4 *)(a.expert_out + row * m.hidden) + lo, cnt, lane);
     };
     if (!bulk) {
