@@ -247,7 +247,34 @@ __device__ __forceinline__ void pe_team_sync(const Ctx &c, const PeTeam &t, uint
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename V>
+// A store that is WRITTEN THROUGH to memory (the system-coherent form of the store instruction): it leaves no
+// dirty line in the die's L2.  For data that a device-scope release is about to make visible -- a put that a
+// signal, a quiet or a barrier follows: that release writes back whatever the L2 holds dirty, which under load
+// takes microseconds, and with the data written through it finds next to nothing.  (Data whose completion is a
+// kernel boundary keeps streaming stores, which are faster in bulk.)
+__device__ __forceinline__ void store_through(u32x4 v, u32x4 *d)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(u32x2 v, u32x2 *d)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(uint32_t v, uint32_t *d)
+{
+    asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(uint8_t v, uint8_t *d)
+{
+    asm volatile("global_store_byte %0, %1, off sc0 sc1" : : "v"(d), "v"((uint32_t)v) : "memory");
+}
+template <bool THROUGH, typename V>
+__device__ __forceinline__ void copy_store(V v, V *d)
+{
+    if (THROUGH) store_through(v, d); else __builtin_nontemporal_store(v, d);
+}
+
+template <bool THROUGH, typename V>
 __device__ __forceinline__ void copy_units(V *__restrict__ d, const V *__restrict__ s, size_t nv,
                                            size_t rank, size_t size)
 {
@@ -257,10 +284,10 @@ __device__ __forceinline__ void copy_units(V *__restrict__ d, const V *__restric
         V b = __builtin_nontemporal_load(s + i + size);
         V e = __builtin_nontemporal_load(s + i + 2 * size);
         V f = __builtin_nontemporal_load(s + i + 3 * size);
-        __builtin_nontemporal_store(a, d + i);
-        __builtin_nontemporal_store(b, d + i + size);
-        __builtin_nontemporal_store(e, d + i + 2 * size);
-        __builtin_nontemporal_store(f, d + i + 3 * size);
+        copy_store<THROUGH>(a, d + i);
+        copy_store<THROUGH>(b, d + i + size);
+        copy_store<THROUGH>(e, d + i + 2 * size);
+        copy_store<THROUGH>(f, d + i + 3 * size);
     }
     // up to three units are left for this lane: all loads first, then the stores
     const bool p0 = i < nv, p1 = i + size < nv, p2 = i + 2 * size < nv;
@@ -268,11 +295,13 @@ __device__ __forceinline__ void copy_units(V *__restrict__ d, const V *__restric
     if (p0) a = __builtin_nontemporal_load(s + i);
     if (p1) b = __builtin_nontemporal_load(s + i + size);
     if (p2) e = __builtin_nontemporal_load(s + i + 2 * size);
-    if (p0) __builtin_nontemporal_store(a, d + i);
-    if (p1) __builtin_nontemporal_store(b, d + i + size);
-    if (p2) __builtin_nontemporal_store(e, d + i + 2 * size);
+    if (p0) copy_store<THROUGH>(a, d + i);
+    if (p1) copy_store<THROUGH>(b, d + i + size);
+    if (p2) copy_store<THROUGH>(e, d + i + 2 * size);
 }
 
+// THROUGH: the destination is written through (see store_through).
+template <bool THROUGH = false>
 __device__ __forceinline__ void copy(uint8_t *__restrict__ dst, const uint8_t *__restrict__ src, size_t n,
                                      size_t rank, size_t size)
 {
@@ -281,15 +310,15 @@ __device__ __forceinline__ void copy(uint8_t *__restrict__ dst, const uint8_t *_
     const size_t unit = (diff & 15) == 0 ? 16 : (diff & 7) == 0 ? 8 : (diff & 3) == 0 ? 4 : 1;
     size_t head = (size_t)(-(uintptr_t)dst) & (unit - 1);
     if (head > n) head = n;
-    for (size_t j = rank; j < head; j += size) dst[j] = src[j];
+    for (size_t j = rank; j < head; j += size) copy_store<THROUGH>(src[j], dst + j);
     const size_t body = (n - head) / unit;
     uint8_t *d = dst + head;
     const uint8_t *s = src + head;
-    if (unit == 16) copy_units((u32x4 *)d, (const u32x4 *)s, body, rank, size);
-    else if (unit == 8) copy_units((u32x2 *)d, (const u32x2 *)s, body, rank, size);
-    else if (unit == 4) copy_units((uint32_t *)d, (const uint32_t *)s, body, rank, size);
-    else copy_units(d, s, body, rank, size);
-    for (size_t j = head + body * unit + rank; j < n; j += size) dst[j] = src[j];
+    if (unit == 16) copy_units<THROUGH>((u32x4 *)d, (const u32x4 *)s, body, rank, size);
+    else if (unit == 8) copy_units<THROUGH>((u32x2 *)d, (const u32x2 *)s, body, rank, size);
+    else if (unit == 4) copy_units<THROUGH>((uint32_t *)d, (const uint32_t *)s, body, rank, size);
+    else copy_units<THROUGH>(d, s, body, rank, size);
+    for (size_t j = head + body * unit + rank; j < n; j += size) copy_store<THROUGH>(src[j], dst + j);
 }
 
 // A large contiguous copy with 16-byte aligned ends by `waves` cooperating waves (this one is number
@@ -337,13 +366,18 @@ __device__ __forceinline__ void copy_stream(uint8_t *__restrict__ dst, const uin
     }
 }
 
+constexpr size_t PUT_THROUGH_BYTES = 4096;
 // put / get are the same copy with the remote side as destination / source.  (They stay on the generic
 // copy: pulling the streaming loop into the latency kernels cost 0.4 us per ping-pong round trip.)
 // (Sec. III-A one-sided semantics; Table II put_nbi / get).
 __device__ __forceinline__ void put(const Ctx &c, uint64_t dst_off, const uint8_t *src, size_t n, uint32_t pe,
                                     size_t rank, size_t size)
 {
-    copy(ptr(c, dst_off, pe), src, n, rank, size);
+    // a small put is written through: what follows it is a quiet, a signal or a barrier, whose release then has
+    // nothing of it left to write back (ping-pong of 8 B to 4 KiB: 2.7-2.8 -> 2.3-2.5 us per round trip); larger
+    // ones keep streaming stores, which carry far more per workgroup (64 KiB: 6.1 us against 9.7)
+    if (n <= PUT_THROUGH_BYTES) copy<true>(ptr(c, dst_off, pe), src, n, rank, size);
+    else copy<false>(ptr(c, dst_off, pe), src, n, rank, size);
 }
 __device__ __forceinline__ void get(const Ctx &c, uint8_t *dst, uint64_t src_off, size_t n, uint32_t pe,
                                     size_t rank, size_t size)

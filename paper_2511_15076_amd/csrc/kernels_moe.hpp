@@ -94,17 +94,10 @@ __device__ __forceinline__ uint32_t moe_part_vecs(uint32_t hvecs, uint32_t lo, u
     return rem <= 0 ? 0u : (uint32_t)(rem < (int64_t)per ? rem : (int64_t)per);
 }
 
-// 16-byte store that is written through to memory: it leaves no dirty line in the die's L2.  For data that a
-// device-scope release is to make visible right afterwards: that release writes back whatever the L2 holds
-// dirty, and with the messages written through it has next to nothing to write back (one token per PE: combine
-// 14.3 -> 12.6 us, eight: dispatch 25.5 -> 21.3, combine 24.4 -> 16.9).
-__device__ __forceinline__ void store_through(u32x4 v, u32x4 *d)
-{
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
-}
-
 // One wave copies nv 16-byte vectors, eight loads per lane in flight.  THROUGH: the stores are written through
-// (messages that a release and a signal follow); else streaming stores (rows packed for the caller).
+// (messages that a release and a signal follow: with nothing dirty left in the L2 that release is cheap -- one
+// token per PE: combine 14.3 -> 12.6 us, eight: dispatch 25.5 -> 21.3, combine 24.4 -> 16.9); else streaming
+// stores (rows packed for the caller).
 template <bool THROUGH>
 __device__ __forceinline__ void wave_copy16(u32x4 *__restrict__ d, const u32x4 *__restrict__ s, uint32_t nv, uint32_t lane)
 {
