@@ -103,7 +103,10 @@ CASES = [
     (4, 8, 64, 2, 48, [64, 31, 32, 0], "uniform", 0.0, 1),      # both kinds of PE in one exchange, one workgroup per PE
     (2, 6, 40, 3, 80, None, "zipf", 1.0, 3),                   # every entry dropped: large batches with nothing to send
     (8, 16, 32, 1, 16, None, "uniform", 0.0, 64),              # more workgroups than messages: nothing fixed, every block claimed
-    (3, 12, 100, 4, 14352, None, "zipf", 0.1, 11),             # long messages of an odd length, odd team size
+    (3, 12, 100, 4, 14352, None, "zipf", 0.1, 11),             # long messages of an odd length, odd team size (a token limit
+                                                               # that is no multiple of 8: the fixed split at every batch size)
+    (3, 12, 104, 4, 14352, None, "zipf", 0.1, 11),             # the same shared out dynamically, packed pair by pair
+    (5, 40, 48, 8, 1040, [48, 40, 0, 33, 48], "uniform", 0.2, 6),  # five PEs: the send order of every PE starts at its own experts
 ]
 
 
