@@ -25,8 +25,12 @@ struct BfsState {
     uint32_t nverts, vpp;        // vertices in total / per PE (block partition)
     uint64_t words;              // bitmap words per PE
     int shift;                   // log2(vpp) if vpp is a power of two, else -1
+    // The search runs on the library's own numbering of the vertices (see k_bfs_relabel): nverts counts its
+    // vertices (npes * vpp: every PE a full block), row_off / nbr are the graph in that numbering, to_orig[i] is the
+    // caller's number of vertex i (SHMEM_BFS_NONE for the padding at the end of a block, which has no edges).
     const uint64_t *row_off;     // CSR row offsets (PE p reads rows of its own vertices)
     const uint32_t *nbr;         // CSR neighbours
+    const uint32_t *to_orig;
     // symmetric offsets of the per-PE state
     uint64_t bitmap_off, pl_off, queue_off[2], big_off, bigscan_off, tails_off;   // pl: (parent, level) pairs, 8 bytes per vertex
     uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
@@ -78,6 +82,25 @@ __device__ __forceinline__ uint64_t bfs_pl(uint32_t parent, int32_t level)
 __device__ __forceinline__ uint64_t *bfs_pl_of(const Ctx &c, const BfsState &s, uint32_t pe)
 {
     return (uint64_t *)ptr(c, s.pl_off, pe);
+}
+
+// Once per graph: the adjacency in the library's numbering.  Vertices are ranked by degree (largest first, ties by
+// the caller's number) and rank r becomes local vertex r / npes of PE r mod npes -- still a 1D partition, every PE
+// holding an equal share of every degree class, with the vertices that most edges point to at the start of every
+// PE's block (that is where the top-down kernels' LDS filter looks, see HubFilter).  A wave copies one row at a
+// time, in the caller's neighbour order, translating the neighbours.
+__global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, const uint32_t *__restrict__ to_orig, const uint32_t *__restrict__ to_int,
+                                                     const uint64_t *__restrict__ row_orig, const uint32_t *__restrict__ nbr_orig,
+                                                     const uint64_t *__restrict__ row_int, uint32_t *__restrict__ nbr_int)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    for (uint64_t i = wave; i < nint; i += waves) {
+        const uint32_t o = to_orig[i];
+        if (o == SHMEM_BFS_NONE) continue;
+        const uint64_t src = row_orig[o], dst = row_int[i], deg = row_int[i + 1] - dst;
+        for (uint64_t e = lane; e < deg; e += 64) nbr_int[dst + e] = to_int[nbr_orig[src + e]];
+    }
 }
 
 // Every owner clears its slice; the root's owner seeds the search.
@@ -711,15 +734,16 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
         const uint64_t l = w * 64 + lane;
         const int32_t lvl = l < count ? (int32_t)(pl[l] >> 32) : -1;
         const bool need = lvl > 0;                       // reached and not the root
-        uint32_t best = SHMEM_BFS_NONE, deg = 0;
+        // "smallest" is by the CALLER's numbers (bo), what is stored is the library's (best)
+        uint32_t best = SHMEM_BFS_NONE, bo = SHMEM_BFS_NONE, deg = 0;
         uint64_t r0 = 0;
         if (need) {
             r0 = s.row_off[first + l];
             deg = (uint32_t)(s.row_off[first + l + 1] - r0);
             if (deg <= CANON_LANE_EDGES)
                 for (uint32_t j = 0; j < deg; ++j) {
-                    const uint32_t u = s.nbr[r0 + j];
-                    if (bfs_level_of(c, s, u) == lvl - 1 && u < best) best = u;
+                    const uint32_t u = s.nbr[r0 + j], uo = s.to_orig[u];
+                    if (bfs_level_of(c, s, u) == lvl - 1 && uo < bo) { bo = uo; best = u; }
                 }
         }
         uint64_t longrows = ballot(need && deg > CANON_LANE_EDGES);   // the wave scans these together
@@ -729,15 +753,19 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
             const uint32_t dj = bcast32(deg, j);
             const uint64_t rj = bcast64(r0, j);
             const int32_t lj = (int32_t)bcast32((uint32_t)lvl, j);
-            uint32_t mn = SHMEM_BFS_NONE;
+            uint64_t mn = ~0ull;                                      // (caller's number, library's number)
             for (uint32_t e0 = 0; e0 < dj; e0 += 64) {
                 if (e0 + lane < dj) {
                     const uint32_t u = s.nbr[rj + e0 + lane];
-                    if (bfs_level_of(c, s, u) == lj - 1 && u < mn) mn = u;
+                    if (bfs_level_of(c, s, u) == lj - 1) mn = min(mn, ((uint64_t)s.to_orig[u] << 32) | u);
                 }
             }
-            for (int off = 32; off > 0; off >>= 1) mn = min(mn, (uint32_t)__shfl_xor((int)mn, off, 64));
-            if (lane == j) best = mn;
+            for (int off = 32; off > 0; off >>= 1) {
+                const uint64_t other = ((uint64_t)(uint32_t)__shfl_xor((int)(uint32_t)(mn >> 32), off, 64) << 32) |
+                                       (uint32_t)__shfl_xor((int)(uint32_t)mn, off, 64);
+                mn = min(mn, other);
+            }
+            if (lane == j) best = mn == ~0ull ? SHMEM_BFS_NONE : (uint32_t)mn;
         }
         if (need) ((uint32_t *)(pl + l))[0] = best;      // the low word of the record
     }
@@ -818,19 +846,18 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
     }
 }
 
-// Every owner splits its (parent, level) records into the caller's flat level / parent arrays.
-__global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, int32_t *level, uint32_t *parent)
+// The (parent, level) records go into the caller's flat level / parent arrays, in the caller's numbering: thread
+// o looks up where vertex o lives (to_int) and translates the parent it finds there (to_orig).
+__global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, uint32_t nverts_orig, const uint32_t *__restrict__ to_int,
+                                                    int32_t *level, uint32_t *parent)
 {
-    const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
-    const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
-    const uint64_t first = (uint64_t)pe * s.vpp;
-    if (first >= s.nverts) return;
-    const uint64_t cnt = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
-    const uint64_t *pl = bfs_pl_of(c, s, pe);
-    for (uint64_t l = rank; l < cnt; l += size) {
-        const uint64_t rec = __builtin_nontemporal_load(pl + l);
-        if (level) __builtin_nontemporal_store((int32_t)(rec >> 32), level + first + l);
-        if (parent) __builtin_nontemporal_store((uint32_t)rec, parent + first + l);
+    const uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, size = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t o = rank; o < nverts_orig; o += size) {
+        const uint32_t i = to_int[o], pe = bfs_owner(s, i);
+        const uint64_t rec = __builtin_nontemporal_load(bfs_pl_of(c, s, pe) + (i - pe * s.vpp));
+        const uint32_t par = (uint32_t)rec;
+        if (level) __builtin_nontemporal_store((int32_t)(rec >> 32), level + o);
+        if (parent) __builtin_nontemporal_store(par == SHMEM_BFS_NONE ? SHMEM_BFS_NONE : s.to_orig[par], parent + o);
     }
 }
 

@@ -66,6 +66,11 @@ struct BfsGraph {
     uint64_t nnz;      // CSR entries (sum of all row lengths)
     void *allocs[12];
     int nallocs;
+    // the graph in the library's numbering (device memory the library allocates at creation and frees at destruction)
+    uint32_t nverts_orig;
+    uint64_t *d_row_int;
+    uint32_t *d_nbr_int, *d_to_int, *d_to_orig;
+    std::vector<uint32_t> to_int;    // host copy: where the root of a search lives
     // the last search, level by level (host clock around each level's launches and its hand-over; the first 64)
     uint32_t last_levels;
     float last_level_us[64];
@@ -765,35 +770,71 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
         offs[i] = (uint64_t)((uint8_t *)p - H.heap);
     }
     shmemx::BfsState &s = g->st;
-    s.nverts = nverts; s.vpp = vpp; s.words = words;
+    auto fail = [&](int rc) {
+        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
+        (void)hipFree(g->d_row_int); (void)hipFree(g->d_nbr_int); (void)hipFree(g->d_to_int); (void)hipFree(g->d_to_orig);
+        delete g;
+        return rc;
+    };
+    g->d_row_int = nullptr; g->d_nbr_int = nullptr; g->d_to_int = nullptr; g->d_to_orig = nullptr;
+    const uint64_t nint64 = (uint64_t)vpp * (uint64_t)H.npes;               // every PE a full block (padded with vertices without edges)
+    if (nint64 >= SHMEM_BFS_NONE) return fail(SHMEM_ERR_INVALID_ARG);
+    const uint32_t nint = (uint32_t)nint64;
+    s.nverts = nint; s.vpp = vpp; s.words = words;
     s.shift = (vpp & (vpp - 1)) == 0 ? (int)__builtin_ctz(vpp) : -1;
-    s.row_off = dev_row_off; s.nbr = dev_nbr;
     s.bitmap_off = offs[0]; s.pl_off = offs[1];
     s.queue_off[0] = offs[2]; s.queue_off[1] = offs[3]; s.big_off = offs[4]; s.bigscan_off = offs[5];
     s.tails_off = offs[6]; s.filter_off = offs[7]; s.front_off = offs[8]; s.prev_off = offs[9]; s.linked_off = offs[10];
     g->mode = SHMEM_BFS_TOP_DOWN; g->canonical = false; g->alpha = BFS_ALPHA; g->beta = BFS_BETA;
-    g->nnz = 0;
-    if (hipMemcpyAsync(H.pinned + 32, dev_row_off + nverts, 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
-        hipStreamSynchronize(H.stream) != hipSuccess) {
-        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
-        delete g;
-        return SHMEM_ERR_DEVICE;
+    g->nverts_orig = nverts;
+    // The library's numbering: vertices ranked by degree, largest first (ties by number), rank r -> local vertex
+    // r / npes of PE r mod npes.  Ranking and the new row offsets are host work, once per graph.
+    try {
+    std::vector<uint64_t> row((size_t)nverts + 1);
+    if (hipMemcpyAsync(row.data(), dev_row_off, row.size() * 8, hipMemcpyDeviceToHost, H.stream) != hipSuccess ||
+        hipStreamSynchronize(H.stream) != hipSuccess) return fail(SHMEM_ERR_DEVICE);
+    g->nnz = row[nverts];
+    if (g->nnz && !dev_nbr) return fail(SHMEM_ERR_INVALID_ARG);
+    for (uint32_t v = 0; v < nverts; ++v) if (row[v + 1] < row[v]) return fail(SHMEM_ERR_INVALID_ARG);
+    std::vector<uint32_t> order(nverts), to_orig(nint, SHMEM_BFS_NONE);
+    for (uint32_t v = 0; v < nverts; ++v) order[v] = v;
+    std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+        const uint64_t da = row[a + 1] - row[a], db = row[b + 1] - row[b];
+        return da != db ? da > db : a < b;
+    });
+    g->to_int.assign(nverts, 0);
+    for (uint32_t r = 0; r < nverts; ++r) {
+        const uint32_t i = (r % (uint32_t)H.npes) * vpp + r / (uint32_t)H.npes;
+        g->to_int[order[r]] = i;
+        to_orig[i] = order[r];
     }
-    g->nnz = H.pinned[32];
-    if (g->nnz && !dev_nbr) {
-        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
-        delete g;
-        return SHMEM_ERR_INVALID_ARG;
+    std::vector<uint32_t>().swap(order);
+    std::vector<uint64_t> row_int((size_t)nint + 1);
+    row_int[0] = 0;
+    for (uint32_t i = 0; i < nint; ++i) {
+        const uint32_t o = to_orig[i];
+        row_int[i + 1] = row_int[i] + (o == SHMEM_BFS_NONE ? 0 : row[o + 1] - row[o]);
     }
+    std::vector<uint64_t>().swap(row);
+    if (hipMalloc((void **)&g->d_row_int, row_int.size() * 8) != hipSuccess || hipMalloc((void **)&g->d_nbr_int, std::max<uint64_t>(g->nnz, 1) * 4) != hipSuccess ||
+        hipMalloc((void **)&g->d_to_int, (size_t)nverts * 4) != hipSuccess || hipMalloc((void **)&g->d_to_orig, (size_t)nint * 4) != hipSuccess)
+        return fail(SHMEM_ERR_NOMEM);
+    if (hipMemcpyAsync(g->d_row_int, row_int.data(), row_int.size() * 8, hipMemcpyHostToDevice, H.stream) != hipSuccess ||
+        hipMemcpyAsync(g->d_to_int, g->to_int.data(), (size_t)nverts * 4, hipMemcpyHostToDevice, H.stream) != hipSuccess ||
+        hipMemcpyAsync(g->d_to_orig, to_orig.data(), (size_t)nint * 4, hipMemcpyHostToDevice, H.stream) != hipSuccess)
+        return fail(SHMEM_ERR_DEVICE);
+    hipLaunchKernelGGL(shmemx::k_bfs_relabel, dim3((unsigned)std::max(1, H.num_cus) * 8), dim3(WG_THREADS), 0, H.stream, nint, g->d_to_orig,
+                       g->d_to_int, dev_row_off, dev_nbr, g->d_row_int, g->d_nbr_int);
+    if (hipStreamSynchronize(H.stream) != hipSuccess) return fail(SHMEM_ERR_DEVICE);   // the host vectors above are done with
+    } catch (const std::bad_alloc &) {
+        return fail(SHMEM_ERR_NOMEM);
+    }
+    s.row_off = g->d_row_int; s.nbr = g->d_nbr_int; s.to_orig = g->d_to_orig;
     s.wgs_per_pe = (uint32_t)wgs_per_pe;     // before any launch that takes the state
     g->wgs_per_pe = wgs_per_pe;
     hipLaunchKernelGGL(shmemx::k_bfs_mark_linked, dim3((unsigned)(H.npes * wgs_per_pe)), dim3(WG_THREADS), 0, H.stream,
                        ctx(), g->st);
-    if (int rc = launched()) {
-        for (int k = 0; k < g->nallocs; ++k) shmem_free(g->allocs[k]);
-        delete g;
-        return rc;
-    }
+    if (int rc = launched()) return fail(rc);
     *graph_out = g;
     return SHMEM_OK;
 }
@@ -805,6 +846,8 @@ int shmem_bfs_destroy(void *graph)
     BfsGraph *g = (BfsGraph *)graph;
     int rc = SHMEM_OK;
     for (int k = 0; k < g->nallocs; ++k) if (shmem_free(g->allocs[k]) != SHMEM_OK) rc = SHMEM_ERR_BAD_FREE;
+    if (hipStreamSynchronize(H.stream) != hipSuccess) rc = SHMEM_ERR_DEVICE;     // nothing in flight reads the graph any more
+    (void)hipFree(g->d_row_int); (void)hipFree(g->d_nbr_int); (void)hipFree(g->d_to_int); (void)hipFree(g->d_to_orig);
     delete g;
     return rc;
 }
@@ -829,7 +872,9 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     if (!graph) return SHMEM_ERR_INVALID_ARG;
     BfsGraph *g = (BfsGraph *)graph;
     const shmemx::BfsState &s = g->st;
-    if (root >= s.nverts) return SHMEM_ERR_INVALID_ARG;
+    if (root >= g->nverts_orig) return SHMEM_ERR_INVALID_ARG;
+    const uint32_t nverts = g->nverts_orig;
+    root = g->to_int[root];                                                  // the search runs on the library's numbering
     g->last_levels = 0;
     shmemx::Ctx c = ctx();
     dim3 grid((unsigned)(H.npes * g->wgs_per_pe)), block(WG_THREADS);
@@ -842,7 +887,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     uint64_t *counts = H.pinned + 16;
     // Frontiers of at least nverts / sort_div vertices are expanded from a queue in vertex order (rewritten from
     // the level's new bits); the frontier bitmap is then kept level by level in top-down searches as well.
-    const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(s.nverts / H.bfs_sort_div, 1024) : UINT64_MAX;
+    const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(nverts / H.bfs_sort_div, 1024) : UINT64_MAX;
     const bool fronts = hybrid || H.bfs_sort_div != 0;
     hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root, (int)(fronts && !hybrid));
     uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;
@@ -863,7 +908,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             // unvisited vertices; switch back when the frontier is small and shrinking
             const uint64_t m_u = g->nnz > cum_mf ? g->nnz - cum_mf : 0;
             if (!bottom_up) bottom_up = m_f > m_u / g->alpha;
-            else if (n_f < s.nverts / g->beta && n_f < n_f_prev) bottom_up = false;
+            else if (n_f < nverts / g->beta && n_f < n_f_prev) bottom_up = false;
         }
         if (!bottom_up && !queue_written) {
             hipLaunchKernelGGL(shmemx::k_bfs_fill_queue, grid, block, 0, H.stream, c, s, L);   // from the frontier bitmap
@@ -906,7 +951,7 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     st.edges_traversed = (hybrid ? counts[2] : counts[1]) / 2;
     if (g->canonical) hipLaunchKernelGGL(shmemx::k_bfs_canonical, grid, block, 0, H.stream, c, s);
     if (dev_level || dev_parent) {
-        hipLaunchKernelGGL(shmemx::k_bfs_gather, grid, block, 0, H.stream, c, s, dev_level, dev_parent);
+        hipLaunchKernelGGL(shmemx::k_bfs_gather, grid, block, 0, H.stream, c, s, nverts, g->d_to_int, dev_level, dev_parent);
         if (hipStreamSynchronize(H.stream) != hipSuccess) return SHMEM_ERR_DEVICE;
     }
     if (stats) *stats = st;
