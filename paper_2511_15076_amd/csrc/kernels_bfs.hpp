@@ -700,11 +700,17 @@ __global__ __launch_bounds__(256) void k_bfs_fill_queue(Ctx c, BfsState s, uint3
         if (total == 0) continue;
         uint64_t base = 0;
         if (lane == 0) base = atomic_fetch_add(fill, (uint64_t)total);
-        base = bcast64(base, 0) + (incl - n);
-        while (bits) {
-            const uint32_t b = (uint32_t)__builtin_ctzll(bits);
-            bits &= bits - 1;
-            queue[base++] = (uint32_t)(first + w * 64 + b);
+        base = bcast64(base, 0);
+        // word by word, the whole wave writing the vertices of one word side by side (in the library's numbering the
+        // best-connected vertices come first, so the words at the start of a block are full and the rest nearly
+        // empty: a lane writing out its own word kept the wave busy for 64 rounds of scattered stores)
+        uint64_t nonempty = ballot(n != 0);
+        while (nonempty) {
+            const uint32_t j = (uint32_t)__builtin_ctzll(nonempty);
+            nonempty &= nonempty - 1;
+            const uint64_t bj = bcast64(bits, j);
+            const uint64_t at = base + bcast32(incl - n, j);
+            if ((bj >> lane) & 1) queue[at + rank_in(bj)] = (uint32_t)(first + (w0 + j) * 64 + lane);
         }
     }
 }
