@@ -275,17 +275,25 @@ int shmem_hash_insert(uint64_t *table_sym, size_t slots_per_pe, const uint64_t *
 int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint64_t *dev_keys, size_t n,
                       uint8_t *dev_found, int wgs_per_pe);
 
-/* Level-synchronous BFS, 1D block vertex partition: owner(v) = v / vpp with
- * vpp = ceil(nverts / npes).  A vertex is claimed with fetch_or on its owner's
- * visited bitmap; the claimer reserves a slot in the owner's next-frontier
- * queue with fetch_add and puts the vertex, its parent and its level there;
- * levels are separated by quiet + barrier_all.
+/* Level-synchronous BFS over a 1D vertex partition.  A vertex is claimed with
+ * fetch_or on its owner's visited bitmap; the claimer reserves a slot in the
+ * owner's next-frontier queue with fetch_add and puts the vertex, its parent
+ * and its level there; levels are separated by quiet + barrier_all.
+ * The partition: shmem_bfs_create ranks the vertices by degree (largest first,
+ * ties by number); the vertex of rank r is local vertex r / npes of PE
+ * r mod npes, so every PE owns vpp = ceil(nverts / npes) vertices with an equal
+ * share of every degree class.  The search runs on that numbering; roots,
+ * levels and parents cross this boundary in the caller's numbering.
  * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
- * neighbours uint32[nnz]; PE p reads only its own rows) and allocates the
- * per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
+ * neighbours uint32[nnz]; they are only read during the call), writes the graph
+ * in the library's numbering into device memory that the library allocates
+ * (4 bytes per CSR entry, 8 per row, two 4-byte maps per vertex; freed by
+ * shmem_bfs_destroy; the ranking is host work, once per graph) and allocates
+ * the per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
  * long-row list and its scan, per-die bitmap copies, frontier and previous-level
  * bitmaps, counters: about 25.4 bytes per owned vertex; parent and level of a
- * vertex are one 8-byte record there, delivered with one put).  Errors: NOMEM, INVALID_ARG. */
+ * vertex are one 8-byte record there, delivered with one put).
+ * Errors: NOMEM, INVALID_ARG (also: row offsets that decrease), DEVICE. */
 typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */
