@@ -49,7 +49,7 @@ enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, 
                   // work handed out to the waves of the two top-down kernels of a level (reset with the level)
                   T_CLAIM_EXPAND = 24 /* batches of frontier vertices */, T_CLAIM_BIG = 25 /* runs of long-row segments */ };
 
-constexpr uint32_t BIG_DEGREE = 1024;  // rows at least this long go to k_bfs_big
+constexpr uint32_t BIG_DEGREE = 512;   // rows at least this long go to k_bfs_big (128 to 512 measure alike, 1024 and 64 are 4 and 7 % slower)
 constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
 constexpr uint32_t EPL = 4;            // edges per lane in flight
 constexpr uint32_t NXCD = 8;           // accelerator dies, each with a private L2
