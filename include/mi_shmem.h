@@ -293,7 +293,8 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * long-row list and its scan, per-die bitmap copies, frontier and previous-level
  * bitmaps, counters: about 25.4 bytes per owned vertex; parent and level of a
  * vertex are one 8-byte record there, delivered with one put).
- * Errors: NOMEM, INVALID_ARG (also: row offsets that decrease), DEVICE. */
+ * Errors: NOMEM, INVALID_ARG (also: row offsets that decrease, a neighbour
+ * that is not below nverts), DEVICE. */
 typedef struct {
     uint32_t nlevels;           /* number of non-empty frontiers               */
     uint64_t reached;           /* vertices with level >= 0                    */

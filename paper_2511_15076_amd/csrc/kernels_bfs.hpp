@@ -89,9 +89,12 @@ __device__ __forceinline__ uint64_t *bfs_pl_of(const Ctx &c, const BfsState &s, 
 // holding an equal share of every degree class, with the vertices that most edges point to at the start of every
 // PE's block (that is where the top-down kernels' LDS filter looks, see HubFilter).  A wave copies one row at a
 // time, in the caller's neighbour order, translating the neighbours.
-__global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, const uint32_t *__restrict__ to_orig, const uint32_t *__restrict__ to_int,
-                                                     const uint64_t *__restrict__ row_orig, const uint32_t *__restrict__ nbr_orig,
-                                                     const uint64_t *__restrict__ row_int, uint32_t *__restrict__ nbr_int)
+// A neighbour that is no vertex (>= nverts_orig) is reported through *bad (host-visible; the row's own vertex is
+// written in its place, so nothing downstream leaves its arrays) and shmem_bfs_create refuses the graph.
+__global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, uint32_t nverts_orig, const uint32_t *__restrict__ to_orig,
+                                                     const uint32_t *__restrict__ to_int, const uint64_t *__restrict__ row_orig,
+                                                     const uint32_t *__restrict__ nbr_orig, const uint64_t *__restrict__ row_int,
+                                                     uint32_t *__restrict__ nbr_int, uint64_t *bad)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
@@ -99,7 +102,11 @@ __global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, const uint32
         const uint32_t o = to_orig[i];
         if (o == SHMEM_BFS_NONE) continue;
         const uint64_t src = row_orig[o], dst = row_int[i], deg = row_int[i + 1] - dst;
-        for (uint64_t e = lane; e < deg; e += 64) nbr_int[dst + e] = to_int[nbr_orig[src + e]];
+        for (uint64_t e = lane; e < deg; e += 64) {
+            const uint32_t u = nbr_orig[src + e];
+            if (u >= nverts_orig) __hip_atomic_store(bad, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            nbr_int[dst + e] = u < nverts_orig ? to_int[u] : (uint32_t)i;
+        }
     }
 }
 

@@ -93,6 +93,23 @@ def test_bfs_on_graphs_without_edges():
                 sh.bfs_destroy(g)
 
 
+def test_bfs_create_refuses_a_broken_graph():
+    # a neighbour that is no vertex, and row offsets that decrease: refused when the graph is created (the library
+    # rewrites the adjacency in its own numbering then, so it sees every entry), nothing left allocated
+    with shmem_world(2, 1 << 20) as (heap, base):
+        row = np.array([0, 2, 3, 4, 4], dtype=np.uint64)
+        for nbr, r in ((np.array([1, 2, 0, 9], dtype=np.uint32), row),              # 9 is no vertex of a graph of 4
+                       (np.array([1, 2, 0, 0], dtype=np.uint32), np.array([0, 2, 1, 4, 4], dtype=np.uint64))):
+            with pytest.raises(sh.ShmemError) as ei:
+                sh.bfs_create(4, to_dev(r), to_dev(nbr), 1)
+            assert ei.value.status == sh.ERR_INVALID_ARG
+        assert sh.malloc(1 << 20) == base                  # the per-PE state went back to the heap
+        sh.free(base)
+        g = sh.bfs_create(4, to_dev(row), to_dev(np.array([1, 2, 0, 0], dtype=np.uint32)), 1)   # the library still works
+        assert sh.bfs(g, 0)["reached"] == 3
+        sh.bfs_destroy(g)
+
+
 def test_init_rejects_buffers_shorter_than_stated():
     # with torch's cache emptied, an allocation of 16 MiB is a block of its own and the runtime knows where it ends
     def status_of(*args):
