@@ -91,21 +91,46 @@ __device__ __forceinline__ uint64_t *bfs_pl_of(const Ctx &c, const BfsState &s, 
 // time, in the caller's neighbour order, translating the neighbours.
 // A neighbour that is no vertex (>= nverts_orig) is reported through *bad (host-visible; the row's own vertex is
 // written in its place, so nothing downstream leaves its arrays) and shmem_bfs_create refuses the graph.
-__global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, uint32_t nverts_orig, const uint32_t *__restrict__ to_orig,
+// Within a row the neighbours are put into four classes by their rank -- the best-connected 1/1024 of the
+// vertices first, then those up to 1/64, up to 1/8, and the rest -- each class in the caller's order: a bottom-up
+// level scans a row until it meets a frontier vertex, and the well-connected neighbours are the likeliest to be
+// in the frontier; top-down, neighbouring lanes then probe bits that lie close together.
+__global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, uint32_t nverts_orig, uint32_t vpp, const uint32_t *__restrict__ to_orig,
                                                      const uint32_t *__restrict__ to_int, const uint64_t *__restrict__ row_orig,
                                                      const uint32_t *__restrict__ nbr_orig, const uint64_t *__restrict__ row_int,
                                                      uint32_t *__restrict__ nbr_int, uint64_t *bad)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    const uint32_t lim0 = max(1u, vpp >> 10), lim1 = max(1u, vpp >> 6), lim2 = max(1u, vpp >> 3);
     for (uint64_t i = wave; i < nint; i += waves) {
         const uint32_t o = to_orig[i];
         if (o == SHMEM_BFS_NONE) continue;
         const uint64_t src = row_orig[o], dst = row_int[i], deg = row_int[i + 1] - dst;
-        for (uint64_t e = lane; e < deg; e += 64) {
+        auto fetch = [&](uint64_t e, uint32_t &t, uint32_t &cls) {       // neighbour e of the row in the library's numbering, its class
             const uint32_t u = nbr_orig[src + e];
             if (u >= nverts_orig) __hip_atomic_store(bad, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            nbr_int[dst + e] = u < nverts_orig ? to_int[u] : (uint32_t)i;
+            t = u < nverts_orig ? to_int[u] : (uint32_t)i;
+            const uint32_t l = t % vpp;
+            cls = l < lim0 ? 0u : l < lim1 ? 1u : l < lim2 ? 2u : 3u;
+        };
+        uint64_t at[4] = {0, 0, 0, 0};                                   // pass 1: how many of each class
+        for (uint64_t e0 = 0; e0 < deg; e0 += 64) {
+            uint32_t t = 0, cls = 4;
+            if (e0 + lane < deg) fetch(e0 + lane, t, cls);
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) at[k] += (uint64_t)__builtin_popcountll(ballot(cls == k));
+        }
+        at[3] = at[0] + at[1] + at[2]; at[2] = at[0] + at[1]; at[1] = at[0]; at[0] = 0;   // -> first place of each class
+        for (uint64_t e0 = 0; e0 < deg; e0 += 64) {                      // pass 2: every neighbour to its place
+            uint32_t t = 0, cls = 4;
+            if (e0 + lane < deg) fetch(e0 + lane, t, cls);
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint64_t m = ballot(cls == k);
+                if (cls == k) nbr_int[dst + at[k] + rank_in(m)] = t;
+                at[k] += (uint64_t)__builtin_popcountll(m);
+            }
         }
     }
 }

@@ -824,7 +824,7 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
         hipMemcpyAsync(g->d_to_orig, to_orig.data(), (size_t)nint * 4, hipMemcpyHostToDevice, H.stream) != hipSuccess)
         return fail(SHMEM_ERR_DEVICE);
     H.pinned[40] = 0;                                                        // set by the kernel if a neighbour is no vertex
-    hipLaunchKernelGGL(shmemx::k_bfs_relabel, dim3((unsigned)std::max(1, H.num_cus) * 8), dim3(WG_THREADS), 0, H.stream, nint, nverts,
+    hipLaunchKernelGGL(shmemx::k_bfs_relabel, dim3((unsigned)std::max(1, H.num_cus) * 8), dim3(WG_THREADS), 0, H.stream, nint, nverts, vpp,
                        g->d_to_orig, g->d_to_int, dev_row_off, dev_nbr, g->d_row_int, g->d_nbr_int, H.pinned + 40);
     if (hipStreamSynchronize(H.stream) != hipSuccess) return fail(SHMEM_ERR_DEVICE);   // the host vectors above are done with
     if (__atomic_load_n(H.pinned + 40, __ATOMIC_ACQUIRE) != 0) return fail(SHMEM_ERR_INVALID_ARG);
