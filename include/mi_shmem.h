@@ -286,7 +286,8 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * levels and parents cross this boundary in the caller's numbering.
  * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
  * neighbours uint32[nnz]; they are only read during the call), writes the graph
- * in the library's numbering into device memory that the library allocates
+ * in the library's numbering (within a row the best-connected neighbours
+ * first) into device memory that the library allocates
  * (4 bytes per CSR entry, 8 per row, two 4-byte maps per vertex; freed by
  * shmem_bfs_destroy; the ranking is host work, once per graph) and allocates
  * the per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
