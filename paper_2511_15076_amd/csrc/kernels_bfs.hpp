@@ -50,8 +50,11 @@ enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, 
                   T_CLAIM_EXPAND = 24 /* batches of frontier vertices */, T_CLAIM_BIG = 25 /* runs of long-row segments */ };
 
 constexpr uint32_t BIG_DEGREE = 512;   // rows at least this long go to k_bfs_big (128 to 512 measure alike, 1024 and 64 are 4 and 7 % slower)
-constexpr uint32_t SEG_EDGES = 256;    // edges per long-row segment = 64 lanes x EPL
-constexpr uint32_t EPL = 4;            // edges per lane in flight
+// edges per lane in flight: four when short rows are expanded packed, eight in the long-row kernel (measured with
+// 2 / 4 / 8 everywhere: the level that claims 7.5 M vertices 1.83 / 1.77 / 1.64 ms, the 7.5 M-vertex level of short rows
+// 1.11 / 1.05 / 1.24)
+constexpr uint32_t EPL_SHORT = 4, EPL_LONG = 8;
+constexpr uint32_t SEG_EDGES = 64 * EPL_LONG;   // edges per long-row segment
 constexpr uint32_t NXCD = 8;           // accelerator dies, each with a private L2
 constexpr uint32_t STAGE_PES = 16;     // winners are staged in LDS when npes <= this
 constexpr uint32_t STAGE_BLOCK = 64;   // staged vertices leave in blocks of this many (one 256-byte put)
@@ -257,6 +260,7 @@ __device__ __forceinline__ void bfs_flush(const Ctx &c, const BfsState &s, const
 // a fetch_or has shown the vertex to be claimed, so a set bit is always true
 // and a missing bit (first probe from this die, or a lost racy update) only
 // costs one more fetch_or.
+template <uint32_t EPL>
 struct Probe {
     uint32_t o[EPL], l[EPL];
     uint64_t *f[EPL];
@@ -268,7 +272,8 @@ struct Probe {
 // or not it is active: with exactly EPL loads per call the compiler can wait for the probes alone
 // later on; loads under a condition make it wait for everything outstanding, the neighbour loads of
 // the next chunk included.
-__device__ __forceinline__ void bfs_probe_issue(const Ctx &c, const BfsState &s, uint32_t xcd, Probe &p,
+template <uint32_t EPL>
+__device__ __forceinline__ void bfs_probe_issue(const Ctx &c, const BfsState &s, uint32_t xcd, Probe<EPL> &p,
                                                 const uint32_t (&v)[EPL])
 {
 #pragma unroll
@@ -284,12 +289,14 @@ __device__ __forceinline__ void bfs_probe_issue(const Ctx &c, const BfsState &s,
 // the chunk are issued before the first result is used: a fetch_or resolves at the memory side, so one
 // round trip covers EPL of them.  Returns false when no lane of the wave had anything to claim (the
 // common case late in a search).
+template <uint32_t EPL>
 struct Claim {
     bool need[EPL], won[EPL];
     uint64_t old[EPL];
 };
 
-__device__ __forceinline__ bool bfs_claim(const Ctx &c, const BfsState &s, const Probe &p, const bool (&act)[EPL], Claim &cl)
+template <uint32_t EPL>
+__device__ __forceinline__ bool bfs_claim(const Ctx &c, const BfsState &s, const Probe<EPL> &p, const bool (&act)[EPL], Claim<EPL> &cl)
 {
     bool any = false;
 #pragma unroll
@@ -311,9 +318,9 @@ __device__ __forceinline__ bool bfs_claim(const Ctx &c, const BfsState &s, const
 
 // second half, part two: update this die's bitmap copy, deliver parent / level, enqueue the winners.
 // (v, u) are the chunk's vertices; the caller has moved on to the next chunk's registers by now.
-template <bool STAGED>
-__device__ __forceinline__ void bfs_deliver(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L, const Probe &p,
-                                            const Claim &cl, const uint32_t (&v)[EPL], const uint32_t (&u)[EPL])
+template <bool STAGED, uint32_t EPL>
+__device__ __forceinline__ void bfs_deliver(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L, const Probe<EPL> &p,
+                                            const Claim<EPL> &cl, const uint32_t (&v)[EPL], const uint32_t (&u)[EPL])
 {
     // the queue first: a full staging block waits for its fetch_add on the owner's tail, and that wait
     // should not have the scattered stores below in front of it
@@ -353,6 +360,7 @@ struct BfsLds {
 template <bool STAGED>
 __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t L)
 {
+    constexpr uint32_t EPL = EPL_SHORT;
     __shared__ BfsLds lds;
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint32_t lane = threadIdx.x & 63, wpw = blockDim.x >> 6;
@@ -433,7 +441,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
 #pragma unroll
         for (uint32_t k = 0; k < EPL; ++k) asm volatile("" : : "v"(vv[k]));   // arrived before the loop is entered (see below)
         for (uint32_t e0 = 0; e0 < total; e0 += 64 * EPL) {
-            Probe pr;
+            Probe<EPL> pr;
             bfs_probe_issue(c, s, xcd, pr, vv);
             const bool more = e0 + 64 * EPL < total;
             fetch(more ? e0 + 64 * EPL : e0, nact, nvv, nuu);  // next neighbours travel while this chunk is probed (the last chunk asks for itself again)
@@ -442,7 +450,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
             // go out: at the top of the loop nothing then has to wait for those to drain.  (The memory
             // counter is in order: waiting for a load issued before a varying number of stores means
             // waiting for all of them.)
-            Claim cl;
+            Claim<EPL> cl;
             const bool claimed = bfs_claim(c, s, pr, act, cl);
             uint32_t cv[EPL], cu[EPL];
 #pragma unroll
@@ -450,7 +458,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
                 asm volatile("" : : "v"(nvv[k]));    // the next neighbours are waited for here, not at the top of the loop
                 cv[k] = vv[k]; cu[k] = uu[k]; act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k];
             }
-            if (claimed) bfs_deliver<STAGED>(c, s, st, L, pr, cl, cv, cu);
+            if (claimed) bfs_deliver<STAGED, EPL>(c, s, st, L, pr, cl, cv, cu);
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -508,6 +516,7 @@ constexpr uint32_t BIG_SAMPLES = 128;     // (with 512 the workgroup no longer f
 template <bool STAGED>
 __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
 {
+    constexpr uint32_t EPL = EPL_LONG;
     __shared__ BfsLds lds;
     __shared__ uint32_t sample[BIG_SAMPLES];
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
@@ -575,11 +584,11 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
 #pragma unroll
         for (uint32_t k = 0; k < EPL; ++k) asm volatile("" : : "v"(vv[k]));   // arrived before the loop is entered
         for (uint32_t t = t0; t < t1; ++t) {
-            Probe pr;
+            Probe<EPL> pr;
             bfs_probe_issue(c, s, xcd, pr, vv);
             const bool more = t + 1 < t1;
             fetch(more ? t + 1 : t, nact, nvv, nuu);         // next segment travels while this one is probed (the last asks for itself again)
-            Claim cl;
+            Claim<EPL> cl;
             const bool claimed = bfs_claim(c, s, pr, act, cl);           // (as in k_bfs_expand)
             uint32_t cv[EPL], cu[EPL];
 #pragma unroll
@@ -587,7 +596,7 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
                 asm volatile("" : : "v"(nvv[k]));    // the next neighbours are waited for here, not at the top of the loop
                 cv[k] = vv[k]; cu[k] = uu[k]; act[k] = nact[k]; vv[k] = nvv[k]; uu[k] = nuu[k];
             }
-            if (claimed) bfs_deliver<STAGED>(c, s, st, L, pr, cl, cv, cu);
+            if (claimed) bfs_deliver<STAGED, EPL>(c, s, st, L, pr, cl, cv, cu);
         }
     }
     bfs_flush<STAGED>(c, s, st, L);
