@@ -11,7 +11,7 @@
 //                  length mix (R-MAT degrees are heavily skewed);
 //   k_bfs_bigscan  prefix sum over the long rows' segment counts (one
 //                  workgroup per PE);
-//   k_bfs_big      the team's waves split the long rows' 256-edge segments
+//   k_bfs_big      the team's waves split the long rows' 512-edge segments
 //                  evenly (each wave takes a run of consecutive segments);
 //   k_bfs_level_end  frontier bitmap / degree sum (direction-optimising modes); its last workgroup
 //                  totals the next frontier, resets counters and hands the counts to the host.
@@ -506,7 +506,7 @@ __global__ __launch_bounds__(1024) void k_bfs_bigscan(Ctx c, BfsState s)
     if (threadIdx.x == 0) { scan[nbig] = carry_s; tails[T_NTASKS] = carry_s; }
 }
 
-// Long rows of level L, as 256-edge segments numbered through all the PE's long rows: a wave takes runs of
+// Long rows of level L, as 512-edge segments numbered through all the PE's long rows: a wave takes runs of
 // up to BIG_RUN consecutive segments, the first by its number, the others claimed from a counter of the PE (see above
 // k_bfs_expand).  Finding the row a run starts in is a search in the segment scan; its upper levels are a
 // sample of the scan that every workgroup keeps in LDS, so a search costs two or three dependent reads of
