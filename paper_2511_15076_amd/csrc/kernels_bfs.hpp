@@ -172,7 +172,8 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
 // ---------------------------------------------------------------------------
 // Per-wave staging of claimed vertices, one small buffer per owner in LDS.
 // A full block of STAGE_BLOCK is written to the owner's queue with ONE fetch_add
-// on its tail and one coalesced 128-byte put; the remainder goes out at kernel end.
+// on its tail and one coalesced 256-byte put; the remainder goes out at kernel end
+// (bfs_flush_workgroup).
 struct Stage {
     uint32_t *cnt;   // [STAGE_PES]
     uint32_t *buf;   // [STAGE_PES][STAGE_CAP]
@@ -229,21 +230,6 @@ __device__ __forceinline__ void bfs_enqueue(const Ctx &c, const BfsState &s, con
             if (won && o == ol) queue[base + rank_in(grp)] = v;       // put v
             m &= ~grp;
         }
-    }
-}
-
-template <bool STAGED>
-__device__ __forceinline__ void bfs_flush(const Ctx &c, const BfsState &s, const Stage &st, uint32_t L)
-{
-    if (!STAGED) return;
-    const uint32_t lane = lane_id();
-    for (uint32_t o = 0; o < (uint32_t)c.npes; ++o) {
-        const uint32_t cn = st.cnt[o];
-        if (cn == 0) continue;
-        uint64_t base = 0;
-        if (lane == 0) base = atomic_fetch_add(bfs_tails(c, s, o) + T_TAIL0 + (L + 1) % 3, (uint64_t)cn);
-        base = bcast64(base, 0);
-        if (lane < cn) ((uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], o))[base + lane] = st.buf[o * STAGE_CAP + lane];
     }
 }
 
@@ -346,7 +332,34 @@ struct BfsLds {
     uint32_t pre[4][64];
     uint32_t u[4][64];
     uint64_t r0[4][64];
+    uint64_t base[STAGE_PES];    // end of the kernel: where the workgroup's leftovers go in every owner's queue
 };
+
+// What is left in the four waves' staging buffers when the kernel ends goes out per WORKGROUP: one fetch_add per
+// owner for all four waves (the lanes of wave 0 issue them side by side), then every wave writes its entries behind
+// those of the waves before it.  A wave flushing on its own made 16 dependent round trips, and a launch put
+// 4096 adds on each of the 16 tails, which the memory takes one at a time: on the level that expands a few dozen
+// hubs -- one chunk per wave, every wave a few winners for every owner -- that was most of the kernel's time.
+// Every thread of the workgroup must call it.
+template <bool STAGED>
+__device__ __forceinline__ void bfs_flush_workgroup(const Ctx &c, const BfsState &s, BfsLds &lds, uint32_t L)
+{
+    if (!STAGED) return;
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (wave == 0 && lane < (uint32_t)c.npes) {
+        const uint32_t tot = lds.cnt[0][lane] + lds.cnt[1][lane] + lds.cnt[2][lane] + lds.cnt[3][lane];
+        lds.base[lane] = tot ? atomic_fetch_add(bfs_tails(c, s, lane) + T_TAIL0 + (L + 1) % 3, (uint64_t)tot) : 0;
+    }
+    __syncthreads();
+    for (uint32_t o = 0; o < (uint32_t)c.npes; ++o) {
+        const uint32_t cn = lds.cnt[wave][o];
+        if (cn == 0) continue;
+        uint64_t at = lds.base[o];
+        for (uint32_t w = 0; w < wave; ++w) at += lds.cnt[w][o];
+        if (lane < cn) ((uint32_t *)ptr(c, s.queue_off[(L + 1) & 1], o))[at + lane] = lds.buf[wave][o * STAGE_CAP + lane];
+    }
+}
 
 // How the top-down kernels of a level share their work inside a PE: it is CLAIMED, not dealt.  A wave takes its
 // first batch (run) by its number and every further one from a counter of the PE when it has finished the one
@@ -462,7 +475,7 @@ __global__ __launch_bounds__(256) void k_bfs_expand(Ctx c, BfsState s, uint32_t 
         }
         __builtin_amdgcn_wave_barrier();
     }
-    bfs_flush<STAGED>(c, s, st, L);
+    bfs_flush_workgroup<STAGED>(c, s, lds, L);
     // degree sum of this level's frontier -> traversed-edge count
     for (int off = 32; off > 0; off >>= 1) degsum += __shfl_down(degsum, off, 64);
     if (lane == 0 && degsum) atomic_fetch_add(tails + T_DEG_EXPANDED, degsum);
@@ -599,7 +612,7 @@ __global__ __launch_bounds__(256) void k_bfs_big(Ctx c, BfsState s, uint32_t L)
             if (claimed) bfs_deliver<STAGED, EPL>(c, s, st, L, pr, cl, cv, cu);
         }
     }
-    bfs_flush<STAGED>(c, s, st, L);
+    bfs_flush_workgroup<STAGED>(c, s, lds, L);
 }
 
 // ---------------------------------------------------------------------------
