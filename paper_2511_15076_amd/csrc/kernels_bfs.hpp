@@ -155,11 +155,10 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     uint64_t *prev = (uint64_t *)ptr(c, s.prev_off, pe);
     for (uint64_t w = rank; w < s.words; w += size)
         prev[w] = (prev_has_root && pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
-    for (uint64_t l = rank; l < s.vpp; l += size) {
-        const bool is_root = pe == ro && l == rl;
-        pl[l] = is_root ? bfs_pl(root, 0) : bfs_pl(SHMEM_BFS_NONE, -1);
-    }
+    // The (parent, level) records are NOT cleared (8 bytes per vertex, more than everything else here together):
+    // a record means something only while its vertex's bit is set in the bitmap, and every reader looks there first.
     if (rank == 0) {
+        if (pe == ro) pl[rl] = bfs_pl(root, 0);
         uint64_t *t = bfs_tails(c, s, pe);
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0; t[T_FILL] = 0;
@@ -790,9 +789,11 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
     if (first >= s.nverts) return;
     const uint64_t count = s.nverts - first < s.vpp ? s.nverts - first : s.vpp;
     uint64_t *pl = bfs_pl_of(c, s, pe);
+    const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
         const uint64_t l = w * 64 + lane;
-        const int32_t lvl = l < count ? (int32_t)(pl[l] >> 32) : -1;
+        const bool reached = l < count && ((vis[w] >> lane) & 1);     // an unreached vertex's record is stale
+        const int32_t lvl = reached ? (int32_t)(pl[l] >> 32) : -1;
         const bool need = lvl > 0;                       // reached and not the root
         // "smallest" is by the CALLER's numbers (bo), what is stored is the library's (best)
         uint32_t best = SHMEM_BFS_NONE, bo = SHMEM_BFS_NONE, deg = 0;
@@ -913,8 +914,9 @@ __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, uint32_t 
 {
     const uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, size = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t o = rank; o < nverts_orig; o += size) {
-        const uint32_t i = to_int[o], pe = bfs_owner(s, i);
-        const uint64_t rec = __builtin_nontemporal_load(bfs_pl_of(c, s, pe) + (i - pe * s.vpp));
+        const uint32_t i = to_int[o], pe = bfs_owner(s, i), l = i - pe * s.vpp;
+        const bool reached = (((const uint64_t *)ptr(c, s.bitmap_off, pe))[l >> 6] >> (l & 63)) & 1;
+        const uint64_t rec = reached ? __builtin_nontemporal_load(bfs_pl_of(c, s, pe) + l) : bfs_pl(SHMEM_BFS_NONE, -1);
         const uint32_t par = (uint32_t)rec;
         if (level) __builtin_nontemporal_store((int32_t)(rec >> 32), level + o);
         if (parent) __builtin_nontemporal_store(par == SHMEM_BFS_NONE ? SHMEM_BFS_NONE : s.to_orig[par], parent + o);
