@@ -34,10 +34,38 @@ struct BfsState {
     // symmetric offsets of the per-PE state
     uint64_t bitmap_off, pl_off, queue_off[2], big_off, bigscan_off, tails_off;   // pl: (parent, level) pairs, 8 bytes per vertex
     uint64_t filter_off;         // NXCD private copies of the bitmap (initiator-side cache, see bfs_probe)
-    uint64_t front_off, prev_off; // frontier bitmap and the bitmap as of the previous level (bottom-up levels)
+    uint64_t front_off, prev_off; // frontier bitmap and the bitmap as of the previous level (bottom-up levels; prev in the claim bitmap's layout)
     uint64_t linked_off;          // bit set = the vertex has at least one neighbour (never changes)
     uint32_t wgs_per_pe;
+    // Layout of the bitmap that takes the claims (bitmap_off only; the die copies, front, prev and linked keep
+    // word w at place w): 0 = word w at place w, else log2 of the block of words inside which 16 consecutive words
+    // are spread over 16 different 128-byte lines (see bfs_vis_word).
+    uint32_t vis_block_log2;
 };
+
+// Place of bitmap word w (bits of local vertices 64 w .. 64 w + 63) in the owner's claim bitmap.  Atomics on ONE
+// 128-byte line are served one after the other whatever words of the line they name (measured: 256 words take 3 G
+// fetch_or/s when they fill 16 lines and 21 G/s on a line each), and in the degree-ranked numbering the
+// best-connected vertices are the first words of every PE: side by side they would share a line per PE, which the
+// claims of a level that expands a few hubs then queue up on.  Inside an aligned block of B words (B / 16 lines)
+// word i of the block goes to line i mod (B / 16), slot i / (B / 16); a last, incomplete block stays as it is.
+__device__ __forceinline__ uint64_t bfs_vis_word(const BfsState &s, uint64_t w)
+{
+    if (s.vis_block_log2 == 0) return w;
+    const uint64_t B = 1ull << s.vis_block_log2, blk = w & ~(B - 1);
+    if (blk + B > s.words) return w;
+    const uint64_t i = w & (B - 1);
+    return blk | ((i & ((B >> 4) - 1)) << 4) | (i >> (s.vis_block_log2 - 4));
+}
+
+// ... and back: the bitmap word that lives at place q
+__device__ __forceinline__ uint64_t bfs_vis_word_at(const BfsState &s, uint64_t q)
+{
+    if (s.vis_block_log2 == 0) return q;
+    const uint64_t B = 1ull << s.vis_block_log2, blk = q & ~(B - 1);
+    if (blk + B > s.words) return q;
+    return blk | ((q & 15) << (s.vis_block_log2 - 4)) | ((q & (B - 1)) >> 4);
+}
 
 // words inside the per-PE tails block (uint64 each)
 enum : uint32_t { T_TAIL0 = 0 /* three rotating frontier counts */, T_NBIG = 4, T_NTASKS = 5,
@@ -149,12 +177,12 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     uint64_t *bm = (uint64_t *)ptr(c, s.bitmap_off, pe);
     uint64_t *pl = bfs_pl_of(c, s, pe);
     for (uint64_t w = rank; w < s.words; w += size)
-        bm[w] = (pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
+        bm[w] = (pe == ro && w == bfs_vis_word(s, rl >> 6)) ? 1ull << (rl & 63) : 0ull;
     uint64_t *flt = (uint64_t *)ptr(c, s.filter_off, pe);
     for (uint64_t w = rank; w < s.words * NXCD; w += size) flt[w] = 0;
     uint64_t *prev = (uint64_t *)ptr(c, s.prev_off, pe);
     for (uint64_t w = rank; w < s.words; w += size)
-        prev[w] = (prev_has_root && pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
+        prev[w] = (prev_has_root && pe == ro && w == bfs_vis_word(s, rl >> 6)) ? 1ull << (rl & 63) : 0ull;   // laid out like the claim bitmap
     // The (parent, level) records are NOT cleared (8 bytes per vertex, more than everything else here together):
     // a record means something only while its vertex's bit is set in the bitmap, and every reader looks there first.
     if (rank == 0) {
@@ -295,7 +323,7 @@ __device__ __forceinline__ bool bfs_claim(const Ctx &c, const BfsState &s, const
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k)
         if (cl.need[k])
-            cl.old[k] = atomic_fetch_or((uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + (p.l[k] >> 6), 1ull << (p.l[k] & 63));   // the claim
+            cl.old[k] = atomic_fetch_or((uint64_t *)ptr(c, s.bitmap_off, p.o[k]) + bfs_vis_word(s, p.l[k] >> 6), 1ull << (p.l[k] & 63));   // the claim
 #pragma unroll
     for (uint32_t k = 0; k < EPL; ++k) cl.won[k] = cl.need[k] && !(cl.old[k] & (1ull << (p.l[k] & 63)));
     return true;
@@ -667,7 +695,8 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
     uint64_t mf = 0;
     uint32_t nfound = 0;   // wave-uniform
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
-        const uint64_t visw = vis[w];
+        const uint64_t vw = bfs_vis_word(s, w);
+        const uint64_t visw = vis[vw];
         const uint64_t todo = ~visw & linked[w];         // unvisited vertices that have neighbours
         if (todo == 0) continue;
         const uint64_t l = w * 64 + lane;
@@ -708,7 +737,7 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
         const bool found = par != SHMEM_BFS_NONE;
         const uint64_t fm = ballot(found);
         if (fm == 0) continue;
-        if (lane == 0) vis[w] = visw | fm;               // this wave is the only writer of the word
+        if (lane == 0) vis[vw] = visw | fm;              // this wave is the only writer of the word
         nfound += (uint32_t)__builtin_popcountll(fm);
         if (found) {
             pl[l] = bfs_pl(par, (int32_t)(L + 1));
@@ -792,7 +821,7 @@ __global__ __launch_bounds__(256) void k_bfs_canonical(Ctx c, BfsState s)
     const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
     for (uint64_t w = my_wave; w * 64 < count; w += team_waves) {
         const uint64_t l = w * 64 + lane;
-        const bool reached = l < count && ((vis[w] >> lane) & 1);     // an unreached vertex's record is stale
+        const bool reached = l < count && ((vis[bfs_vis_word(s, w)] >> lane) & 1);     // an unreached vertex's record is stale
         const int32_t lvl = reached ? (int32_t)(pl[l] >> 32) : -1;
         const bool need = lvl > 0;                       // reached and not the root
         // "smallest" is by the CALLER's numbers (bo), what is stored is the library's (best)
@@ -849,10 +878,12 @@ __global__ __launch_bounds__(256) void k_bfs_level_end(Ctx c, BfsState s, uint32
     if (do_front) {
         const uint64_t *vis = (const uint64_t *)ptr(c, s.bitmap_off, pe);
         uint64_t *front = (uint64_t *)ptr(c, s.front_off, pe), *prev = (uint64_t *)ptr(c, s.prev_off, pe);
-        for (uint64_t w = rank; w < s.words; w += size) {
-            const uint64_t v = vis[w];
-            front[w] = v & ~prev[w];
-            prev[w] = v;
+        // vis and prev are walked as they lie (prev has the claim bitmap's layout); only the frontier word is
+        // stored where its number says
+        for (uint64_t q = rank; q < s.words; q += size) {
+            const uint64_t v = vis[q];
+            front[bfs_vis_word_at(s, q)] = v & ~prev[q];
+            prev[q] = v;
         }
     }
     if (do_degree) {
@@ -915,7 +946,7 @@ __global__ __launch_bounds__(256) void k_bfs_gather(Ctx c, BfsState s, uint32_t 
     const uint64_t rank = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, size = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t o = rank; o < nverts_orig; o += size) {
         const uint32_t i = to_int[o], pe = bfs_owner(s, i), l = i - pe * s.vpp;
-        const bool reached = (((const uint64_t *)ptr(c, s.bitmap_off, pe))[l >> 6] >> (l & 63)) & 1;
+        const bool reached = (((const uint64_t *)ptr(c, s.bitmap_off, pe))[bfs_vis_word(s, l >> 6)] >> (l & 63)) & 1;
         const uint64_t rec = reached ? __builtin_nontemporal_load(bfs_pl_of(c, s, pe) + l) : bfs_pl(SHMEM_BFS_NONE, -1);
         const uint32_t par = (uint32_t)rec;
         if (level) __builtin_nontemporal_store((int32_t)(rec >> 32), level + o);

@@ -782,6 +782,12 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
     const uint32_t nint = (uint32_t)nint64;
     s.nverts = nint; s.vpp = vpp; s.words = words;
     s.shift = (vpp & (vpp - 1)) == 0 ? (int)__builtin_ctz(vpp) : -1;
+    // blocks of up to 4096 words (256 lines) inside which the claim bitmap spreads neighbouring words over lines
+    s.vis_block_log2 = 0;
+    if (words >= 32) {
+        uint32_t lg = 63u - (uint32_t)__builtin_clzll((unsigned long long)words);
+        s.vis_block_log2 = lg > 12 ? 12 : lg;
+    }
     s.bitmap_off = offs[0]; s.pl_off = offs[1];
     s.queue_off[0] = offs[2]; s.queue_off[1] = offs[3]; s.big_off = offs[4]; s.bigscan_off = offs[5];
     s.tails_off = offs[6]; s.filter_off = offs[7]; s.front_off = offs[8]; s.prev_off = offs[9]; s.linked_off = offs[10];
