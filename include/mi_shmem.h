@@ -313,7 +313,8 @@ int shmem_bfs_destroy(void *graph);
  * level and queue entry are then local writes -- when the frontier's row lengths
  * add up to more than 1/alpha of those of the unvisited vertices, and back to
  * top-down when the frontier is below nverts/beta and shrinking (alpha, beta = 0:
- * the defaults, 30 and 24).  BOTTOM_UP forces bottom-up on every level (for
+ * the defaults, 30 and 24); the root's own level is always expanded top-down (its
+ * frontier is one vertex).  BOTTOM_UP forces bottom-up on every level (for
  * tests).  Levels, frontier sizes and counts are the same in every mode; parents
  * may differ (all are valid).  OR-ing SHMEM_BFS_CANONICAL_PARENTS into the mode
  * adds a pass after the search that rewrites every parent to the smallest

@@ -168,8 +168,11 @@ __global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, uint32_t nve
 
 // Every owner clears its slice; the root's owner seeds the search.
 // `prev_has_root`: the snapshot of the bitmap "as of the previous level" starts with the root in it (searches
-// that derive a level's frontier bitmap from the first level on without a level-end pass for level 0).
-__global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t root, int prev_has_root)
+// that derive a level's frontier bitmap level by level).  `make_front` (direction-optimising modes): level 0's
+// frontier bitmap, the root alone, and its row length as the first degree sum.  The root's row length also goes
+// to `host_root_deg` (GPU-mapped host memory).
+__global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t root, int prev_has_root, int make_front,
+                                                  uint64_t *host_root_deg)
 {
     const uint32_t pe = blockIdx.x / s.wgs_per_pe, wg = blockIdx.x % s.wgs_per_pe;
     const uint64_t rank = (uint64_t)wg * blockDim.x + threadIdx.x, size = (uint64_t)s.wgs_per_pe * blockDim.x;
@@ -183,6 +186,10 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
     uint64_t *prev = (uint64_t *)ptr(c, s.prev_off, pe);
     for (uint64_t w = rank; w < s.words; w += size)
         prev[w] = (prev_has_root && pe == ro && w == bfs_vis_word(s, rl >> 6)) ? 1ull << (rl & 63) : 0ull;   // laid out like the claim bitmap
+    if (make_front) {
+        uint64_t *front = (uint64_t *)ptr(c, s.front_off, pe);
+        for (uint64_t w = rank; w < s.words; w += size) front[w] = (pe == ro && w == (rl >> 6)) ? 1ull << (rl & 63) : 0ull;
+    }
     // The (parent, level) records are NOT cleared (8 bytes per vertex, more than everything else here together):
     // a record means something only while its vertex's bit is set in the bitmap, and every reader looks there first.
     if (rank == 0) {
@@ -191,7 +198,12 @@ __global__ __launch_bounds__(256) void k_bfs_init(Ctx c, BfsState s, uint32_t ro
         t[T_TAIL0 + 0] = pe == ro ? 1 : 0; t[T_TAIL0 + 1] = 0; t[T_TAIL0 + 2] = 0;
         t[T_NBIG] = 0; t[T_NTASKS] = 0; t[T_ARRIVE] = 0; t[T_DEG_EXPANDED] = 0; t[T_DEG_FOUND] = 0; t[T_FILL] = 0;
         t[T_CLAIM_EXPAND] = 0; t[T_CLAIM_BIG] = 0;
-        if (pe == ro) ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
+        if (pe == ro) {
+            ((uint32_t *)ptr(c, s.queue_off[0], pe))[0] = root;
+            const uint64_t deg = s.row_off[root + 1] - s.row_off[root];
+            if (make_front) t[T_DEG_FOUND] = deg;
+            host_root_deg[0] = deg;
+        }
         if (pe == 0) c.scratch[W_WORK + 4] = 0;   // arrival count of the level-end kernel
     }
 }

@@ -64,6 +64,7 @@ struct BfsGraph {
     bool canonical;    // rewrite the parents into the canonical tree after the search
     uint32_t alpha, beta;  // direction thresholds
     uint64_t nnz;      // CSR entries (sum of all row lengths)
+    uint32_t n_long;   // vertices with rows of BIG_DEGREE entries and more: the first n_long of the degree ranking
     void *allocs[12];
     int nallocs;
     // the graph in the library's numbering (device memory the library allocates at creation and frees at destruction)
@@ -809,7 +810,9 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
         return da != db ? da > db : a < b;
     });
     g->to_int.assign(nverts, 0);
+    g->n_long = 0;
     for (uint32_t r = 0; r < nverts; ++r) {
+        if (row[order[r] + 1] - row[order[r]] >= shmemx::BIG_DEGREE) g->n_long = r + 1;
         const uint32_t i = (r % (uint32_t)H.npes) * vpp + r / (uint32_t)H.npes;
         g->to_int[order[r]] = i;
         to_orig[i] = order[r];
@@ -897,12 +900,13 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
     // the level's new bits); the frontier bitmap is then kept level by level in top-down searches as well.
     const uint64_t sort_from = H.bfs_sort_div ? std::max<uint64_t>(nverts / H.bfs_sort_div, 1024) : UINT64_MAX;
     const bool fronts = hybrid || H.bfs_sort_div != 0;
-    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root, (int)(fronts && !hybrid));
+    // The start also leaves what a level end would: the root as the frontier bitmap and as the previous level's
+    // snapshot, its row length as the first degree sum (direction-optimising modes) and, for the host, in counts[4],
+    // which is read after the first level (its hand-over orders the two).  Level 0 therefore runs top-down in the
+    // direction-optimising mode whatever the root's degree: its frontier is one vertex.
+    hipLaunchKernelGGL(shmemx::k_bfs_init, grid, block, 0, H.stream, c, s, root, (int)fronts, (int)hybrid, counts + 4);
     uint64_t n_f = 1, n_f_prev = 0, m_f = 0, cum_mf = 0;
-    if (hybrid) {
-        if (int rc = bfs_level_end(s, 0u, true, true, g->wgs_per_pe, counts)) return rc;
-        m_f = cum_mf = counts[2];
-    }
+    const uint32_t root_rank = (root % s.vpp) * (uint32_t)H.npes + root / s.vpp;
     st.frontier_size[0] = 1;
     st.reached = 1;
     bool bottom_up = false;
@@ -930,14 +934,18 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
             s2.wgs_per_pe = s.wgs_per_pe * 2;
             hipLaunchKernelGGL(shmemx::k_bfs_bottomup, dim3(grid.x * 2), block, 0, H.stream, c, s2, L);
             queue_written = false;
-        } else if (staged) {
-            hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
-            hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
-            hipLaunchKernelGGL(shmemx::k_bfs_big<true>, grid, block, 0, H.stream, c, s, L);
         } else {
-            hipLaunchKernelGGL(shmemx::k_bfs_expand<false>, grid, block, 0, H.stream, c, s, L);
-            hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
-            hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
+            // the long-row pass is left out where the host can tell that the frontier has no long row: the root by
+            // its rank, a later frontier by its degree sum (known in the direction-optimising modes) -- the first and
+            // the last levels of a search, which are little more than their launches
+            const bool no_long = g->n_long == 0 || (L == 0 ? root_rank >= g->n_long : (hybrid && m_f < shmemx::BIG_DEGREE));
+            if (staged) hipLaunchKernelGGL(shmemx::k_bfs_expand<true>, grid, block, 0, H.stream, c, s, L);
+            else hipLaunchKernelGGL(shmemx::k_bfs_expand<false>, grid, block, 0, H.stream, c, s, L);
+            if (!no_long) {
+                hipLaunchKernelGGL(shmemx::k_bfs_bigscan, dim3((unsigned)H.npes), dim3(1024), 0, H.stream, c, s);
+                if (staged) hipLaunchKernelGGL(shmemx::k_bfs_big<true>, grid, block, 0, H.stream, c, s, L);
+                else hipLaunchKernelGGL(shmemx::k_bfs_big<false>, grid, block, 0, H.stream, c, s, L);
+            }
         }
         if (int rc = bfs_level_end(s, L + 1, fronts, hybrid && !bottom_up, g->wgs_per_pe, counts)) return rc;
         if (L < 64) {
@@ -952,7 +960,10 @@ int shmem_bfs(void *graph, uint32_t root, int32_t *dev_level, uint32_t *dev_pare
         if (L < 64) st.frontier_size[L] = counts[0];
         st.reached += counts[0];
         n_f_prev = n_f; n_f = counts[0];
-        if (hybrid) { m_f = counts[2] - cum_mf; cum_mf = counts[2]; }
+        if (hybrid) {
+            if (L == 1) cum_mf = counts[4];          // the root's row length, written by the start of the search
+            m_f = counts[2] - cum_mf; cum_mf = counts[2];
+        }
     }
     st.nlevels = L;
     g->last_levels = L < 64 ? L : 64;
