@@ -482,6 +482,9 @@ def extra_bfs(sh, torch, ceilings=None, scale=24, npes=16, wgs=64, nroots=64):
                                        "achieved": round(stream_bytes / med_ms / 1e6, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                        "frac": round(stream_bytes / med_ms / 1e6 / HBM_PEAK_GBS, 4),
                                        "GTEPS_at_peak": round(hm / (stream_bytes / med_ms / 1e6 / HBM_PEAK_GBS), 1)}}
+            if name != "top_down":
+                res["roofline_stream"]["note"] = ("the bytes are those of the top-down method (every reached vertex's whole row); a bottom-up "
+                                                  "level stops at a row's first frontier neighbour, so this is an effective rate, not traffic")
             if name == "top_down" and "randread8_2MiB_Gops" in c:
                 pr = float(np.median(probes))
                 res["roofline_probes"] = {"bound": "L2 random-probe rate", "ceiling": c["randread8_2MiB_Gops"], "unit": "G probes/s",
