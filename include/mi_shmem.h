@@ -222,13 +222,16 @@ int shmem_op_batch_noalloc(int npes, size_t heap_bytes_per_pe, void *dev_heap, c
  * PUT/GET move `count` bytes; IPUT/IGET move `count` elements of elem_bytes
  * with the given strides (local_stride applies to the local side).  The ops of
  * a cell are independent and unordered; completion is the kernel boundary.
- * Bandwidth cells -- PUT/GET of 1 KiB and more with 16-byte aligned sizes and
+ * Bandwidth cells -- PUT/GET of 256 bytes and more with 16-byte aligned sizes and
  * placement, asked for with at least one workgroup per compute unit -- run on
  * one larger workgroup per compute unit (compute units / npes per PE) that
  * streams through LDS at a paced rate.  Where a PE's operations make enough
  * work (whole multiples of 4 KiB: at least 32 tasks of 4 KiB per workgroup in
  * whole blocks of four; other sizes: messages that fill at least nine tenths
- * of their 1 KiB rows, at least 128 rows per workgroup) the workgroups claim
+ * of their 1 KiB rows, at least 128 rows per workgroup; messages of 512 bytes,
+ * and of 256 bytes when fewer than 128 workgroups per PE are asked for, two or
+ * four to a row, if ops_per_pe and nslots are multiples of that and the rows are
+ * as many) the workgroups claim
  * it block by block from a per-PE counter in the scratch words (the counters
  * are zero between launches; MI_SHMEM_STREAM_DYNAMIC=0 in the environment of
  * shmem_init switches that off); else whole multiples of 4 KiB walk fixed

@@ -240,9 +240,17 @@ struct RowWalker {
     }
 };
 
+// Messages of 256 or 512 bytes (any power of two from 16 up would do): a row is 1024 / count consecutive operations (their slots are consecutive,
+// the host sees to it that a row never wraps round the slots), walked as one operation of one row whose slot
+// pitch is that of the whole group; inside the row every lane adds the place of its own message.
+struct StreamPacked : StreamRows {
+    uint32_t lane_s, lane_d;    // this lane's 16 bytes inside the group, on the source and on the destination side
+};
+
 template <class Plan> struct StreamWalk;
 template <> struct StreamWalk<StreamPlan> { typedef BlockWalker type; };
 template <> struct StreamWalk<StreamRows> { typedef RowWalker type; };
+template <> struct StreamWalk<StreamPacked> { typedef RowWalker type; };
 
 typedef __attribute__((address_space(3))) uint32_t lds_u32_t;
 typedef __attribute__((address_space(1))) uint64_t glb_u64_t;
@@ -265,7 +273,8 @@ __device__ __forceinline__ void stream_copy_dyn(const Plan &p, uint64_t *claim, 
                                                 uint32_t nteams, uint32_t claim_stride, uint8_t *ring, uint32_t *q_generic)
 {
     constexpr uint32_t S = ST_RING, B = ST_BLOCK, Q = ST_QUEUE;
-    constexpr bool ROWS = __is_same(Plan, StreamRows);
+    constexpr bool PACKED = __is_same(Plan, StreamPacked);
+    constexpr bool ROWS = __is_same(Plan, StreamRows) || PACKED;
     static_assert(ST_STATIC * B >= S && (Q & (Q - 1)) == 0 && Q >= ST_STATIC + S / B + 4, "queue and static prefix cover the read-ahead");
     volatile lds_u32_t *const q = (volatile lds_u32_t *)q_generic;
     const uint32_t lane16 = (threadIdx.x & 63) * 16;
@@ -292,7 +301,9 @@ __device__ __forceinline__ void stream_copy_dyn(const Plan &p, uint64_t *claim, 
                 ++w.j;
             }
             const uint8_t *g;
-            if constexpr (ROWS) {
+            if constexpr (PACKED) {
+                g = p.src + (uint64_t)w.slot * p.spitch + p.lane_s;
+            } else if constexpr (ROWS) {
                 // (the lanes beyond a short last row fetch its last vector once more: nothing is predicated, and the
                 // writers, which do the same, put the same bytes in the same place)
                 const uint32_t at = min(lane16, (w.r + 1 == p.rpo ? p.tail : 1024u) - 16);
@@ -329,8 +340,14 @@ __device__ __forceinline__ void stream_copy_dyn(const Plan &p, uint64_t *claim, 
                     wb.start(p, blk, wr + ST_WRITERS);
                     ++wa.j;
                 }
-                uint8_t *da = p.dst + (uint64_t)wa.slot * p.dpitch + (uint64_t)wa.r * 1024 + min(lane16, (wa.r + 1 == p.rpo ? p.tail : 1024u) - 16);
-                uint8_t *db = p.dst + (uint64_t)wb.slot * p.dpitch + (uint64_t)wb.r * 1024 + min(lane16, (wb.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                uint8_t *da, *db;
+                if constexpr (PACKED) {
+                    da = p.dst + (uint64_t)wa.slot * p.dpitch + p.lane_d;
+                    db = p.dst + (uint64_t)wb.slot * p.dpitch + p.lane_d;
+                } else {
+                    da = p.dst + (uint64_t)wa.slot * p.dpitch + (uint64_t)wa.r * 1024 + min(lane16, (wa.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                    db = p.dst + (uint64_t)wb.slot * p.dpitch + (uint64_t)wb.r * 1024 + min(lane16, (wb.r + 1 == p.rpo ? p.tail : 1024u) - 16);
+                }
                 wa.next(p); wb.next(p);
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_barrier();
@@ -503,6 +520,36 @@ __global__ __launch_bounds__(ST_DYN_THREADS) void k_copy_sweep_stream_rows(Ctx c
     p.step_r = 4 % p.rpo; p.step_s = 4 / p.rpo;
     p.nslots = a.nslots;
     p.nrows = p.rpo * a.ops_per_pe;
+    p.team = a.team; p.rank = blockIdx.x % a.team;
+    p.rot = (uint32_t)(((uint64_t)ST_ROT * 4 * pe) % p.nrows);
+    p.period = a.period;
+    uint64_t *const claim0 = &c.scratch[W_PE_BASE + 8];
+    stream_copy_dyn(p, claim0 + (uint64_t)pe * W_PE_WORDS, &c.scratch[W_WORK + 8], claim0, (uint32_t)c.npes, W_PE_WORDS, ring, q);
+}
+
+// Dynamic claiming for messages of 256 or 512 bytes (a power of two below 1024), 1024 / count of them per row (ops_per_pe and nslots are
+// multiples of that, the group's pitch is below 2^32; at least 2 * ST_STATIC blocks of rows per workgroup).
+__global__ __launch_bounds__(ST_DYN_THREADS) void k_copy_sweep_stream_packed(Ctx c, StreamSweepArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t ring[ST_RING * ST_CHUNK];
+    __shared__ uint32_t q[ST_QUEUE + 1];
+    const uint32_t pe = blockIdx.x / a.team, peer = (pe + 1) % (uint32_t)c.npes;
+    uint8_t *const lbase = ptr(c, a.local_off, pe);
+    uint8_t *const rbase = ptr(c, a.remote_off, peer);
+    const bool is_put = a.kind == SHMEM_OP_PUT;
+    const uint32_t count = (uint32_t)a.count, per_row = 1024 / count, lane16 = (threadIdx.x & 63) * 16;
+    const uint64_t spitch = is_put ? a.local_slot : a.remote_slot, dpitch = is_put ? a.remote_slot : a.local_slot;
+    StreamPacked p;
+    p.src = is_put ? lbase : rbase;
+    p.dst = is_put ? rbase : lbase;
+    p.spitch = spitch * per_row;
+    p.dpitch = dpitch * per_row;
+    p.lane_s = (uint32_t)((lane16 / count) * spitch) + lane16 % count;
+    p.lane_d = (uint32_t)((lane16 / count) * dpitch) + lane16 % count;
+    p.rpo = 1; p.tail = 1024;
+    p.step_r = 0; p.step_s = 4;
+    p.nslots = a.nslots / per_row;
+    p.nrows = a.ops_per_pe / per_row;
     p.team = a.team; p.rank = blockIdx.x % a.team;
     p.rot = (uint32_t)(((uint64_t)ST_ROT * 4 * pe) % p.nrows);
     p.period = a.period;

@@ -295,7 +295,18 @@ int sweep_stream_kind(bool is_strided, uint64_t count, uint64_t remote_slot, uin
     const bool dynamic = H.stream_dynamic && team > 1;
     if (whole && dynamic && ntasks % shmemx::ST_BLOCK == 0 && ntasks < (1ull << 31) &&
         ntasks / shmemx::ST_BLOCK >= 2ull * shmemx::ST_STATIC * team) return 1;
-    const uint64_t rpo = (count + 1023) / 1024, nrows = rpo * (uint64_t)ops_per_pe, rows_per_block = 4 * shmemx::ST_BLOCK;
+    const uint64_t rows_per_block = 4 * shmemx::ST_BLOCK;
+    if (dynamic && (count == 512 || (count == 256 && wgs_per_pe < 128))) {
+        // several messages to a row: whole groups only, a group never wraps round the slots.  (Measured at 65,536
+        // messages per PE, launches of 30 to 90 us in which the streaming kernel's start and end weigh: 512 bytes
+        // 0.65 / 0.70 / 0.73 of peak on the register path with 32 / 64 / 256 workgroups per PE asked for, 0.75 here;
+        // 256 bytes 0.60 / 0.67 / 0.70 against 0.68; 128 bytes 0.57 / 0.58 / 0.62 against 0.55, so those stay.)
+        const uint64_t per_row = 1024 / count;
+        if (ops_per_pe % per_row == 0 && nslots % per_row == 0 && std::max(remote_slot, local_slot) * per_row < (1ull << 32) &&
+            (uint64_t)ops_per_pe / per_row / rows_per_block >= 2ull * shmemx::ST_STATIC * team) return 4;
+        return 0;
+    }
+    const uint64_t rpo = (count + 1023) / 1024, nrows = rpo * (uint64_t)ops_per_pe;
     if (dynamic && count * 10 >= rpo * 1024 * 9 && nrows < (1ull << 31) &&
         nrows / rows_per_block >= 2ull * shmemx::ST_STATIC * team) return 3;
     if (!whole || ntasks >= UINT32_MAX || ntasks < (uint64_t)team * shmemx::ST_RING) return 0;
@@ -656,6 +667,8 @@ int shmem_copy_sweep(int kind, void *remote_sym, void *local_sym, size_t count, 
             hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_dyn, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
         else if (how == 3)
             hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_rows, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
+        else if (how == 4)
+            hipLaunchKernelGGL(shmemx::k_copy_sweep_stream_packed, dim3(grid), dim3(shmemx::ST_DYN_THREADS), 0, H.stream, ctx(), sa);
         else
             hipLaunchKernelGGL(shmemx::k_copy_sweep_stream, dim3(grid), dim3(shmemx::ST_THREADS), 0, H.stream, ctx(), sa);
         return launched();
@@ -675,7 +688,7 @@ int shmem_copy_sweep_geometry(int kind, void *remote_sym, void *local_sym, size_
     const int how = sweep_stream_kind(kind >= SHMEM_OP_IPUT, count, remote_slot_bytes, local_slot_bytes, off_of(remote_sym),
                                       off_of(local_sym), nslots, ops_per_pe, wgs_per_pe, &team);
     if (workgroups_out) *workgroups_out = how ? H.npes * (int)team : H.npes * wgs_per_pe;
-    if (threads_out) *threads_out = how == 1 || how == 3 ? (int)shmemx::ST_DYN_THREADS : how == 2 ? (int)shmemx::ST_THREADS : WG_THREADS;
+    if (threads_out) *threads_out = how == 1 || how == 3 || how == 4 ? (int)shmemx::ST_DYN_THREADS : how == 2 ? (int)shmemx::ST_THREADS : WG_THREADS;
     return SHMEM_OK;
 }
 

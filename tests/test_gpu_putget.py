@@ -341,6 +341,13 @@ STREAM_CASES = [
     (8, workgen.OP_PUT, 2048, 8190, 8190, 32),           # rows not a multiple of sixteen: the last block is short
     (8, workgen.OP_GET, 14336, 301, 301, 64),            # 4214 rows: six rows in the last block; two of the last task's rows are none
     (4, workgen.OP_PUT, 1024, 8195, 1000, 64),           # an odd number of rows
+    (8, workgen.OP_PUT, 512, 8192, 1000, 32),            # from here on: several messages to a row
+    (8, workgen.OP_GET, 256, 16400, 500, 64),            # 4100 rows: the last block is short
+    (4, workgen.OP_PUT, 256, 32776, 4096, 64),
+    (4, workgen.OP_PUT, 128, 65544, 4096, 64),           # register path: too short for the streaming kernel to pay
+    (8, workgen.OP_GET, 256, 16400, 500, 128),           # the same
+    (8, workgen.OP_GET, 512, 8200, 8200, 256),
+    (8, workgen.OP_PUT, 256, 16384, 1001, 32),           # the slots are no whole groups: register path
     (8, workgen.OP_PUT, 2048, 1000, 1000, 32),           # too few rows to claim, and no whole 4 KiB tasks: not streamed
     (8, workgen.OP_PUT, 14352, 600, 600, 64),            # the 14,352-byte dispatch message: fourteen rows and 16 bytes
     (8, workgen.OP_GET, 4080, 4100, 999, 32),            # a last row 16 bytes short
@@ -350,17 +357,22 @@ STREAM_CASES = [
 ]
 
 
-def _stream_threads(npes, count, nops, dynamic=True):
+def _stream_threads(npes, count, nops, dynamic=True, nslots=None, wgs=0):
     """Workgroup size the library is expected to choose for a streaming cell: 448 (a seventh wave that claims the
     work) either for whole 4 KiB tasks in whole blocks of four, at least eight blocks per workgroup, or for 1 KiB
     rows when the messages fill at least nine tenths of their rows and the PE's rows make at least eight blocks of
-    sixteen per workgroup; else 384 (fixed shares of 4 KiB tasks, at least sixteen per workgroup); 256 for cells
-    that do not stream."""
+    sixteen per workgroup, or for messages of 512 bytes (256 bytes when fewer than 128 workgroups per PE are asked
+    for) in whole groups of one row with as many rows;
+    else 384 (fixed shares of 4 KiB tasks, at least sixteen per workgroup); 256 for cells that do not stream."""
     if count % 16:
         return 256
     team, rpo, whole, ntasks = 256 // npes, (count + 1023) // 1024, count % 4096 == 0, count // 4096 * nops
     rows = rpo * nops
     claiming = dynamic and team > 1
+    if count in (128, 256, 512):
+        per_row = 1024 // count
+        ok = claiming and (count == 512 or (count == 256 and wgs < 128)) and nops % per_row == 0 and (nslots or nops) % per_row == 0 and nops // per_row // 16 >= 8 * team
+        return 448 if ok else 256
     if whole and claiming and ntasks % 4 == 0 and ntasks // 4 >= 8 * team:
         return 448
     if claiming and count * 10 >= rpo * 1024 * 9 and rows // 16 >= 8 * team:
@@ -373,7 +385,7 @@ def _stream_threads(npes, count, nops, dynamic=True):
 def test_copy_sweep_streaming_cell(case, dynamic, monkeypatch):
     npes, kind, count, nops, nslots, wgs = case
     if not dynamic:
-        if _stream_threads(npes, count, nops) != 448:
+        if _stream_threads(npes, count, nops, True, nslots, wgs) != 448:
             pytest.skip("this cell has a fixed task assignment anyway")
         monkeypatch.setenv("MI_SHMEM_STREAM_DYNAMIC", "0")        # read by shmem_init
     rslot = count + 4096 + 256
@@ -394,7 +406,7 @@ def test_copy_sweep_streaming_cell(case, dynamic, monkeypatch):
         heap.copy_(torch.from_numpy(init.reshape(-1)))
         wgs_launched, threads = sh.copy_sweep_geometry(kind, base + remote_off, base + local_off, count, rslot, lslot, nslots,
                                                        nops, wgs)
-        assert threads == _stream_threads(npes, count, nops, dynamic)
+        assert threads == _stream_threads(npes, count, nops, dynamic, nslots, wgs)
         assert wgs_launched == (npes * (256 // npes) if threads != 256 else npes * wgs)
         sh.copy_sweep(kind, base + remote_off, base + local_off, count, 1, 1, 1, rslot, lslot, nslots, nops, wgs)
         sh.stream_sync()
