@@ -354,6 +354,25 @@ def test_bfs_deep_graphs(mode):
     run_bfs_case(row, nbr, [0, 350, 699, 759], 3, 2, mode)
 
 
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING | sh.BFS_CANONICAL_PARENTS, sh.BFS_BOTTOM_UP])
+def test_bfs_searches_on_one_graph_do_not_see_each_other(mode):
+    # two components (an R-MAT graph on the even vertex numbers and another on the odd ones) searched in turn
+    # on one graph object: what a search leaves behind for the vertices of the other component (parent / level
+    # records, bitmaps, queues) must not show in the next one, whose own component is all it may reach
+    r1, n1 = workgen.rmat_csr(11)
+    r2, n2 = workgen.rmat_csr(11, seed=77)
+    na, nb = len(r1) - 1, len(r2) - 1
+    src = np.r_[np.repeat(np.arange(na, dtype=np.uint32), np.diff(r1).astype(np.int64)) * 2,
+                np.repeat(np.arange(nb, dtype=np.uint32), np.diff(r2).astype(np.int64)) * 2 + 1].astype(np.uint32)
+    dst = np.r_[n1.astype(np.uint32) * 2, n2.astype(np.uint32) * 2 + 1].astype(np.uint32)
+    keep = src < dst                                   # every undirected edge once; csr_from_edges stores both directions
+    row, nbr = workgen.csr_from_edges(2 * max(na, nb), src[keep], dst[keep])
+    deg = np.diff(row)
+    even = [int(v) for v in np.flatnonzero(deg > 0) if v % 2 == 0]
+    odd = [int(v) for v in np.flatnonzero(deg > 0) if v % 2 == 1]
+    run_bfs_case(row, nbr, [even[0], odd[0], even[len(even) // 2], odd[-1], even[0]], 5, 3, mode)
+
+
 @pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP])
 def test_bfs_tiny_and_hub_graphs(mode):
     # a path, an isolated pair, and a star whose centre has more neighbours than
