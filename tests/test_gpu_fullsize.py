@@ -61,6 +61,53 @@ def test_config2_bench_cells(nbytes):
             heap.view(torch.int64).random_()                     # fresh payload for the next kind
 
 
+@pytest.mark.parametrize("nbytes,wgs", [(256, 64), (512, 32), (512, 256), (1024, 64), (14336, 256), (14352, 32)])
+def test_config2_sweep_cells_below_1mib(nbytes, wgs):
+    # cells of the full sweep that the streaming copy takes in other shapes than whole 4 KiB tasks (several messages
+    # to a 1 KiB row; rows with a short last one), at the sweep's own sizes: 65,536 messages per PE (or 256 MiB), every
+    # message in its own slot of the next multiple of 256 bytes
+    npes, seg = 8, 1 << 30
+    slot = (nbytes + 255) // 256 * 256
+    ops = min((1 << 28) // nbytes, 1 << 16)
+    nslots = max(1, min((seg // 2) // slot, (1 << 28) // slot))
+    rng = np.random.default_rng(nbytes)
+    with shmem_world(npes, seg) as (heap, base):
+        heap.view(torch.int64).random_()
+        h = heap.view(npes, seg)
+        touched = min(ops, nslots)                              # (the sweep's 14,352-byte cell goes round its slots once)
+        local, remote, span = 0, seg // 2, touched * slot
+        for kind in (sh.OP_PUT, sh.OP_GET):
+            src_off, dst_off = (local, remote) if kind == sh.OP_PUT else (remote, local)
+            before = h[:, dst_off:dst_off + span + 4096].clone()
+            threads = sh.copy_sweep_geometry(kind, base + remote, base + local, nbytes, slot, slot, nslots, ops, wgs)[1]
+            assert threads == 448                                  # the streaming copy with claimed work
+            sh.copy_sweep(kind, base + remote, base + local, nbytes, 1, 1, 1, slot, slot, nslots, ops, wgs)
+            sh.stream_sync()
+            for p in range(npes):
+                peer = (p + 1) % npes
+                src_pe, dst_pe = (p, peer) if kind == sh.OP_PUT else (peer, p)
+                got = h[dst_pe, dst_off:dst_off + span].view(touched, slot)
+                assert torch.equal(got[:, :nbytes], h[src_pe, src_off:src_off + span].view(touched, slot)[:, :nbytes])
+                if slot > nbytes:                                  # the bytes between the messages are as they were
+                    assert torch.equal(got[:, nbytes:], before[dst_pe, :span].view(touched, slot)[:, nbytes:])
+                assert torch.equal(h[dst_pe, dst_off + span:dst_off + span + 4096], before[dst_pe, span:])
+            for _ in range(6):                                     # sampled messages, each computed by the oracle
+                p = int(rng.integers(0, npes)); peer = (p + 1) % npes
+                k = int(rng.integers(0, touched))
+                src_pe, dst_pe = (p, peer) if kind == sh.OP_PUT else (peer, p)
+                w = oracle.World(2, 1 << 16, oracle.SHUFFLED, 1)
+                w.heap(0)[:] = 0; w.heap(1)[:] = 0
+                w.heap(0 if kind == sh.OP_PUT else 1)[:nbytes] = h[src_pe, src_off + k * slot:src_off + k * slot + nbytes].cpu().numpy()
+                if kind == sh.OP_PUT:
+                    w.put(0, 32768, 0, nbytes, 1); w.quiet(0)
+                    exp = w.heap(1)[32768:32768 + nbytes]
+                else:
+                    w.get(0, 32768, 0, nbytes, 1)
+                    exp = w.heap(0)[32768:32768 + nbytes]
+                assert np.array_equal(h[dst_pe, dst_off + k * slot:dst_off + k * slot + nbytes].cpu().numpy(), exp)
+            heap.view(torch.int64).random_()
+
+
 # The strided cells bench.py times: uint32, 4 MiB of payload per op (2^20 elements), 256 workgroups per PE, 8 PEs;
 # gather (the read side strided), scatter (the written side strided) and both, at strides 2, 16 and 64.  The heap is
 # random, so every byte between the elements of a strided destination is a sentinel that must survive.
