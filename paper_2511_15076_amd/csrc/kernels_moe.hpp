@@ -49,7 +49,9 @@ constexpr uint32_t MOE_PARTS = 2;             // large batches: pieces of a mess
 // Whole messages as pieces (MOE_PARTS = 1) are excluded: the one measurement run with them produced no output for
 // two minutes and was ended by its time limit, and reading the code has not shown why.
 static_assert(MOE_PARTS >= 2, "see above");
-constexpr uint32_t MOE_RANGES = 512;          // ranges of routes one workgroup can take in a dispatch
+constexpr uint32_t MOE_RANGES = 256;          // ranges of units one workgroup can take (blocks grow with the batch so that
+                                              // one workgroup's list holds them all; at 512 the dispatch kernel's LDS was
+                                              // 55,040 bytes as allocated and three workgroups did not fit a compute unit)
 // per-PE control words, after the combine flags in the signal array
 enum : uint32_t { MOE_CTL_COMBINES = 0, MOE_CTL_ARRIVALS = 1, MOE_CTL_SEND_CLAIM = 2, MOE_CTL_SEND_DONE = 3,
                   MOE_CTL_RECV_CLAIM = 4, MOE_CTL_RECV_DONE = 5, MOE_CTL_COMB_CLAIM = 6, MOE_CTL_COMB_DONE = 7, MOE_CTL_WORDS = 8 };
@@ -233,7 +235,11 @@ template <class F>
 __device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
                                           uint32_t wave, uint32_t lane, F &&work)
 {
-    constexpr uint32_t B = MOE_BLOCK, BP = MOE_BLOCK * MOE_PARTS;            // units, pieces per claimed block
+    // units per claimed block: MOE_BLOCK, or as many as it takes for the lists of the PE's workgroups to hold every
+    // block between them (at most N / (2 B) + W + 1 blocks are claimed, a list takes MOE_RANGES - 1 besides the fixed
+    // range, and a workgroup whose list is full stops claiming) -- top-k lists of dozens of experts on a team of one
+    const uint32_t B = max(MOE_BLOCK, N / (2 * (W * (MOE_RANGES - 3) - 1)) + 1);
+    const uint32_t BP = B * MOE_PARTS;                                       // pieces per claimed block
     const uint32_t S = N / (2 * W) / B * B, Ns = S * W;                      // fixed units per workgroup, and in all
     const uint32_t NB = (N - Ns + B - 1) / B;                                // blocks to claim
     const uint32_t k0 = S ? 1u : 0u, p0 = S * MOE_PARTS;                     // ranges, pieces of the fixed part
@@ -252,10 +258,10 @@ __device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N
                 if (k <= at + 1) break;
                 __builtin_amdgcn_s_sleep(1);
             }
-            uint64_t cv = 0;
-            if (lane == 0) cv = atomic_fetch_add(claim, 1);
+            uint64_t cv = NB;                                                // a full list claims nothing more: the
+            if (lane == 0 && k < MOE_RANGES) cv = atomic_fetch_add(claim, 1);   // other workgroups take the rest
             const uint32_t blk = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)min(cv, (uint64_t)0xffffffffu));
-            if (blk >= NB || k >= MOE_RANGES) {                              // (a full list: the other workgroups take the rest)
+            if (blk >= NB) {
                 if (lane == 0) *(volatile uint32_t *)&q.pub = k | 0x80000000u;
                 break;
             }

@@ -107,6 +107,9 @@ CASES = [
                                                                # that is no multiple of 8: the fixed split at every batch size)
     (3, 12, 104, 4, 14352, None, "zipf", 0.1, 11),             # the same shared out dynamically, packed pair by pair
     (5, 40, 48, 8, 1040, [48, 40, 0, 33, 48], "uniform", 0.2, 6),  # five PEs: the send order of every PE starts at its own experts
+    (2, 128, 128, 64, 32, None, "uniform", 0.0, 1),            # 8192 routes per PE on ONE workgroup: more blocks of four than its
+                                                               # list of ranges holds, so the blocks grow
+    (2, 128, 128, 64, 32, [128, 97], "zipf", 0.1, 2),
 ]
 
 
@@ -200,7 +203,7 @@ def test_argument_checks():
 
 def test_full_size_batch_as_benchmarked():
     # the largest cell bench.py times: 8 PEs, 288 experts, top-8, 128 tokens of 14,336 bytes per PE, with
-    # the team sizes it uses (36 workgroups per PE for small batches, 32 -- one per CU -- for large ones);
+    # the team sizes it uses (36 workgroups per PE for small batches, 32 -- one per CU -- or 64 for large ones);
     # the oracle affords the whole batch (8192 messages)
     P, E, T, K, Hb = 8, 288, 128, 8, 14336
     topk, ntok = workgen.moe_routing(npes=P, num_experts=E, max_tokens=T, topk=K, ntok=T)
@@ -208,9 +211,14 @@ def test_full_size_batch_as_benchmarked():
     want = oracle_run(P, E, T, K, Hb, x, topk, ntok, rounds=1, mutate=bump)
     with shmem_world(P, heap_bytes_for(P, E, T, K, Hb)):
         dm = DevMoe(P, E, T, K, Hb)
-        for wgs in (36, 32):
+        for wgs in (36, 32, 64, 96):
             got = dm.dispatch(x, topk, ntok, wgs)
             check_dispatch(got, want[0][0])
             comb = dm.combine(bump(got[0], got[3]), wgs)
             assert np.array_equal(comb, want[0][2])
+        # 100 workgroups per PE are more than the 256 compute units hold at once (three of these workgroups each,
+        # by their LDS as it is handed out, in whole units): refused on the host, not left to run into its bounded waits
+        with pytest.raises(sh.ShmemError) as ei:
+            dm.dispatch(x, topk, ntok, 100)
+        assert ei.value.status == sh.ERR_INVALID_ARG
         dm.close()
