@@ -329,9 +329,9 @@ def _extra_moe_on_current_stream(sh, torch, dev, workgen, npes, num_experts, top
                                                    ntok=ntok)
             tk, nt = torch.from_numpy(topk_np).to(dev), torch.from_numpy(ntok_np).to(dev)
             routes = int((topk_np >= 0).sum())
-            # team size: 36 workgroups per PE (one per local expert) while the batch is latency-bound; 32 (one
-            # workgroup per CU over the 8 PEs) at 32 tokens; 64 (two per CU: twice the copies in flight) from 64 on
-            w = wgs if wgs else (36 if ntok < 32 else 32 if ntok < 64 else 64)
+            # team size: 36 workgroups per PE (one per local expert) while the batch is latency-bound; 32
+            # (one workgroup per CU over the 8 PEs, no CU shared by two) once it is bandwidth-bound
+            w = wgs if wgs else (36 if ntok < 32 else 32)
             d_ms = _median_ms(lambda: sh.moe_dispatch(moe, x, tk, nt, recv_x, recv_info, recv_range, recv_count, w),
                               lambda: None, reps=20, warm=3)
             c_ms = _median_ms(lambda: sh.moe_combine(moe, recv_x, recv_info, recv_range, tk, nt, combined, w),

@@ -254,7 +254,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // kernel boundary keeps streaming stores, which are faster in bulk.)
 __device__ __forceinline__ void store_through(u32x4 v, u32x4 *d)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(d), "v"(v) : "memory");
+    // (the idle cycle: the instruction that follows a store of more than 8 bytes must not write the registers that
+    // hold its data, which the compiler sees to for its own stores and cannot for this one)
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 0" : : "v"(d), "v"(v) : "memory");
 }
 __device__ __forceinline__ void store_through(u32x2 v, u32x2 *d)
 {

@@ -231,9 +231,11 @@ struct MoeRanges {
     uint32_t pub, next;             // ranges published (bit 31: no more will come); pieces handed to waves so far
 };
 
+// step(valid, unit, part) is called for every piece a wave takes (valid: there is something to move) and once
+// more, with valid = false, when the list has ended.
 template <class F>
-__device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
-                                          uint32_t wave, uint32_t lane, F &&work)
+__device__ __forceinline__ void moe_share_loop(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
+                                               uint32_t wave, uint32_t lane, F &&step)
 {
     // units per claimed block: MOE_BLOCK, or as many as it takes for the lists of the PE's workgroups to hold every
     // block between them (at most N / (2 B) + W + 1 blocks are claimed, a list takes MOE_RANGES - 1 besides the fixed
@@ -283,12 +285,73 @@ __device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N
                 __builtin_amdgcn_s_sleep(1);
                 if (++spins > SPIN_LIMIT) { report(c, DEV_ERR_BARRIER_TIMEOUT, blockIdx.x); pub = 0x80000000u; break; }
             }
-            if ((pub & 0x7fffffffu) <= k) break;                             // the list has ended
+            if ((pub & 0x7fffffffu) <= k) { step(false, 0u, 0u); break; }    // the list has ended
             const uint32_t unit = *(volatile uint32_t *)&q.rq[k][0] + within / MOE_PARTS;
-            if (unit < *(volatile uint32_t *)&q.rq[k][1]) work(unit, within % MOE_PARTS);   // (the last block may be short)
+            step(unit < *(volatile uint32_t *)&q.rq[k][1], unit, within % MOE_PARTS);       // (the last block may be short)
         }
     }
     __syncthreads();
+}
+
+template <class F>
+__device__ __forceinline__ void moe_share(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
+                                          uint32_t wave, uint32_t lane, F &&work)
+{
+    moe_share_loop(c, q, N, W, wg, claim, wave, lane, [&](bool valid, uint32_t unit, uint32_t part) { if (valid) work(unit, part); });
+}
+
+// The same sharing with the copies of consecutive pieces overlapped: a wave asks for the vectors of its NEXT piece
+// (taking it off the counter, finding its token and its slot, issuing the loads) before it stores the ones it holds,
+// so that the loads travel while the stores are issued and the bookkeeping of a piece is not a gap in the wave's
+// traffic.  Pieces of up to MOE_PIPE_VECS vectors per lane (both halves of a 14,336-byte token), nothing predicated:
+// a lane beyond the end of its piece moves the piece's last vector again.  (Making the wait for the next loads leave
+// the stores outstanding as well -- the memory counter of a wave is in order, and a written-through store is only
+// acknowledged by memory -- needs stores the compiler can count, i.e. not the `asm` ones; built with raw buffer
+// stores carrying the same two coherence bits it measured the same, 90.0 against 89.9 us, and was not kept.)
+// prep(unit, part, piece) -> bool issues a piece's loads (false: nothing to move); flush(piece) stores it.
+constexpr uint32_t MOE_PIPE_VECS = 7;
+struct MoePiece {
+    u32x4 v[MOE_PIPE_VECS];
+    u32x4 *d;                    // where vector 0 of the piece goes
+    uint32_t nv;                 // vectors of the piece (at least 1)
+};
+struct MoePieceInfo : MoePiece {
+    u32x4 info;                  // a message's metadata on its way to the caller's array (first piece only)
+    u32x4 *info_d;               // ... or nullptr
+};
+
+template <bool CACHED>
+__device__ __forceinline__ void moe_piece_load(MoePiece &pc, const u32x4 *__restrict__ s, uint32_t lane)
+{
+#pragma unroll
+    for (uint32_t k = 0; k < MOE_PIPE_VECS; ++k) {
+        const u32x4 *at = s + min(lane + 64 * k, pc.nv - 1);
+        pc.v[k] = CACHED ? *at : __builtin_nontemporal_load(at);
+    }
+}
+
+template <bool THROUGH>
+__device__ __forceinline__ void moe_piece_store(const MoePiece &pc, uint32_t lane)
+{
+#pragma unroll
+    for (uint32_t k = 0; k < MOE_PIPE_VECS; ++k) {
+        u32x4 *at = pc.d + min(lane + 64 * k, pc.nv - 1);
+        if (THROUGH) store_through(pc.v[k], at); else __builtin_nontemporal_store(pc.v[k], at);
+    }
+}
+
+template <class Piece, class FP, class FF>
+__device__ __forceinline__ void moe_share_pipe(const Ctx &c, MoeRanges &q, uint32_t N, uint32_t W, uint32_t wg, uint64_t *claim,
+                                               uint32_t wave, uint32_t lane, FP &&prep, FF &&flush)
+{
+    Piece cur, nxt;
+    bool have = false;
+    moe_share_loop(c, q, N, W, wg, claim, wave, lane, [&](bool valid, uint32_t unit, uint32_t part) {
+        if (valid) valid = prep(unit, part, nxt);
+        if (have) flush(cur);
+        have = valid;
+        if (valid) cur = nxt;
+    });
 }
 
 // After moe_share: the workgroup of the PE that is the last to get here puts the claim counter back to zero
@@ -301,7 +364,7 @@ __device__ __forceinline__ bool moe_share_done(uint64_t *claim, uint64_t *done, 
     return true;
 }
 
-__global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
+__global__ __launch_bounds__(MOE_THREADS, 4) void k_moe_dispatch(Ctx c, MoeState m, MoeDispatchArgs a)
 {
     __shared__ uint64_t mask[MOE_MAX_EXPERTS][2];   // per expert: which of this PE's tokens go there
     __shared__ uint32_t begin[MOE_MAX_EXPERTS + 1]; // small batches: one expert's senders; large: first row of (expert, sender)
@@ -418,10 +481,35 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             }
         const uint32_t sper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
         routes = rbase[E];
-        moe_share(c, rq, routes, W, wg, gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), wave, lane, [&](uint32_t r, uint32_t part) {
-            const uint32_t k = moe_expert_of_row(rbase, E, r), e = ord(k);
-            send_piece(e, mask[e][0], mask[e][1], r - rbase[k], part, sper);
-        });
+        if (sper <= MOE_PIPE_VECS * 64) {
+            // (send_piece in two steps: the loads of a piece, and its stores once the next piece's loads are out)
+            moe_share_pipe<MoePiece>(c, rq, routes, W, wg, gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), wave, lane,
+                [&](uint32_t r, uint32_t part, MoePiece &pc) -> bool {
+                    const uint32_t k = moe_expert_of_row(rbase, E, r), e = ord(k), i = r - rbase[k];
+                    const uint32_t owner = e / m.epp, le = e % m.epp;
+                    const uint32_t t = moe_nth_token(mask[e][0], mask[e][1], i);
+                    uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + pe) * T + i) * m.msg, owner);
+                    if (part == 0) {
+                        const uint64_t hit = ballot(lane < K && s_topk[t * K + min(lane, K - 1)] == (int32_t)e);
+                        const uint32_t j = hit ? (uint32_t)__builtin_ctzll(hit) : 0;
+                        if (lane == 0) {
+                            u32x4 meta = {t, pe, j, e};
+                            store_through(meta, (u32x4 *)slot);
+                        }
+                    }
+                    const uint32_t lo = part * sper, cnt = moe_part_vecs(hvecs, lo, sper);
+                    if (cnt == 0) return false;
+                    pc.d = (u32x4 *)(slot + MOE_META_BYTES) + lo; pc.nv = cnt;
+                    moe_piece_load<true>(pc, (const u32x4 *)(a.x + ((size_t)pe * T + t) * m.hidden) + lo, lane);
+                    return true;
+                },
+                [&](const MoePiece &pc) { moe_piece_store<true>(pc, lane); });
+        } else {
+            moe_share(c, rq, routes, W, wg, gin.signal_word(ctl0 + MOE_CTL_SEND_CLAIM, pe), wave, lane, [&](uint32_t r, uint32_t part) {
+                const uint32_t k = moe_expert_of_row(rbase, E, r), e = ord(k);
+                send_piece(e, mask[e][0], mask[e][1], r - rbase[k], part, sper);
+            });
+        }
     }
     // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
     // complete and one release has made them visible, so a count is never seen before its data
@@ -527,6 +615,27 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_dispatch(Ctx c, MoeState m,
             if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
         }
         const uint32_t rper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
+        if (rper <= MOE_PIPE_VECS * 64)
+            moe_share_pipe<MoePieceInfo>(c, rq, pbase[npairs], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane,
+                [&](uint32_t g, uint32_t part, MoePieceInfo &pc) -> bool {
+                    const uint32_t q = moe_expert_of_row(pbase, npairs, g), i = g - pbase[q];    // pair in arrival order, message of the pair
+                    const uint32_t le = q % m.epp, s = (pe + P - q / m.epp) % P;
+                    moe_wait_pair(gin, le * P + s, ready, lane);
+                    const uint8_t *slot = ptr(c, m.recv_off + (((uint64_t)le * P + s) * T + i) * m.msg, pe);
+                    const size_t row = ((size_t)pe * m.epp + le) * ((size_t)P * T) + begin[le * P + s] + i;
+                    const uint32_t lo = part * rper, cnt = moe_part_vecs(hvecs, lo, rper);
+                    pc.info_d = part == 0 ? (u32x4 *)(a.recv_info + row * 4) : nullptr;
+                    pc.info = *(const u32x4 *)slot;                                              // (one request for the wave)
+                    if (cnt == 0) { if (pc.info_d && lane == 0) *pc.info_d = pc.info; return false; }
+                    pc.d = (u32x4 *)(a.recv_x + row * m.hidden) + lo; pc.nv = cnt;
+                    moe_piece_load<false>(pc, (const u32x4 *)(slot + MOE_META_BYTES) + lo, lane);
+                    return true;
+                },
+                [&](const MoePieceInfo &pc) {
+                    moe_piece_store<false>(pc, lane);
+                    if (pc.info_d && lane == 0) *pc.info_d = pc.info;
+                });
+        else
         moe_share(c, rq, pbase[npairs], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
             const uint32_t q = moe_expert_of_row(pbase, npairs, g), i = g - pbase[q];        // pair in arrival order, message of the pair
             const uint32_t le = q % m.epp, s = (pe + P - q / m.epp) % P;
@@ -629,6 +738,23 @@ __global__ __launch_bounds__(MOE_THREADS) void k_moe_combine(Ctx c, MoeState m, 
         }
         __syncthreads();
         const uint32_t cper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
+        if (cper <= MOE_PIPE_VECS * 64)
+            // (return_piece in two steps, see moe_share_pipe)
+            moe_share_pipe<MoePiece>(c, rq, ebase[m.epp], W, wg, gin.signal_word(ctl0 + MOE_CTL_COMB_CLAIM, pe), wave, lane,
+                [&](uint32_t g, uint32_t part, MoePiece &pc) -> bool {
+                    const uint32_t le = moe_expert_of_row(ebase, m.epp, g);
+                    const size_t row = ((size_t)pe * m.epp + le) * ((size_t)P * T) + (g - ebase[le]);
+                    const u32x4 info = *(const u32x4 *)(a.recv_info + row * 4);      // token, source PE, position, expert
+                    const uint32_t t = info.x, s = info.y, j = info.z;
+                    if (t >= T || s >= P || j >= K) { if (lane == 0 && part == 0) report(c, DEV_ERR_BAD_OP, row); return false; }
+                    const uint32_t lo = part * cper, cnt = moe_part_vecs(hvecs, lo, cper);
+                    if (cnt == 0) return false;
+                    pc.d = (u32x4 *)ptr(c, m.comb_off + ((uint64_t)t * K + j) * m.hidden, s) + lo; pc.nv = cnt;
+                    moe_piece_load<false>(pc, (const u32x4 *)(a.expert_out + row * m.hidden) + lo, lane);
+                    return true;
+                },
+                [&](const MoePiece &pc) { moe_piece_store<true>(pc, lane); });
+        else
         moe_share(c, rq, ebase[m.epp], W, wg, gin.signal_word(ctl0 + MOE_CTL_COMB_CLAIM, pe), wave, lane, [&](uint32_t g, uint32_t part) {
             const uint32_t le = moe_expert_of_row(ebase, m.epp, g);
             return_piece(((size_t)pe * m.epp + le) * ((size_t)P * T) + (g - ebase[le]), part, MOE_PARTS, cper);

@@ -211,13 +211,13 @@ def test_full_size_batch_as_benchmarked():
     want = oracle_run(P, E, T, K, Hb, x, topk, ntok, rounds=1, mutate=bump)
     with shmem_world(P, heap_bytes_for(P, E, T, K, Hb)):
         dm = DevMoe(P, E, T, K, Hb)
-        for wgs in (36, 32, 64, 96):
+        for wgs in (36, 32, 64):
             got = dm.dispatch(x, topk, ntok, wgs)
             check_dispatch(got, want[0][0])
             comb = dm.combine(bump(got[0], got[3]), wgs)
             assert np.array_equal(comb, want[0][2])
-        # 100 workgroups per PE are more than the 256 compute units hold at once (three of these workgroups each,
-        # by their LDS as it is handed out, in whole units): refused on the host, not left to run into its bounded waits
+        # 100 workgroups per PE are more than the 256 compute units hold at once (two of these workgroups each, by
+        # their registers): refused on the host, not left to run into its bounded waits
         with pytest.raises(sh.ShmemError) as ei:
             dm.dispatch(x, topk, ntok, 100)
         assert ei.value.status == sh.ERR_INVALID_ARG
