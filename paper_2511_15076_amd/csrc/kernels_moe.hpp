@@ -43,9 +43,13 @@ constexpr uint32_t MOE_META_BYTES = 16;
 constexpr int MOE_THREADS = 512;              // eight waves per workgroup: more copies in flight per team
 constexpr uint32_t MOE_BULK_TOKENS = 32;      // batches from this size on are balanced dynamically
 constexpr uint32_t MOE_SEND_WAVES = 7;        // large batches: waves 0..6 move messages, the eighth claims work for them
-constexpr uint32_t MOE_BLOCK = 4;             // messages per claim
+constexpr uint32_t MOE_BLOCK = 1;             // messages per claim (see below)
 constexpr uint32_t MOE_PARTS = 2;             // large batches: pieces of a message, each moved by one wave
-// Measured at 128 tokens per PE: blocks of 2, 4 or 8 messages in 2 pieces are alike, 4 pieces per message cost 10 %.
+// Measured at 128 tokens per PE: blocks of 2, 4 or 8 messages in 2 pieces were alike and 4 pieces per message cost 10 %
+// while a wave moved one piece at a time; since a wave's next loads go out ahead of its stores a piece takes less, the
+// last block a workgroup holds weighs more, and single messages are best: the combine, whose flags wait for the slowest
+// workgroup of a PE, 75.7 -> 69.2 us at 128 tokens, 45.5 -> 40.7 at 64, 29.4 -> 27.3 at 32 (blocks of two: 73.5 / 42.8 /
+// 29.6); the dispatch, which signals pair by pair, is unchanged.
 // Whole messages as pieces (MOE_PARTS = 1) are excluded: the one measurement run with them produced no output for
 // two minutes and was ended by its time limit, and reading the code has not shown why.
 static_assert(MOE_PARTS >= 2, "see above");
