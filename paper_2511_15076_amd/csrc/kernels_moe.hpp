@@ -514,6 +514,57 @@ __global__ __launch_bounds__(MOE_THREADS, 4) void k_moe_dispatch(Ctx c, MoeState
                 send_piece(e, mask[e][0], mask[e][1], r - rbase[k], part, sper);
             });
         }
+        // While this workgroup's last stores are on their way (the release below waits for them), it reads ALL the PE's
+        // announced counts -- they were sent before any message -- and lays out what it will receive: see the receive
+        // phase below.  (Done after the release, these microseconds were a gap between the two phases.)
+        {
+            const uint32_t npairs = m.epp * P;
+            for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) {
+                const uint32_t n = min(moe_poll_announced(gin, i), T);
+                begin[i] = n;
+                const uint32_t le = i / P, s = i % P, phase = (pe + P - s) % P;
+                pbase[phase * m.epp + le + 1] = n;                           // counts in arrival order, summed up below
+                ready[i] = 0;
+            }
+            __syncthreads();
+            for (uint32_t le = threadIdx.x; le < m.epp; le += blockDim.x) {  // counts -> first rows within the expert
+                uint32_t run = 0;
+                for (uint32_t s = 0; s < P; ++s) {
+                    const uint32_t n = begin[le * P + s];
+                    begin[le * P + s] = run;
+                    run += n;
+                }
+                ebase[le + 1] = run;
+            }
+            if (wave == 1) {                                                 // running sum over the pairs: every lane a stretch
+                const uint32_t per = (npairs + 63) / 64, q0 = min(lane * per, npairs), q1 = min(q0 + per, npairs);
+                uint32_t sum = 0;
+                for (uint32_t q = q0; q < q1; ++q) sum += pbase[q + 1];
+                uint32_t incl = sum;
+                for (uint32_t d = 1; d < 64; d <<= 1) {
+                    const uint32_t up = (uint32_t)__shfl_up((int)incl, d);
+                    if (lane >= d) incl += up;
+                }
+                uint32_t run = incl - sum;
+                for (uint32_t q = q0; q < q1; ++q) { run += pbase[q + 1]; pbase[q + 1] = run; }
+                if (lane == 0) pbase[0] = 0;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                ebase[0] = 0;
+                for (uint32_t le = 0; le < m.epp; ++le) ebase[le + 1] += ebase[le];
+            }
+            __syncthreads();
+            for (uint32_t le = wg; le < m.epp; le += W) {                    // the bookkeeping of an expert: one workgroup
+                const uint32_t total = ebase[le + 1] - ebase[le];
+                for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
+                    const uint32_t b = begin[le * P + s], nx = s + 1 < P ? begin[le * P + s + 1] : total;
+                    a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)b;
+                    a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(nx - b);
+                }
+                if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
+            }
+        }
     }
     // counts: zero-byte put + SignalAdd per (this PE, expert) pair -- after every wave's messages are
     // complete and one release has made them visible, so a count is never seen before its data
@@ -581,43 +632,8 @@ __global__ __launch_bounds__(MOE_THREADS, 4) void k_moe_dispatch(Ctx c, MoeState
         // workgroups that finish sending early pack what is complete while the last messages are still in flight.
         // The signals are put back to zero by the workgroup of the PE that finishes last.
         const uint32_t npairs = m.epp * P;
-        for (uint32_t i = threadIdx.x; i < npairs; i += blockDim.x) {
-            const uint32_t n = min(moe_poll_announced(gin, i), T);
-            begin[i] = n;
-            const uint32_t le = i / P, s = i % P, phase = (pe + P - s) % P;
-            pbase[phase * m.epp + le + 1] = n;                               // counts in arrival order, summed up below
-            ready[i] = 0;
-        }
-        __syncthreads();
-        for (uint32_t le = threadIdx.x; le < m.epp; le += blockDim.x) {      // counts -> first rows within the expert
-            uint32_t run = 0;
-            for (uint32_t s = 0; s < P; ++s) {
-                const uint32_t n = begin[le * P + s];
-                begin[le * P + s] = run;
-                run += n;
-            }
-            ebase[le + 1] = run;
-        }
-        if (threadIdx.x == 64) {
-            pbase[0] = 0;
-            for (uint32_t q = 0; q < npairs; ++q) pbase[q + 1] += pbase[q];
-        }
         if (threadIdx.x < 64) acquire();                                     // once: see moe_wait_pair
         wg_acquire();
-        if (threadIdx.x == 0) {
-            ebase[0] = 0;
-            for (uint32_t le = 0; le < m.epp; ++le) ebase[le + 1] += ebase[le];
-        }
-        __syncthreads();
-        for (uint32_t le = wg; le < m.epp; le += W) {                        // the bookkeeping of an expert: one workgroup
-            const uint32_t total = ebase[le + 1] - ebase[le];
-            for (uint32_t s = threadIdx.x; s < P; s += blockDim.x) {
-                const uint32_t b = begin[le * P + s], nx = s + 1 < P ? begin[le * P + s + 1] : total;
-                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2] = (int32_t)b;
-                a.recv_range[(((size_t)pe * m.epp + le) * P + s) * 2 + 1] = (int32_t)(nx - b);
-            }
-            if (threadIdx.x == 0) a.recv_count[(size_t)pe * m.epp + le] = (int32_t)total;
-        }
         const uint32_t rper = (hvecs + MOE_PARTS - 1) / MOE_PARTS;
         if (rper <= MOE_PIPE_VECS * 64)
             moe_share_pipe<MoePieceInfo>(c, rq, pbase[npairs], W, wg, gin.signal_word(ctl0 + MOE_CTL_RECV_CLAIM, pe), wave, lane,
