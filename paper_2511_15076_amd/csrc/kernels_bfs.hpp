@@ -718,8 +718,13 @@ __global__ __launch_bounds__(256) void k_bfs_bottomup(Ctx c, BfsState s, uint32_
             r0 = s.row_off[first + l];
             deg = (uint32_t)(s.row_off[first + l + 1] - r0);
             const uint32_t own = deg < BU_LANE_EDGES ? deg : BU_LANE_EDGES;   // the lane's own share of the row
-            // four neighbours and their four frontier words travel together; the first hit in row order wins
-            for (uint32_t j = 0; j < own && par == SHMEM_BFS_NONE; j += BU_BATCH) {
+            // the first neighbour alone (the best-connected of the row: the likeliest to be in the frontier) ...
+            if (own) {
+                const uint32_t u0 = s.nbr[r0];
+                if (bfs_in_front(c, s, u0)) par = u0;
+            }
+            // ... then four neighbours and their four frontier words travel together; the first hit in row order wins
+            for (uint32_t j = 1; j < own && par == SHMEM_BFS_NONE; j += BU_BATCH) {
                 uint32_t u[BU_BATCH];
                 bool in[BU_BATCH];
 #pragma unroll
