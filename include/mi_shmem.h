@@ -507,7 +507,10 @@ int shmem_moe_destroy(shmem_moe_t moe);
  * order.  Rows beyond dev_recv_count are not written.  An expert id >=
  * num_experts or repeated within a token sets the device fault word
  * (shmem_stream_sync: BAD_TARGET / BAD_OP); that entry is skipped.  The waits
- * are bounded.  wgs_per_pe workgroups per PE must all be co-resident.
+ * are bounded.  wgs_per_pe workgroups (of 512 threads) per PE must all be
+ * co-resident: on an MI355X two fit a compute unit, i.e. npes * wgs_per_pe <=
+ * 512 (INVALID_ARG beyond); one per compute unit measures best for batches of
+ * 32 tokens per PE and more, one per local expert below.
  * Errors: NOT_INIT, INVALID_ARG, ALIGN, DEVICE. */
 int shmem_moe_dispatch(shmem_moe_t moe, const void *dev_x, const int32_t *dev_topk, const int32_t *dev_ntok,
                        void *dev_recv_x, int32_t *dev_recv_info, int32_t *dev_recv_range, int32_t *dev_recv_count,
