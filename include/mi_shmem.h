@@ -289,10 +289,14 @@ int shmem_hash_lookup(const uint64_t *table_sym, size_t slots_per_pe, const uint
  * levels and parents cross this boundary in the caller's numbering.
  * shmem_bfs_create takes the CSR arrays (DEVICE: row offsets uint64[nverts+1],
  * neighbours uint32[nnz]; they are only read during the call), writes the graph
- * in the library's numbering (within a row the best-connected neighbours
- * first) into device memory that the library allocates
+ * in the library's numbering (every row sorted by its neighbours' degree rank,
+ * the best-connected first) into device memory that the library allocates
  * (4 bytes per CSR entry, 8 per row, two 4-byte maps per vertex; freed by
- * shmem_bfs_destroy; the ranking is host work, once per graph) and allocates
+ * shmem_bfs_destroy; the ranking is host work, once per graph; sorting the rows
+ * takes as much again plus the sort's workspace while the call lasts, and is
+ * left out -- the rows then only grouped into four classes of rank -- if that
+ * memory cannot be had, for nnz >= 2^32 - 1, or with MI_SHMEM_BFS_SORT_ROWS=0
+ * in the environment of shmem_init) and allocates
  * the per-PE state from the symmetric heap (bitmap, level, parent, two queues, a
  * long-row list and its scan, per-die bitmap copies, frontier and previous-level
  * bitmaps, counters: about 25.4 bytes per owned vertex; parent and level of a

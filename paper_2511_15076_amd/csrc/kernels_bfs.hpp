@@ -166,6 +166,17 @@ __global__ __launch_bounds__(256) void k_bfs_relabel(uint32_t nint, uint32_t nve
     }
 }
 
+// Neighbour entries between the library's vertex number (owner * vpp + local) and the vertex's degree rank
+// (local * npes + owner), in place: around the sort of the rows by rank.
+__global__ __launch_bounds__(256) void k_bfs_rekey(uint32_t *nbr, uint64_t nnz, uint32_t vpp, uint32_t npes, int to_rank)
+{
+    const uint64_t size = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += size) {
+        const uint32_t x = nbr[e];
+        nbr[e] = to_rank ? (x % vpp) * npes + x / vpp : (x % npes) * vpp + x / npes;
+    }
+}
+
 // Every owner clears its slice; the root's owner seeds the search.
 // `prev_has_root`: the snapshot of the bitmap "as of the previous level" starts with the root in it (searches
 // that derive a level's frontier bitmap level by level).  `make_front` (direction-optimising modes): level 0's

@@ -13,6 +13,7 @@
 #include <mutex>
 #include <new>
 #include <vector>
+#include <rocprim/device/device_segmented_radix_sort.hpp>   // once per graph: shmem_bfs_create sorts the rows of its adjacency
 
 #include "../../include/mi_shmem.h"
 #include "host_logic.hpp"
@@ -45,6 +46,7 @@ struct Host {
     int num_cus = 0;
     int wall_khz = 100000;         // rate of the constant-rate clock the streaming copy paces itself by
     bool stream_dynamic = true;    // bandwidth cells claim their tasks dynamically (kernels_stream.hpp)
+    int bfs_sort_rows = 1;         // BFS: the rows of the library's adjacency are sorted by the neighbours' degree rank
     uint32_t bfs_sort_div = 0;     // BFS: frontiers of nverts / this many vertices and more are expanded in vertex order (0: never)
     double stream_pace_ns = 0;     // pacing of the streaming copy: ns per 4 KiB task and workgroup when 256 workgroups stream
     bool cooperative = false;      // cooperative launches for kernels with in-kernel waits
@@ -396,6 +398,8 @@ int shmem_init(int npes, size_t heap_bytes_per_pe, void *dev_heap, void *dev_scr
     if (!(H.stream_pace_ns >= 0.0 && H.stream_pace_ns < 1e6)) H.stream_pace_ns = STREAM_PACE_NS;
     const char *sortdiv = getenv("MI_SHMEM_BFS_SORT_DIV");    // measurement aid: 0 = frontiers are never put in vertex order
     H.bfs_sort_div = sortdiv ? (uint32_t)strtoul(sortdiv, nullptr, 10) : BFS_SORT_DIV;
+    const char *sortrows = getenv("MI_SHMEM_BFS_SORT_ROWS");            // measurement aid: 0 = rows left in four classes of rank
+    H.bfs_sort_rows = sortrows ? atoi(sortrows) != 0 : 1;
     const char *dyn = getenv("MI_SHMEM_STREAM_DYNAMIC");
     H.stream_dynamic = !dyn || atoi(dyn) != 0;
     H.alloc.reset((uint64_t)(uintptr_t)dev_heap, (uint64_t)heap_bytes_per_pe);
@@ -861,6 +865,37 @@ int shmem_bfs_create(uint32_t nverts, const uint64_t *dev_row_off, const uint32_
                        g->d_to_orig, g->d_to_int, dev_row_off, dev_nbr, g->d_row_int, g->d_nbr_int, H.pinned + 40);
     if (hipStreamSynchronize(H.stream) != hipSuccess) return fail(SHMEM_ERR_DEVICE);   // the host vectors above are done with
     if (__atomic_load_n(H.pinned + 40, __ATOMIC_ACQUIRE) != 0) return fail(SHMEM_ERR_INVALID_ARG);
+    if (H.bfs_sort_rows && g->nnz > 0 && g->nnz < UINT32_MAX) {
+        // Every row is then sorted by the degree rank of its neighbours, the best-connected first (a segmented radix
+        // sort over the whole adjacency; the entries are turned into ranks and back around it).  The 64 neighbours that
+        // one wave instruction probes are then next to each other in rank, i.e. at about the same local vertex of every
+        // owner: one line of every owner's bitmap instead of up to 64 lines.  If the memory for it cannot be had, the
+        // rows stay as the relabelling left them (in four classes of rank).
+        uint32_t *sorted = nullptr;
+        void *temp = nullptr;
+        size_t temp_bytes = 0;
+        unsigned bits = 1;
+        while (bits < 32 && (1ull << bits) < nint64) ++bits;
+        const dim3 kgrid((unsigned)std::max(1, H.num_cus) * 8), kblock(WG_THREADS);
+        const uint64_t *row_begin = g->d_row_int, *row_end = g->d_row_int + 1;
+        bool ok = hipMalloc((void **)&sorted, g->nnz * 4) == hipSuccess &&
+                  rocprim::segmented_radix_sort_keys(nullptr, temp_bytes, g->d_nbr_int, sorted, (unsigned)g->nnz, (unsigned)nint,
+                                                     row_begin, row_end, 0u, bits, H.stream) == hipSuccess &&
+                  hipMalloc(&temp, std::max<size_t>(temp_bytes, 16)) == hipSuccess;
+        if (ok) {
+            hipLaunchKernelGGL(shmemx::k_bfs_rekey, kgrid, kblock, 0, H.stream, g->d_nbr_int, g->nnz, vpp, (uint32_t)H.npes, 1);
+            ok = rocprim::segmented_radix_sort_keys(temp, temp_bytes, g->d_nbr_int, sorted, (unsigned)g->nnz, (unsigned)nint,
+                                                    row_begin, row_end, 0u, bits, H.stream) == hipSuccess;
+            hipLaunchKernelGGL(shmemx::k_bfs_rekey, kgrid, kblock, 0, H.stream, ok ? sorted : g->d_nbr_int, g->nnz, vpp, (uint32_t)H.npes, 0);
+            if (hipStreamSynchronize(H.stream) != hipSuccess) { (void)hipFree(temp); (void)hipFree(sorted); return fail(SHMEM_ERR_DEVICE); }
+        }
+        if (temp) (void)hipFree(temp);
+        if (ok) { (void)hipFree(g->d_nbr_int); g->d_nbr_int = sorted; }
+        else {
+            if (sorted) (void)hipFree(sorted);
+            (void)hipGetLastError();
+        }
+    }
     } catch (const std::bad_alloc &) {
         return fail(SHMEM_ERR_NOMEM);
     }
