@@ -343,6 +343,16 @@ def test_bfs_frontier_order(sort_div, mode, monkeypatch):
         run_bfs_case(row, nbr, workgen.bfs_roots(row, 2), npes, wgs, mode)
 
 
+@pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN | sh.BFS_CANONICAL_PARENTS, sh.BFS_DIRECTION_OPTIMIZING])
+def test_bfs_rows_left_unsorted(mode, monkeypatch):
+    # the library sorts the rows of its copy of the adjacency by the neighbours' degree rank; without that (the
+    # path it also takes when the sort's memory cannot be had) the rows are only grouped by rank: same results
+    monkeypatch.setenv("MI_SHMEM_BFS_SORT_ROWS", "0")             # read by shmem_init
+    for scale, npes, wgs in ((13, 16, 4), (15, 3, 8)):
+        row, nbr = workgen.rmat_csr(scale)
+        run_bfs_case(row, nbr, workgen.bfs_roots(row, 2), npes, wgs, mode)
+
+
 @pytest.mark.parametrize("mode", [sh.BFS_TOP_DOWN, sh.BFS_DIRECTION_OPTIMIZING, sh.BFS_BOTTOM_UP | sh.BFS_CANONICAL_PARENTS])
 def test_bfs_deep_graphs(mode):
     # far more levels than the 64 whose sizes the statistics record: a path of 700 vertices with a few chords
